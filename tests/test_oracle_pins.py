@@ -1,0 +1,381 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the GPU or the HIP library.  Each pin names the
+passage of the paper it rests on.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import br_oracle as oc
+from oracle.jacobi import jacobi_eigh
+from oracle.metrics import misalignment, one_one_norm, orthogonality_defect, rel_err
+from paper_2602_03515_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _paper_adam_scalar(W0, grads, lr, b1, b2, eps, wd=0.0):
+    """Scalar loop of the 'standard Adam update' equation of Section 3.1:
+    epsilon inside the root, no bias correction."""
+    m, n = W0.shape
+    W = [[float(W0[i, j]) for j in range(n)] for i in range(m)]
+    M = [[0.0] * n for _ in range(m)]
+    S = [[0.0] * n for _ in range(m)]
+    for G in grads:
+        for i in range(m):
+            for j in range(n):
+                g = float(G[i, j])
+                M[i][j] = b1 * M[i][j] + (1.0 - b1) * g
+                S[i][j] = b2 * S[i][j] + (1.0 - b2) * (g * g)
+                x = M[i][j] / math.sqrt(S[i][j] + eps)
+                W[i][j] = W[i][j] - lr * x - lr * wd * W[i][j]
+    return np.array(W), np.array(M), np.array(S)
+
+
+def _paper_adam_vec(W0, grads, lr, b1, b2, eps):
+    W = np.array(W0, dtype=np.float64)
+    M = np.zeros_like(W)
+    S = np.zeros_like(W)
+    out = []
+    for G in grads:
+        M = b1 * M + (1 - b1) * G
+        S = b2 * S + (1 - b2) * G * G
+        W = W - lr * M / np.sqrt(S + eps)
+        out.append(W.copy())
+    return out
+
+
+# ---------------------------------------------------------------- P1: identity basis is Adam
+def test_identity_basis_is_paper_form_adam_scalar_loop():
+    rng = np.random.default_rng(10)
+    W0 = rng.standard_normal((5, 7))
+    grads = [rng.standard_normal((5, 7)) for _ in range(12)]
+    hp = oc.Hyper(beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.01)
+    for geometry in ("bilateral", "unilateral"):
+        hp.geometry = geometry
+        st, W, _ = oc.run_fixed_gradients(W0, grads, hp, 1e-3, freq=0)
+        Wr, Mr, Sr = _paper_adam_scalar(W0, grads, 1e-3, 0.9, 0.95, 1e-8, 0.01)
+        # Q = I: the matrix products only add exact zeros, so the match is to rounding
+        assert np.abs(W - Wr).max() <= 4e-16 * np.abs(Wr).max()
+        assert np.abs(st.M - Mr).max() <= 1e-16
+        assert np.abs(st.S - Sr).max() <= 1e-16
+    # an unrotated tensor takes the same path without any product: bit-identical
+    st, W, _ = oc.run_fixed_gradients(W0, grads, hp, 1e-3, freq=5, rotate=False)
+    assert np.array_equal(W, Wr) and np.array_equal(st.M, Mr) and np.array_equal(st.S, Sr)
+
+
+@pytest.mark.parametrize("wd", [0.0, 0.05])
+def test_textbook_flags_match_torch_adam(wd):
+    rng = np.random.default_rng(11)
+    W0 = rng.standard_normal((6, 4))
+    grads = [rng.standard_normal((6, 4)) for _ in range(15)]
+    hp = oc.Hyper(beta1=0.8, beta2=0.97, eps=1e-6, weight_decay=wd,
+                  bias_correction=True, eps_outside_sqrt=True)
+    _, W, _ = oc.run_fixed_gradients(W0, grads, hp, 3e-3, freq=0)
+    p = torch.nn.Parameter(torch.tensor(W0, dtype=torch.float64))
+    opt = torch.optim.AdamW([p], lr=3e-3, betas=(0.8, 0.97), eps=1e-6, weight_decay=wd)
+    for G in grads:
+        p.grad = torch.tensor(G, dtype=torch.float64)
+        opt.step()
+    assert np.abs(W - p.detach().numpy()).max() < 1e-12
+
+
+def test_moment_closed_forms_for_constant_gradient():
+    """EMA of a constant: M_t = (1 - b1^t) G, L_t = (1 - b2^t) G G^T (Alg. 1 l.4, Alg. 2 l.2, l.5)."""
+    rng = np.random.default_rng(12)
+    G = rng.standard_normal((4, 6))
+    hp = oc.Hyper(beta1=0.9, beta2=0.95)
+    st = oc.MatrixState(4, 6, hp)
+    for t in range(1, 8):
+        oc.ingest(st, G, hp)
+        assert np.allclose(st.M, (1 - 0.9 ** t) * G, rtol=1e-13, atol=0)
+        assert np.allclose(st.L, (1 - 0.95 ** t) * np.einsum("ik,jk->ij", G, G), rtol=1e-12, atol=1e-15)
+        assert np.allclose(st.R, (1 - 0.95 ** t) * np.einsum("ki,kj->ij", G, G), rtol=1e-12, atol=1e-15)
+    hp2 = oc.Hyper(beta1=0.9, beta2=0.95, stat_beta=0.5)
+    st2 = oc.MatrixState(4, 6, hp2)
+    oc.ingest(st2, G, hp2)
+    assert np.allclose(st2.L, 0.5 * G @ G.T)
+
+
+# ---------------------------------------------------------------- QR and Power
+@pytest.mark.parametrize("n", [1, 2, 7, 33])
+def test_householder_qr_matches_lapack_and_is_unique(n):
+    rng = np.random.default_rng(20 + n)
+    P = rng.standard_normal((n, n)) * np.exp(rng.standard_normal((1, n)))
+    Q, R = oc.householder_qr(P)
+    assert orthogonality_defect(Q) < 1e-13
+    assert np.abs(Q @ R - P).max() < 1e-12 * np.abs(P).max()
+    assert np.array_equal(R, np.triu(R)) and (np.diag(R) >= 0).all()
+    q, r = np.linalg.qr(P)
+    q = q * np.where(np.diag(r) < 0, -1.0, 1.0)[None, :]
+    assert np.abs(Q - q).max() < 1e-11
+
+
+def test_householder_qr_rank_deficient_and_zero_column():
+    rng = np.random.default_rng(25)
+    B = rng.standard_normal((9, 3))
+    P = B @ B.T                     # rank 3
+    P[:, 5] = 0.0
+    Q, R = oc.householder_qr(P)
+    assert orthogonality_defect(Q) < 1e-13
+    assert np.abs(Q @ R - P).max() < 1e-12
+    Qz, Rz = oc.householder_qr(np.zeros((4, 4)))
+    assert np.array_equal(Qz, np.eye(4)) and np.array_equal(Rz, np.zeros((4, 4)))
+
+
+def test_jacobi_matches_lapack_eigh():
+    rng = np.random.default_rng(30)
+    B = rng.standard_normal((8, 8))
+    A = B @ B.T
+    w, V = jacobi_eigh(A)
+    wl = np.linalg.eigvalsh(A)[::-1]
+    assert np.allclose(w, wl, rtol=1e-12)
+    assert np.abs(A @ V - V * w[None, :]).max() < 1e-11
+
+
+def test_repeated_power_qr_converges_to_jacobi_eigenvectors_8x8():
+    """Orthogonal iteration: Power(A, Q) repeated on a fixed SPD A with distinct
+    eigenvalues reaches the eigenvectors, ordered by descending eigenvalue."""
+    rng = np.random.default_rng(31)
+    V = synth.haar_orthogonal(rng, 8)
+    lam = 2.0 ** -np.arange(8)
+    A = (V * lam[None, :]) @ V.T
+    w, E = jacobi_eigh(A)
+    assert np.allclose(w, lam, rtol=1e-12)
+    Q = np.eye(8)
+    for _ in range(80):
+        Q = oc.power_qr(A, Q, 1)
+    align = np.abs(np.sum(E * Q, axis=0))
+    assert align.min() > 1 - 1e-10
+    # two multiplications then one QR spans the same nested subspaces as two Power calls
+    Q2a = oc.power_qr(A, oc.power_qr(A, np.eye(8), 1), 1)
+    Q2b = oc.power_qr(A, np.eye(8), 2)
+    assert np.abs(Q2a - Q2b).max() < 1e-9
+
+
+def test_refresh_keeps_basis_orthogonal_and_stats_psd():
+    W0, grads = synth.spiked_gradients(seed=3, m=24, n=40, steps=12)
+    hp = oc.Hyper()
+    st = oc.MatrixState(24, 40, hp)
+    W = W0.astype(np.float64)
+    for G in grads:
+        W = oc.optimizer_step(st, W, G, 1e-3, hp, freq=3)
+        assert np.array_equal(st.L, st.L.T) or np.abs(st.L - st.L.T).max() < 1e-18
+        assert np.abs(st.R - st.R.T).max() < 1e-18
+        assert orthogonality_defect(st.QL) < 1e-12 and orthogonality_defect(st.QR) < 1e-12
+    wl, _ = jacobi_eigh(st.L)
+    assert wl.min() >= -1e-12 * np.trace(st.L)
+    assert not np.allclose(st.QL, np.eye(24))     # the basis did move
+
+
+# ---------------------------------------------------------------- P5: fixed-rotation equivalence
+@pytest.mark.parametrize("shape", [(6, 9), (9, 6), (7, 7)])
+def test_fixed_rotation_equals_adam_in_rotated_coordinates(shape):
+    """Appendix 'Adam's equivalence under fixed rotation': running Adam on
+    W~ = A^T W B with gradients A^T G B and mapping back gives the same iterates."""
+    m, n = shape
+    rng = np.random.default_rng(40)
+    A = synth.haar_orthogonal(rng, m)
+    B = synth.haar_orthogonal(rng, n)
+    W0 = rng.standard_normal((m, n))
+    grads = [rng.standard_normal((m, n)) for _ in range(10)]
+    hp = oc.Hyper()
+    st = oc.MatrixState(m, n, hp)
+    st.QL, st.QR = A.copy(), B.copy()
+    W = W0.copy()
+    ref = _paper_adam_vec(A.T @ W0 @ B, [A.T @ G @ B for G in grads], 1e-2, 0.9, 0.95, 1e-8)
+    for G, Wt in zip(grads, ref):
+        W = oc.optimizer_step(st, W, G, 1e-2, hp, freq=0)
+        assert np.abs(W - A @ Wt @ B.T).max() < 1e-13
+    # a transposed convention (W~ = A W B^T) must NOT pass: the pin is sensitive to it
+    wrong = _paper_adam_vec(A @ W0 @ B.T, [A @ G @ B.T for G in grads], 1e-2, 0.9, 0.95, 1e-8)
+    assert np.abs(W - A.T @ wrong[-1] @ B).max() > 1e-4
+
+
+def test_norms_preserved_by_rotation():
+    m, n = 10, 14
+    rng = np.random.default_rng(41)
+    hp = oc.Hyper()
+    st = oc.MatrixState(m, n, hp)
+    st.QL, st.QR = synth.haar_orthogonal(rng, m), synth.haar_orthogonal(rng, n)
+    G = rng.standard_normal((m, n))
+    oc.ingest(st, G, hp)
+    oc.step(st, np.zeros((m, n)), G, 1.0, hp)
+    assert abs(np.linalg.norm(st.last["G_rot"]) - np.linalg.norm(G)) < 1e-12
+    assert abs(np.linalg.norm(st.last["dW"]) - np.linalg.norm(st.last["X"])) < 1e-12
+
+
+# ---------------------------------------------------------------- P7: geometry
+def test_unilateral_rotates_smaller_side_and_equals_bilateral_with_identity():
+    assert oc.rotated_sides(8, 20, "unilateral") == (True, False)
+    assert oc.rotated_sides(20, 8, "unilateral") == (False, True)
+    assert oc.rotated_sides(8, 8, "unilateral") == (True, False)      # Algorithm 2 keeps U
+    assert oc.rotated_sides(8, 20, "bilateral") == (True, True)
+    assert oc.rotated_sides(8, 20, "bilateral", rotate=False) == (False, False)
+    W0, grads = synth.spiked_gradients(seed=5, m=20, n=8, steps=9)
+    hp_u = oc.Hyper(geometry="unilateral")
+    st_u, W_u, _ = oc.run_fixed_gradients(W0, grads, hp_u, 1e-3, freq=3)
+    assert st_u.QL is None and st_u.L is None and st_u.QR.shape == (8, 8)
+    # bilateral run whose left factor is pinned to the identity after every refresh
+    hp_b = oc.Hyper(geometry="bilateral")
+    st_b = oc.MatrixState(20, 8, hp_b)
+    W = W0.astype(np.float64)
+    for G in grads:
+        t = st_b.t + 1
+        oc.ingest(st_b, G, hp_b)
+        if t % 3 == 0:
+            oc.refresh(st_b, hp_b)
+            st_b.QL = np.eye(20)                                       # V <- I of Alg. 2, mirrored
+        W = oc.step(st_b, W, G, 1e-3, hp_b)
+    assert np.abs(W - W_u).max() < 1e-14
+    assert np.abs(st_b.QR - st_u.QR).max() < 1e-14
+
+
+def test_update_invariant_to_column_signs_of_basis():
+    m, n = 7, 5
+    rng = np.random.default_rng(42)
+    A, B = synth.haar_orthogonal(rng, m), synth.haar_orthogonal(rng, n)
+    sa = np.where(rng.random(m) < 0.5, -1.0, 1.0)
+    sb = np.where(rng.random(n) < 0.5, -1.0, 1.0)
+    grads = [rng.standard_normal((m, n)) for _ in range(4)]
+    outs = []
+    for QL, QR in ((A, B), (A * sa[None, :], B * sb[None, :])):
+        hp = oc.Hyper()
+        st = oc.MatrixState(m, n, hp)
+        st.QL, st.QR = QL.copy(), QR.copy()
+        W = np.zeros((m, n))
+        for G in grads:
+            W = oc.optimizer_step(st, W, G, 1e-2, hp, freq=0)
+        outs.append((W, st.S))
+    assert np.abs(outs[0][0] - outs[1][0]).max() < 1e-15
+    assert np.abs(outs[0][1] - outs[1][1]).max() < 1e-15
+
+
+# ---------------------------------------------------------------- P8: Fisher-consistent sampling
+def test_basis_converges_to_known_kronecker_eigenvectors():
+    """Kronecker lemma in the proof of Theorem 3.1: with E[g g^T] = H_R (x) H_L the
+    statistics are multiples of the factors, so the estimated bases must reach the
+    factors' eigenvectors."""
+    rng = np.random.default_rng(50)
+    m, n = 12, 8
+    V_L, V_R = synth.haar_orthogonal(rng, m), synth.haar_orthogonal(rng, n)
+    lam_L, lam_R = 0.6 ** np.arange(m), 0.6 ** np.arange(n)
+    samples = synth.fisher_samples(51, V_L, lam_L, V_R, lam_R, 1500)
+    hp = oc.Hyper(beta1=0.9, beta2=0.999)
+    st = oc.MatrixState(m, n, hp)
+    W = np.zeros((m, n))
+    for G in samples:
+        W = oc.optimizer_step(st, W, G, 1e-3, hp, freq=5)
+    # sample mean of G G^T against tr(H_R) H_L
+    Lbar = sum(G @ G.T for G in samples) / len(samples)
+    H_L = (V_L * lam_L[None, :]) @ V_L.T
+    assert rel_err(Lbar, lam_R.sum() * H_L) < 0.1
+    k = 5                                           # well-resolved leading directions
+    assert np.abs(np.sum(V_L[:, :k] * st.QL[:, :k], axis=0)).min() > 0.97
+    assert np.abs(np.sum(V_R[:, :k] * st.QR[:, :k], axis=0)).min() > 0.97
+    H_R = (V_R * lam_R[None, :]) @ V_R.T
+    assert misalignment(st.QL, H_L) < 0.5 * misalignment(np.eye(m), H_L)
+    assert misalignment(st.QR, H_R) < 0.5 * misalignment(np.eye(n), H_R)
+
+
+# ---------------------------------------------------------------- P9: (1,1)-norm facts
+def test_one_one_norm_kronecker_product_and_theorem_ordering():
+    rng = np.random.default_rng(60)
+    A = rng.standard_normal((3, 3))
+    B = rng.standard_normal((4, 4))
+    assert abs(one_one_norm(np.kron(A, B)) - one_one_norm(A) * one_one_norm(B)) < 1e-12
+    V_L, V_R = synth.haar_orthogonal(rng, 6), synth.haar_orthogonal(rng, 5)
+    lam_L, lam_R = rng.uniform(0.1, 1, 6), rng.uniform(0.1, 1, 5)
+    H_L = (V_L * lam_L[None, :]) @ V_L.T
+    H_R = (V_R * lam_R[None, :]) @ V_R.T
+    full = one_one_norm(np.kron(H_R, H_L))
+    uni = one_one_norm(np.kron(H_R, V_L.T @ H_L @ V_L))
+    bi = one_one_norm(np.kron(V_R.T @ H_R @ V_R, V_L.T @ H_L @ V_L))
+    assert bi <= uni <= full
+    assert abs(bi - lam_L.sum() * lam_R.sum()) < 1e-10
+    # vec(A X C) = (C^T (x) A) vec(X) with column-stacking vec
+    X = rng.standard_normal((6, 5))
+    lhs = (V_L.T @ X @ V_R).reshape(-1, order="F")
+    assert np.abs(lhs - np.kron(V_R.T, V_L.T) @ X.reshape(-1, order="F")).max() < 1e-12
+
+
+# ---------------------------------------------------------------- P10: memory table
+def test_memory_overhead_table():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "memory_overhead_table.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    for source, geometry, attn, mlp in rows:
+        for shape, printed in (((4096, 4096), float(attn)), ((4096, 14336), float(mlp))):
+            gib = 4 * oc.extra_state_floats(*shape, geometry, source) / 2 ** 30
+            assert abs(gib - printed) <= 0.0051, (source, geometry, shape, gib, printed)
+
+
+# ---------------------------------------------------------------- P11: delay
+def test_delay_indexing_and_zero_delay():
+    assert [oc.delayed_weight_index(t, 3) for t in range(1, 8)] == [0, 0, 0, 0, 1, 2, 3]
+    assert [oc.delayed_weight_index(t, 0) for t in range(1, 5)] == [0, 1, 2, 3]
+    prob = synth.quadratic_problem(seed=4, m=10, n=6)
+    hp = oc.Hyper()
+    seen = []
+    grad = lambda W, t: (seen.append(W.copy()), prob.gradient(W, t))[1]
+    st, W, _ = oc.run_delayed(grad, prob.W0, hp, 1e-2, freq=4, tau=0, steps=9)
+    # undelayed loop written out directly
+    st2 = oc.MatrixState(10, 6, hp)
+    W2 = prob.W0.astype(np.float64)
+    for t in range(1, 10):
+        W2 = oc.optimizer_step(st2, W2, prob.gradient(W2, t), 1e-2, hp, freq=4)
+    assert np.array_equal(W, W2)
+    # tau = 2: the iterate handed to the gradient at step t is W_{max(t-3, 0)}
+    iterates = []
+    st3, W3, _ = oc.run_delayed(prob.gradient, prob.W0, hp, 1e-2, freq=4, tau=2, steps=6,
+                                record=lambda t, s, w: iterates.append(w.copy()))
+    seen.clear()
+    oc.run_delayed(grad, prob.W0, hp, 1e-2, freq=4, tau=2, steps=6)
+    expect = [prob.W0.astype(np.float64)] * 3 + iterates[:3]
+    for a, b in zip(seen, expect):
+        assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------- bf16 rounding
+def test_bf16_round_matches_torch_and_ties_to_even():
+    rng = np.random.default_rng(70)
+    x = np.concatenate([rng.standard_normal(4000) * np.exp(rng.uniform(-20, 20, 4000)),
+                        np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -1.0 - 2 ** -8, 0.0, 65280.0])])
+    x = x.astype(np.float32)
+    ref = torch.tensor(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(oc.bf16_round(x), ref)
+    assert oc.bf16_round(np.array([1.0 + 2 ** -8]))[0] == 1.0                 # tie -> even
+    assert oc.bf16_round(np.array([1.0 + 3 * 2 ** -8]))[0] == 1.0 + 2 ** -6   # tie -> even (up)
+    assert np.array_equal(synth.to_bf16_f32(x).astype(np.float64), ref)
+
+
+def test_literal_schedule_flag_updates_statistics_only_on_refresh():
+    W0, grads = synth.spiked_gradients(seed=6, m=6, n=6, steps=6)
+    hp = oc.Hyper(stats_on_refresh_only=True)
+    st = oc.MatrixState(6, 6, hp)
+    W = W0.astype(np.float64)
+    for G in grads:
+        W = oc.optimizer_step(st, W, G, 1e-3, hp, freq=3)
+    G3, G6 = grads[2].astype(np.float64), grads[5].astype(np.float64)
+    assert np.allclose(st.L, 0.95 * 0.05 * G3 @ G3.T + 0.05 * G6 @ G6.T, rtol=1e-12)
+
+
+def test_first_moment_source_uses_momentum_gram():
+    """Algorithm 2, first-order source: Power(M M^T, U), no L/R buffers.  With a
+    rank-one mean gradient the leading basis vectors are its singular vectors
+    (first-order analogue of Theorem 3.1)."""
+    rng = np.random.default_rng(80)
+    u = rng.standard_normal(9); u /= np.linalg.norm(u)
+    v = rng.standard_normal(6); v /= np.linalg.norm(v)
+    hp = oc.Hyper(source="first")
+    st = oc.MatrixState(9, 6, hp)
+    assert st.L is None and st.R is None
+    W = np.zeros((9, 6))
+    for t in range(1, 13):
+        G = 3.0 * np.outer(u, v) + 0.01 * rng.standard_normal((9, 6))
+        W = oc.optimizer_step(st, W, G, 1e-3, hp, freq=2)
+    assert abs(st.QL[:, 0] @ u) > 0.999 and abs(st.QR[:, 0] @ v) > 0.999
