@@ -1,0 +1,205 @@
+/*
+ * br.h -- C ABI of the basis-rotation optimizer step for AMD MI355X (gfx950).
+ *
+ * The library applies "Adam with basis rotation" (Algorithm 1 of the paper) with
+ * the second-moment "Eigenbasis-Estimation" of Algorithm 2 to a list of weight
+ * matrices, one pipeline stage's share, on one GPU.  Every step of the path runs in
+ * hand-written HIP kernels; there is no CPU fallback.
+ *
+ * Per optimizer step t = 1, 2, ... the caller issues, in Algorithm 1's order:
+ *
+ *     br_accumulate_stats(ctx, grads, n)          first moment + Kronecker statistics
+ *     if (t % freq == 0) br_refresh_basis(ctx)    Eigenbasis-Estimation (Power + QR)
+ *     br_step(ctx, params, grads, n, lr_t)        rotate, Adam in the rotated basis, rotate back
+ *
+ * The refresh schedule, the learning-rate schedule and the ring of delayed
+ * gradients (Appendix B: the gradient consumed at step t was evaluated at
+ * W_{max(t-1-tau,0)}) are host policy outside the library: the library only ever
+ * sees the pointer of the gradient to consume.
+ *
+ * Conventions
+ *   layout     every matrix is row-major and contiguous: element (i, j) of an
+ *              m x n matrix is at base[i*n + j]; m = rows.
+ *   memory     all pointers named dev_* / params / grads entries are DEVICE pointers,
+ *              16-byte aligned; arrays of pointers and descriptor arrays are HOST
+ *              memory, read during the call only.
+ *   ownership  the caller owns parameters, gradients and the single workspace
+ *              buffer.  The library never allocates or frees device memory; it keeps
+ *              pointers into the workspace until br_destroy.
+ *   streams    all work is enqueued on the HIP stream given to br_init (a
+ *              hipStream_t passed as void*, NULL = the null stream).  No call
+ *              synchronises with the host except br_profile_end.
+ *   errors     every call returns a br_status; nothing throws or aborts.  Argument
+ *              errors are detected on the host before anything is launched.  After
+ *              BR_ERR_HIP the context is unusable (sticky).  br_last_error gives text.
+ *   threads    one context, one calling thread at a time.
+ *   determinism identical inputs give bit-identical outputs (no floating-point
+ *              atomics anywhere).
+ */
+#ifndef BR_H_
+#define BR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct br_ctx br_ctx; /* opaque, host memory, owned by the library */
+
+typedef enum {
+  BR_OK = 0,
+  BR_ERR_INVALID_ARG = 1, /* null pointer, bad enum, bad count                       */
+  BR_ERR_SHAPE = 2,       /* non-positive or too large dimension, n_mats mismatch    */
+  BR_ERR_DTYPE = 3,       /* unknown element type                                    */
+  BR_ERR_STATE = 4,       /* calls out of order (e.g. br_step without its statistics) */
+  BR_ERR_WORKSPACE = 5,   /* workspace too small or misaligned                       */
+  BR_ERR_HIP = 6,         /* a HIP runtime call failed; sticky                       */
+  BR_ERR_UNSUPPORTED = 7  /* a documented option that this build does not implement  */
+} br_status;
+
+typedef enum { BR_F32 = 0, BR_BF16 = 1 } br_dtype;
+
+/* Rotation geometry G of Algorithm 2.  Unilateral rotates only the side of size
+ * min(m, n) (Section 3.2; memory-overhead appendix); a square matrix keeps the
+ * left factor, as Algorithm 2 lines 7-9 do. */
+typedef enum { BR_BILATERAL = 0, BR_UNILATERAL = 1 } br_geometry;
+
+/* Approximation source S of Algorithm 2.  SECOND keeps L, R (lines 1-9); FIRST uses
+ * M M^T and M^T M at refresh time and keeps no statistics buffers (lines 11-19). */
+typedef enum { BR_SRC_SECOND = 0, BR_SRC_FIRST = 1 } br_source;
+
+/* Input precision of the matrix-core contractions.  F32 issues FP32 MFMA. */
+typedef enum { BR_MATH_F32 = 0, BR_MATH_BF16 = 1, BR_MATH_BF16X3 = 2 } br_math;
+
+/* Which buffer br_get_state returns. */
+typedef enum {
+  BR_STATE_M = 0,      /* first moment, original space, m x n  (Algorithm 1 line 4)      */
+  BR_STATE_S = 1,      /* second moment in the rotated basis, m x n  (line 10)           */
+  BR_STATE_L = 2,      /* EMA of G G^T, m x m  (Algorithm 2 line 2)                      */
+  BR_STATE_R = 3,      /* EMA of G^T G, n x n  (Algorithm 2 line 5)                      */
+  BR_STATE_QL = 4,     /* left rotation U, m x m                                         */
+  BR_STATE_QR = 5,     /* right rotation V, n x n                                        */
+  BR_STATE_MASTER = 6, /* FP32 master weights of a BF16 parameter, m x n                 */
+  BR_STATE_NORMS = 7   /* 1 x 2: ||G~||_F^2 and ||X||_F^2 of the latest step             */
+} br_state_kind;
+
+typedef struct {
+  int64_t m, n;        /* rows, columns                                                  */
+  int32_t param_dtype; /* br_dtype of the parameter buffer                               */
+  int32_t grad_dtype;  /* br_dtype of the gradient buffer                                */
+  int32_t rotate;      /* 0: plain Adam for this tensor (embeddings etc., App. D)        */
+  int32_t reserved;    /* must be 0                                                      */
+} br_matrix_desc;
+
+typedef struct {
+  float beta1, beta2;  /* Adam moment decay rates (Algorithm 1 lines 4, 10)              */
+  float eps;           /* inside the square root, as Algorithm 1 line 11 has it          */
+  float weight_decay;  /* decoupled: W <- W - lr*wd*W on the pre-step W; 0 = Algorithm 1 */
+  float stat_beta;     /* decay of L, R; negative: use beta2 (Algorithm 2 lines 2, 5)    */
+  int32_t geometry;    /* br_geometry                                                    */
+  int32_t source;      /* br_source                                                      */
+  int32_t power_iters; /* multiplications by L (R) before the single QR; paper: 1        */
+  int32_t bias_correction;  /* 1: divide moments by (1 - beta^t); 0 = Algorithm 1        */
+  int32_t eps_outside_sqrt; /* 1: m / (sqrt(s) + eps);            0 = Algorithm 1        */
+  int32_t math;        /* br_math                                                        */
+  int32_t compute_norms;    /* 1: keep ||G~||_F^2, ||X||_F^2 per matrix (BR_STATE_NORMS) */
+  int32_t reserved;    /* must be 0                                                      */
+} br_hparams;
+
+/* One line per kernel symbol of a profiled region (see br_profile_begin). */
+typedef struct {
+  char kernel[64];   /* short name of the kernel family/instance                        */
+  int64_t launches;  /* launches recorded                                               */
+  double ms;         /* sum of HIP-event durations of those launches, milliseconds      */
+  double flops;      /* algorithmic floating-point operations of those launches         */
+  double bytes;      /* algorithmic HBM bytes of those launches                         */
+} br_profile_entry;
+
+/*
+ * Size of the workspace br_init needs for these matrices: `state_bytes` holds the
+ * optimizer state (M, S~, L, R, Q_L, Q_R, master weights: the FP32 buffers of the
+ * memory-overhead appendix), `scratch_bytes` the temporaries of one step or one
+ * refresh.  The workspace must be at least state_bytes + scratch_bytes long and
+ * 256-byte aligned.  Host-only; launches nothing.
+ */
+br_status br_workspace_bytes(const br_matrix_desc* descs, int32_t n_mats, const br_hparams* hp,
+                             size_t* state_bytes, size_t* scratch_bytes);
+
+/*
+ * Create a context over `n_mats` matrices.  Zero-fills the state, sets
+ * Q_L = Q_R = I (so the steps before the first refresh are plain Adam) and t = 0.
+ * `dev_workspace` is device memory of `workspace_bytes` bytes owned by the caller,
+ * which must outlive the context.  `hip_stream` is a hipStream_t.
+ */
+br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, const br_hparams* hp,
+                  void* dev_workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Consume this step's (delayed) gradients: M <- beta1 M + (1-beta1) G for every
+ * matrix (Algorithm 1 line 4) and, for the second-order source,
+ * L <- b L + (1-b) G G^T, R <- b R + (1-b) G^T G on the rotated sides
+ * (Algorithm 2 lines 2, 5), accumulated every step.
+ * `grads`: host array of n_mats device pointers, matrix i being m_i x n_i of
+ * grad_dtype.  Must be called exactly once before each br_step.
+ */
+br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_mats);
+
+/*
+ * Eigenbasis-Estimation for every rotated side (Algorithm 2 lines 3, 6 and
+ * Section 3.2): P <- A^power_iters Q with A = L or R (first-order source: M M^T,
+ * M^T M), then Q <- the orthogonal factor of the Householder QR of P with
+ * diag(R) >= 0.  Needs no gradients; uses the statistics as they stand.
+ */
+br_status br_refresh_basis(br_ctx* ctx);
+
+/*
+ * Algorithm 1 lines 8-11 for every matrix: G~ = Q_L^T G Q_R, M~ = Q_L^T M Q_R,
+ * S~ <- beta2 S~ + (1-beta2) G~.G~, X = M~ / sqrt(S~ + eps),
+ * W <- W - lr * Q_L X Q_R^T - lr * weight_decay * W.  Increments t.
+ * `params`: host array of device pointers to the weights (param_dtype), updated in
+ * place; a BF16 parameter is the round-to-nearest-even image of its FP32 master
+ * copy kept in the state (initialised from the parameter at the first step).
+ * `grads`: the same gradients that were given to br_accumulate_stats.
+ * Returns BR_ERR_STATE if br_accumulate_stats has not run since the last step.
+ */
+br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, int32_t n_mats,
+                  float lr);
+
+/*
+ * Borrow a pointer to one state buffer of matrix `mat` (valid until br_destroy).
+ * The caller may read or overwrite it between calls (tests inject a fixed basis;
+ * a checkpoint is a copy of the state part of the workspace plus t).
+ * A buffer that does not exist for this matrix (e.g. L of an unrotated side)
+ * returns BR_ERR_INVALID_ARG.
+ */
+br_status br_get_state(br_ctx* ctx, int32_t mat, int32_t which, void** dev_ptr, int64_t* rows,
+                       int64_t* cols);
+
+/* Number of completed steps t, and a way to set it when restoring a checkpoint. */
+br_status br_get_step_count(const br_ctx* ctx, int64_t* t);
+br_status br_set_step_count(br_ctx* ctx, int64_t t);
+
+/*
+ * Timing for the benchmark.  Between br_profile_begin and br_profile_end every kernel
+ * launch is bracketed by HIP events on the context's stream.  br_profile_end
+ * synchronises the stream, stops recording and writes one entry per kernel symbol (at
+ * most `cap`) with launch counts, summed durations and algorithmic work.
+ */
+br_status br_profile_begin(br_ctx* ctx);
+br_status br_profile_end(br_ctx* ctx, br_profile_entry* out, int32_t cap, int32_t* n_out);
+
+/* Text of the latest error of this context ("" if none).  Never NULL. */
+const char* br_last_error(const br_ctx* ctx);
+
+/* Library version string, e.g. "br-hip 0.1 gfx950". */
+const char* br_version(void);
+
+/* Free the host-side context.  Device memory stays the caller's. */
+void br_destroy(br_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BR_H_ */

@@ -1,0 +1,743 @@
+// Host logic of the C ABI declared in include/br.h: argument validation, workspace
+// layout, grouping of same-shape matrices into batched launches, and the sequencing of
+// Algorithm 1 / Algorithm 2 as kernel launches on the caller's stream.
+#include "../../include/br.h"
+#include "br_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+namespace {
+
+constexpr int kStepChunk = 16;     // matrices per batched step launch ([G|M] doubles it to BR_MAXB)
+constexpr int kRefreshChunk = 32;  // factor matrices per batched refresh launch
+constexpr int64_t kMaxDim = 1 << 24;
+constexpr size_t kNormPartialBytes = (size_t)BR_MAXB * 2 * BR_NORM_BLOCKS * sizeof(float);
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct MatState {
+  br_matrix_desc d;
+  bool rot_l = false, rot_r = false;
+  float *M = nullptr, *S = nullptr, *L = nullptr, *R = nullptr, *QL = nullptr, *QR = nullptr;
+  float *master = nullptr, *norms = nullptr;
+  bool master_ready = false;
+};
+
+struct Group {  // matrices that can share a batched launch
+  int64_t m, n;
+  int pdt, gdt;
+  bool rot_l, rot_r;
+  std::vector<int> idx;
+};
+
+struct RefreshJob {
+  int mat;
+  bool left;
+};
+
+struct ProfRec {
+  const char* name;
+  size_t ev;  // index of the start event; the stop event follows it
+  double flops, bytes;
+};
+
+struct Layout {
+  size_t state_bytes = 0, scratch_bytes = 0;
+  std::vector<Group> groups;
+  std::map<int64_t, std::vector<RefreshJob>> refresh;  // factor order -> jobs
+};
+
+}  // namespace
+
+struct br_ctx {
+  std::vector<MatState> mats;
+  br_hparams hp;
+  Layout lay;
+  hipStream_t stream = nullptr;
+  char* scratch = nullptr;
+  int64_t t = 0;
+  bool stats_fresh = false;
+  bool dead = false;
+  std::string err;
+  bool prof_on = false;
+  std::vector<hipEvent_t> events;
+  size_t events_used = 0;
+  std::vector<ProfRec> recs;
+};
+
+namespace {
+
+thread_local std::string g_static_err;
+
+br_status fail(br_ctx* c, br_status st, const std::string& msg) {
+  if (c) c->err = msg;
+  return st;
+}
+
+void sides(const br_matrix_desc& d, const br_hparams& hp, bool* l, bool* r) {
+  *l = *r = false;
+  if (!d.rotate) return;
+  if (hp.geometry == BR_BILATERAL) {
+    *l = *r = true;
+  } else if (d.m <= d.n) {
+    *l = true;  // smaller side; a square matrix keeps the left factor (Algorithm 2 lines 7-9)
+  } else {
+    *r = true;
+  }
+}
+
+br_status validate(const br_matrix_desc* descs, int32_t n_mats, const br_hparams* hp, std::string* why) {
+  if (!descs || !hp) { *why = "null descriptor or hyper-parameter pointer"; return BR_ERR_INVALID_ARG; }
+  if (n_mats <= 0) { *why = "n_mats must be positive"; return BR_ERR_INVALID_ARG; }
+  if (hp->geometry != BR_BILATERAL && hp->geometry != BR_UNILATERAL) { *why = "unknown geometry"; return BR_ERR_INVALID_ARG; }
+  if (hp->source != BR_SRC_SECOND && hp->source != BR_SRC_FIRST) { *why = "unknown source"; return BR_ERR_INVALID_ARG; }
+  if (hp->math != BR_MATH_F32 && hp->math != BR_MATH_BF16 && hp->math != BR_MATH_BF16X3) { *why = "unknown math mode"; return BR_ERR_INVALID_ARG; }
+  if (hp->math != BR_MATH_F32) { *why = "only BR_MATH_F32 is implemented"; return BR_ERR_UNSUPPORTED; }
+  if (hp->power_iters < 1 || hp->power_iters > 8) { *why = "power_iters must be in 1..8"; return BR_ERR_INVALID_ARG; }
+  if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f)) { *why = "beta1/beta2 must be in [0,1)"; return BR_ERR_INVALID_ARG; }
+  if (!(hp->stat_beta < 1.f)) { *why = "stat_beta must be below 1 (negative selects beta2)"; return BR_ERR_INVALID_ARG; }
+  if (!(hp->eps >= 0.f) || !(hp->weight_decay >= 0.f)) { *why = "eps and weight_decay must be non-negative"; return BR_ERR_INVALID_ARG; }
+  if (hp->reserved != 0) { *why = "br_hparams.reserved must be 0"; return BR_ERR_INVALID_ARG; }
+  for (int i = 0; i < n_mats; ++i) {
+    const br_matrix_desc& d = descs[i];
+    if (d.m <= 0 || d.n <= 0 || d.m > kMaxDim || d.n > kMaxDim) { *why = "matrix " + std::to_string(i) + ": dimensions must be in 1..2^24"; return BR_ERR_SHAPE; }
+    if ((d.param_dtype != BR_F32 && d.param_dtype != BR_BF16) || (d.grad_dtype != BR_F32 && d.grad_dtype != BR_BF16)) { *why = "matrix " + std::to_string(i) + ": unknown dtype"; return BR_ERR_DTYPE; }
+    if (d.reserved != 0) { *why = "br_matrix_desc.reserved must be 0"; return BR_ERR_INVALID_ARG; }
+  }
+  return BR_OK;
+}
+
+// Bytes of step scratch one matrix of a group needs (all buffers m x n FP32, 256-byte aligned).
+int step_buffers(const Group& g) {
+  int nb = 0;
+  if (g.rot_l && g.rot_r) nb = 4;
+  else if (g.rot_l || g.rot_r) nb = 2;
+  if (g.gdt == BR_BF16 && (g.rot_l || g.rot_r)) nb += 1;  // FP32 image of the gradient
+  return nb;
+}
+
+struct RefreshScratch {
+  size_t P0, P1, gram, Vc, Y, W, T, diag, total;
+};
+
+RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
+  RefreshScratch r;
+  size_t kk = align256((size_t)k * k * 4);
+  size_t panels = (size_t)((k + BR_QR_NB - 1) / BR_QR_NB);
+  size_t off = 0;
+  r.P0 = off; off += kk;
+  r.P1 = off; if (hp.power_iters > 1) off += kk;
+  r.gram = off; if (hp.source == BR_SRC_FIRST) off += kk;
+  r.Vc = off; off += align256((size_t)k * BR_QR_NB * 4);
+  r.Y = off; off += align256((size_t)k * BR_QR_NB * 4);
+  r.W = off; off += align256((size_t)k * BR_QR_NB * 4);
+  r.T = off; off += align256(panels * BR_QR_NB * BR_QR_NB * 4);
+  r.diag = off; off += align256((size_t)k * 4);
+  r.total = off;
+  return r;
+}
+
+void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Layout* lay) {
+  lay->groups.clear();
+  lay->refresh.clear();
+  size_t state = 0, scratch = 0;
+  for (int i = 0; i < n_mats; ++i) {
+    const br_matrix_desc& d = descs[i];
+    bool l, r;
+    sides(d, hp, &l, &r);
+    size_t mn = align256((size_t)d.m * d.n * 4);
+    state += 2 * mn;  // M, S
+    if (hp.source == BR_SRC_SECOND) {
+      if (l) state += align256((size_t)d.m * d.m * 4);
+      if (r) state += align256((size_t)d.n * d.n * 4);
+    }
+    if (l) state += align256((size_t)d.m * d.m * 4);
+    if (r) state += align256((size_t)d.n * d.n * 4);
+    if (d.param_dtype == BR_BF16) state += mn;
+    state += 256;  // norms
+    Group* g = nullptr;
+    for (auto& c : lay->groups)
+      if (c.m == d.m && c.n == d.n && c.pdt == d.param_dtype && c.gdt == d.grad_dtype && c.rot_l == l && c.rot_r == r) g = &c;
+    if (!g) {
+      lay->groups.push_back(Group{d.m, d.n, d.param_dtype, d.grad_dtype, l, r, {}});
+      g = &lay->groups.back();
+    }
+    g->idx.push_back(i);
+    if (l) lay->refresh[d.m].push_back(RefreshJob{i, true});
+    if (r) lay->refresh[d.n].push_back(RefreshJob{i, false});
+  }
+  for (auto& g : lay->groups) {
+    size_t chunk = std::min<size_t>(g.idx.size(), kStepChunk);
+    size_t need = chunk * step_buffers(g) * align256((size_t)g.m * g.n * 4);
+    scratch = std::max(scratch, need);
+  }
+  for (auto& kv : lay->refresh) {
+    size_t chunk = std::min<size_t>(kv.second.size(), kRefreshChunk);
+    scratch = std::max(scratch, chunk * refresh_scratch(kv.first, hp).total);
+  }
+  lay->state_bytes = state;
+  lay->scratch_bytes = scratch + kNormPartialBytes;
+}
+
+// ---- launch bookkeeping ------------------------------------------------------------------
+bool hip_ok(br_ctx* c, hipError_t e, const char* what) {
+  if (e == hipSuccess) return true;
+  c->dead = true;
+  c->err = std::string(what) + ": " + hipGetErrorString(e);
+  return false;
+}
+
+struct Timed {  // brackets one launch (or a region) with events while profiling is on
+  br_ctx* c;
+  bool live = false;
+  Timed(br_ctx* ctx, const char* name, double flops, double bytes) : c(ctx) {
+    if (!c->prof_on) return;
+    if (c->events_used + 2 > c->events.size()) {
+      size_t want = c->events.size() + 512;
+      while (c->events.size() < want) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        c->events.push_back(e);
+      }
+    }
+    c->recs.push_back(ProfRec{name, c->events_used, flops, bytes});
+    live = (hipEventRecord(c->events[c->events_used], c->stream) == hipSuccess);
+    if (!live) c->recs.pop_back();
+  }
+  ~Timed() {
+    if (!live) return;
+    if (hipEventRecord(c->events[c->events_used + 1], c->stream) != hipSuccess) c->recs.pop_back();
+    else c->events_used += 2;
+  }
+};
+
+bool gemm(br_ctx* c, const BrGemmArgs& a, const BrGemmBatch& b, bool profile = true) {
+  const char* name = nullptr;
+  double flops = 2.0 * a.M * a.N * (double)a.K * a.batch;
+  if (a.mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (a.M + 127) / 128));
+  if (profile && c->prof_on) {
+    (void)br_launch_gemm(nullptr, BrGemmArgs{0, 0, 0, 0, 0, 0, a.transA, a.transB, 0, 0, 0, 0}, b, &name);
+    Timed tm(c, name, flops, 0.0);
+    return hip_ok(c, br_launch_gemm(c->stream, a, b, nullptr), "gemm launch");
+  }
+  return hip_ok(c, br_launch_gemm(c->stream, a, b, nullptr), "gemm launch");
+}
+
+inline float* scratch_buf(br_ctx* c, size_t per_mat_bufs, size_t bytes_each, int mat_in_chunk, int which) {
+  return reinterpret_cast<float*>(c->scratch + kNormPartialBytes + ((size_t)mat_in_chunk * per_mat_bufs + which) * bytes_each);
+}
+
+}  // namespace
+
+// =========================================================================================
+extern "C" {
+
+const char* br_version(void) { return "br-hip 0.1 gfx950"; }
+
+const char* br_last_error(const br_ctx* ctx) { return ctx ? ctx->err.c_str() : g_static_err.c_str(); }
+
+br_status br_workspace_bytes(const br_matrix_desc* descs, int32_t n_mats, const br_hparams* hp, size_t* state_bytes,
+                             size_t* scratch_bytes) {
+  std::string why;
+  br_status st = validate(descs, n_mats, hp, &why);
+  if (st != BR_OK) { g_static_err = why; return st; }
+  if (!state_bytes || !scratch_bytes) { g_static_err = "null output pointer"; return BR_ERR_INVALID_ARG; }
+  Layout lay;
+  plan(descs, n_mats, *hp, &lay);
+  *state_bytes = lay.state_bytes;
+  *scratch_bytes = lay.scratch_bytes;
+  return BR_OK;
+}
+
+br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, const br_hparams* hp, void* dev_workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  if (!out) { g_static_err = "null context output pointer"; return BR_ERR_INVALID_ARG; }
+  *out = nullptr;
+  std::string why;
+  br_status st = validate(descs, n_mats, hp, &why);
+  if (st != BR_OK) { g_static_err = why; return st; }
+  if (!dev_workspace) { g_static_err = "null workspace"; return BR_ERR_INVALID_ARG; }
+  if (reinterpret_cast<uintptr_t>(dev_workspace) & 255u) { g_static_err = "workspace must be 256-byte aligned"; return BR_ERR_WORKSPACE; }
+  br_ctx* c = new (std::nothrow) br_ctx();
+  if (!c) { g_static_err = "out of host memory"; return BR_ERR_INVALID_ARG; }
+  c->hp = *hp;
+  if (c->hp.stat_beta < 0.f) c->hp.stat_beta = c->hp.beta2;
+  plan(descs, n_mats, c->hp, &c->lay);
+  if (workspace_bytes < c->lay.state_bytes + c->lay.scratch_bytes) {
+    g_static_err = "workspace too small: need " + std::to_string(c->lay.state_bytes + c->lay.scratch_bytes) + " bytes";
+    delete c;
+    return BR_ERR_WORKSPACE;
+  }
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  char* p = reinterpret_cast<char*>(dev_workspace);
+  c->mats.resize(n_mats);
+  for (int i = 0; i < n_mats; ++i) {
+    MatState& m = c->mats[i];
+    m.d = descs[i];
+    sides(m.d, c->hp, &m.rot_l, &m.rot_r);
+    size_t mn = align256((size_t)m.d.m * m.d.n * 4);
+    auto take = [&](size_t bytes) { float* q = reinterpret_cast<float*>(p); p += bytes; return q; };
+    m.M = take(mn);
+    m.S = take(mn);
+    if (c->hp.source == BR_SRC_SECOND) {
+      if (m.rot_l) m.L = take(align256((size_t)m.d.m * m.d.m * 4));
+      if (m.rot_r) m.R = take(align256((size_t)m.d.n * m.d.n * 4));
+    }
+    if (m.rot_l) m.QL = take(align256((size_t)m.d.m * m.d.m * 4));
+    if (m.rot_r) m.QR = take(align256((size_t)m.d.n * m.d.n * 4));
+    if (m.d.param_dtype == BR_BF16) m.master = take(mn);
+    m.norms = take(256);
+  }
+  c->scratch = reinterpret_cast<char*>(dev_workspace) + c->lay.state_bytes;
+  // zero state, identity bases
+  if (!hip_ok(c, hipMemsetAsync(dev_workspace, 0, c->lay.state_bytes, c->stream), "state clear")) {
+    g_static_err = c->err; delete c; return BR_ERR_HIP;
+  }
+  for (auto& kv : c->lay.refresh) {
+    const auto& jobs = kv.second;
+    for (size_t off = 0; off < jobs.size(); off += BR_MAXB) {
+      float* ptrs[BR_MAXB];
+      int b = (int)std::min<size_t>(BR_MAXB, jobs.size() - off);
+      for (int i = 0; i < b; ++i) {
+        const MatState& m = c->mats[jobs[off + i].mat];
+        ptrs[i] = jobs[off + i].left ? m.QL : m.QR;
+      }
+      if (!hip_ok(c, br_launch_set_identity(c->stream, ptrs, b, (int)kv.first), "identity init")) {
+        g_static_err = c->err; delete c; return BR_ERR_HIP;
+      }
+    }
+  }
+  *out = c;
+  return BR_OK;
+}
+
+void br_destroy(br_ctx* ctx) {
+  if (!ctx) return;
+  for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+br_status br_get_step_count(const br_ctx* ctx, int64_t* t) {
+  if (!ctx || !t) return BR_ERR_INVALID_ARG;
+  *t = ctx->t;
+  return BR_OK;
+}
+
+br_status br_set_step_count(br_ctx* ctx, int64_t t) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  if (t < 0) return fail(ctx, BR_ERR_INVALID_ARG, "step count must be non-negative");
+  ctx->t = t;
+  for (auto& m : ctx->mats) m.master_ready = (t > 0) && m.master;
+  return BR_OK;
+}
+
+br_status br_get_state(br_ctx* ctx, int32_t mat, int32_t which, void** dev_ptr, int64_t* rows, int64_t* cols) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  if (!dev_ptr || !rows || !cols) return fail(ctx, BR_ERR_INVALID_ARG, "null output pointer");
+  if (mat < 0 || mat >= (int32_t)ctx->mats.size()) return fail(ctx, BR_ERR_INVALID_ARG, "matrix index out of range");
+  MatState& m = ctx->mats[mat];
+  float* p = nullptr;
+  int64_t r = 0, cdim = 0;
+  switch (which) {
+    case BR_STATE_M: p = m.M; r = m.d.m; cdim = m.d.n; break;
+    case BR_STATE_S: p = m.S; r = m.d.m; cdim = m.d.n; break;
+    case BR_STATE_L: p = m.L; r = cdim = m.d.m; break;
+    case BR_STATE_R: p = m.R; r = cdim = m.d.n; break;
+    case BR_STATE_QL: p = m.QL; r = cdim = m.d.m; break;
+    case BR_STATE_QR: p = m.QR; r = cdim = m.d.n; break;
+    case BR_STATE_MASTER: p = m.master; r = m.d.m; cdim = m.d.n; break;
+    case BR_STATE_NORMS: p = m.norms; r = 1; cdim = 2; break;
+    default: return fail(ctx, BR_ERR_INVALID_ARG, "unknown state kind");
+  }
+  if (!p) return fail(ctx, BR_ERR_INVALID_ARG, "this matrix has no such buffer");
+  *dev_ptr = p;
+  *rows = r;
+  *cols = cdim;
+  return BR_OK;
+}
+
+static br_status check_call(br_ctx* ctx, const void* const* a, const void* const* b, bool need_b, int32_t n_mats) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  if (ctx->dead) return BR_ERR_HIP;
+  if (!a || (need_b && !b)) return fail(ctx, BR_ERR_INVALID_ARG, "null pointer array");
+  if (n_mats != (int32_t)ctx->mats.size()) return fail(ctx, BR_ERR_SHAPE, "n_mats differs from br_init");
+  for (int i = 0; i < n_mats; ++i) {
+    if (!a[i] || (need_b && !b[i])) return fail(ctx, BR_ERR_INVALID_ARG, "null device pointer for matrix " + std::to_string(i));
+    if ((reinterpret_cast<uintptr_t>(a[i]) & 15u) || (need_b && (reinterpret_cast<uintptr_t>(b[i]) & 15u)))
+      return fail(ctx, BR_ERR_INVALID_ARG, "device pointers must be 16-byte aligned (matrix " + std::to_string(i) + ")");
+  }
+  return BR_OK;
+}
+
+br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_mats) {
+  br_status st = check_call(ctx, grads, nullptr, false, n_mats);
+  if (st != BR_OK) return st;
+  br_ctx* c = ctx;
+  if (c->stats_fresh) return fail(c, BR_ERR_STATE, "br_accumulate_stats called twice without br_step");
+  const br_hparams& hp = c->hp;
+  for (const Group& g : c->lay.groups) {
+    const int64_t count = g.m * g.n;
+    const size_t mn = align256((size_t)count * 4);
+    const int nbuf = step_buffers(g);
+    const bool rotated = g.rot_l || g.rot_r;
+    const bool need_g32 = rotated && g.gdt == BR_BF16;
+    for (size_t off = 0; off < g.idx.size(); off += kStepChunk) {
+      const int B = (int)std::min<size_t>(kStepChunk, g.idx.size() - off);
+      BrPtrBatch pb;
+      std::memset(&pb, 0, sizeof(pb));
+      const float* g32[kStepChunk];
+      for (int i = 0; i < B; ++i) {
+        const MatState& m = c->mats[g.idx[off + i]];
+        pb.in0[i] = grads[g.idx[off + i]];
+        pb.out0[i] = m.M;
+        pb.out1[i] = need_g32 ? scratch_buf(c, nbuf, mn, i, nbuf - 1) : nullptr;
+        g32[i] = need_g32 ? reinterpret_cast<const float*>(pb.out1[i]) : reinterpret_cast<const float*>(grads[g.idx[off + i]]);
+      }
+      {
+        double bytes = (double)count * B * (8.0 + (g.gdt == BR_BF16 ? 2.0 : 4.0) + (need_g32 ? 4.0 : 0.0));
+        Timed tm(c, "br_ema_first_moment", 2.0 * count * B, bytes);
+        if (!hip_ok(c, br_launch_ema(c->stream, pb, B, count, g.gdt == BR_BF16, hp.beta1), "first-moment launch")) return BR_ERR_HIP;
+      }
+      if (hp.source != BR_SRC_SECOND || !rotated) continue;
+      BrGemmBatch gb;
+      std::memset(&gb, 0, sizeof(gb));
+      if (g.rot_l) {  // L <- b L + (1-b) G G^T
+        for (int i = 0; i < B; ++i) { gb.A[i] = g32[i]; gb.B[i] = g32[i]; gb.C[i] = c->mats[g.idx[off + i]].L; }
+        BrGemmArgs a{(int)g.m, (int)g.m, (int)g.n, (int)g.n, (int)g.n, (int)g.m, 0, 1, 1.0f - hp.stat_beta, hp.stat_beta, B, 1};
+        if (!gemm(c, a, gb)) return BR_ERR_HIP;
+      }
+      if (g.rot_r) {  // R <- b R + (1-b) G^T G
+        for (int i = 0; i < B; ++i) { gb.A[i] = g32[i]; gb.B[i] = g32[i]; gb.C[i] = c->mats[g.idx[off + i]].R; }
+        BrGemmArgs a{(int)g.n, (int)g.n, (int)g.m, (int)g.n, (int)g.n, (int)g.n, 1, 0, 1.0f - hp.stat_beta, hp.stat_beta, B, 1};
+        if (!gemm(c, a, gb)) return BR_ERR_HIP;
+      }
+    }
+  }
+  c->stats_fresh = true;
+  return BR_OK;
+}
+
+// Blocked Householder QR of the k x k matrices P (in place) for a batch of jobs, orthogonal
+// factor written to Q with the sign convention diag(R) >= 0.
+static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs, char* base,
+                     size_t stride) {
+  const int npanels = (k + BR_QR_NB - 1) / BR_QR_NB;
+  auto Vc = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.Vc); };
+  auto Y = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.Y); };
+  auto W = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.W); };
+  auto T = [&](int i, int pnl) { return reinterpret_cast<float*>(base + i * stride + rs.T) + (size_t)pnl * BR_QR_NB * BR_QR_NB; };
+  auto D = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.diag); };
+  BrQrPanelBatch pb;
+  BrGemmBatch gb;
+  for (int pnl = 0; pnl < npanels; ++pnl) {
+    const int j0 = pnl * BR_QR_NB;
+    const int nb = std::min(BR_QR_NB, k - j0);
+    const int rows = k - j0;
+    const int nt = k - j0 - nb;
+    std::memset(&pb, 0, sizeof(pb));
+    for (int i = 0; i < B; ++i) {
+      pb.A[i] = P[i] + (size_t)j0 * k + j0;
+      pb.Vc[i] = Vc(i);
+      pb.T[i] = T(i, pnl);
+      pb.diag[i] = D(i) + j0;
+    }
+    if (!hip_ok(c, br_launch_qr_panel(c->stream, pb, B, rows, nb, k), "qr panel launch")) return false;
+    if (nt <= 0) continue;
+    std::memset(&gb, 0, sizeof(gb));
+    // Yt = Vc T^T
+    for (int i = 0; i < B; ++i) { gb.A[i] = Vc(i); gb.B[i] = T(i, pnl); gb.C[i] = Y(i); }
+    if (!gemm(c, BrGemmArgs{rows, BR_QR_NB, BR_QR_NB, BR_QR_NB, BR_QR_NB, BR_QR_NB, 0, 1, 1.f, 0.f, B, 0}, gb, false)) return false;
+    // W = Vc^T C,  C = trailing columns of the panel's rows
+    for (int i = 0; i < B; ++i) { gb.A[i] = Vc(i); gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
+    if (!gemm(c, BrGemmArgs{BR_QR_NB, nt, rows, BR_QR_NB, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    // C <- C - Yt W
+    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)j0 * k + j0 + nb; }
+    if (!gemm(c, BrGemmArgs{rows, nt, BR_QR_NB, BR_QR_NB, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
+  }
+  // Q = H_1 ... H_k applied to the identity, last block reflector first.
+  if (!hip_ok(c, br_launch_set_identity(c->stream, Q, B, k), "identity launch")) return false;
+  for (int pnl = npanels - 1; pnl >= 0; --pnl) {
+    const int j0 = pnl * BR_QR_NB;
+    const int nb = std::min(BR_QR_NB, k - j0);
+    const int rows = k - j0;
+    std::memset(&pb, 0, sizeof(pb));
+    for (int i = 0; i < B; ++i) {
+      pb.A[i] = P[i] + (size_t)j0 * k + j0;
+      pb.Vc[i] = Vc(i);
+    }
+    if (!hip_ok(c, br_launch_qr_extract_v(c->stream, pb, B, rows, nb, k), "qr extract launch")) return false;
+    std::memset(&gb, 0, sizeof(gb));
+    // Y = Vc T
+    for (int i = 0; i < B; ++i) { gb.A[i] = Vc(i); gb.B[i] = T(i, pnl); gb.C[i] = Y(i); }
+    if (!gemm(c, BrGemmArgs{rows, BR_QR_NB, BR_QR_NB, BR_QR_NB, BR_QR_NB, BR_QR_NB, 0, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    // W = Vc^T Qsub,  Qsub = Q[j0:, j0:]
+    for (int i = 0; i < B; ++i) { gb.A[i] = Vc(i); gb.B[i] = Q[i] + (size_t)j0 * k + j0; gb.C[i] = W(i); }
+    if (!gemm(c, BrGemmArgs{BR_QR_NB, rows, rows, BR_QR_NB, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    // Qsub <- Qsub - Y W
+    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Q[i] + (size_t)j0 * k + j0; }
+    if (!gemm(c, BrGemmArgs{rows, rows, BR_QR_NB, BR_QR_NB, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
+  }
+  const float* dg[BR_MAXB];
+  for (int i = 0; i < B; ++i) dg[i] = D(i);
+  return hip_ok(c, br_launch_qr_fix_signs(c->stream, Q, dg, B, k), "sign fix launch");
+}
+
+br_status br_refresh_basis(br_ctx* ctx) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  if (ctx->dead) return BR_ERR_HIP;
+  br_ctx* c = ctx;
+  const br_hparams& hp = c->hp;
+  char* base = c->scratch + kNormPartialBytes;
+  for (auto& kv : c->lay.refresh) {
+    const int k = (int)kv.first;
+    const auto& jobs = kv.second;
+    const RefreshScratch rs = refresh_scratch(k, hp);
+    for (size_t off = 0; off < jobs.size(); off += kRefreshChunk) {
+      const int B = (int)std::min<size_t>(kRefreshChunk, jobs.size() - off);
+      float* Q[BR_MAXB];
+      float* P0[BR_MAXB];
+      float* P1[BR_MAXB];
+      const float* A[BR_MAXB];
+      BrGemmBatch gb;
+      std::memset(&gb, 0, sizeof(gb));
+      for (int i = 0; i < B; ++i) {
+        const RefreshJob& j = jobs[off + i];
+        const MatState& m = c->mats[j.mat];
+        Q[i] = j.left ? m.QL : m.QR;
+        P0[i] = reinterpret_cast<float*>(base + i * rs.total + rs.P0);
+        P1[i] = reinterpret_cast<float*>(base + i * rs.total + rs.P1);
+        if (hp.source == BR_SRC_SECOND) {
+          A[i] = j.left ? m.L : m.R;
+        } else {  // first-order source: Gram matrix of the first moment (Algorithm 2 lines 12, 14)
+          float* gram = reinterpret_cast<float*>(base + i * rs.total + rs.gram);
+          A[i] = gram;
+          BrGemmBatch one;
+          std::memset(&one, 0, sizeof(one));
+          one.A[0] = m.M; one.B[0] = m.M; one.C[0] = gram;
+          BrGemmArgs a = j.left ? BrGemmArgs{k, k, (int)m.d.n, (int)m.d.n, (int)m.d.n, k, 0, 1, 1.f, 0.f, 1, 1}
+                                : BrGemmArgs{k, k, (int)m.d.m, (int)m.d.n, (int)m.d.n, k, 1, 0, 1.f, 0.f, 1, 1};
+          if (!gemm(c, a, one)) return BR_ERR_HIP;
+        }
+      }
+      // P <- A^iters Q
+      float** src = Q;
+      float** dst = P0;
+      for (int it = 0; it < hp.power_iters; ++it) {
+        for (int i = 0; i < B; ++i) { gb.A[i] = A[i]; gb.B[i] = src[i]; gb.C[i] = dst[i]; }
+        if (!gemm(c, BrGemmArgs{k, k, k, k, k, k, 0, 0, 1.f, 0.f, B, 0}, gb)) return BR_ERR_HIP;
+        src = dst;
+        dst = (dst == P0) ? P1 : P0;
+      }
+      {
+        Timed tm(c, "qr_householder(region)", (8.0 / 3.0) * (double)k * k * k * B, 0.0);
+        if (!qr_batch(c, B, k, src, Q, rs, base, rs.total)) return BR_ERR_HIP;
+      }
+    }
+  }
+  return BR_OK;
+}
+
+br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, int32_t n_mats, float lr) {
+  br_status st = check_call(ctx, reinterpret_cast<const void* const*>(params), grads, true, n_mats);
+  if (st != BR_OK) return st;
+  br_ctx* c = ctx;
+  if (!c->stats_fresh) return fail(c, BR_ERR_STATE, "br_step needs br_accumulate_stats for this step first");
+  if (!(lr == lr)) return fail(c, BR_ERR_INVALID_ARG, "learning rate is NaN");
+  const br_hparams& hp = c->hp;
+  const int64_t t = c->t + 1;
+  BrAdamArgs aa;
+  aa.beta2 = hp.beta2;
+  aa.eps = hp.eps;
+  aa.c1 = hp.bias_correction ? (float)(1.0 / (1.0 - std::pow((double)hp.beta1, (double)t))) : 1.0f;
+  aa.c2 = hp.bias_correction ? (float)(1.0 / (1.0 - std::pow((double)hp.beta2, (double)t))) : 1.0f;
+  aa.eps_outside = hp.eps_outside_sqrt;
+  aa.compute_norms = hp.compute_norms;
+  const float decay = 1.0f - lr * hp.weight_decay;
+  float* partials = reinterpret_cast<float*>(c->scratch);
+
+  for (const Group& g : c->lay.groups) {
+    const int64_t count = g.m * g.n;
+    const size_t mn = align256((size_t)count * 4);
+    const int nbuf = step_buffers(g);
+    const bool rotated = g.rot_l || g.rot_r;
+    const int m = (int)g.m, n = (int)g.n;
+    for (size_t off = 0; off < g.idx.size(); off += kStepChunk) {
+      const int B = (int)std::min<size_t>(kStepChunk, g.idx.size() - off);
+      float* Wp[kStepChunk];       // FP32 weights that receive the update
+      uint16_t* shadow[kStepChunk];  // BF16 parameter image, or null
+      const float* G32[kStepChunk];
+      for (int i = 0; i < B; ++i) {
+        MatState& ms = c->mats[g.idx[off + i]];
+        void* prm = params[g.idx[off + i]];
+        if (g.pdt == BR_BF16) {
+          if (!ms.master_ready) {
+            if (!hip_ok(c, br_launch_bf16_to_f32(c->stream, reinterpret_cast<const uint16_t*>(prm), ms.master, count), "master init")) return BR_ERR_HIP;
+            ms.master_ready = true;
+          }
+          Wp[i] = ms.master;
+          shadow[i] = reinterpret_cast<uint16_t*>(prm);
+        } else {
+          Wp[i] = reinterpret_cast<float*>(prm);
+          shadow[i] = nullptr;
+        }
+      }
+      if (!rotated) {
+        BrPtrBatch pb;
+        std::memset(&pb, 0, sizeof(pb));
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          pb.in0[i] = grads[g.idx[off + i]];
+          pb.in1[i] = ms.M;
+          pb.out0[i] = ms.S;
+          pb.out1[i] = Wp[i];
+        }
+        BrPlainArgs pa{hp.beta2, hp.eps, aa.c1, aa.c2, lr, decay, hp.eps_outside_sqrt, g.gdt == BR_BF16};
+        double bytes = (double)count * B * (4.0 + 8.0 + 8.0 + (g.gdt == BR_BF16 ? 2.0 : 4.0) + (g.pdt == BR_BF16 ? 2.0 : 0.0));
+        Timed tm(c, "br_adam_plain", 10.0 * count * B, bytes);
+        if (!hip_ok(c, br_launch_adam_plain(c->stream, pb, shadow, B, count, pa), "plain adam launch")) return BR_ERR_HIP;
+        continue;
+      }
+      // FP32 image of BF16 gradients
+      for (int i = 0; i < B; ++i) {
+        const void* gp = grads[g.idx[off + i]];
+        if (g.gdt == BR_BF16) {
+          float* dst = scratch_buf(c, nbuf, mn, i, nbuf - 1);
+          if (!hip_ok(c, br_launch_bf16_to_f32(c->stream, reinterpret_cast<const uint16_t*>(gp), dst, count), "gradient widen")) return BR_ERR_HIP;
+          G32[i] = dst;
+        } else {
+          G32[i] = reinterpret_cast<const float*>(gp);
+        }
+      }
+      BrGemmBatch gb;
+      std::memset(&gb, 0, sizeof(gb));
+      float* Gt[kStepChunk];
+      float* Mt[kStepChunk];
+      if (g.rot_l && g.rot_r) {
+        // T = Q_L^T [G | M]   (buffers 0, 1), then [G~ | M~] = T Q_R   (buffers 2, 3)
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          gb.A[i] = ms.QL; gb.B[i] = G32[i]; gb.C[i] = scratch_buf(c, nbuf, mn, i, 0);
+          gb.A[B + i] = ms.QL; gb.B[B + i] = ms.M; gb.C[B + i] = scratch_buf(c, nbuf, mn, i, 1);
+        }
+        if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, 2 * B, 0}, gb)) return BR_ERR_HIP;
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          Gt[i] = scratch_buf(c, nbuf, mn, i, 2);
+          Mt[i] = scratch_buf(c, nbuf, mn, i, 3);
+          gb.A[i] = scratch_buf(c, nbuf, mn, i, 0); gb.B[i] = ms.QR; gb.C[i] = Gt[i];
+          gb.A[B + i] = scratch_buf(c, nbuf, mn, i, 1); gb.B[B + i] = ms.QR; gb.C[B + i] = Mt[i];
+        }
+        if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, 2 * B, 0}, gb)) return BR_ERR_HIP;
+      } else {
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          Gt[i] = scratch_buf(c, nbuf, mn, i, 0);
+          Mt[i] = scratch_buf(c, nbuf, mn, i, 1);
+          if (g.rot_l) {
+            gb.A[i] = ms.QL; gb.B[i] = G32[i]; gb.C[i] = Gt[i];
+            gb.A[B + i] = ms.QL; gb.B[B + i] = ms.M; gb.C[B + i] = Mt[i];
+          } else {
+            gb.A[i] = G32[i]; gb.B[i] = ms.QR; gb.C[i] = Gt[i];
+            gb.A[B + i] = ms.M; gb.B[B + i] = ms.QR; gb.C[B + i] = Mt[i];
+          }
+        }
+        BrGemmArgs a = g.rot_l ? BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, 2 * B, 0}
+                               : BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, 2 * B, 0};
+        if (!gemm(c, a, gb)) return BR_ERR_HIP;
+      }
+      {  // Adam in the rotated basis; X overwrites M~
+        BrPtrBatch pb;
+        std::memset(&pb, 0, sizeof(pb));
+        float* norms[kStepChunk];
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          pb.in0[i] = Gt[i];
+          pb.out0[i] = ms.S;
+          pb.out1[i] = Mt[i];
+          norms[i] = ms.norms;
+        }
+        Timed tm(c, "br_adam_rotated", 8.0 * count * B, 20.0 * count * B);
+        if (!hip_ok(c, br_launch_adam_rotated(c->stream, pb, B, count, aa, partials, norms), "rotated adam launch")) return BR_ERR_HIP;
+      }
+      // rotate back and apply: W <- decay W - lr Q_L X Q_R^T
+      std::memset(&gb, 0, sizeof(gb));
+      if (g.rot_l && g.rot_r) {
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          gb.A[i] = ms.QL; gb.B[i] = Mt[i]; gb.C[i] = scratch_buf(c, nbuf, mn, i, 0);
+        }
+        if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 0, 0, 1.f, 0.f, B, 0}, gb)) return BR_ERR_HIP;
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          gb.A[i] = scratch_buf(c, nbuf, mn, i, 0); gb.B[i] = ms.QR; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
+        }
+        if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 1, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
+      } else if (g.rot_l) {
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          gb.A[i] = ms.QL; gb.B[i] = Mt[i]; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
+        }
+        if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 0, 0, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
+      } else {
+        for (int i = 0; i < B; ++i) {
+          const MatState& ms = c->mats[g.idx[off + i]];
+          gb.A[i] = Mt[i]; gb.B[i] = ms.QR; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
+        }
+        if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 1, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
+      }
+    }
+  }
+  c->t = t;
+  c->stats_fresh = false;
+  return BR_OK;
+}
+
+br_status br_profile_begin(br_ctx* ctx) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  if (ctx->dead) return BR_ERR_HIP;
+  ctx->recs.clear();
+  ctx->events_used = 0;
+  ctx->prof_on = true;
+  return BR_OK;
+}
+
+br_status br_profile_end(br_ctx* ctx, br_profile_entry* out, int32_t cap, int32_t* n_out) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  if (!out || !n_out || cap <= 0) return fail(ctx, BR_ERR_INVALID_ARG, "null or empty profile output");
+  ctx->prof_on = false;
+  if (!hip_ok(ctx, hipStreamSynchronize(ctx->stream), "profile sync")) return BR_ERR_HIP;
+  std::vector<br_profile_entry> acc;
+  for (const ProfRec& r : ctx->recs) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ctx->events[r.ev], ctx->events[r.ev + 1]) != hipSuccess) continue;
+    br_profile_entry* e = nullptr;
+    for (auto& x : acc)
+      if (std::strncmp(x.kernel, r.name, sizeof(x.kernel) - 1) == 0) e = &x;
+    if (!e) {
+      br_profile_entry ne;
+      std::memset(&ne, 0, sizeof(ne));
+      std::strncpy(ne.kernel, r.name, sizeof(ne.kernel) - 1);
+      acc.push_back(ne);
+      e = &acc.back();
+    }
+    e->launches += 1;
+    e->ms += ms;
+    e->flops += r.flops;
+    e->bytes += r.bytes;
+  }
+  int32_t n = (int32_t)std::min<size_t>(acc.size(), (size_t)cap);
+  for (int32_t i = 0; i < n; ++i) out[i] = acc[i];
+  *n_out = n;
+  ctx->recs.clear();
+  ctx->events_used = 0;
+  return BR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,257 @@
+// Elementwise kernels of the basis-rotation step: HBM-bound, coalesced 16-byte accesses,
+// grid-stride loops sized to several workgroups per compute unit, batched over matrices
+// through blockIdx.y.
+//
+//   br_ema_first_moment   M <- beta1 M + (1-beta1) G                  (Algorithm 1 line 4)
+//   br_adam_rotated       S~ <- beta2 S~ + (1-beta2) G~.G~ ; X = M~/sqrt(S~+eps)
+//                                                                     (Algorithm 1 lines 10-11)
+//   br_adam_plain         the same update for tensors that are not rotated, fused with
+//                         the weight update (embeddings, LM head: experimental details)
+//   br_norm_finalize      deterministic second stage of the per-matrix norm reductions
+#include "br_internal.h"
+
+namespace br {
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float4 load_grad4(const void* g, int64_t i4, bool bf16) {
+  if (bf16) {
+    uint2 raw = reinterpret_cast<const uint2*>(g)[i4];
+    return make_float4(__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u),
+                       __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xffff0000u));
+  }
+  return reinterpret_cast<const float4*>(g)[i4];
+}
+
+__device__ __forceinline__ float load_grad1(const void* g, int64_t i, bool bf16) {
+  return bf16 ? bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(g)[i]) : reinterpret_cast<const float*>(g)[i];
+}
+
+__global__ __launch_bounds__(256) void br_ema_first_moment(BrPtrBatch p, int64_t count, int grad_bf16, float beta1) {
+  const int b = blockIdx.y;
+  const void* __restrict__ G = p.in0[b];
+  float* __restrict__ M = reinterpret_cast<float*>(p.out0[b]);
+  float* __restrict__ G32 = reinterpret_cast<float*>(p.out1[b]);
+  const float w = 1.0f - beta1;
+  const int64_t n4 = count >> 2;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    float4 g = load_grad4(G, i, grad_bf16);
+    float4 m = reinterpret_cast<float4*>(M)[i];
+    m.x = beta1 * m.x + w * g.x;
+    m.y = beta1 * m.y + w * g.y;
+    m.z = beta1 * m.z + w * g.z;
+    m.w = beta1 * m.w + w * g.w;
+    reinterpret_cast<float4*>(M)[i] = m;
+    if (G32) reinterpret_cast<float4*>(G32)[i] = g;
+  }
+  if (blockIdx.x == 0) {
+    for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
+      float g = load_grad1(G, i, grad_bf16);
+      M[i] = beta1 * M[i] + w * g;
+      if (G32) G32[i] = g;
+    }
+  }
+}
+
+__device__ __forceinline__ float adam_x(float m, float s, const BrAdamArgs& a) {
+  float num = m * a.c1;
+  float den = s * a.c2;
+  return a.eps_outside ? num / (sqrtf(den) + a.eps) : num / sqrtf(den + a.eps);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// partials layout: [batch][2][gridDim.x]
+__global__ __launch_bounds__(256) void br_adam_rotated(BrPtrBatch p, int64_t count, BrAdamArgs a, float* partials) {
+  __shared__ float red[2][4];
+  const int b = blockIdx.y;
+  const float* __restrict__ Gt = reinterpret_cast<const float*>(p.in0[b]);
+  float* __restrict__ S = reinterpret_cast<float*>(p.out0[b]);
+  float* __restrict__ X = reinterpret_cast<float*>(p.out1[b]);
+  const float w = 1.0f - a.beta2;
+  const int64_t n4 = count >> 2;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  float sg = 0.f, sx = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    float4 g = reinterpret_cast<const float4*>(Gt)[i];
+    float4 s = reinterpret_cast<float4*>(S)[i];
+    float4 m = reinterpret_cast<float4*>(X)[i];
+    s.x = a.beta2 * s.x + w * (g.x * g.x);
+    s.y = a.beta2 * s.y + w * (g.y * g.y);
+    s.z = a.beta2 * s.z + w * (g.z * g.z);
+    s.w = a.beta2 * s.w + w * (g.w * g.w);
+    float4 x = make_float4(adam_x(m.x, s.x, a), adam_x(m.y, s.y, a), adam_x(m.z, s.z, a), adam_x(m.w, s.w, a));
+    reinterpret_cast<float4*>(S)[i] = s;
+    reinterpret_cast<float4*>(X)[i] = x;
+    if (a.compute_norms) {
+      sg += g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
+      sx += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+    }
+  }
+  if (blockIdx.x == 0) {
+    for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
+      float g = Gt[i];
+      float s = a.beta2 * S[i] + w * (g * g);
+      float x = adam_x(X[i], s, a);
+      S[i] = s;
+      X[i] = x;
+      if (a.compute_norms) {
+        sg += g * g;
+        sx += x * x;
+      }
+    }
+  }
+  if (a.compute_norms) {
+    sg = wave_sum(sg);
+    sx = wave_sum(sx);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+      red[0][wave] = sg;
+      red[1][wave] = sx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float* dst = partials + (size_t)b * 2 * gridDim.x;
+      dst[blockIdx.x] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+      dst[gridDim.x + blockIdx.x] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
+  }
+}
+
+struct NormOut {
+  float* norms[BR_MAXB];
+};
+
+__global__ __launch_bounds__(64) void br_norm_finalize(const float* partials, int nblocks, NormOut out) {
+  const int b = blockIdx.x;
+  const float* src = partials + (size_t)b * 2 * nblocks;
+  float s0 = 0.f, s1 = 0.f;
+  for (int i = threadIdx.x; i < nblocks; i += 64) {
+    s0 += src[i];
+    s1 += src[nblocks + i];
+  }
+  s0 = wave_sum(s0);
+  s1 = wave_sum(s1);
+  if (threadIdx.x == 0 && out.norms[b]) {
+    out.norms[b][0] = s0;
+    out.norms[b][1] = s1;
+  }
+}
+
+struct ShadowPtrs {
+  uint16_t* p[BR_MAXB];
+};
+
+__global__ __launch_bounds__(256) void br_adam_plain(BrPtrBatch p, ShadowPtrs sh, int64_t count, BrPlainArgs a) {
+  const int b = blockIdx.y;
+  const void* __restrict__ G = p.in0[b];
+  const float* __restrict__ M = reinterpret_cast<const float*>(p.in1[b]);
+  float* __restrict__ S = reinterpret_cast<float*>(p.out0[b]);
+  float* __restrict__ W = reinterpret_cast<float*>(p.out1[b]);
+  uint16_t* __restrict__ shadow = sh.p[b];
+  const float w = 1.0f - a.beta2;
+  BrAdamArgs aa;
+  aa.beta2 = a.beta2; aa.eps = a.eps; aa.c1 = a.c1; aa.c2 = a.c2; aa.eps_outside = a.eps_outside; aa.compute_norms = 0;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+    float g = load_grad1(G, i, a.grad_bf16);
+    float s = a.beta2 * S[i] + w * (g * g);
+    float x = adam_x(M[i], s, aa);
+    float wv = a.decay * W[i] - a.lr * x;
+    S[i] = s;
+    W[i] = wv;
+    if (shadow) shadow[i] = f32_to_bf16_rne(wv);
+  }
+}
+
+struct MatPtrs {
+  float* p[BR_MAXB];
+};
+
+__global__ __launch_bounds__(256) void br_set_identity(MatPtrs m, int n) {
+  float* __restrict__ Q = m.p[blockIdx.y];
+  const int64_t total = (int64_t)n * n;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+    int64_t r = i / n;
+    Q[i] = (i - r * n == r) ? 1.0f : 0.0f;
+  }
+}
+
+__global__ __launch_bounds__(256) void br_bf16_to_f32(const uint16_t* __restrict__ src, float* __restrict__ dst,
+                                                      int64_t count) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
+    dst[i] = bf16_bits_to_f32(src[i]);
+}
+
+static inline int grid_for(int64_t work_items, int batch) {
+  // ~8 workgroups of 256 per compute unit across the whole launch, at least one per matrix
+  int64_t blocks = (work_items + 255) / 256;
+  int64_t cap = (256 * 8 + batch - 1) / batch;
+  if (cap < 1) cap = 1;
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  return (int)blocks;
+}
+
+}  // namespace br
+
+hipError_t br_launch_ema(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16, float beta1) {
+  if (batch <= 0 || count <= 0) return hipSuccess;
+  dim3 grid(br::grid_for(count / 4 + 1, batch), batch);
+  hipLaunchKernelGGL(br::br_ema_first_moment, grid, dim3(256), 0, s, p, count, grad_bf16, beta1);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_adam_rotated(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, const BrAdamArgs& a,
+                                  float* norm_partials, float* const* norms) {
+  if (batch <= 0 || count <= 0) return hipSuccess;
+  int gx = br::grid_for(count / 4 + 1, batch);
+  if (gx > BR_NORM_BLOCKS) gx = BR_NORM_BLOCKS;
+  dim3 grid(gx, batch);
+  hipLaunchKernelGGL(br::br_adam_rotated, grid, dim3(256), 0, s, p, count, a, norm_partials);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !a.compute_norms) return e;
+  br::NormOut out;
+  for (int i = 0; i < BR_MAXB; ++i) out.norms[i] = (i < batch) ? norms[i] : nullptr;
+  hipLaunchKernelGGL(br::br_norm_finalize, dim3(batch), dim3(64), 0, s, norm_partials, gx, out);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_adam_plain(hipStream_t s, const BrPtrBatch& p, uint16_t* const* shadow, int batch, int64_t count,
+                                const BrPlainArgs& a) {
+  if (batch <= 0 || count <= 0) return hipSuccess;
+  br::ShadowPtrs sh;
+  for (int i = 0; i < BR_MAXB; ++i) sh.p[i] = (i < batch) ? shadow[i] : nullptr;
+  dim3 grid(br::grid_for(count, batch), batch);
+  hipLaunchKernelGGL(br::br_adam_plain, grid, dim3(256), 0, s, p, sh, count, a);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_set_identity(hipStream_t s, float* const* mats, int batch, int n) {
+  if (batch <= 0 || n <= 0) return hipSuccess;
+  br::MatPtrs m;
+  for (int i = 0; i < BR_MAXB; ++i) m.p[i] = (i < batch) ? mats[i] : nullptr;
+  dim3 grid(br::grid_for((int64_t)n * n, batch), batch);
+  hipLaunchKernelGGL(br::br_set_identity, grid, dim3(256), 0, s, m, n);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_bf16_to_f32(hipStream_t s, const uint16_t* src, float* dst, int64_t count) {
+  if (count <= 0) return hipSuccess;
+  hipLaunchKernelGGL(br::br_bf16_to_f32, dim3(br::grid_for(count, 1)), dim3(256), 0, s, src, dst, count);
+  return hipGetLastError();
+}

@@ -1,0 +1,253 @@
+// Batched FP32 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32).
+//
+// Serves every dense contraction of the path: the statistics G G^T and G^T G
+// (Algorithm 2 lines 2, 5), the power-iteration product L Q and the block-reflector
+// updates of the QR (Section 3.2), the rotations Q_L^T G Q_R (Algorithm 1 lines 8-9)
+// and the rotate-back-and-apply W <- W - lr Q_L X Q_R^T (line 11).
+//
+// Design: a 128 x 128 output tile per 256-thread workgroup (four wave64s in a 2 x 2
+// grid, each owning 64 x 64 = four 32 x 32 MFMA accumulators), K advanced 16 at a
+// time through double-buffered LDS.  Both operands sit in LDS k-major ([k][m] and
+// [k][n]) so that one MFMA operand fetch is one conflict-free ds_read_b32 per lane;
+// operands whose storage is k-minor are transposed on their way into LDS.
+// Workgroup ids are remapped so that each XCD (own L2) works on a contiguous run of
+// tiles.
+#include "br_internal.h"
+
+namespace {
+
+constexpr int BM = 128;
+constexpr int BN = 128;
+constexpr int BK = 16;
+constexpr int LDS_LD = 132;  // 128 + 4: keeps float4 rows 16-byte aligned, shifts banks by 4 per k
+constexpr int NUM_XCD = 8;
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct GemmKernArgs {
+  int M, N, K;
+  int lda, ldb, ldc;
+  float alpha, beta;
+  int tiles_m, tiles_n;
+  int total_tiles;
+  int mirror;
+};
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Load four consecutive elements of a stored row; out-of-range elements read as zero.
+template <bool VEC>
+__device__ __forceinline__ float4 load4(const float* __restrict__ base, int row, int col, int ld,
+                                        int rows, int cols) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (row < rows && col < cols) {
+    const float* p = base + (size_t)row * (size_t)ld + col;
+    if (VEC && col + 3 < cols) {
+      v = *reinterpret_cast<const float4*>(p);
+    } else {
+      v.x = p[0];
+      if (col + 1 < cols) v.y = p[1];
+      if (col + 2 < cols) v.z = p[2];
+      if (col + 3 < cols) v.w = p[3];
+    }
+  }
+  return v;
+}
+
+// One operand tile (BK x 128 in LDS, [k][d]).  KMAJOR: the operand is stored with k as
+// its row index (rows = K extent, cols = tile extent).  Otherwise it is stored with the
+// tile dimension as its row index and is transposed while being written to LDS.
+template <bool KMAJOR, bool VEC>
+struct TileLoader {
+  float4 r[2];
+  __device__ __forceinline__ void fetch(const float* __restrict__ base, int ld, int d0, int k0,
+                                        int D, int K, int tid) {
+    if (KMAJOR) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        int k = (tid >> 5) + 8 * i;
+        int d = (tid & 31) * 4;
+        r[i] = load4<VEC>(base, k0 + k, d0 + d, ld, K, D);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        int d = (tid >> 2) + 64 * i;
+        int k = (tid & 3) * 4;
+        r[i] = load4<VEC>(base, d0 + d, k0 + k, ld, D, K);
+      }
+    }
+  }
+  __device__ __forceinline__ void stash(float (*lds)[LDS_LD], int tid) const {
+    if (KMAJOR) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        int k = (tid >> 5) + 8 * i;
+        int d = (tid & 31) * 4;
+        *reinterpret_cast<float4*>(&lds[k][d]) = r[i];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        int d = (tid >> 2) + 64 * i;
+        int k = (tid & 3) * 4;
+        lds[k + 0][d] = r[i].x;
+        lds[k + 1][d] = r[i].y;
+        lds[k + 2][d] = r[i].z;
+        lds[k + 3][d] = r[i].w;
+      }
+    }
+  }
+};
+
+template <bool TA, bool TB, bool VEC>
+__global__ __launch_bounds__(256) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBatch batch) {
+  __shared__ __attribute__((aligned(16))) float As[2][BK][LDS_LD];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDS_LD];
+
+  // XCD-aware remap: hardware deals consecutive workgroup ids round-robin to the 8 XCDs;
+  // give each XCD a contiguous run of logical tiles so neighbours share operands in its L2.
+  int bid = blockIdx.x;
+  const int nblk = gridDim.x;
+  const int per = nblk / NUM_XCD;
+  if (bid < per * NUM_XCD) bid = (bid % NUM_XCD) * per + bid / NUM_XCD;
+
+  int mat, tm, tn;
+  {
+    int per_mat = g.total_tiles;
+    mat = bid / per_mat;
+    int t = bid - mat * per_mat;
+    if (g.mirror) {
+      // t enumerates tiles with tm >= tn: t = tm (tm + 1) / 2 + tn
+      int r = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+      while ((r + 1) * (r + 2) / 2 <= t) ++r;
+      while (r * (r + 1) / 2 > t) --r;
+      tm = r;
+      tn = t - r * (r + 1) / 2;
+    } else {
+      tm = t / g.tiles_n;
+      tn = t - tm * g.tiles_n;
+    }
+  }
+  const float* __restrict__ A = batch.A[mat];
+  const float* __restrict__ B = batch.B[mat];
+  float* __restrict__ C = batch.C[mat];
+  uint16_t* __restrict__ shadow = batch.shadow[mat];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  TileLoader<TA, VEC> la;    // op(A) = A^T  <=> A stored K x M  <=> k-major
+  TileLoader<!TB, VEC> lb;   // op(B) = B    <=> B stored K x N  <=> k-major
+
+  const int nkt = (g.K + BK - 1) / BK;
+  la.fetch(A, g.lda, m0, 0, g.M, g.K, tid);
+  lb.fetch(B, g.ldb, n0, 0, g.N, g.K, tid);
+  la.stash(As[0], tid);
+  lb.stash(Bs[0], tid);
+  __syncthreads();
+
+  const int lk = lane >> 5;  // which of the two k of an MFMA this lane feeds
+  const int li = lane & 31;  // row of A / column of B inside the 32-wide MFMA tile
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nkt) {
+      la.fetch(A, g.lda, m0, (kt + 1) * BK, g.M, g.K, tid);
+      lb.fetch(B, g.ldb, n0, (kt + 1) * BK, g.N, g.K, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      float a0 = As[cur][kk + lk][wm * 64 + li];
+      float a1 = As[cur][kk + lk][wm * 64 + 32 + li];
+      float b0 = Bs[cur][kk + lk][wn * 64 + li];
+      float b1 = Bs[cur][kk + lk][wn * 64 + 32 + li];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+    if (kt + 1 < nkt) {
+      la.stash(As[cur ^ 1], tid);
+      lb.stash(Bs[cur ^ 1], tid);
+    }
+    __syncthreads();
+  }
+
+  // Epilogue.  Accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4 and
+  // column l%32 of its 32 x 32 tile.
+  const bool use_beta = (g.beta != 0.0f);
+  const bool off_diag = g.mirror && (tm != tn);
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+      const int col = n0 + wn * 64 + ni * 32 + li;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+        if (row < g.M && col < g.N) {
+          size_t off = (size_t)row * (size_t)g.ldc + col;
+          float val = g.alpha * acc[mi][ni][v];
+          if (use_beta) val += g.beta * C[off];
+          C[off] = val;
+          if (shadow) shadow[off] = f32_to_bf16_rne(val);
+          if (off_diag) C[(size_t)col * (size_t)g.ldc + row] = val;
+        }
+      }
+    }
+  }
+}
+
+template <bool TA, bool TB>
+hipError_t launch_variant(hipStream_t s, const GemmKernArgs& k, const BrGemmBatch& b, int grid, bool vec) {
+  if (vec)
+    hipLaunchKernelGGL((br_gemm_f32_mfma<TA, TB, true>), dim3(grid), dim3(256), 0, s, k, b);
+  else
+    hipLaunchKernelGGL((br_gemm_f32_mfma<TA, TB, false>), dim3(grid), dim3(256), 0, s, k, b);
+  return hipGetLastError();
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch& b, const char** kernel_name) {
+  static const char* names[4] = {"br_gemm_f32_mfma<nn>", "br_gemm_f32_mfma<nt>", "br_gemm_f32_mfma<tn>",
+                                 "br_gemm_f32_mfma<tt>"};
+  if (kernel_name) *kernel_name = names[(a.transA ? 2 : 0) + (a.transB ? 1 : 0)];
+  if (a.batch <= 0 || a.M <= 0 || a.N <= 0) return hipSuccess;
+  if (a.batch > BR_MAXB || a.K < 0) return hipErrorInvalidValue;
+  if (a.mirror && (a.M != a.N)) return hipErrorInvalidValue;
+  GemmKernArgs k;
+  k.M = a.M; k.N = a.N; k.K = a.K;
+  k.lda = a.lda; k.ldb = a.ldb; k.ldc = a.ldc;
+  k.alpha = a.alpha; k.beta = a.beta;
+  k.tiles_m = (a.M + BM - 1) / BM;
+  k.tiles_n = (a.N + BN - 1) / BN;
+  k.mirror = a.mirror ? 1 : 0;
+  k.total_tiles = k.mirror ? k.tiles_m * (k.tiles_m + 1) / 2 : k.tiles_m * k.tiles_n;
+  long long grid = (long long)k.total_tiles * a.batch;
+  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  bool vec = (a.lda % 4 == 0) && (a.ldb % 4 == 0);
+  for (int i = 0; i < a.batch && vec; ++i) vec = aligned16(b.A[i]) && aligned16(b.B[i]);
+  if (!a.transA && !a.transB) return launch_variant<false, false>(s, k, b, (int)grid, vec);
+  if (!a.transA && a.transB) return launch_variant<false, true>(s, k, b, (int)grid, vec);
+  if (a.transA && !a.transB) return launch_variant<true, false>(s, k, b, (int)grid, vec);
+  return launch_variant<true, true>(s, k, b, (int)grid, vec);
+}

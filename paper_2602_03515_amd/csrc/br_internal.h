@@ -1,0 +1,89 @@
+// Internal launch interface between the host logic (br_api.hip) and the kernels.
+// Everything here is device-pointer + size based; no torch types anywhere.
+#ifndef BR_INTERNAL_H_
+#define BR_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define BR_MAXB 32  // matrices handled by one batched launch (pointers travel as kernel arguments)
+
+// ---- batched GEMM on FP32 matrix cores -------------------------------------------------
+// C_b = alpha * op(A_b) * op(B_b) + beta * C_b,  b = 0..batch-1, all row-major.
+// op(A) is M x K: stored M x K (lda >= K) when transA == 0, K x M (lda >= M) when transA == 1.
+// op(B) is K x N: stored K x N (ldb >= N) when transB == 0, N x K (ldb >= K) when transB == 1.
+// shadow_b (optional): bfloat16 image of the final C_b (same ld as C), written with RNE.
+// mirror: C is square and symmetric (A-op and B-op are transposes of each other): only tiles
+//         on or below the diagonal are computed, each is also stored transposed.
+struct BrGemmBatch {
+  const float* A[BR_MAXB];
+  const float* B[BR_MAXB];
+  float* C[BR_MAXB];
+  uint16_t* shadow[BR_MAXB];
+};
+
+struct BrGemmArgs {
+  int M, N, K;
+  int lda, ldb, ldc;
+  int transA, transB;
+  float alpha, beta;
+  int batch;
+  int mirror;
+};
+
+hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch& b, const char** kernel_name);
+
+// ---- elementwise ----------------------------------------------------------------------
+struct BrPtrBatch {
+  const void* in0[BR_MAXB];
+  const void* in1[BR_MAXB];
+  void* out0[BR_MAXB];
+  void* out1[BR_MAXB];
+};
+
+// M <- beta1 M + (1-beta1) G.  in0 = G (f32 or bf16), out0 = M (f32), out1 = optional f32 copy of G.
+hipError_t br_launch_ema(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16,
+                         float beta1);
+
+struct BrAdamArgs {
+  float beta2, eps;
+  float c1, c2;  // bias-correction multipliers for the first/second moment (1 when disabled)
+  int eps_outside;
+  int compute_norms;
+};
+// in0 = G~, out0 = S (in place), out1 = M~ on entry, X on exit.  norm_partials: per-matrix
+// [2][BR_NORM_BLOCKS] partial sums, reduced by br_launch_norm_finalize into norms[b][2].
+#define BR_NORM_BLOCKS 256
+hipError_t br_launch_adam_rotated(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count,
+                                  const BrAdamArgs& a, float* norm_partials, float* const* norms_host_ptrs);
+
+// Plain Adam for unrotated tensors, fully fused: in0 = G (f32/bf16), in1 = M (already updated),
+// out0 = S, out1 = W master (f32); shadow = optional bf16 parameter image.
+struct BrPlainArgs {
+  float beta2, eps, c1, c2, lr, decay;  // decay = 1 - lr*wd
+  int eps_outside, grad_bf16;
+};
+hipError_t br_launch_adam_plain(hipStream_t s, const BrPtrBatch& p, uint16_t* const* shadow, int batch,
+                                int64_t count, const BrPlainArgs& a);
+
+hipError_t br_launch_set_identity(hipStream_t s, float* const* mats, int batch, int n);
+hipError_t br_launch_bf16_to_f32(hipStream_t s, const uint16_t* src, float* dst, int64_t count);
+
+// ---- QR ---------------------------------------------------------------------------------
+#define BR_QR_NB 32  // panel width of the blocked Householder factorisation
+
+struct BrQrPanelBatch {
+  float* A[BR_MAXB];     // top-left corner of the panel inside the matrix being factorised
+  float* Vc[BR_MAXB];    // rows x BR_QR_NB clean copy of the reflectors (unit diagonal, zeros above)
+  float* T[BR_MAXB];     // BR_QR_NB x BR_QR_NB upper-triangular block-reflector factor
+  float* diag[BR_MAXB];  // nb diagonal entries of R for this panel
+};
+// Householder-factorise the rows x nb panel in place (reflectors below the diagonal, R on and
+// above), one workgroup per matrix.
+hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda);
+// Copy the reflectors of an already factorised panel back out into Vc.
+hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda);
+// Q[:, j] *= sign(diag[j]) (zero counts as +).
+hipError_t br_launch_qr_fix_signs(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n);
+
+#endif  // BR_INTERNAL_H_

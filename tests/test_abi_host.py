@@ -1,0 +1,129 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, sizes workspaces as the memory-overhead appendix says, and rejects bad arguments
+before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_03515_amd import binding
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    header = open(os.path.join(ROOT, "include", "br.h")).read()
+    declared = set(re.findall(r"\b(br_[a-z_]+)\s*\(", header))
+    assert {"br_init", "br_accumulate_stats", "br_refresh_basis", "br_step"} <= declared
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in br.h but not exported"
+    assert set(B.EXPORTED) == declared
+    assert "gfx950" in B.br_version()
+
+
+def test_struct_layouts_match_header(B):
+    assert ctypes.sizeof(B.br_matrix_desc) == 32
+    assert ctypes.sizeof(B.br_hparams) == 52
+    assert ctypes.sizeof(B.br_profile_entry) == 96
+
+
+def test_workspace_state_bytes_follow_memory_table(B):
+    """Extra FP32 memory beyond Adam's two moments: 2(m^2+n^2) floats bilateral, 2 min(m,n)^2
+    unilateral; half of that for the first-order source (memory-overhead appendix)."""
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "memory_overhead_table.txt"))
+            if l.strip() and not l.startswith("#")]
+    for source, geometry, attn, mlp in rows:
+        hp = B.make_hparams(geometry=B.BR_BILATERAL if geometry == "bilateral" else B.BR_UNILATERAL,
+                            source=B.BR_SRC_SECOND if source == "second" else B.BR_SRC_FIRST)
+        for shape, printed in (((4096, 4096), float(attn)), ((4096, 14336), float(mlp))):
+            state, scratch = B.br_workspace_bytes(B.make_descs([shape]), hp)
+            extra = state - 2 * shape[0] * shape[1] * 4 - 256
+            assert abs(extra / 2 ** 30 - printed) <= 0.0051, (source, geometry, shape, extra / 2 ** 30)
+            assert scratch > 0
+    # transposed MLP shape under unilateral rotation keeps the 4096-side factor
+    uni = B.make_hparams(geometry=B.BR_UNILATERAL)
+    a, _ = B.br_workspace_bytes(B.make_descs([(4096, 14336)]), uni)
+    b, _ = B.br_workspace_bytes(B.make_descs([(14336, 4096)]), uni)
+    assert a == b
+    # BF16 parameters add an FP32 master copy; unrotated tensors add nothing beyond Adam
+    s32, _ = B.br_workspace_bytes(B.make_descs([(512, 256, B.BR_F32, B.BR_F32, 0)]), uni)
+    s16, _ = B.br_workspace_bytes(B.make_descs([(512, 256, B.BR_BF16, B.BR_BF16, 0)]), uni)
+    assert s32 == 2 * 512 * 256 * 4 + 256 and s16 == 3 * 512 * 256 * 4 + 256
+
+
+def test_stage_state_bytes_3b_class():
+    from paper_2602_03515_amd import binding as B, synth
+    state, scratch = B.br_workspace_bytes(B.make_descs(synth.STAGE_3B), B.make_hparams())
+    closed_form = sum(4 * (2 * m * n + 2 * m * m + 2 * n * n) for m, n in synth.STAGE_3B)
+    assert abs(closed_form - 18.86e9) < 0.01e9
+    assert 0 <= state - closed_form <= 56 * 256 * 8
+
+
+@pytest.mark.parametrize("bad, status", [
+    (dict(shapes=[(0, 4)]), "BR_ERR_SHAPE"),
+    (dict(shapes=[(4, -1)]), "BR_ERR_SHAPE"),
+    (dict(shapes=[(4, 4, 7, 0, 1)]), "BR_ERR_DTYPE"),
+    (dict(shapes=[(4, 4)], geometry=5), "BR_ERR_INVALID_ARG"),
+    (dict(shapes=[(4, 4)], source=2), "BR_ERR_INVALID_ARG"),
+    (dict(shapes=[(4, 4)], power_iters=0), "BR_ERR_INVALID_ARG"),
+    (dict(shapes=[(4, 4)], beta1=1.0), "BR_ERR_INVALID_ARG"),
+    (dict(shapes=[(4, 4)], eps=-1.0), "BR_ERR_INVALID_ARG"),
+    (dict(shapes=[(4, 4)], math=1), "BR_ERR_UNSUPPORTED"),
+    (dict(shapes=[]), "BR_ERR_INVALID_ARG"),
+])
+def test_invalid_arguments_are_rejected_on_the_host(B, bad, status):
+    shapes = bad.pop("shapes")
+    hp = B.make_hparams(**bad)
+    with pytest.raises(B.BrError) as e:
+        B.br_workspace_bytes(B.make_descs(shapes) if shapes else (B.br_matrix_desc * 0)(), hp)
+    assert B.STATUS_NAMES[e.value.status] == status
+    assert str(e.value)
+    # br_init validates the same way before it touches the device
+    with pytest.raises(B.BrError) as e2:
+        B.br_init(B.make_descs(shapes) if shapes else (B.br_matrix_desc * 0)(), hp, 256, 1 << 20)
+    assert B.STATUS_NAMES[e2.value.status] == status
+
+
+def test_init_rejects_null_misaligned_and_small_workspace(B):
+    d, hp = B.make_descs([(8, 8)]), B.make_hparams()
+    with pytest.raises(B.BrError) as e:
+        B.br_init(d, hp, 0, 1 << 20)
+    assert e.value.status == B.BR_ERR_INVALID_ARG
+    with pytest.raises(B.BrError) as e:
+        B.br_init(d, hp, 0x1000 + 16, 1 << 20)
+    assert e.value.status == B.BR_ERR_WORKSPACE
+    with pytest.raises(B.BrError) as e:
+        B.br_init(d, hp, 0x1000, 64)
+    assert e.value.status == B.BR_ERR_WORKSPACE and "need" in str(e.value)
+
+
+def test_null_context_calls_return_errors(B):
+    assert B._lib.br_refresh_basis(None) == B.BR_ERR_INVALID_ARG
+    assert B._lib.br_accumulate_stats(None, None, 0) == B.BR_ERR_INVALID_ARG
+    assert B._lib.br_step(None, None, None, 0, 0.0) == B.BR_ERR_INVALID_ARG
+    B._lib.br_destroy(None)
+
+
+def test_delay_ring_indexing():
+    from paper_2602_03515_amd.ring import GradientRing, delayed_index
+    assert [delayed_index(t, 3) for t in range(1, 8)] == [0, 0, 0, 0, 1, 2, 3]
+    ring = GradientRing(3)
+    ring.push("W0")
+    seen = []
+    for t in range(1, 8):
+        seen.append(ring.stale())
+        ring.push(f"W{t}")
+    assert seen == ["W0", "W0", "W0", "W0", "W1", "W2", "W3"]
+    r0 = GradientRing(0)
+    r0.push("W0")
+    assert r0.stale() == "W0"
+    r0.push("W1")
+    assert r0.stale() == "W1"
+    with pytest.raises(ValueError):
+        GradientRing(-1)

@@ -1,0 +1,272 @@
+"""Parity of the HIP library with the CPU oracle, element by element, through the C ABI.
+
+Tolerance (FP32 matrix-core math): max|a-b| / max|b| <= 1e-4 per tensor, applied to the
+weights, to every per-step update W_t - W_{t-1}, to the cumulative update, and to every
+state buffer; the bases are compared directly (same sign convention) and must be
+orthogonal to 1e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import br_oracle as oc
+from oracle.metrics import orthogonality_defect, rel_err
+from paper_2602_03515_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def harness():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_harness
+    return gpu_harness
+
+
+def _storage_floor(W, dW, bf16_params=False):
+    """The library keeps weights in FP32 (the master copy for BF16 parameters), so an update read
+    back as a difference of stored weights is only known to one FP32 ulp of the weights.  Relative
+    to the update that is 2^-23 max|W| / max|dW|; it is added to the tolerance of update
+    comparisons (it vanishes when W0 = 0, which a dedicated test uses)."""
+    scale = np.abs(dW).max()
+    return float(2.0 ** -23 * np.abs(W).max() / scale) if scale > 0 else 0.0
+
+
+def _run(h, W0s, grads_per_step, freq, lr, tol=TOL, check_q=True, **kw):
+    sb = h.SideBySide(W0s, freq=freq, lr=lr, **kw)
+    prev_gpu = [sb.gpu_weights(i) for i in range(len(W0s))]
+    prev_ref = [w.copy() for w in sb.W_ref]
+    w0 = [w.copy() for w in sb.W_ref]
+    for t, grads in enumerate(grads_per_step, 1):
+        sb.step(grads)
+        for i in range(len(W0s)):
+            g_now, r_now = sb.gpu_weights(i), sb.W_ref[i]
+            e = rel_err(g_now - prev_gpu[i], r_now - prev_ref[i])
+            lim = tol + _storage_floor(r_now, r_now - prev_ref[i], kw.get("bf16_params", False))
+            assert e <= lim, f"step {t} matrix {i}: update rel err {e:.3e} > {lim:.3e}"
+            prev_gpu[i], prev_ref[i] = g_now, r_now.copy()
+    for i in range(len(W0s)):
+        e = rel_err(sb.gpu_weights(i) - w0[i], sb.W_ref[i] - w0[i])
+        lim = tol + _storage_floor(sb.W_ref[i], sb.W_ref[i] - w0[i], kw.get("bf16_params", False))
+        assert e <= lim, f"matrix {i}: cumulative update rel err {e:.3e} > {lim:.3e}"
+    worst = sb.compare_state(tol, check_q=check_q)
+    for i, st in enumerate(sb.states):
+        for which, Q in ((sb.B.BR_STATE_QL, st.QL), (sb.B.BR_STATE_QR, st.QR)):
+            if Q is not None:
+                assert orthogonality_defect(h.to_np(sb.opt.state(i, which))) < 1e-5
+    return sb, worst
+
+
+def test_config1_256x256_bilateral_20_steps(harness):
+    """256 x 256 FP32, bilateral, refresh every 5 steps, 20 steps (delay tau = 3 only renames
+    gradient buffers because these gradients do not depend on the weights)."""
+    W0, grads = synth.spiked_gradients(seed=0, m=256, n=256, steps=20, noise_std=0.1)
+    sb, worst = _run(harness, [W0], [[g] for g in grads], freq=5, lr=1e-3)
+    print("config 1 worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
+    assert sb.opt.step_count == 20
+
+
+def test_config1_updates_from_zero_weights(harness):
+    """Same gradients as config 1 but W0 = 0: the weights ARE the cumulative update, so the
+    1e-4 bar applies to the rotated updates with no storage floor."""
+    _, grads = synth.spiked_gradients(seed=0, m=256, n=256, steps=12, noise_std=0.1)
+    W0 = np.zeros((256, 256), dtype=np.float32)
+    sb = harness.SideBySide([W0], freq=5, lr=1e-3)
+    for t, g in enumerate(grads, 1):
+        sb.step([g])
+        e = rel_err(sb.gpu_weights(0), sb.W_ref[0])
+        assert e <= TOL, f"step {t}: {e:.3e}"
+    sb.compare_state(TOL)
+
+
+@pytest.mark.parametrize("shape", [(200, 136), (136, 200), (37, 53), (1, 1), (257, 129)])
+def test_ragged_shapes_bilateral(harness, shape):
+    m, n = shape
+    W0, grads = synth.spiked_gradients(seed=7, m=m, n=n, steps=7, noise_std=0.1)
+    _run(harness, [W0], [[g] for g in grads], freq=3, lr=1e-3)
+
+
+@pytest.mark.parametrize("shape", [(1, 40), (40, 1), (130, 3)])
+def test_rank_deficient_statistics(harness, shape):
+    """When G G^T cannot reach full rank before the refresh, the QR of L Q is rank deficient: the
+    basis vectors spanning the null space are not unique (any orthonormal completion is a valid
+    QR), so the bases themselves are not compared.  The update at the refresh step is still
+    unique, because the rotated first moment vanishes along those vectors.  Refresh on the last
+    step; compare every update, M, S, L, R, and require an orthogonal basis."""
+    m, n = shape
+    W0, grads = synth.spiked_gradients(seed=7, m=m, n=n, steps=5, noise_std=0.1)
+    _run(harness, [W0], [[g] for g in grads], freq=5, lr=1e-3, check_q=False)
+
+
+@pytest.mark.parametrize("shape", [(96, 200), (200, 96), (64, 64)])
+def test_unilateral_rotates_smaller_side(harness, shape):
+    m, n = shape
+    W0, grads = synth.spiked_gradients(seed=8, m=m, n=n, steps=7, noise_std=0.1)
+    sb, _ = _run(harness, [W0], [[g] for g in grads], freq=3, lr=1e-3, geometry=1)
+    B = sb.B
+    assert sb.opt.has_state(0, B.BR_STATE_QL) == (m <= n)
+    assert sb.opt.has_state(0, B.BR_STATE_QR) == (m > n)
+    assert sb.opt.has_state(0, B.BR_STATE_L) == (m <= n)
+
+
+def test_batched_mixed_shapes_and_unrotated_tensor(harness):
+    shapes = [(160, 160), (160, 288), (288, 160), (160, 160), (160, 288), (500, 64)]
+    rotate = [True, True, True, True, True, False]
+    rng = np.random.default_rng(3)
+    W0s, seqs = [], []
+    for k, (m, n) in enumerate(shapes):
+        W0, grads = synth.lowrank_gradients(seed=20 + k, m=m, n=n, steps=6, rank=16, sigma=0.01)
+        W0s.append(W0)
+        seqs.append(grads)
+    steps = [[seqs[k][t] for k in range(len(shapes))] for t in range(6)]
+    _run(harness, W0s, steps, freq=4, lr=1e-3, rotate=rotate, weight_decay=0.01)
+
+
+def test_more_matrices_than_one_launch_batch(harness):
+    """40 same-shape matrices: three step chunks and two refresh chunks."""
+    W0s, seqs = [], []
+    for k in range(40):
+        W0, grads = synth.spiked_gradients(seed=100 + k, m=48, n=40, steps=3, noise_std=0.1)
+        W0s.append(W0)
+        seqs.append(grads)
+    steps = [[seqs[k][t] for k in range(40)] for t in range(3)]
+    _run(harness, W0s, steps, freq=2, lr=1e-3)
+
+
+def test_fixed_injected_basis_matches_rotated_adam(harness):
+    """Fixed-rotation equivalence appendix: overwrite Q_L, Q_R with Haar matrices and never
+    refresh; the oracle gets the same bases."""
+    m, n = 136, 72
+    rng = np.random.default_rng(5)
+    A, Bm = synth.haar_orthogonal(rng, m), synth.haar_orthogonal(rng, n)
+    W0, grads = synth.spiked_gradients(seed=9, m=m, n=n, steps=5, noise_std=0.1)
+    sb = harness.SideBySide([W0], freq=0, lr=1e-2)
+    A32, B32 = A.astype(np.float32), Bm.astype(np.float32)
+    sb.opt.state(0, sb.B.BR_STATE_QL).copy_(torch.from_numpy(A32))
+    sb.opt.state(0, sb.B.BR_STATE_QR).copy_(torch.from_numpy(B32))
+    sb.states[0].QL, sb.states[0].QR = A32.astype(np.float64), B32.astype(np.float64)
+    w0 = sb.W_ref[0].copy()
+    for g in grads:
+        sb.step([g])
+    assert rel_err(sb.gpu_weights(0) - w0, sb.W_ref[0] - w0) <= TOL
+    sb.compare_state(TOL)
+
+
+def test_textbook_flags_power_iters_and_stat_beta(harness):
+    # two multiplications square the condition number of L Q; 4 x 64 = 256 samples keep the
+    # 80 x 80 factor at a condition number of about a dozen, so FP32 resolves the basis to 1e-4
+    W0, grads = synth.spiked_gradients(seed=11, m=64, n=80, steps=8, noise_std=0.1)
+    _run(harness, [W0], [[g] for g in grads], freq=4, lr=1e-3, bias_correction=1, eps_outside_sqrt=1,
+         power_iters=2, stat_beta=0.9, eps=1e-6, beta1=0.8, beta2=0.99)
+
+
+@pytest.mark.parametrize("shape", [(48, 200), (200, 48)])
+def test_first_moment_source_unilateral(harness, shape):
+    """First-order source (Algorithm 2 lines 11-19): Power(M M^T, U) with no L/R buffers.  A wide
+    noisy M keeps M M^T well conditioned, so the bases are compared directly."""
+    m, n = shape
+    W0, grads = synth.lowrank_gradients(seed=12, m=m, n=n, steps=6, rank=8, sigma=0.05)
+    sb, _ = _run(harness, [W0], [[g] for g in grads], freq=2, lr=1e-3, source=1, geometry=1)
+    assert not sb.opt.has_state(0, sb.B.BR_STATE_L) and not sb.opt.has_state(0, sb.B.BR_STATE_R)
+
+
+def test_first_moment_source_bilateral_square(harness):
+    """Square M: cond(M M^T) = cond(M)^2 is large, so the trailing basis vectors are resolved
+    only to cond * 2^-24 in FP32 and are not compared; updates, M, S and orthogonality are."""
+    W0, grads = synth.lowrank_gradients(seed=12, m=64, n=64, steps=6, rank=64, sigma=0.05)
+    _run(harness, [W0], [[g] for g in grads], freq=2, lr=1e-3, source=1, check_q=False)
+
+
+def test_bf16_params_and_grads_hidden_256_layer(harness):
+    """Transformer-layer matrices shrunk to hidden 256 (Q/K/V/O 256^2, gate/up 256 x 704, down
+    704 x 256), BF16 parameters and gradients, FP32 master and state, refresh every 10 steps."""
+    shapes = [(256, 256)] * 4 + [(256, 704)] * 2 + [(704, 256)]
+    W0s, seqs = [], []
+    for k, (m, n) in enumerate(shapes):
+        W0, grads = synth.lowrank_gradients(seed=2 * 1000 + k, m=m, n=n, steps=12, rank=64, sigma=0.01, bf16=True)
+        W0s.append(W0)
+        seqs.append(grads)
+    steps = [[seqs[k][t] for k in range(len(shapes))] for t in range(12)]
+    sb, _ = _run(harness, W0s, steps, freq=10, lr=1e-3, bf16_params=True, bf16_grads=True)
+    # the BF16 parameter is the RNE image of the master copy: bit-exact against the GPU's own
+    # master, and within one BF16 ulp of the oracle's image
+    for i in range(len(shapes)):
+        master = sb.opt.state(i, sb.B.BR_STATE_MASTER)
+        assert torch.equal(master.to(torch.bfloat16), sb.params[i])
+        ref = oc.bf16_round(sb.W_ref[i])
+        got = harness.to_np(sb.params[i])
+        assert np.abs(got - ref).max() <= 2.0 ** -7 * np.abs(ref).max()
+        assert (got != ref).mean() < 0.01
+
+
+def test_norms_option(harness):
+    W0, grads = synth.spiked_gradients(seed=13, m=120, n=88, steps=3, noise_std=0.1)
+    sb = harness.SideBySide([W0], freq=2, lr=1e-3, compute_norms=1)
+    for g in grads:
+        sb.step([g])
+    norms = harness.to_np(sb.opt.state(0, sb.B.BR_STATE_NORMS))[0]
+    last = sb.states[0].last
+    assert abs(norms[0] - np.sum(last["G_rot"] ** 2)) <= 1e-4 * np.sum(last["G_rot"] ** 2)
+    assert abs(norms[1] - np.sum(last["X"] ** 2)) <= 1e-4 * np.sum(last["X"] ** 2)
+    # rotation preserves the Frobenius norm of the gradient
+    assert abs(norms[0] - np.sum(np.asarray(grads[-1], dtype=np.float64) ** 2)) <= 1e-4 * norms[0]
+
+
+def test_run_to_run_determinism_and_checkpoint_resume(harness):
+    W0, grads = synth.spiked_gradients(seed=14, m=96, n=160, steps=8, noise_std=0.1)
+
+    def run(n_steps, resume_from=None):
+        sb = harness.SideBySide([W0], freq=3, lr=1e-3)
+        if resume_from is not None:
+            ws, w, t = resume_from
+            sb.opt.workspace[:sb.opt.state_bytes].copy_(ws)
+            sb.params[0].copy_(w)
+            sb.B.br_set_step_count(sb.opt.ctx, t)
+            start = t
+        else:
+            start = 0
+        for g in grads[start:n_steps]:
+            sb.opt.step([harness.to_dev(g)])
+        torch.cuda.synchronize()
+        return sb
+
+    a, b = run(8), run(8)
+    assert torch.equal(a.params[0], b.params[0])
+    assert torch.equal(a.opt.workspace[:a.opt.state_bytes], b.opt.workspace[:b.opt.state_bytes])
+    half = run(4)
+    snap = (half.opt.workspace[:half.opt.state_bytes].clone(), half.params[0].clone(), 4)
+    c = run(8, resume_from=snap)
+    assert torch.equal(a.params[0], c.params[0])
+    assert torch.equal(a.opt.workspace[:a.opt.state_bytes], c.opt.workspace[:c.opt.state_bytes])
+
+
+def test_error_paths_leave_kernels_unlaunched(harness):
+    from paper_2602_03515_amd import binding as B
+    W = torch.zeros(8, 8, device="cuda")
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+    opt = BasisRotationAdam([W], freq=2)
+    g = torch.ones(8, 8, device="cuda")
+    with pytest.raises(B.BrError) as e:
+        B.br_step(opt.ctx, [W.data_ptr()], [g.data_ptr()], 1e-3)          # no statistics yet
+    assert e.value.status == B.BR_ERR_STATE
+    with pytest.raises(B.BrError) as e:
+        B.br_accumulate_stats(opt.ctx, [g.data_ptr(), g.data_ptr()])      # wrong count
+    assert e.value.status == B.BR_ERR_SHAPE
+    with pytest.raises(B.BrError) as e:
+        B.br_accumulate_stats(opt.ctx, [0])                               # null gradient
+    assert e.value.status == B.BR_ERR_INVALID_ARG
+    with pytest.raises(B.BrError) as e:
+        B.br_accumulate_stats(opt.ctx, [g.data_ptr() + 4])                # misaligned
+    assert e.value.status == B.BR_ERR_INVALID_ARG
+    B.br_accumulate_stats(opt.ctx, [g.data_ptr()])
+    with pytest.raises(B.BrError) as e:
+        B.br_accumulate_stats(opt.ctx, [g.data_ptr()])                    # twice
+    assert e.value.status == B.BR_ERR_STATE
+    with pytest.raises(B.BrError):
+        B.br_get_state(opt.ctx, 3, B.BR_STATE_M)
+    B.br_step(opt.ctx, [W.data_ptr()], [g.data_ptr()], 1e-3)
+    torch.cuda.synchronize()
+    assert torch.isfinite(W).all() and opt.step_count == 1
