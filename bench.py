@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the basis-rotation optimizer step on one MI355X.
+
+A "step" is one pass of the whole hot path over one pipeline stage's matrices: take the
+delayed gradient from the ring, first moment + Kronecker statistics, basis refresh when
+t mod freq == 0, rotate, Adam in the rotated basis, rotate back and apply.  Inputs are
+synthetic and resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3}   # MI355X dense FP32 matrix-core peak
+PEAK_HBM_GBS = 8000.0
+TAU = 3
+FREQ = 10
+
+
+def workload(name):
+    from paper_2602_03515_amd import synth
+    if name == "stage3b":
+        return list(synth.STAGE_3B), "3B-class pipeline stage: 8 layers x (4x 2560x2560, 2x 2560x6912, 1x 6912x2560) = 56 matrices"
+    if name == "layer3b":
+        return list(synth.STAGE_3B_LAYER), "one layer of the 3B-class stage (7 matrices)"
+    if name == "layer2048":
+        return list(synth.LLAMA_LAYER_2048), "one Llama-style layer, hidden 2048 (7 matrices)"
+    if name == "small":
+        return [(256, 256)], "single 256x256 matrix"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def make_inputs(shapes, slots, seed, device, sigma=0.01, rank=64):
+    """Low-rank-plus-noise gradients generated on the device: G = A diag(1/i) B^T + sigma N, one
+    tensor per ring slot and matrix; weights ~ 0.02 N(0,1)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    params, ring = [], [[] for _ in range(slots)]
+    s = 1.0 / torch.arange(1, rank + 1, device=device, dtype=torch.float32)
+    for (m, n) in shapes:
+        A, _ = torch.linalg.qr(torch.randn(m, rank, generator=gen, device=device))
+        Bm, _ = torch.linalg.qr(torch.randn(n, rank, generator=gen, device=device))
+        signal = (A * s[None, :]) @ Bm.T
+        params.append(0.02 * torch.randn(m, n, generator=gen, device=device))
+        for k in range(slots):
+            ring[k].append((signal + sigma * torch.randn(m, n, generator=gen, device=device)).contiguous())
+        del A, Bm, signal
+    return params, ring
+
+
+def cpu_baseline(seconds_hint=20.0):
+    """The float64 oracle as it stands, timed on this host's cores on a bounded sample of the same
+    workload: one layer of the stage (7 matrices), one ordinary (non-refresh) step."""
+    import numpy as np
+    from oracle import br_oracle as oc
+    from paper_2602_03515_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    hp = oc.Hyper().rounded_to_f32()
+    rng = np.random.default_rng(2)
+    shapes = list(synth.STAGE_3B_LAYER)
+    t_total, params = 0.0, 0
+    done = []
+    for (m, n) in shapes:
+        G = (0.01 * rng.standard_normal((m, n))).astype(np.float32)
+        W = (0.02 * rng.standard_normal((m, n))).astype(np.float32)
+        st = oc.MatrixState(m, n, hp)
+        t0 = time.perf_counter()
+        oc.optimizer_step(st, W, G, 1e-3, hp, freq=0)
+        t_total += time.perf_counter() - t0
+        params += m * n
+        done.append(f"{m}x{n}")
+        if t_total > 1.5 * seconds_hint:
+            break
+    return {"value": params / t_total, "unit": "params/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{len(done)} matrices of one stage layer ({', '.join(done)}), one non-refresh step each, "
+                      f"float64 numpy, {t_total:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="stage3b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (one pipeline stage's share); --gpus must be 1", file=sys.stderr)
+        raise SystemExit(2)
+
+    import torch
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        raise SystemExit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    shapes, desc = workload(args.workload)
+    n_params = sum(m * n for m, n in shapes)
+    params, ring = make_inputs(shapes, TAU + 1, seed=2, device=dev)
+    opt = BasisRotationAdam(params, freq=FREQ, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8)
+    torch.cuda.synchronize()
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        opt.step(ring[t % (TAU + 1)])          # the ring hands over the slot filled tau steps ago
+    torch.cuda.synchronize()
+
+    B.br_profile_begin(opt.ctx)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        t += 1
+        opt.step(ring[t % (TAU + 1)])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.br_profile_end(opt.ctx)
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    refreshes = sum(1 for k in range(args.warmup + 1, args.warmup + args.steps + 1) if k % FREQ == 0)
+    gemm = [p for p in prof if p["kernel"].startswith("br_gemm")]
+    dom = max(gemm, key=lambda p: p["ms"]) if gemm else None
+    roofline = None
+    if dom:
+        avg_ms = dom["ms"] / dom["launches"]
+        achieved = dom["flops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": achieved, "peak": PEAK_TFLOPS["f32"],
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS["f32"], "traffic": None,
+                    "launches": dom["launches"], "avg_launch_ms": avg_ms}
+    breakdown = {p["kernel"]: {"launches": p["launches"], "ms_per_step": p["ms"] / args.steps,
+                               "tflops": (p["flops"] / (p["ms"] * 1e-3) / 1e12) if p["ms"] > 0 else None,
+                               "gbs": (p["bytes"] / (p["ms"] * 1e-3) / 1e9) if p["ms"] > 0 and p["bytes"] > 0 else None}
+                 for p in prof}
+    out = {
+        "metric": "rotated-optimizer steps/sec per stage (params/s)",
+        "value": n_params * args.steps / elapsed,
+        "unit": "params/s",
+        "steps_per_s": args.steps / elapsed,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "params": n_params, "geometry": "bilateral",
+                   "source": "second", "refresh_every": FREQ, "refreshes_in_timed_region": refreshes,
+                   "power_iters": 1, "delay_tau": TAU, "param_dtype": "f32", "grad_dtype": "f32",
+                   "math": "fp32 MFMA", "state_bytes": opt.state_bytes, "scratch_bytes": opt.scratch_bytes},
+        "roofline": roofline,
+        "kernels": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

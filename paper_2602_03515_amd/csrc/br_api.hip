@@ -124,21 +124,23 @@ int step_buffers(const Group& g) {
 }
 
 struct RefreshScratch {
-  size_t P0, P1, gram, Vc, Y, W, T, diag, total;
+  size_t P0, P1, gram, V, Y, W, T, Tp, G, diag, total;
 };
 
 RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   RefreshScratch r;
   size_t kk = align256((size_t)k * k * 4);
-  size_t panels = (size_t)((k + BR_QR_NB - 1) / BR_QR_NB);
+  size_t blocks = (size_t)((k + BR_QR_NBO - 1) / BR_QR_NBO);
   size_t off = 0;
   r.P0 = off; off += kk;
   r.P1 = off; if (hp.power_iters > 1) off += kk;
   r.gram = off; if (hp.source == BR_SRC_FIRST) off += kk;
-  r.Vc = off; off += align256((size_t)k * BR_QR_NB * 4);
-  r.Y = off; off += align256((size_t)k * BR_QR_NB * 4);
-  r.W = off; off += align256((size_t)k * BR_QR_NB * 4);
-  r.T = off; off += align256(panels * BR_QR_NB * BR_QR_NB * 4);
+  r.V = off; off += align256((size_t)k * BR_QR_NBO * 4);       // reflectors of one outer block
+  r.Y = off; off += align256((size_t)k * BR_QR_NBO * 4);       // V T or V T^T
+  r.W = off; off += align256((size_t)k * BR_QR_NBO * 4);       // V^T C
+  r.T = off; off += align256(blocks * BR_QR_NBO * BR_QR_NBO * 4);  // one factor per outer block
+  r.Tp = off; off += align256((size_t)(BR_QR_NBO / BR_QR_NB) * BR_QR_NB * BR_QR_NB * 4);
+  r.G = off; off += align256((size_t)BR_QR_NBO * BR_QR_NBO * 4);
   r.diag = off; off += align256((size_t)k * 4);
   r.total = off;
   return r;
@@ -425,64 +427,96 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 }
 
 // Blocked Householder QR of the k x k matrices P (in place) for a batch of jobs, orthogonal
-// factor written to Q with the sign convention diag(R) >= 0.
+// factor written to Q with the sign convention diag(R) >= 0.  Two-level blocking: inner panels
+// of BR_QR_NB columns are factorised by the panel kernel and applied inside their outer block
+// of BR_QR_NBO columns; the outer block's reflectors are then merged into one compact-WY factor
+// and applied to the trailing matrix with K = BR_QR_NBO contractions.
 static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs, char* base,
                      size_t stride) {
-  const int npanels = (k + BR_QR_NB - 1) / BR_QR_NB;
-  auto Vc = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.Vc); };
+  const int NB = BR_QR_NB, NBO = BR_QR_NBO;
+  const int nblocks = (k + NBO - 1) / NBO;
+  auto V = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.V); };
   auto Y = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.Y); };
   auto W = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.W); };
-  auto T = [&](int i, int pnl) { return reinterpret_cast<float*>(base + i * stride + rs.T) + (size_t)pnl * BR_QR_NB * BR_QR_NB; };
+  auto T = [&](int i, int blk) { return reinterpret_cast<float*>(base + i * stride + rs.T) + (size_t)blk * NBO * NBO; };
+  auto Tp = [&](int i, int pnl) { return reinterpret_cast<float*>(base + i * stride + rs.Tp) + (size_t)pnl * NB * NB; };
+  auto G = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.G); };
   auto D = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.diag); };
   BrQrPanelBatch pb;
   BrGemmBatch gb;
-  for (int pnl = 0; pnl < npanels; ++pnl) {
-    const int j0 = pnl * BR_QR_NB;
-    const int nb = std::min(BR_QR_NB, k - j0);
-    const int rows = k - j0;
-    const int nt = k - j0 - nb;
-    std::memset(&pb, 0, sizeof(pb));
-    for (int i = 0; i < B; ++i) {
-      pb.A[i] = P[i] + (size_t)j0 * k + j0;
-      pb.Vc[i] = Vc(i);
-      pb.T[i] = T(i, pnl);
-      pb.diag[i] = D(i) + j0;
+  for (int blk = 0; blk < nblocks; ++blk) {
+    const int J0 = blk * NBO;
+    const int nbo = std::min(NBO, k - J0);  // columns of this outer block
+    const int rows = k - J0;                // rows of this outer block
+    const int npanels = (nbo + NB - 1) / NB;
+    for (int pnl = 0; pnl < npanels; ++pnl) {
+      const int j0 = J0 + pnl * NB;
+      const int nb = std::min(NB, k - j0);
+      const int prow = k - j0;
+      std::memset(&pb, 0, sizeof(pb));
+      for (int i = 0; i < B; ++i) {
+        pb.A[i] = P[i] + (size_t)j0 * k + j0;
+        pb.Vc[i] = V(i) + (size_t)(pnl * NB) * NBO + pnl * NB;
+        pb.T[i] = Tp(i, pnl);
+        pb.diag[i] = D(i) + j0;
+      }
+      if (!hip_ok(c, br_launch_qr_panel(c->stream, pb, B, prow, nb, k, NBO, pnl * NB), "qr panel launch")) return false;
+      const int nin = J0 + nbo - (j0 + nb);  // columns of the outer block still to the right
+      if (nin <= 0) continue;
+      std::memset(&gb, 0, sizeof(gb));
+      // Yt = Vp Tp^T  (prow x NB), Vp = this panel's slice of V
+      for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = Tp(i, pnl); gb.C[i] = Y(i); }
+      if (!gemm(c, BrGemmArgs{prow, NB, NB, NBO, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb, false)) return false;
+      // W = Vp^T C, C = the outer block's remaining columns in the panel's rows
+      for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
+      if (!gemm(c, BrGemmArgs{NB, nin, prow, NBO, k, NBO, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+      // C <- C - Yt W
+      for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)j0 * k + j0 + nb; }
+      if (!gemm(c, BrGemmArgs{prow, nin, NB, NB, NBO, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
     }
-    if (!hip_ok(c, br_launch_qr_panel(c->stream, pb, B, rows, nb, k), "qr panel launch")) return false;
+    // Merge the panels' factors: G = V^T V, then T_blk from the inner factors and G.
+    const float* gp[BR_MAXB];
+    const float* tpp[BR_MAXB];
+    float* tb[BR_MAXB];
+    std::memset(&gb, 0, sizeof(gb));
+    if (npanels > 1) {
+      for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = V(i); gb.C[i] = G(i); }
+      if (!gemm(c, BrGemmArgs{NBO, NBO, rows, NBO, NBO, NBO, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    }
+    for (int i = 0; i < B; ++i) { gp[i] = G(i); tpp[i] = Tp(i, 0); tb[i] = T(i, blk); }
+    if (!hip_ok(c, br_launch_qr_build_t(c->stream, gp, tpp, tb, B, npanels), "qr factor merge launch")) return false;
+    const int nt = k - J0 - nbo;
     if (nt <= 0) continue;
-    std::memset(&gb, 0, sizeof(gb));
-    // Yt = Vc T^T
-    for (int i = 0; i < B; ++i) { gb.A[i] = Vc(i); gb.B[i] = T(i, pnl); gb.C[i] = Y(i); }
-    if (!gemm(c, BrGemmArgs{rows, BR_QR_NB, BR_QR_NB, BR_QR_NB, BR_QR_NB, BR_QR_NB, 0, 1, 1.f, 0.f, B, 0}, gb, false)) return false;
-    // W = Vc^T C,  C = trailing columns of the panel's rows
-    for (int i = 0; i < B; ++i) { gb.A[i] = Vc(i); gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
-    if (!gemm(c, BrGemmArgs{BR_QR_NB, nt, rows, BR_QR_NB, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
-    // C <- C - Yt W
-    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)j0 * k + j0 + nb; }
-    if (!gemm(c, BrGemmArgs{rows, nt, BR_QR_NB, BR_QR_NB, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
+    // Yt = V T^T ; W = V^T C ; C <- C - Yt W   on the trailing columns
+    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
+    if (!gemm(c, BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 1, 1.f, 0.f, B, 0}, gb, false)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = P[i] + (size_t)J0 * k + J0 + nbo; gb.C[i] = W(i); }
+    if (!gemm(c, BrGemmArgs{NBO, nt, rows, NBO, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)J0 * k + J0 + nbo; }
+    if (!gemm(c, BrGemmArgs{rows, nt, NBO, NBO, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
   }
-  // Q = H_1 ... H_k applied to the identity, last block reflector first.
+  // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before block blk is
+  // applied, Q differs from the identity only in Q[J1:, J1:] with J1 the next block's offset,
+  // so only the columns from J0 on change.
   if (!hip_ok(c, br_launch_set_identity(c->stream, Q, B, k), "identity launch")) return false;
-  for (int pnl = npanels - 1; pnl >= 0; --pnl) {
-    const int j0 = pnl * BR_QR_NB;
-    const int nb = std::min(BR_QR_NB, k - j0);
-    const int rows = k - j0;
+  for (int blk = nblocks - 1; blk >= 0; --blk) {
+    const int J0 = blk * NBO;
+    const int nbo = std::min(NBO, k - J0);
+    const int rows = k - J0;
     std::memset(&pb, 0, sizeof(pb));
     for (int i = 0; i < B; ++i) {
-      pb.A[i] = P[i] + (size_t)j0 * k + j0;
-      pb.Vc[i] = Vc(i);
+      pb.A[i] = P[i] + (size_t)J0 * k + J0;
+      pb.Vc[i] = V(i);
     }
-    if (!hip_ok(c, br_launch_qr_extract_v(c->stream, pb, B, rows, nb, k), "qr extract launch")) return false;
+    if (!hip_ok(c, br_launch_qr_extract_v(c->stream, pb, B, rows, nbo, k, NBO), "qr extract launch")) return false;
     std::memset(&gb, 0, sizeof(gb));
-    // Y = Vc T
-    for (int i = 0; i < B; ++i) { gb.A[i] = Vc(i); gb.B[i] = T(i, pnl); gb.C[i] = Y(i); }
-    if (!gemm(c, BrGemmArgs{rows, BR_QR_NB, BR_QR_NB, BR_QR_NB, BR_QR_NB, BR_QR_NB, 0, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
-    // W = Vc^T Qsub,  Qsub = Q[j0:, j0:]
-    for (int i = 0; i < B; ++i) { gb.A[i] = Vc(i); gb.B[i] = Q[i] + (size_t)j0 * k + j0; gb.C[i] = W(i); }
-    if (!gemm(c, BrGemmArgs{BR_QR_NB, rows, rows, BR_QR_NB, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
-    // Qsub <- Qsub - Y W
-    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Q[i] + (size_t)j0 * k + j0; }
-    if (!gemm(c, BrGemmArgs{rows, rows, BR_QR_NB, BR_QR_NB, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
+    // Y = V T ; W = V^T Qsub ; Qsub <- Qsub - Y W,  Qsub = Q[J0:, J0:]
+    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
+    if (!gemm(c, BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Q[i] + (size_t)J0 * k + J0; gb.C[i] = W(i); }
+    if (!gemm(c, BrGemmArgs{NBO, rows, rows, NBO, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Q[i] + (size_t)J0 * k + J0; }
+    if (!gemm(c, BrGemmArgs{rows, rows, NBO, NBO, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
   }
   const float* dg[BR_MAXB];
   for (int i = 0; i < B; ++i) dg[i] = D(i);

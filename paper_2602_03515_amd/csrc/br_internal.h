@@ -70,19 +70,28 @@ hipError_t br_launch_set_identity(hipStream_t s, float* const* mats, int batch, 
 hipError_t br_launch_bf16_to_f32(hipStream_t s, const uint16_t* src, float* dst, int64_t count);
 
 // ---- QR ---------------------------------------------------------------------------------
-#define BR_QR_NB 32  // panel width of the blocked Householder factorisation
+#define BR_QR_NB 32    // inner panel width of the blocked Householder factorisation
+#define BR_QR_NBO 128  // outer block width: four inner panels share one trailing-matrix update
 
 struct BrQrPanelBatch {
   float* A[BR_MAXB];     // top-left corner of the panel inside the matrix being factorised
-  float* Vc[BR_MAXB];    // rows x BR_QR_NB clean copy of the reflectors (unit diagonal, zeros above)
+  float* Vc[BR_MAXB];    // clean copy of the reflectors (unit diagonal, zeros above), row stride ldv
   float* T[BR_MAXB];     // BR_QR_NB x BR_QR_NB upper-triangular block-reflector factor
   float* diag[BR_MAXB];  // nb diagonal entries of R for this panel
 };
 // Householder-factorise the rows x nb panel in place (reflectors below the diagonal, R on and
 // above), one workgroup per matrix.
-hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda);
-// Copy the reflectors of an already factorised panel back out into Vc.
-hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda);
+// Vc points at this panel's first row and first column inside a reflector block of row stride
+// ldv; the pre_rows rows of that block above it are zero-filled in the panel's columns.
+hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda, int ldv,
+                              int pre_rows);
+// Copy the reflectors of an already factorised block of nb columns out into Vc (rows x width).
+hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda,
+                                  int width);
+// Assemble the BR_QR_NBO-wide block-reflector factor from npanels inner factors and the Gram
+// matrix of the block's reflectors.
+hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const float* const* Tp, float* const* T, int batch,
+                                int npanels);
 // Q[:, j] *= sign(diag[j]) (zero counts as +).
 hipError_t br_launch_qr_fix_signs(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n);
 

@@ -73,7 +73,8 @@ __device__ __forceinline__ void panel_reduce(float acc[4], float (*red)[32], flo
   __syncthreads();
 }
 
-__global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int rows, int nb, int lda, int vec_ok) {
+__global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int rows, int nb, int lda, int vec_ok,
+                                                          int ldv, int pre_rows) {
   __shared__ float red[QR_WAVES][32];
   __shared__ float comb[32];
   __shared__ float dvec[32];
@@ -195,7 +196,13 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
     const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
     Tg[i] = (r < nb && c < nb) ? Tl[r][c] : 0.f;
   }
-  // Clean copy of the reflectors: unit diagonal, zeros above it and right of column nb.
+  // Clean copy of the reflectors: unit diagonal, zeros above it and right of column nb.  The
+  // copy is a 32-column slice of a wider reflector block (row stride ldv); the pre_rows rows of
+  // that block above this panel's first row are zero in these columns.
+  for (int i = tid; i < pre_rows * BR_QR_NB; i += QR_THREADS) {
+    const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
+    Vc[-(ptrdiff_t)(r + 1) * ldv + c] = 0.f;
+  }
   for (int it = 0; it < nsweeps; ++it) {
     const int r = rg + QR_ROWS_PER_SWEEP * it;
     if (r < rows) {
@@ -206,22 +213,70 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
         const int c = c0 + q;
         a[q] = (c >= nb || c > r) ? 0.f : ((c == r) ? 1.0f : a[q]);
       }
-      *reinterpret_cast<float4*>(Vc + (size_t)r * BR_QR_NB + c0) = make_float4(a[0], a[1], a[2], a[3]);
+      *reinterpret_cast<float4*>(Vc + (size_t)r * ldv + c0) = make_float4(a[0], a[1], a[2], a[3]);
     }
   }
 }
 
-__global__ __launch_bounds__(256) void br_qr_extract_v(BrQrPanelBatch p, int rows, int nb, int lda) {
+// Vc (rows x width, row stride width) <- reflectors stored below the diagonal of an already
+// factorised block of nb <= width columns: unit diagonal, zeros above, zero padding right of nb.
+__global__ __launch_bounds__(256) void br_qr_extract_v(BrQrPanelBatch p, int rows, int nb, int lda, int width) {
   const float* __restrict__ A = p.A[blockIdx.y];
   float* __restrict__ Vc = p.Vc[blockIdx.y];
-  const int64_t total = (int64_t)rows * BR_QR_NB;
+  const int64_t total = (int64_t)rows * width;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-    const int r = (int)(i / BR_QR_NB), c = (int)(i - (int64_t)r * BR_QR_NB);
+    const int r = (int)(i / width), c = (int)(i - (int64_t)r * width);
     float v = 0.f;
     if (c < nb) v = (c > r) ? 0.f : ((c == r) ? 1.0f : A[(size_t)r * lda + c]);
     Vc[i] = v;
   }
+}
+
+// Merge the 32-wide block-reflector factors of one outer block into its BR_QR_NBO-wide factor:
+//   T = [ T_a  -T_a (V_a^T V_b) T_b ]
+//       [ 0     T_b             ]      applied panel by panel,
+// with the cross products V_a^T V_b read from the Gram matrix G = V^T V of the outer block.
+// One 256-thread workgroup per matrix; everything lives in LDS.
+struct BuildTArgs {
+  const float* G[BR_MAXB];   // BR_QR_NBO x BR_QR_NBO
+  const float* Tp[BR_MAXB];  // npanels consecutive BR_QR_NB x BR_QR_NB factors
+  float* T[BR_MAXB];         // BR_QR_NBO x BR_QR_NBO output
+};
+
+__global__ __launch_bounds__(256) void br_qr_build_t(BuildTArgs a, int npanels) {
+  __shared__ float T[BR_QR_NBO][BR_QR_NBO + 1];
+  __shared__ float Z[BR_QR_NBO][BR_QR_NB + 1];
+  const float* __restrict__ G = a.G[blockIdx.x];
+  const float* __restrict__ Tp = a.Tp[blockIdx.x];
+  float* __restrict__ Tout = a.T[blockIdx.x];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < BR_QR_NBO * BR_QR_NBO; i += 256) T[i / BR_QR_NBO][i % BR_QR_NBO] = 0.f;
+  __syncthreads();
+  for (int pnl = 0; pnl < npanels; ++pnl) {
+    const int o = pnl * BR_QR_NB;
+    for (int i = tid; i < BR_QR_NB * BR_QR_NB; i += 256)
+      T[o + i / BR_QR_NB][o + i % BR_QR_NB] = Tp[(size_t)pnl * BR_QR_NB * BR_QR_NB + i];
+    __syncthreads();
+    if (pnl == 0) continue;
+    // Z = T[0:o, 0:o] * G[0:o, o:o+32]
+    for (int i = tid; i < o * BR_QR_NB; i += 256) {
+      const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
+      float s = 0.f;
+      for (int l = r; l < o; ++l) s += T[r][l] * G[(size_t)l * BR_QR_NBO + o + c];
+      Z[r][c] = s;
+    }
+    __syncthreads();
+    // T[0:o, o:o+32] = -Z * T_b
+    for (int i = tid; i < o * BR_QR_NB; i += 256) {
+      const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
+      float s = 0.f;
+      for (int l = 0; l <= c; ++l) s += Z[r][l] * T[o + l][o + c];
+      T[r][o + c] = -s;
+    }
+    __syncthreads();
+  }
+  for (int i = tid; i < BR_QR_NBO * BR_QR_NBO; i += 256) Tout[i] = T[i / BR_QR_NBO][i % BR_QR_NBO];
 }
 
 struct SignArgs {
@@ -242,21 +297,39 @@ __global__ __launch_bounds__(256) void br_qr_fix_signs(SignArgs a, int n) {
 
 }  // namespace br
 
-hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda) {
+hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda, int ldv,
+                              int pre_rows) {
   if (batch <= 0) return hipSuccess;
-  if (batch > BR_MAXB || rows < nb || nb < 1 || nb > BR_QR_NB || lda < nb) return hipErrorInvalidValue;
+  if (batch > BR_MAXB || rows < nb || nb < 1 || nb > BR_QR_NB || lda < nb || ldv < BR_QR_NB || (ldv & 3) || pre_rows < 0)
+    return hipErrorInvalidValue;
   int vec = (lda % 4 == 0);
   for (int i = 0; i < batch && vec; ++i) vec = ((reinterpret_cast<uintptr_t>(p.A[i]) & 15u) == 0);
-  hipLaunchKernelGGL(br::br_qr_panel, dim3(batch), dim3(br::QR_THREADS), 0, s, p, rows, nb, lda, vec);
+  hipLaunchKernelGGL(br::br_qr_panel, dim3(batch), dim3(br::QR_THREADS), 0, s, p, rows, nb, lda, vec, ldv, pre_rows);
   return hipGetLastError();
 }
 
-hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda) {
+hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda,
+                                  int width) {
   if (batch <= 0) return hipSuccess;
-  if (batch > BR_MAXB || rows < nb || nb < 1 || nb > BR_QR_NB) return hipErrorInvalidValue;
-  int64_t blocks = ((int64_t)rows * BR_QR_NB + 255) / 256;
-  if (blocks > 256) blocks = 256;
-  hipLaunchKernelGGL(br::br_qr_extract_v, dim3((int)blocks, batch), dim3(256), 0, s, p, rows, nb, lda);
+  if (batch > BR_MAXB || rows < nb || nb < 1 || nb > width) return hipErrorInvalidValue;
+  int64_t blocks = ((int64_t)rows * width + 255) / 256;
+  int64_t cap = (4096 + batch - 1) / batch;
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL(br::br_qr_extract_v, dim3((int)blocks, batch), dim3(256), 0, s, p, rows, nb, lda, width);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const float* const* Tp, float* const* T, int batch,
+                                int npanels) {
+  if (batch <= 0) return hipSuccess;
+  if (batch > BR_MAXB || npanels < 1 || npanels * BR_QR_NB > BR_QR_NBO) return hipErrorInvalidValue;
+  br::BuildTArgs a;
+  for (int i = 0; i < BR_MAXB; ++i) {
+    a.G[i] = (i < batch) ? G[i] : nullptr;
+    a.Tp[i] = (i < batch) ? Tp[i] : nullptr;
+    a.T[i] = (i < batch) ? T[i] : nullptr;
+  }
+  hipLaunchKernelGGL(br::br_qr_build_t, dim3(batch), dim3(256), 0, s, a, npanels);
   return hipGetLastError();
 }
 
