@@ -82,7 +82,8 @@ typedef enum {
   BR_STATE_QL = 4,     /* left rotation U, m x m                                         */
   BR_STATE_QR = 5,     /* right rotation V, n x n                                        */
   BR_STATE_MASTER = 6, /* FP32 master weights of a BF16 parameter, m x n                 */
-  BR_STATE_NORMS = 7   /* 1 x 2: ||G~||_F^2 and ||X||_F^2 of the latest step             */
+  BR_STATE_NORMS = 7,  /* 1 x 2: ||G~||_F^2 and ||X||_F^2 of the latest step             */
+  BR_STATE_MROT = 8    /* cached rotated first moment M~, m x n (cache_rotated_moment)   */
 } br_state_kind;
 
 typedef struct {
@@ -105,7 +106,12 @@ typedef struct {
   int32_t eps_outside_sqrt; /* 1: m / (sqrt(s) + eps);            0 = Algorithm 1        */
   int32_t math;        /* br_math                                                        */
   int32_t compute_norms;    /* 1: keep ||G~||_F^2, ||X||_F^2 per matrix (BR_STATE_NORMS) */
-  int32_t reserved;    /* must be 0                                                      */
+  int32_t cache_rotated_moment; /* 1: also keep M~ = Q_L^T M Q_R in the state and, while the
+                          basis is unchanged, advance it by M~ <- beta1 M~ + (1-beta1) G~
+                          (equal to rotating M, by linearity) instead of rotating M every
+                          step; M~ is recomputed from M after every refresh.  Costs m*n
+                          floats per rotated matrix, saves a quarter of the step's
+                          contractions.  0: rotate M every step (Algorithm 1 line 9 as is). */
 } br_hparams;
 
 /* One line per kernel symbol of a profiled region (see br_profile_begin). */
@@ -170,12 +176,20 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
 /*
  * Borrow a pointer to one state buffer of matrix `mat` (valid until br_destroy).
  * The caller may read or overwrite it between calls (tests inject a fixed basis;
- * a checkpoint is a copy of the state part of the workspace plus t).
+ * a checkpoint is a copy of the state part of the workspace plus t); after writing
+ * Q_L, Q_R or M call br_notify_state_written.
  * A buffer that does not exist for this matrix (e.g. L of an unrotated side)
  * returns BR_ERR_INVALID_ARG.
  */
 br_status br_get_state(br_ctx* ctx, int32_t mat, int32_t which, void** dev_ptr, int64_t* rows,
                        int64_t* cols);
+
+/*
+ * Tell the library that the caller has overwritten Q_L, Q_R or M through pointers from
+ * br_get_state: quantities derived from them (the cached M~) are rebuilt at the next step.
+ * Not needed after restoring a whole-state checkpoint taken between steps.
+ */
+br_status br_notify_state_written(br_ctx* ctx);
 
 /* Number of completed steps t, and a way to set it when restoring a checkpoint. */
 br_status br_get_step_count(const br_ctx* ctx, int64_t* t);

@@ -28,7 +28,8 @@ BR_F32, BR_BF16 = 0, 1
 BR_BILATERAL, BR_UNILATERAL = 0, 1
 BR_SRC_SECOND, BR_SRC_FIRST = 0, 1
 BR_MATH_F32, BR_MATH_BF16, BR_MATH_BF16X3 = 0, 1, 2
-BR_STATE_M, BR_STATE_S, BR_STATE_L, BR_STATE_R, BR_STATE_QL, BR_STATE_QR, BR_STATE_MASTER, BR_STATE_NORMS = range(8)
+BR_STATE_M, BR_STATE_S, BR_STATE_L, BR_STATE_R, BR_STATE_QL, BR_STATE_QR, BR_STATE_MASTER, BR_STATE_NORMS, \
+    BR_STATE_MROT = range(9)
 
 STATUS_NAMES = ["BR_OK", "BR_ERR_INVALID_ARG", "BR_ERR_SHAPE", "BR_ERR_DTYPE", "BR_ERR_STATE",
                 "BR_ERR_WORKSPACE", "BR_ERR_HIP", "BR_ERR_UNSUPPORTED"]
@@ -43,7 +44,7 @@ class br_hparams(C.Structure):
     _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float),
                 ("stat_beta", C.c_float), ("geometry", C.c_int32), ("source", C.c_int32),
                 ("power_iters", C.c_int32), ("bias_correction", C.c_int32), ("eps_outside_sqrt", C.c_int32),
-                ("math", C.c_int32), ("compute_norms", C.c_int32), ("reserved", C.c_int32)]
+                ("math", C.c_int32), ("compute_norms", C.c_int32), ("cache_rotated_moment", C.c_int32)]
 
 
 class br_profile_entry(C.Structure):
@@ -68,6 +69,8 @@ _lib.br_step.restype = C.c_int
 _lib.br_get_state.argtypes = [_ctx_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_int64),
                               C.POINTER(C.c_int64)]
 _lib.br_get_state.restype = C.c_int
+_lib.br_notify_state_written.argtypes = [_ctx_p]
+_lib.br_notify_state_written.restype = C.c_int
 _lib.br_get_step_count.argtypes = [_ctx_p, C.POINTER(C.c_int64)]
 _lib.br_get_step_count.restype = C.c_int
 _lib.br_set_step_count.argtypes = [_ctx_p, C.c_int64]
@@ -84,7 +87,7 @@ _lib.br_destroy.argtypes = [_ctx_p]
 _lib.br_destroy.restype = None
 
 EXPORTED = ["br_workspace_bytes", "br_init", "br_accumulate_stats", "br_refresh_basis", "br_step", "br_get_state",
-            "br_get_step_count", "br_set_step_count", "br_profile_begin", "br_profile_end", "br_last_error",
+            "br_notify_state_written", "br_get_step_count", "br_set_step_count", "br_profile_begin", "br_profile_end", "br_last_error",
             "br_version", "br_destroy"]
 
 
@@ -112,9 +115,10 @@ def make_descs(shapes: Sequence, param_dtype=BR_F32, grad_dtype=BR_F32, rotate=1
 
 def make_hparams(beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, stat_beta=-1.0, geometry=BR_BILATERAL,
                  source=BR_SRC_SECOND, power_iters=1, bias_correction=0, eps_outside_sqrt=0, math=BR_MATH_F32,
-                 compute_norms=0) -> br_hparams:
+                 compute_norms=0, cache_rotated_moment=1) -> br_hparams:
     return br_hparams(beta1, beta2, eps, weight_decay, stat_beta, geometry, source, power_iters,
-                      int(bias_correction), int(eps_outside_sqrt), math, int(compute_norms), 0)
+                      int(bias_correction), int(eps_outside_sqrt), math, int(compute_norms),
+                      int(cache_rotated_moment))
 
 
 def _ptr_array(ptrs: Sequence[int]):
@@ -169,6 +173,10 @@ def br_get_state(ctx, mat: int, which: int):
     p, r, c = C.c_void_p(), C.c_int64(), C.c_int64()
     _check(_lib.br_get_state(ctx, mat, which, C.byref(p), C.byref(r), C.byref(c)), "br_get_state", ctx)
     return p.value, r.value, c.value
+
+
+def br_notify_state_written(ctx):
+    _check(_lib.br_notify_state_written(ctx), "br_notify_state_written", ctx)
 
 
 def br_get_step_count(ctx) -> int:

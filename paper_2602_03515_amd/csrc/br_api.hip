@@ -26,7 +26,7 @@ struct MatState {
   br_matrix_desc d;
   bool rot_l = false, rot_r = false;
   float *M = nullptr, *S = nullptr, *L = nullptr, *R = nullptr, *QL = nullptr, *QR = nullptr;
-  float *master = nullptr, *norms = nullptr;
+  float *master = nullptr, *norms = nullptr, *Mrot = nullptr;
   bool master_ready = false;
 };
 
@@ -64,6 +64,7 @@ struct br_ctx {
   char* scratch = nullptr;
   int64_t t = 0;
   bool stats_fresh = false;
+  bool mrot_valid = true;  // cached M~ equals Q_L^T M Q_R (true at t = 0: both are zero)
   bool dead = false;
   std::string err;
   bool prof_on = false;
@@ -104,7 +105,7 @@ br_status validate(const br_matrix_desc* descs, int32_t n_mats, const br_hparams
   if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f)) { *why = "beta1/beta2 must be in [0,1)"; return BR_ERR_INVALID_ARG; }
   if (!(hp->stat_beta < 1.f)) { *why = "stat_beta must be below 1 (negative selects beta2)"; return BR_ERR_INVALID_ARG; }
   if (!(hp->eps >= 0.f) || !(hp->weight_decay >= 0.f)) { *why = "eps and weight_decay must be non-negative"; return BR_ERR_INVALID_ARG; }
-  if (hp->reserved != 0) { *why = "br_hparams.reserved must be 0"; return BR_ERR_INVALID_ARG; }
+  if (hp->cache_rotated_moment != 0 && hp->cache_rotated_moment != 1) { *why = "cache_rotated_moment must be 0 or 1"; return BR_ERR_INVALID_ARG; }
   for (int i = 0; i < n_mats; ++i) {
     const br_matrix_desc& d = descs[i];
     if (d.m <= 0 || d.n <= 0 || d.m > kMaxDim || d.n > kMaxDim) { *why = "matrix " + std::to_string(i) + ": dimensions must be in 1..2^24"; return BR_ERR_SHAPE; }
@@ -114,12 +115,15 @@ br_status validate(const br_matrix_desc* descs, int32_t n_mats, const br_hparams
   return BR_OK;
 }
 
-// Bytes of step scratch one matrix of a group needs (all buffers m x n FP32, 256-byte aligned).
-int step_buffers(const Group& g) {
+// Number of m x n FP32 scratch buffers one matrix of a group needs during a step.
+// Bilateral: T1 = Q_L^T G (later Q_L X), G~ (later X), T2 = Q_L^T M, and M~ unless it is cached
+// in the state.  Unilateral: G~ (later X), and M~ unless cached.  Plus an FP32 image of a BF16
+// gradient (last slot).
+int step_buffers(const Group& g, const br_hparams& hp) {
   int nb = 0;
-  if (g.rot_l && g.rot_r) nb = 4;
-  else if (g.rot_l || g.rot_r) nb = 2;
-  if (g.gdt == BR_BF16 && (g.rot_l || g.rot_r)) nb += 1;  // FP32 image of the gradient
+  if (g.rot_l && g.rot_r) nb = hp.cache_rotated_moment ? 3 : 4;
+  else if (g.rot_l || g.rot_r) nb = hp.cache_rotated_moment ? 1 : 2;
+  if (g.gdt == BR_BF16 && (g.rot_l || g.rot_r)) nb += 1;
   return nb;
 }
 
@@ -163,6 +167,7 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
     if (l) state += align256((size_t)d.m * d.m * 4);
     if (r) state += align256((size_t)d.n * d.n * 4);
     if (d.param_dtype == BR_BF16) state += mn;
+    if ((l || r) && hp.cache_rotated_moment) state += mn;
     state += 256;  // norms
     Group* g = nullptr;
     for (auto& c : lay->groups)
@@ -177,7 +182,7 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
   }
   for (auto& g : lay->groups) {
     size_t chunk = std::min<size_t>(g.idx.size(), kStepChunk);
-    size_t need = chunk * step_buffers(g) * align256((size_t)g.m * g.n * 4);
+    size_t need = chunk * step_buffers(g, hp) * align256((size_t)g.m * g.n * 4);
     scratch = std::max(scratch, need);
   }
   for (auto& kv : lay->refresh) {
@@ -295,6 +300,7 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
     if (m.rot_l) m.QL = take(align256((size_t)m.d.m * m.d.m * 4));
     if (m.rot_r) m.QR = take(align256((size_t)m.d.n * m.d.n * 4));
     if (m.d.param_dtype == BR_BF16) m.master = take(mn);
+    if ((m.rot_l || m.rot_r) && c->hp.cache_rotated_moment) m.Mrot = take(mn);
     m.norms = take(256);
   }
   c->scratch = reinterpret_cast<char*>(dev_workspace) + c->lay.state_bytes;
@@ -340,6 +346,12 @@ br_status br_set_step_count(br_ctx* ctx, int64_t t) {
   return BR_OK;
 }
 
+br_status br_notify_state_written(br_ctx* ctx) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  ctx->mrot_valid = false;
+  return BR_OK;
+}
+
 br_status br_get_state(br_ctx* ctx, int32_t mat, int32_t which, void** dev_ptr, int64_t* rows, int64_t* cols) {
   if (!ctx) return BR_ERR_INVALID_ARG;
   if (!dev_ptr || !rows || !cols) return fail(ctx, BR_ERR_INVALID_ARG, "null output pointer");
@@ -356,6 +368,7 @@ br_status br_get_state(br_ctx* ctx, int32_t mat, int32_t which, void** dev_ptr, 
     case BR_STATE_QR: p = m.QR; r = cdim = m.d.n; break;
     case BR_STATE_MASTER: p = m.master; r = m.d.m; cdim = m.d.n; break;
     case BR_STATE_NORMS: p = m.norms; r = 1; cdim = 2; break;
+    case BR_STATE_MROT: p = m.Mrot; r = m.d.m; cdim = m.d.n; break;
     default: return fail(ctx, BR_ERR_INVALID_ARG, "unknown state kind");
   }
   if (!p) return fail(ctx, BR_ERR_INVALID_ARG, "this matrix has no such buffer");
@@ -387,7 +400,7 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
   for (const Group& g : c->lay.groups) {
     const int64_t count = g.m * g.n;
     const size_t mn = align256((size_t)count * 4);
-    const int nbuf = step_buffers(g);
+    const int nbuf = step_buffers(g, hp);
     const bool rotated = g.rot_l || g.rot_r;
     const bool need_g32 = rotated && g.gdt == BR_BF16;
     for (size_t off = 0; off < g.idx.size(); off += kStepChunk) {
@@ -529,6 +542,7 @@ br_status br_refresh_basis(br_ctx* ctx) {
   br_ctx* c = ctx;
   const br_hparams& hp = c->hp;
   char* base = c->scratch + kNormPartialBytes;
+  c->mrot_valid = false;  // the bases change: M~ must be rebuilt from M at the next step
   for (auto& kv : c->lay.refresh) {
     const int k = (int)kv.first;
     const auto& jobs = kv.second;
@@ -587,24 +601,33 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
   const br_hparams& hp = c->hp;
   const int64_t t = c->t + 1;
   BrAdamArgs aa;
+  aa.beta1 = hp.beta1;
   aa.beta2 = hp.beta2;
   aa.eps = hp.eps;
   aa.c1 = hp.bias_correction ? (float)(1.0 / (1.0 - std::pow((double)hp.beta1, (double)t))) : 1.0f;
   aa.c2 = hp.bias_correction ? (float)(1.0 / (1.0 - std::pow((double)hp.beta2, (double)t))) : 1.0f;
   aa.eps_outside = hp.eps_outside_sqrt;
   aa.compute_norms = hp.compute_norms;
+  // With the cache on and the basis unchanged since the last step, M~ advances by its own EMA;
+  // otherwise it is obtained by rotating M (and stored in the cache when there is one).
+  const bool cached = hp.cache_rotated_moment != 0;
+  const bool advance = cached && c->mrot_valid;
+  aa.update_mrot = advance ? 1 : 0;
   const float decay = 1.0f - lr * hp.weight_decay;
   float* partials = reinterpret_cast<float*>(c->scratch);
 
   for (const Group& g : c->lay.groups) {
     const int64_t count = g.m * g.n;
     const size_t mn = align256((size_t)count * 4);
-    const int nbuf = step_buffers(g);
+    const int nbuf = step_buffers(g, hp);
     const bool rotated = g.rot_l || g.rot_r;
+    const bool bilateral = g.rot_l && g.rot_r;
     const int m = (int)g.m, n = (int)g.n;
+    // scratch slots
+    const int sT1 = 0, sGt = bilateral ? 1 : 0, sT2 = 2, sMt = bilateral ? 3 : 1;
     for (size_t off = 0; off < g.idx.size(); off += kStepChunk) {
       const int B = (int)std::min<size_t>(kStepChunk, g.idx.size() - off);
-      float* Wp[kStepChunk];       // FP32 weights that receive the update
+      float* Wp[kStepChunk];         // FP32 weights that receive the update
       uint16_t* shadow[kStepChunk];  // BF16 parameter image, or null
       const float* G32[kStepChunk];
       for (int i = 0; i < B; ++i) {
@@ -653,27 +676,29 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
       std::memset(&gb, 0, sizeof(gb));
       float* Gt[kStepChunk];
       float* Mt[kStepChunk];
-      if (g.rot_l && g.rot_r) {
-        // T = Q_L^T [G | M]   (buffers 0, 1), then [G~ | M~] = T Q_R   (buffers 2, 3)
+      for (int i = 0; i < B; ++i) {
+        const MatState& ms = c->mats[g.idx[off + i]];
+        Gt[i] = scratch_buf(c, nbuf, mn, i, sGt);
+        Mt[i] = cached ? ms.Mrot : scratch_buf(c, nbuf, mn, i, sMt);
+      }
+      const int nrot = advance ? B : 2 * B;  // rotate G only, or G and M
+      if (bilateral) {
+        // T = Q_L^T [G | M], then [G~ | M~] = T Q_R
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
-          gb.A[i] = ms.QL; gb.B[i] = G32[i]; gb.C[i] = scratch_buf(c, nbuf, mn, i, 0);
-          gb.A[B + i] = ms.QL; gb.B[B + i] = ms.M; gb.C[B + i] = scratch_buf(c, nbuf, mn, i, 1);
+          gb.A[i] = ms.QL; gb.B[i] = G32[i]; gb.C[i] = scratch_buf(c, nbuf, mn, i, sT1);
+          gb.A[B + i] = ms.QL; gb.B[B + i] = ms.M; gb.C[B + i] = scratch_buf(c, nbuf, mn, i, sT2);
         }
-        if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, 2 * B, 0}, gb)) return BR_ERR_HIP;
+        if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, nrot, 0}, gb)) return BR_ERR_HIP;
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
-          Gt[i] = scratch_buf(c, nbuf, mn, i, 2);
-          Mt[i] = scratch_buf(c, nbuf, mn, i, 3);
-          gb.A[i] = scratch_buf(c, nbuf, mn, i, 0); gb.B[i] = ms.QR; gb.C[i] = Gt[i];
-          gb.A[B + i] = scratch_buf(c, nbuf, mn, i, 1); gb.B[B + i] = ms.QR; gb.C[B + i] = Mt[i];
+          gb.A[i] = scratch_buf(c, nbuf, mn, i, sT1); gb.B[i] = ms.QR; gb.C[i] = Gt[i];
+          gb.A[B + i] = scratch_buf(c, nbuf, mn, i, sT2); gb.B[B + i] = ms.QR; gb.C[B + i] = Mt[i];
         }
-        if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, 2 * B, 0}, gb)) return BR_ERR_HIP;
+        if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, nrot, 0}, gb)) return BR_ERR_HIP;
       } else {
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
-          Gt[i] = scratch_buf(c, nbuf, mn, i, 0);
-          Mt[i] = scratch_buf(c, nbuf, mn, i, 1);
           if (g.rot_l) {
             gb.A[i] = ms.QL; gb.B[i] = G32[i]; gb.C[i] = Gt[i];
             gb.A[B + i] = ms.QL; gb.B[B + i] = ms.M; gb.C[B + i] = Mt[i];
@@ -682,52 +707,52 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
             gb.A[B + i] = ms.M; gb.B[B + i] = ms.QR; gb.C[B + i] = Mt[i];
           }
         }
-        BrGemmArgs a = g.rot_l ? BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, 2 * B, 0}
-                               : BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, 2 * B, 0};
+        BrGemmArgs a = g.rot_l ? BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, nrot, 0}
+                               : BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, nrot, 0};
         if (!gemm(c, a, gb)) return BR_ERR_HIP;
       }
-      {  // Adam in the rotated basis; X overwrites M~
-        BrPtrBatch pb;
-        std::memset(&pb, 0, sizeof(pb));
-        float* norms[kStepChunk];
+      {  // Adam in the rotated basis; X overwrites G~
+        BrAdamBatch ab;
+        std::memset(&ab, 0, sizeof(ab));
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
-          pb.in0[i] = Gt[i];
-          pb.out0[i] = ms.S;
-          pb.out1[i] = Mt[i];
-          norms[i] = ms.norms;
+          ab.GX[i] = Gt[i];
+          ab.S[i] = ms.S;
+          ab.Mrot[i] = Mt[i];
+          ab.norms[i] = ms.norms;
         }
-        Timed tm(c, "br_adam_rotated", 8.0 * count * B, 20.0 * count * B);
-        if (!hip_ok(c, br_launch_adam_rotated(c->stream, pb, B, count, aa, partials, norms), "rotated adam launch")) return BR_ERR_HIP;
+        Timed tm(c, "br_adam_rotated", 8.0 * count * B, (advance ? 24.0 : 20.0) * count * B);
+        if (!hip_ok(c, br_launch_adam_rotated(c->stream, ab, B, count, aa, partials), "rotated adam launch")) return BR_ERR_HIP;
       }
-      // rotate back and apply: W <- decay W - lr Q_L X Q_R^T
+      // rotate back and apply: W <- decay W - lr Q_L X Q_R^T   (X sits in the G~ buffer)
       std::memset(&gb, 0, sizeof(gb));
-      if (g.rot_l && g.rot_r) {
+      if (bilateral) {
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
-          gb.A[i] = ms.QL; gb.B[i] = Mt[i]; gb.C[i] = scratch_buf(c, nbuf, mn, i, 0);
+          gb.A[i] = ms.QL; gb.B[i] = Gt[i]; gb.C[i] = scratch_buf(c, nbuf, mn, i, sT1);
         }
         if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 0, 0, 1.f, 0.f, B, 0}, gb)) return BR_ERR_HIP;
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
-          gb.A[i] = scratch_buf(c, nbuf, mn, i, 0); gb.B[i] = ms.QR; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
+          gb.A[i] = scratch_buf(c, nbuf, mn, i, sT1); gb.B[i] = ms.QR; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
         }
         if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 1, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
       } else if (g.rot_l) {
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
-          gb.A[i] = ms.QL; gb.B[i] = Mt[i]; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
+          gb.A[i] = ms.QL; gb.B[i] = Gt[i]; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
         }
         if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 0, 0, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
       } else {
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
-          gb.A[i] = Mt[i]; gb.B[i] = ms.QR; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
+          gb.A[i] = Gt[i]; gb.B[i] = ms.QR; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
         }
         if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 1, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
       }
     }
   }
+  c->mrot_valid = true;
   c->t = t;
   c->stats_fresh = false;
   return BR_OK;

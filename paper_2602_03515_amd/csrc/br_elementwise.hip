@@ -61,7 +61,8 @@ __global__ __launch_bounds__(256) void br_ema_first_moment(BrPtrBatch p, int64_t
   }
 }
 
-__device__ __forceinline__ float adam_x(float m, float s, const BrAdamArgs& a) {
+template <class Args>
+__device__ __forceinline__ float adam_x(float m, float s, const Args& a) {
   float num = m * a.c1;
   float den = s * a.c2;
   return a.eps_outside ? num / (sqrtf(den) + a.eps) : num / sqrtf(den + a.eps);
@@ -74,27 +75,36 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // partials layout: [batch][2][gridDim.x]
-__global__ __launch_bounds__(256) void br_adam_rotated(BrPtrBatch p, int64_t count, BrAdamArgs a, float* partials) {
+__global__ __launch_bounds__(256) void br_adam_rotated(BrAdamBatch p, int64_t count, BrAdamArgs a, float* partials) {
   __shared__ float red[2][4];
   const int b = blockIdx.y;
-  const float* __restrict__ Gt = reinterpret_cast<const float*>(p.in0[b]);
-  float* __restrict__ S = reinterpret_cast<float*>(p.out0[b]);
-  float* __restrict__ X = reinterpret_cast<float*>(p.out1[b]);
-  const float w = 1.0f - a.beta2;
+  float* __restrict__ GX = p.GX[b];
+  float* __restrict__ S = p.S[b];
+  float* __restrict__ Mr = p.Mrot[b];
+  const float w2 = 1.0f - a.beta2;
+  const float w1 = 1.0f - a.beta1;
+  const bool upd = a.update_mrot != 0;
   const int64_t n4 = count >> 2;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   float sg = 0.f, sx = 0.f;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-    float4 g = reinterpret_cast<const float4*>(Gt)[i];
+    float4 g = reinterpret_cast<const float4*>(GX)[i];
     float4 s = reinterpret_cast<float4*>(S)[i];
-    float4 m = reinterpret_cast<float4*>(X)[i];
-    s.x = a.beta2 * s.x + w * (g.x * g.x);
-    s.y = a.beta2 * s.y + w * (g.y * g.y);
-    s.z = a.beta2 * s.z + w * (g.z * g.z);
-    s.w = a.beta2 * s.w + w * (g.w * g.w);
+    float4 m = reinterpret_cast<float4*>(Mr)[i];
+    if (upd) {
+      m.x = a.beta1 * m.x + w1 * g.x;
+      m.y = a.beta1 * m.y + w1 * g.y;
+      m.z = a.beta1 * m.z + w1 * g.z;
+      m.w = a.beta1 * m.w + w1 * g.w;
+      reinterpret_cast<float4*>(Mr)[i] = m;
+    }
+    s.x = a.beta2 * s.x + w2 * (g.x * g.x);
+    s.y = a.beta2 * s.y + w2 * (g.y * g.y);
+    s.z = a.beta2 * s.z + w2 * (g.z * g.z);
+    s.w = a.beta2 * s.w + w2 * (g.w * g.w);
     float4 x = make_float4(adam_x(m.x, s.x, a), adam_x(m.y, s.y, a), adam_x(m.z, s.z, a), adam_x(m.w, s.w, a));
     reinterpret_cast<float4*>(S)[i] = s;
-    reinterpret_cast<float4*>(X)[i] = x;
+    reinterpret_cast<float4*>(GX)[i] = x;
     if (a.compute_norms) {
       sg += g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
       sx += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
@@ -102,11 +112,16 @@ __global__ __launch_bounds__(256) void br_adam_rotated(BrPtrBatch p, int64_t cou
   }
   if (blockIdx.x == 0) {
     for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
-      float g = Gt[i];
-      float s = a.beta2 * S[i] + w * (g * g);
-      float x = adam_x(X[i], s, a);
+      float g = GX[i];
+      float m = Mr[i];
+      if (upd) {
+        m = a.beta1 * m + w1 * g;
+        Mr[i] = m;
+      }
+      float s = a.beta2 * S[i] + w2 * (g * g);
+      float x = adam_x(m, s, a);
       S[i] = s;
-      X[i] = x;
+      GX[i] = x;
       if (a.compute_norms) {
         sg += g * g;
         sx += x * x;
@@ -130,11 +145,7 @@ __global__ __launch_bounds__(256) void br_adam_rotated(BrPtrBatch p, int64_t cou
   }
 }
 
-struct NormOut {
-  float* norms[BR_MAXB];
-};
-
-__global__ __launch_bounds__(64) void br_norm_finalize(const float* partials, int nblocks, NormOut out) {
+__global__ __launch_bounds__(64) void br_norm_finalize(const float* partials, int nblocks, BrAdamBatch out) {
   const int b = blockIdx.x;
   const float* src = partials + (size_t)b * 2 * nblocks;
   float s0 = 0.f, s1 = 0.f;
@@ -162,13 +173,11 @@ __global__ __launch_bounds__(256) void br_adam_plain(BrPtrBatch p, ShadowPtrs sh
   float* __restrict__ W = reinterpret_cast<float*>(p.out1[b]);
   uint16_t* __restrict__ shadow = sh.p[b];
   const float w = 1.0f - a.beta2;
-  BrAdamArgs aa;
-  aa.beta2 = a.beta2; aa.eps = a.eps; aa.c1 = a.c1; aa.c2 = a.c2; aa.eps_outside = a.eps_outside; aa.compute_norms = 0;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
     float g = load_grad1(G, i, a.grad_bf16);
     float s = a.beta2 * S[i] + w * (g * g);
-    float x = adam_x(M[i], s, aa);
+    float x = adam_x(M[i], s, a);
     float wv = a.decay * W[i] - a.lr * x;
     S[i] = s;
     W[i] = wv;
@@ -216,8 +225,8 @@ hipError_t br_launch_ema(hipStream_t s, const BrPtrBatch& p, int batch, int64_t 
   return hipGetLastError();
 }
 
-hipError_t br_launch_adam_rotated(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, const BrAdamArgs& a,
-                                  float* norm_partials, float* const* norms) {
+hipError_t br_launch_adam_rotated(hipStream_t s, const BrAdamBatch& p, int batch, int64_t count, const BrAdamArgs& a,
+                                  float* norm_partials) {
   if (batch <= 0 || count <= 0) return hipSuccess;
   int gx = br::grid_for(count / 4 + 1, batch);
   if (gx > BR_NORM_BLOCKS) gx = BR_NORM_BLOCKS;
@@ -225,9 +234,7 @@ hipError_t br_launch_adam_rotated(hipStream_t s, const BrPtrBatch& p, int batch,
   hipLaunchKernelGGL(br::br_adam_rotated, grid, dim3(256), 0, s, p, count, a, norm_partials);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !a.compute_norms) return e;
-  br::NormOut out;
-  for (int i = 0; i < BR_MAXB; ++i) out.norms[i] = (i < batch) ? norms[i] : nullptr;
-  hipLaunchKernelGGL(br::br_norm_finalize, dim3(batch), dim3(64), 0, s, norm_partials, gx, out);
+  hipLaunchKernelGGL(br::br_norm_finalize, dim3(batch), dim3(64), 0, s, norm_partials, gx, p);
   return hipGetLastError();
 }
 

@@ -46,16 +46,22 @@ hipError_t br_launch_ema(hipStream_t s, const BrPtrBatch& p, int batch, int64_t 
                          float beta1);
 
 struct BrAdamArgs {
-  float beta2, eps;
-  float c1, c2;  // bias-correction multipliers for the first/second moment (1 when disabled)
+  float beta1, beta2, eps;
+  float c1, c2;     // bias-correction multipliers for the first/second moment (1 when disabled)
   int eps_outside;
   int compute_norms;
+  int update_mrot;  // 1: M~ <- beta1 M~ + (1-beta1) G~ before it is used (cached rotated moment)
 };
-// in0 = G~, out0 = S (in place), out1 = M~ on entry, X on exit.  norm_partials: per-matrix
-// [2][BR_NORM_BLOCKS] partial sums, reduced by br_launch_norm_finalize into norms[b][2].
+struct BrAdamBatch {
+  float* GX[BR_MAXB];     // G~ on entry, X = M~ / sqrt(S~ + eps) on exit
+  float* S[BR_MAXB];      // second moment in the rotated basis, updated in place
+  float* Mrot[BR_MAXB];   // rotated first moment; rewritten when update_mrot
+  float* norms[BR_MAXB];  // per matrix [||G~||^2, ||X||^2] when compute_norms
+};
+// norm_partials: [batch][2][BR_NORM_BLOCKS] per-workgroup sums, reduced by a second kernel.
 #define BR_NORM_BLOCKS 256
-hipError_t br_launch_adam_rotated(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count,
-                                  const BrAdamArgs& a, float* norm_partials, float* const* norms_host_ptrs);
+hipError_t br_launch_adam_rotated(hipStream_t s, const BrAdamBatch& p, int batch, int64_t count,
+                                  const BrAdamArgs& a, float* norm_partials);
 
 // Plain Adam for unrotated tensors, fully fused: in0 = G (f32/bf16), in1 = M (already updated),
 // out0 = S, out1 = W master (f32); shadow = optional bf16 parameter image.

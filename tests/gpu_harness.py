@@ -24,6 +24,7 @@ def oracle_hyper(**kw):
                   eps_outside_sqrt=bool(kw.pop("eps_outside_sqrt", 0)))
     kw.pop("compute_norms", None)
     kw.pop("math", None)
+    kw.pop("cache_rotated_moment", None)
     assert not kw, kw
     return hp.rounded_to_f32()
 

@@ -40,14 +40,15 @@ def test_workspace_state_bytes_follow_memory_table(B):
             if l.strip() and not l.startswith("#")]
     for source, geometry, attn, mlp in rows:
         hp = B.make_hparams(geometry=B.BR_BILATERAL if geometry == "bilateral" else B.BR_UNILATERAL,
-                            source=B.BR_SRC_SECOND if source == "second" else B.BR_SRC_FIRST)
+                            source=B.BR_SRC_SECOND if source == "second" else B.BR_SRC_FIRST,
+                            cache_rotated_moment=0)
         for shape, printed in (((4096, 4096), float(attn)), ((4096, 14336), float(mlp))):
             state, scratch = B.br_workspace_bytes(B.make_descs([shape]), hp)
             extra = state - 2 * shape[0] * shape[1] * 4 - 256
             assert abs(extra / 2 ** 30 - printed) <= 0.0051, (source, geometry, shape, extra / 2 ** 30)
             assert scratch > 0
     # transposed MLP shape under unilateral rotation keeps the 4096-side factor
-    uni = B.make_hparams(geometry=B.BR_UNILATERAL)
+    uni = B.make_hparams(geometry=B.BR_UNILATERAL, cache_rotated_moment=0)
     a, _ = B.br_workspace_bytes(B.make_descs([(4096, 14336)]), uni)
     b, _ = B.br_workspace_bytes(B.make_descs([(14336, 4096)]), uni)
     assert a == b
@@ -55,14 +56,20 @@ def test_workspace_state_bytes_follow_memory_table(B):
     s32, _ = B.br_workspace_bytes(B.make_descs([(512, 256, B.BR_F32, B.BR_F32, 0)]), uni)
     s16, _ = B.br_workspace_bytes(B.make_descs([(512, 256, B.BR_BF16, B.BR_BF16, 0)]), uni)
     assert s32 == 2 * 512 * 256 * 4 + 256 and s16 == 3 * 512 * 256 * 4 + 256
+    # the optional cache of the rotated first moment costs one more m x n buffer per rotated matrix
+    on, _ = B.br_workspace_bytes(B.make_descs([(512, 256)]), B.make_hparams(cache_rotated_moment=1))
+    off, _ = B.br_workspace_bytes(B.make_descs([(512, 256)]), B.make_hparams(cache_rotated_moment=0))
+    assert on - off == 512 * 256 * 4
 
 
 def test_stage_state_bytes_3b_class():
     from paper_2602_03515_amd import binding as B, synth
-    state, scratch = B.br_workspace_bytes(B.make_descs(synth.STAGE_3B), B.make_hparams())
+    state, scratch = B.br_workspace_bytes(B.make_descs(synth.STAGE_3B), B.make_hparams(cache_rotated_moment=0))
     closed_form = sum(4 * (2 * m * n + 2 * m * m + 2 * n * n) for m, n in synth.STAGE_3B)
     assert abs(closed_form - 18.86e9) < 0.01e9
     assert 0 <= state - closed_form <= 56 * 256 * 8
+    cached, _ = B.br_workspace_bytes(B.make_descs(synth.STAGE_3B), B.make_hparams(cache_rotated_moment=1))
+    assert cached - state == 4 * sum(m * n for m, n in synth.STAGE_3B)
 
 
 @pytest.mark.parametrize("bad, status", [
@@ -75,6 +82,7 @@ def test_stage_state_bytes_3b_class():
     (dict(shapes=[(4, 4)], beta1=1.0), "BR_ERR_INVALID_ARG"),
     (dict(shapes=[(4, 4)], eps=-1.0), "BR_ERR_INVALID_ARG"),
     (dict(shapes=[(4, 4)], math=1), "BR_ERR_UNSUPPORTED"),
+    (dict(shapes=[(4, 4)], cache_rotated_moment=2), "BR_ERR_INVALID_ARG"),
     (dict(shapes=[]), "BR_ERR_INVALID_ARG"),
 ])
 def test_invalid_arguments_are_rejected_on_the_host(B, bad, status):

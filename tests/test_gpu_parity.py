@@ -147,12 +147,51 @@ def test_fixed_injected_basis_matches_rotated_adam(harness):
     A32, B32 = A.astype(np.float32), Bm.astype(np.float32)
     sb.opt.state(0, sb.B.BR_STATE_QL).copy_(torch.from_numpy(A32))
     sb.opt.state(0, sb.B.BR_STATE_QR).copy_(torch.from_numpy(B32))
+    sb.B.br_notify_state_written(sb.opt.ctx)
     sb.states[0].QL, sb.states[0].QR = A32.astype(np.float64), B32.astype(np.float64)
     w0 = sb.W_ref[0].copy()
     for g in grads:
         sb.step([g])
     assert rel_err(sb.gpu_weights(0) - w0, sb.W_ref[0] - w0) <= TOL
     sb.compare_state(TOL)
+
+
+def test_injected_basis_midway_rebuilds_cached_rotated_moment(harness):
+    """Overwrite the bases after a few steps (M is non-zero by then): with the cache on, the
+    rotated first moment must be rebuilt from M, not advanced from its stale value."""
+    m, n = 72, 136
+    rng = np.random.default_rng(6)
+    A32 = synth.haar_orthogonal(rng, m).astype(np.float32)
+    B32 = synth.haar_orthogonal(rng, n).astype(np.float32)
+    W0, grads = synth.spiked_gradients(seed=10, m=m, n=n, steps=6, noise_std=0.1)
+    sb = harness.SideBySide([W0], freq=0, lr=1e-2, cache_rotated_moment=1)
+    w0 = sb.W_ref[0].copy()
+    for t, g in enumerate(grads, 1):
+        if t == 4:
+            sb.opt.state(0, sb.B.BR_STATE_QL).copy_(torch.from_numpy(A32))
+            sb.opt.state(0, sb.B.BR_STATE_QR).copy_(torch.from_numpy(B32))
+            sb.B.br_notify_state_written(sb.opt.ctx)
+            sb.states[0].QL, sb.states[0].QR = A32.astype(np.float64), B32.astype(np.float64)
+        sb.step([g])
+    assert rel_err(sb.gpu_weights(0) - w0, sb.W_ref[0] - w0) <= TOL + _storage_floor(sb.W_ref[0], sb.W_ref[0] - w0)
+    sb.compare_state(TOL)
+    mrot = harness.to_np(sb.opt.state(0, sb.B.BR_STATE_MROT))
+    assert rel_err(mrot, sb.states[0].last["M_rot"]) <= TOL
+
+
+@pytest.mark.parametrize("geometry", [0, 1])
+def test_cached_and_recomputed_rotated_moment_agree(harness, geometry):
+    """M~ advanced by its own EMA between refreshes (cache on) equals M~ rotated from M every
+    step (cache off, Algorithm 1 line 9 as printed) up to FP32 rounding; both match the oracle."""
+    W0, grads = synth.spiked_gradients(seed=15, m=104, n=168, steps=9, noise_std=0.1)
+    out = []
+    for cache in (0, 1):
+        sb, _ = _run(harness, [W0], [[g] for g in grads], freq=4, lr=1e-3, geometry=geometry,
+                     cache_rotated_moment=cache)
+        assert sb.opt.has_state(0, sb.B.BR_STATE_MROT) == bool(cache)
+        out.append(sb.gpu_weights(0))
+    w0 = np.asarray(W0, dtype=np.float64)
+    assert rel_err(out[0] - w0, out[1] - w0) <= 2e-5 + _storage_floor(out[1], out[1] - w0)
 
 
 def test_textbook_flags_power_iters_and_stat_beta(harness):
