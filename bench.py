@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="stage3b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) so that HBM byte counters "
+                         "collected by a profiler can be scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (one pipeline stage's share); --gpus must be 1", file=sys.stderr)
@@ -114,6 +117,14 @@ def main():
     params, ring = make_inputs(shapes, TAU + 1, seed=2, device=dev)
     opt = BasisRotationAdam(params, freq=FREQ, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8)
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     t = 0
     for _ in range(args.warmup):

@@ -19,6 +19,7 @@ constexpr int kStepChunk = 16;     // matrices per batched step launch ([G|M] do
 constexpr int kRefreshChunk = 32;  // factor matrices per batched refresh launch
 constexpr int64_t kMaxDim = 1 << 24;
 constexpr size_t kNormPartialBytes = (size_t)BR_MAXB * 2 * BR_NORM_BLOCKS * sizeof(float);
+constexpr size_t kSplitKBytes = (size_t)64 << 20;  // partial products of the QR's split-K contractions
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -187,7 +188,7 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
   }
   for (auto& kv : lay->refresh) {
     size_t chunk = std::min<size_t>(kv.second.size(), kRefreshChunk);
-    scratch = std::max(scratch, chunk * refresh_scratch(kv.first, hp).total);
+    scratch = std::max(scratch, chunk * refresh_scratch(kv.first, hp).total + kSplitKBytes);
   }
   lay->state_bytes = state;
   lay->scratch_bytes = scratch + kNormPartialBytes;
@@ -225,11 +226,19 @@ struct Timed {  // brackets one launch (or a region) with events while profiling
   }
 };
 
-bool gemm(br_ctx* c, const BrGemmArgs& a, const BrGemmBatch& b, bool profile = true) {
-  const char* name = nullptr;
-  double flops = 2.0 * a.M * a.N * (double)a.K * a.batch;
-  if (a.mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (a.M + 127) / 128));
-  if (profile && c->prof_on) {
+// step = true: one of the optimizer step's contractions (timed individually while profiling).
+// step = false: a contraction inside the QR (split-K capable variant, timed as part of the region).
+bool gemm(br_ctx* c, BrGemmArgs a, const BrGemmBatch& b, bool step = true, float* partial = nullptr) {
+  if (!step) {
+    a.qr_role = 1;
+    a.partial = partial;
+    a.partial_floats = partial ? kSplitKBytes / sizeof(float) : 0;
+    return hip_ok(c, br_launch_gemm(c->stream, a, b, nullptr), "gemm launch");
+  }
+  if (c->prof_on) {
+    const char* name = nullptr;
+    double flops = 2.0 * a.M * a.N * (double)a.K * a.batch;
+    if (a.mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (a.M + 127) / 128));
     (void)br_launch_gemm(nullptr, BrGemmArgs{0, 0, 0, 0, 0, 0, a.transA, a.transB, 0, 0, 0, 0}, b, &name);
     Timed tm(c, name, flops, 0.0);
     return hip_ok(c, br_launch_gemm(c->stream, a, b, nullptr), "gemm launch");
@@ -445,7 +454,7 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 // of BR_QR_NBO columns; the outer block's reflectors are then merged into one compact-WY factor
 // and applied to the trailing matrix with K = BR_QR_NBO contractions.
 static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs, char* base,
-                     size_t stride) {
+                     size_t stride, float* partial) {
   const int NB = BR_QR_NB, NBO = BR_QR_NBO;
   const int nblocks = (k + NBO - 1) / NBO;
   auto V = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.V); };
@@ -479,13 +488,13 @@ static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, 
       std::memset(&gb, 0, sizeof(gb));
       // Yt = Vp Tp^T  (prow x NB), Vp = this panel's slice of V
       for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = Tp(i, pnl); gb.C[i] = Y(i); }
-      if (!gemm(c, BrGemmArgs{prow, NB, NB, NBO, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb, false)) return false;
+      if (!gemm(c, BrGemmArgs{prow, NB, NB, NBO, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
       // W = Vp^T C, C = the outer block's remaining columns in the panel's rows
       for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
-      if (!gemm(c, BrGemmArgs{NB, nin, prow, NBO, k, NBO, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+      if (!gemm(c, BrGemmArgs{NB, nin, prow, NBO, k, NBO, 1, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
       // C <- C - Yt W
       for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)j0 * k + j0 + nb; }
-      if (!gemm(c, BrGemmArgs{prow, nin, NB, NB, NBO, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
+      if (!gemm(c, BrGemmArgs{prow, nin, NB, NB, NBO, k, 0, 0, -1.f, 1.f, B, 0}, gb, false, partial)) return false;
     }
     // Merge the panels' factors: G = V^T V, then T_blk from the inner factors and G.
     const float* gp[BR_MAXB];
@@ -494,7 +503,7 @@ static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, 
     std::memset(&gb, 0, sizeof(gb));
     if (npanels > 1) {
       for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = V(i); gb.C[i] = G(i); }
-      if (!gemm(c, BrGemmArgs{NBO, NBO, rows, NBO, NBO, NBO, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+      if (!gemm(c, BrGemmArgs{NBO, NBO, rows, NBO, NBO, NBO, 1, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
     }
     for (int i = 0; i < B; ++i) { gp[i] = G(i); tpp[i] = Tp(i, 0); tb[i] = T(i, blk); }
     if (!hip_ok(c, br_launch_qr_build_t(c->stream, gp, tpp, tb, B, npanels), "qr factor merge launch")) return false;
@@ -502,11 +511,11 @@ static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, 
     if (nt <= 0) continue;
     // Yt = V T^T ; W = V^T C ; C <- C - Yt W   on the trailing columns
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
-    if (!gemm(c, BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 1, 1.f, 0.f, B, 0}, gb, false)) return false;
+    if (!gemm(c, BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 1, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = P[i] + (size_t)J0 * k + J0 + nbo; gb.C[i] = W(i); }
-    if (!gemm(c, BrGemmArgs{NBO, nt, rows, NBO, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    if (!gemm(c, BrGemmArgs{NBO, nt, rows, NBO, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
     for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)J0 * k + J0 + nbo; }
-    if (!gemm(c, BrGemmArgs{rows, nt, NBO, NBO, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
+    if (!gemm(c, BrGemmArgs{rows, nt, NBO, NBO, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb, false, partial)) return false;
   }
   // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before block blk is
   // applied, Q differs from the identity only in Q[J1:, J1:] with J1 the next block's offset,
@@ -525,11 +534,11 @@ static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, 
     std::memset(&gb, 0, sizeof(gb));
     // Y = V T ; W = V^T Qsub ; Qsub <- Qsub - Y W,  Qsub = Q[J0:, J0:]
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
-    if (!gemm(c, BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    if (!gemm(c, BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Q[i] + (size_t)J0 * k + J0; gb.C[i] = W(i); }
-    if (!gemm(c, BrGemmArgs{NBO, rows, rows, NBO, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb, false)) return false;
+    if (!gemm(c, BrGemmArgs{NBO, rows, rows, NBO, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
     for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Q[i] + (size_t)J0 * k + J0; }
-    if (!gemm(c, BrGemmArgs{rows, rows, NBO, NBO, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb, false)) return false;
+    if (!gemm(c, BrGemmArgs{rows, rows, NBO, NBO, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb, false, partial)) return false;
   }
   const float* dg[BR_MAXB];
   for (int i = 0; i < B; ++i) dg[i] = D(i);
@@ -585,7 +594,7 @@ br_status br_refresh_basis(br_ctx* ctx) {
       }
       {
         Timed tm(c, "qr_householder(region)", (8.0 / 3.0) * (double)k * k * k * B, 0.0);
-        if (!qr_batch(c, B, k, src, Q, rs, base, rs.total)) return BR_ERR_HIP;
+        if (!qr_batch(c, B, k, src, Q, rs, base, rs.total, reinterpret_cast<float*>(base + (size_t)B * rs.total))) return BR_ERR_HIP;
       }
     }
   }

@@ -14,6 +14,8 @@
 // tiles.
 #include "br_internal.h"
 
+#include <algorithm>
+
 namespace {
 
 constexpr int BM = 128;
@@ -31,6 +33,9 @@ struct GemmKernArgs {
   int tiles_m, tiles_n;
   int total_tiles;
   int mirror;
+  int splitk;        // SPLIT kernels only: number of K ranges per output tile
+  int kt_per_split;  // K tiles (of BK) per range
+  float* partial;    // SPLIT kernels with splitk > 1: [batch][splitk][M][N] partial products
 };
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -105,7 +110,16 @@ struct TileLoader {
   }
 };
 
-template <bool TA, bool TB, bool VEC>
+}  // namespace
+
+namespace br {
+
+// SPLIT = false: the contraction kernel of the optimizer step.  SPLIT = true: the variant used
+// inside the QR factorisation, whose skinny products (32 or 128 output rows, K = thousands)
+// would otherwise run on a handful of workgroups: blockIdx additionally selects one of
+// `splitk` K ranges and the partial product goes to `partial`, summed in a fixed order by
+// br_splitk_reduce (deterministic, no atomics).
+template <bool TA, bool TB, bool VEC, bool SPLIT>
 __global__ __launch_bounds__(256) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBatch batch) {
   __shared__ __attribute__((aligned(16))) float As[2][BK][LDS_LD];
   __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDS_LD];
@@ -117,9 +131,13 @@ __global__ __launch_bounds__(256) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBa
   const int per = nblk / NUM_XCD;
   if (bid < per * NUM_XCD) bid = (bid % NUM_XCD) * per + bid / NUM_XCD;
 
-  int mat, tm, tn;
+  int mat, tm, tn, split = 0;
   {
     int per_mat = g.total_tiles;
+    if (SPLIT) {
+      split = bid % g.splitk;
+      bid /= g.splitk;
+    }
     mat = bid / per_mat;
     int t = bid - mat * per_mat;
     if (g.mirror) {
@@ -156,17 +174,22 @@ __global__ __launch_bounds__(256) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBa
   TileLoader<TA, VEC> la;    // op(A) = A^T  <=> A stored K x M  <=> k-major
   TileLoader<!TB, VEC> lb;   // op(B) = B    <=> B stored K x N  <=> k-major
 
-  const int nkt = (g.K + BK - 1) / BK;
-  la.fetch(A, g.lda, m0, 0, g.M, g.K, tid);
-  lb.fetch(B, g.ldb, n0, 0, g.N, g.K, tid);
+  int kt0 = 0;
+  int nkt = (g.K + BK - 1) / BK;
+  if (SPLIT) {
+    kt0 = split * g.kt_per_split;
+    nkt = min(nkt, kt0 + g.kt_per_split);
+  }
+  la.fetch(A, g.lda, m0, kt0 * BK, g.M, g.K, tid);
+  lb.fetch(B, g.ldb, n0, kt0 * BK, g.N, g.K, tid);
   la.stash(As[0], tid);
   lb.stash(Bs[0], tid);
   __syncthreads();
 
   const int lk = lane >> 5;  // which of the two k of an MFMA this lane feeds
   const int li = lane & 31;  // row of A / column of B inside the 32-wide MFMA tile
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int cur = kt & 1;
+  for (int kt = kt0; kt < nkt; ++kt) {
+    const int cur = (kt - kt0) & 1;
     if (kt + 1 < nkt) {
       la.fetch(A, g.lda, m0, (kt + 1) * BK, g.M, g.K, tid);
       lb.fetch(B, g.ldb, n0, (kt + 1) * BK, g.N, g.K, tid);
@@ -191,6 +214,21 @@ __global__ __launch_bounds__(256) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBa
 
   // Epilogue.  Accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4 and
   // column l%32 of its 32 x 32 tile.
+  if (SPLIT && g.splitk > 1) {
+    float* __restrict__ P = g.partial + ((size_t)mat * g.splitk + split) * (size_t)g.M * g.N;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int col = n0 + wn * 64 + ni * 32 + li;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+          if (row < g.M && col < g.N) P[(size_t)row * g.N + col] = g.alpha * acc[mi][ni][v];
+        }
+      }
+    return;
+  }
   const bool use_beta = (g.beta != 0.0f);
   const bool off_diag = g.mirror && (tm != tn);
 #pragma unroll
@@ -214,13 +252,45 @@ __global__ __launch_bounds__(256) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBa
   }
 }
 
-template <bool TA, bool TB>
+struct ReduceArgs {
+  float* C[BR_MAXB];
+};
+
+// C_b = beta C_b + sum_s partial[b][s]   (fixed summation order)
+__global__ __launch_bounds__(256) void br_splitk_reduce(ReduceArgs r, const float* __restrict__ partial, int M, int N,
+                                                        int ldc, int splitk, float beta) {
+  float* __restrict__ C = r.C[blockIdx.y];
+  const size_t mn = (size_t)M * N;
+  const float* __restrict__ P = partial + (size_t)blockIdx.y * splitk * mn;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < mn; i += stride) {
+    float s = 0.f;
+    for (int k = 0; k < splitk; ++k) s += P[(size_t)k * mn + i];
+    const size_t row = i / N, col = i - row * N;
+    float* dst = C + row * (size_t)ldc + col;
+    *dst = (beta != 0.0f) ? beta * *dst + s : s;
+  }
+}
+
+}  // namespace br
+
+namespace {
+
+template <bool TA, bool TB, bool SPLIT>
 hipError_t launch_variant(hipStream_t s, const GemmKernArgs& k, const BrGemmBatch& b, int grid, bool vec) {
   if (vec)
-    hipLaunchKernelGGL((br_gemm_f32_mfma<TA, TB, true>), dim3(grid), dim3(256), 0, s, k, b);
+    hipLaunchKernelGGL((br::br_gemm_f32_mfma<TA, TB, true, SPLIT>), dim3(grid), dim3(256), 0, s, k, b);
   else
-    hipLaunchKernelGGL((br_gemm_f32_mfma<TA, TB, false>), dim3(grid), dim3(256), 0, s, k, b);
+    hipLaunchKernelGGL((br::br_gemm_f32_mfma<TA, TB, false, SPLIT>), dim3(grid), dim3(256), 0, s, k, b);
   return hipGetLastError();
+}
+
+template <bool SPLIT>
+hipError_t launch_any(hipStream_t s, const BrGemmArgs& a, const GemmKernArgs& k, const BrGemmBatch& b, int grid, bool vec) {
+  if (!a.transA && !a.transB) return launch_variant<false, false, SPLIT>(s, k, b, grid, vec);
+  if (!a.transA && a.transB) return launch_variant<false, true, SPLIT>(s, k, b, grid, vec);
+  if (a.transA && !a.transB) return launch_variant<true, false, SPLIT>(s, k, b, grid, vec);
+  return launch_variant<true, true, SPLIT>(s, k, b, grid, vec);
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -228,9 +298,10 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 }  // namespace
 
 hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch& b, const char** kernel_name) {
-  static const char* names[4] = {"br_gemm_f32_mfma<nn>", "br_gemm_f32_mfma<nt>", "br_gemm_f32_mfma<tn>",
-                                 "br_gemm_f32_mfma<tt>"};
-  if (kernel_name) *kernel_name = names[(a.transA ? 2 : 0) + (a.transB ? 1 : 0)];
+  static const char* names[8] = {"br_gemm_f32_mfma<nn>", "br_gemm_f32_mfma<nt>", "br_gemm_f32_mfma<tn>",
+                                 "br_gemm_f32_mfma<tt>", "br_gemm_f32_mfma<nn,split>", "br_gemm_f32_mfma<nt,split>",
+                                 "br_gemm_f32_mfma<tn,split>", "br_gemm_f32_mfma<tt,split>"};
+  if (kernel_name) *kernel_name = names[(a.qr_role ? 4 : 0) + (a.transA ? 2 : 0) + (a.transB ? 1 : 0)];
   if (a.batch <= 0 || a.M <= 0 || a.N <= 0) return hipSuccess;
   if (a.batch > BR_MAXB || a.K < 0) return hipErrorInvalidValue;
   if (a.mirror && (a.M != a.N)) return hipErrorInvalidValue;
@@ -242,12 +313,34 @@ hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch&
   k.tiles_n = (a.N + BN - 1) / BN;
   k.mirror = a.mirror ? 1 : 0;
   k.total_tiles = k.mirror ? k.tiles_m * (k.tiles_m + 1) / 2 : k.tiles_m * k.tiles_n;
+  k.splitk = 1;
+  k.kt_per_split = (a.K + BK - 1) / BK;
+  k.partial = nullptr;
   long long grid = (long long)k.total_tiles * a.batch;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   bool vec = (a.lda % 4 == 0) && (a.ldb % 4 == 0);
   for (int i = 0; i < a.batch && vec; ++i) vec = aligned16(b.A[i]) && aligned16(b.B[i]);
-  if (!a.transA && !a.transB) return launch_variant<false, false>(s, k, b, (int)grid, vec);
-  if (!a.transA && a.transB) return launch_variant<false, true>(s, k, b, (int)grid, vec);
-  if (a.transA && !a.transB) return launch_variant<true, false>(s, k, b, (int)grid, vec);
-  return launch_variant<true, true>(s, k, b, (int)grid, vec);
+  if (!a.qr_role) return launch_any<false>(s, a, k, b, (int)grid, vec);
+  // Split K when the launch would leave most of the 256 compute units idle.
+  const int nkt = (a.K + BK - 1) / BK;
+  if (a.partial && !a.mirror && grid < 384 && nkt >= 32) {
+    long long want = (768 + grid - 1) / grid;
+    long long by_k = nkt / 8;  // at least 8 K tiles (128 columns of K) per range
+    long long by_mem = (long long)(a.partial_floats / ((size_t)a.M * a.N * a.batch));
+    long long sk = std::min(std::min(want, by_k), std::min<long long>(by_mem, 64));
+    if (sk > 1) {
+      k.kt_per_split = (int)((nkt + sk - 1) / sk);
+      k.splitk = (nkt + k.kt_per_split - 1) / k.kt_per_split;
+      k.partial = a.partial;
+    }
+  }
+  hipError_t e = launch_any<true>(s, a, k, b, (int)(grid * k.splitk), vec);
+  if (e != hipSuccess || k.splitk == 1) return e;
+  br::ReduceArgs r;
+  for (int i = 0; i < BR_MAXB; ++i) r.C[i] = (i < a.batch) ? b.C[i] : nullptr;
+  long long blocks = ((long long)a.M * a.N + 255) / 256;
+  if (blocks > 64) blocks = 64;
+  hipLaunchKernelGGL(br::br_splitk_reduce, dim3((int)blocks, a.batch), dim3(256), 0, s, r, k.partial, a.M, a.N, a.ldc,
+                     k.splitk, a.beta);
+  return hipGetLastError();
 }

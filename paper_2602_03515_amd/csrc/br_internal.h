@@ -29,6 +29,9 @@ struct BrGemmArgs {
   float alpha, beta;
   int batch;
   int mirror;
+  int qr_role = 0;             // 1: launch the split-K capable variant used inside the QR
+  float* partial = nullptr;    // qr_role: scratch for split-K partial products (optional)
+  size_t partial_floats = 0;   // its capacity in floats
 };
 
 hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch& b, const char** kernel_name);

@@ -6,7 +6,7 @@
 // This file holds the panel kernel (one 1024-thread workgroup per matrix of the batch);
 // the trailing-matrix and Q-forming updates are GEMMs issued by the host logic.
 //
-// Panel kernel, one pass per column.  A panel row is 32 floats = one 128-byte line; it
+// Panel kernel (br_qr_panel), one pass per column.  A panel row is 32 floats = one 128-byte line; it
 // is owned by 8 adjacent lanes (4 columns each), so every wave64 access touches 8 whole
 // lines.  Pass j applies reflector H_j to the rest of the panel and, in the same sweep
 // over the rows, accumulates (a) the dot products of the NEXT column with all later
@@ -19,49 +19,62 @@ namespace br {
 constexpr int QR_THREADS = 1024;
 constexpr int QR_ROWS_PER_SWEEP = QR_THREADS / 8;  // 128
 constexpr int QR_WAVES = QR_THREADS / 64;          // 16
+constexpr int QR_RESIDENT_SWEEPS = 18;             // panels of up to 2304 rows live in registers
+constexpr int QR_STREAM_SWEEPS = 8;                // taller panels stream through, 8 loads in flight
 
-__device__ __forceinline__ void panel_load(const float* __restrict__ row, int c0, int nb, bool vec, float a[4]) {
+// One lane's four columns of a panel row travel as a float4 VALUE (never through a pointer), so
+// that groups of rows stay in registers.
+__device__ __forceinline__ float4 panel_load(const float* __restrict__ row, int c0, int nb, bool vec) {
+  float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
   if (vec && c0 + 3 < nb) {
-    float4 t = *reinterpret_cast<const float4*>(row + c0);
-    a[0] = t.x; a[1] = t.y; a[2] = t.z; a[3] = t.w;
+    t = *reinterpret_cast<const float4*>(row + c0);
   } else {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) a[q] = (c0 + q < nb) ? row[c0 + q] : 0.f;
+    if (c0 < nb) t.x = row[c0];
+    if (c0 + 1 < nb) t.y = row[c0 + 1];
+    if (c0 + 2 < nb) t.z = row[c0 + 2];
+    if (c0 + 3 < nb) t.w = row[c0 + 3];
+  }
+  return t;
+}
+
+__device__ __forceinline__ void panel_store(float* __restrict__ row, int c0, int nb, bool vec, float4 a) {
+  if (vec && c0 + 3 < nb) {
+    *reinterpret_cast<float4*>(row + c0) = a;
+  } else {
+    if (c0 < nb) row[c0] = a.x;
+    if (c0 + 1 < nb) row[c0 + 1] = a.y;
+    if (c0 + 2 < nb) row[c0 + 2] = a.z;
+    if (c0 + 3 < nb) row[c0 + 3] = a.w;
   }
 }
 
-__device__ __forceinline__ void panel_store(float* __restrict__ row, int c0, int nb, bool vec, const float a[4]) {
-  if (vec && c0 + 3 < nb) {
-    *reinterpret_cast<float4*>(row + c0) = make_float4(a[0], a[1], a[2], a[3]);
-  } else {
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      if (c0 + q < nb) row[c0 + q] = a[q];
-  }
-}
-
-__device__ __forceinline__ float pick4(const float a[4], int q) {
-  float r = a[0];
-  r = (q == 1) ? a[1] : r;
-  r = (q == 2) ? a[2] : r;
-  r = (q == 3) ? a[3] : r;
+__device__ __forceinline__ float pick4(float4 a, int q) {
+  float r = a.x;
+  r = (q == 1) ? a.y : r;
+  r = (q == 2) ? a.z : r;
+  r = (q == 3) ? a.w : r;
   return r;
 }
 
 // Sum acc[] over all threads that own the same columns; result for column c in comb[c].
-__device__ __forceinline__ void panel_reduce(float acc[4], float (*red)[32], float* comb, int tid) {
+__device__ __forceinline__ float group_sum(float v) {
+  v += __shfl_xor(v, 8, 64);
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+__device__ __forceinline__ void panel_reduce(float4 acc, float (*red)[32], float* comb, int tid) {
   const int lane = tid & 63, wave = tid >> 6, sub = tid & 7;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    float v = acc[q];
-    v += __shfl_xor(v, 8, 64);
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    acc[q] = v;
-  }
+  acc.x = group_sum(acc.x);
+  acc.y = group_sum(acc.y);
+  acc.z = group_sum(acc.z);
+  acc.w = group_sum(acc.w);
   if (lane < 8) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) red[wave][sub * 4 + q] = acc[q];
+    red[wave][sub * 4 + 0] = acc.x;
+    red[wave][sub * 4 + 1] = acc.y;
+    red[wave][sub * 4 + 2] = acc.z;
+    red[wave][sub * 4 + 3] = acc.w;
   }
   __syncthreads();
   if (tid < 32) {
@@ -73,13 +86,70 @@ __device__ __forceinline__ void panel_reduce(float acc[4], float (*red)[32], flo
   __syncthreads();
 }
 
+// State shared by all rows during pass j.
+struct PassParams {
+  int j, jn;          // current column, owner column of the next one
+  float scale, beta;  // v = x * scale below the diagonal; R_jj
+  float4 w;           // tau * (v^T A[:, c]) for this lane's four columns (0 for c <= j)
+};
+
+__device__ __forceinline__ float apply_col(float a, int c, int r, float v, float w, const PassParams& pp) {
+  if (c > pp.j) return a - v * w;
+  if (c == pp.j) return (r == pp.j) ? pp.beta : v;
+  return a;
+}
+
+__device__ __forceinline__ float acc_col(float acc, float a, int c, int r, float v, float xn, int j) {
+  if (c < j) return acc + a * v;
+  if (c > j && r > j) return acc + xn * a;
+  return acc;
+}
+
+// Apply reflector j to one row (columns c0..c0+3 of row r, in `a`) and accumulate this row's
+// contribution to the dot products needed by pass j + 1 and by column j of T.
+__device__ __forceinline__ void pass_row(float4& a, int r, bool active, const PassParams& pp, int c0, int group_base,
+                                         float4& acc, float* pivnext) {
+  const int j = pp.j;
+  const float aj = __shfl(pick4(a, j & 3), group_base | (j >> 2), 64);
+  const float v = (r == j) ? 1.0f : aj * pp.scale;
+  a.x = apply_col(a.x, c0 + 0, r, v, pp.w.x, pp);
+  a.y = apply_col(a.y, c0 + 1, r, v, pp.w.y, pp);
+  a.z = apply_col(a.z, c0 + 2, r, v, pp.w.z, pp);
+  a.w = apply_col(a.w, c0 + 3, r, v, pp.w.w, pp);
+  const float xn = __shfl(pick4(a, pp.jn & 3), group_base | (pp.jn >> 2), 64);
+  if (active) {
+    acc.x = acc_col(acc.x, a.x, c0 + 0, r, v, xn, j);
+    acc.y = acc_col(acc.y, a.y, c0 + 1, r, v, xn, j);
+    acc.z = acc_col(acc.z, a.z, c0 + 2, r, v, xn, j);
+    acc.w = acc_col(acc.w, a.w, c0 + 3, r, v, xn, j);
+    if (r == j + 1) *reinterpret_cast<float4*>(pivnext + c0) = a;
+  }
+}
+
+__device__ __forceinline__ float4 clean_v(float4 a, int c0, int r, int nb) {
+  float4 o;
+  o.x = (c0 + 0 >= nb || c0 + 0 > r) ? 0.f : ((c0 + 0 == r) ? 1.0f : a.x);
+  o.y = (c0 + 1 >= nb || c0 + 1 > r) ? 0.f : ((c0 + 1 == r) ? 1.0f : a.y);
+  o.z = (c0 + 2 >= nb || c0 + 2 > r) ? 0.f : ((c0 + 2 == r) ? 1.0f : a.z);
+  o.w = (c0 + 3 >= nb || c0 + 3 > r) ? 0.f : ((c0 + 3 == r) ? 1.0f : a.w);
+  return o;
+}
+
+__device__ __forceinline__ float4 fma4(float s, float4 a, float4 acc) {
+  return make_float4(acc.x + s * a.x, acc.y + s * a.y, acc.z + s * a.z, acc.w + s * a.w);
+}
+
+// U: rows are processed in groups of U sweeps (U * 128 rows) so that U independent 16-byte
+// loads are in flight per lane.  RESIDENT: the whole panel (rows <= U * 128) stays in
+// registers from the first load to the final store; the passes touch no memory at all.
+template <int U, bool RESIDENT>
 __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int rows, int nb, int lda, int vec_ok,
                                                           int ldv, int pre_rows) {
   __shared__ float red[QR_WAVES][32];
   __shared__ float comb[32];
-  __shared__ float dvec[32];
+  __shared__ __attribute__((aligned(16))) float dvec[32];
   __shared__ float zl[32];
-  __shared__ float pivrow[2][32];
+  __shared__ __attribute__((aligned(16))) float pivrow[2][32];
   __shared__ float Tl[32][33];
 
   float* __restrict__ A = p.A[blockIdx.x];
@@ -103,21 +173,46 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   }
   __syncthreads();
 
-  float acc[4];
+  float4 ra[RESIDENT ? U : 1];
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (RESIDENT) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int r = rg + QR_ROWS_PER_SWEEP * u;
+      ra[u] = zero4;
+      if (r < rows) ra[u] = panel_load(A + (size_t)r * lda, c0, nb, vec);
+    }
+  }
+
   // Pre-pass: dot products of column 0 with every column; stash row 0.
-  acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
-  for (int it = 0; it < nsweeps; ++it) {
-    const int r = rg + QR_ROWS_PER_SWEEP * it;
-    const bool active = r < rows;
-    float a[4] = {0.f, 0.f, 0.f, 0.f};
-    if (active) panel_load(A + (size_t)r * lda, c0, nb, vec, a);
-    const float x0 = __shfl(a[0], group_base, 64);
-    if (active) {
+  float4 acc = zero4;
+  if (RESIDENT) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) acc[q] += x0 * a[q];
-      if (r == 0) {
+    for (int u = 0; u < U; ++u) {
+      const int r = rg + QR_ROWS_PER_SWEEP * u;
+      const float x0 = __shfl(ra[u].x, group_base, 64);
+      if (r < rows) {
+        acc = fma4(x0, ra[u], acc);
+        if (r == 0) *reinterpret_cast<float4*>(&pivrow[0][c0]) = ra[u];
+      }
+    }
+  } else {
+    for (int it0 = 0; it0 < nsweeps; it0 += U) {
+      float4 a[U];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) pivrow[0][c0 + q] = a[q];
+      for (int u = 0; u < U; ++u) {
+        const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
+        a[u] = zero4;
+        if (r < rows) a[u] = panel_load(A + (size_t)r * lda, c0, nb, vec);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
+        const float x0 = __shfl(a[u].x, group_base, 64);
+        if (r < rows) {
+          acc = fma4(x0, a[u], acc);
+          if (r == 0) *reinterpret_cast<float4*>(&pivrow[0][c0]) = a[u];
+        }
       }
     }
   }
@@ -129,48 +224,54 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
     const int cur = j & 1;
     const float alpha = pivrow[cur][j];
     const float normsq = dvec[j];
-    float beta = 0.f, tau = 0.f, scale = 0.f;
+    float tau = 0.f;
+    PassParams pp;
+    pp.j = j;
+    pp.jn = (j + 1 < 32) ? j + 1 : 31;  // unused when j + 1 == nb
+    pp.beta = 0.f;
+    pp.scale = 0.f;
     if (normsq > 0.f) {
       const float nrm = sqrtf(normsq);
-      beta = (alpha >= 0.f) ? -nrm : nrm;
-      tau = (beta - alpha) / beta;
-      scale = 1.0f / (alpha - beta);
+      pp.beta = (alpha >= 0.f) ? -nrm : nrm;
+      tau = (pp.beta - alpha) / pp.beta;
+      pp.scale = 1.0f / (alpha - pp.beta);
     }
-    float w[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int c = c0 + q;
-      const float pr = pivrow[cur][c];
-      w[q] = (c > j && c < nb) ? tau * (pr + scale * (dvec[c] - alpha * pr)) : 0.f;
+    {
+      const float4 pr = *reinterpret_cast<const float4*>(&pivrow[cur][c0]);
+      const float4 dv = *reinterpret_cast<const float4*>(&dvec[c0]);
+      pp.w.x = (c0 + 0 > j && c0 + 0 < nb) ? tau * (pr.x + pp.scale * (dv.x - alpha * pr.x)) : 0.f;
+      pp.w.y = (c0 + 1 > j && c0 + 1 < nb) ? tau * (pr.y + pp.scale * (dv.y - alpha * pr.y)) : 0.f;
+      pp.w.z = (c0 + 2 > j && c0 + 2 < nb) ? tau * (pr.z + pp.scale * (dv.z - alpha * pr.z)) : 0.f;
+      pp.w.w = (c0 + 3 > j && c0 + 3 < nb) ? tau * (pr.w + pp.scale * (dv.w - alpha * pr.w)) : 0.f;
     }
-    const int jn = (j + 1 < 32) ? j + 1 : 31;  // owner of the next column (unused when j + 1 == nb)
-    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
-    for (int it = j / QR_ROWS_PER_SWEEP; it < nsweeps; ++it) {
-      const int r = rg + QR_ROWS_PER_SWEEP * it;
-      const bool active = (r >= j) && (r < rows);
-      float a[4] = {0.f, 0.f, 0.f, 0.f};
-      float* rowp = A + (size_t)r * lda;
-      if (active) panel_load(rowp, c0, nb, vec, a);
-      const float aj = __shfl(pick4(a, j & 3), group_base | (j >> 2), 64);
-      const float v = (r == j) ? 1.0f : aj * scale;
+    acc = zero4;
+    if (RESIDENT) {
+      const int u0 = j / QR_ROWS_PER_SWEEP;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int c = c0 + q;
-        if (c > j) a[q] -= v * w[q];
-        else if (c == j) a[q] = (r == j) ? beta : v;
-      }
-      const float xn = __shfl(pick4(a, jn & 3), group_base | (jn >> 2), 64);
-      if (active) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int c = c0 + q;
-          if (c < j) acc[q] += a[q] * v;
-          else if (c > j && r > j) acc[q] += xn * a[q];
+      for (int u = 0; u < U; ++u) {
+        if (u >= u0 && u < nsweeps) {  // uniform across the workgroup
+          const int r = rg + QR_ROWS_PER_SWEEP * u;
+          pass_row(ra[u], r, (r >= j) && (r < rows), pp, c0, group_base, acc, pivrow[cur ^ 1]);
         }
-        panel_store(rowp, c0, nb, vec, a);
-        if (r == j + 1) {
+      }
+    } else {
+      for (int it0 = j / QR_ROWS_PER_SWEEP; it0 < nsweeps; it0 += U) {
+        float4 a[U];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) pivrow[cur ^ 1][c0 + q] = a[q];
+        for (int u = 0; u < U; ++u) {
+          const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
+          a[u] = zero4;
+          if ((r >= j) && (r < rows)) a[u] = panel_load(A + (size_t)r * lda, c0, nb, vec);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
+          pass_row(a[u], r, (r >= j) && (r < rows), pp, c0, group_base, acc, pivrow[cur ^ 1]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
+          if ((r >= j) && (r < rows)) panel_store(A + (size_t)r * lda, c0, nb, vec, a[u]);
         }
       }
     }
@@ -186,7 +287,7 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
       Tl[tid][j] = -tau * s;
     } else if (tid == j) {
       Tl[j][j] = tau;
-      diag[j] = beta;
+      diag[j] = pp.beta;
     }
     __syncthreads();
   }
@@ -203,17 +304,22 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
     const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
     Vc[-(ptrdiff_t)(r + 1) * ldv + c] = 0.f;
   }
-  for (int it = 0; it < nsweeps; ++it) {
-    const int r = rg + QR_ROWS_PER_SWEEP * it;
-    if (r < rows) {
-      float a[4];
-      panel_load(A + (size_t)r * lda, c0, nb, vec, a);
+  if (RESIDENT) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int c = c0 + q;
-        a[q] = (c >= nb || c > r) ? 0.f : ((c == r) ? 1.0f : a[q]);
+    for (int u = 0; u < U; ++u) {
+      const int r = rg + QR_ROWS_PER_SWEEP * u;
+      if (r < rows) {
+        panel_store(A + (size_t)r * lda, c0, nb, vec, ra[u]);
+        *reinterpret_cast<float4*>(Vc + (size_t)r * ldv + c0) = clean_v(ra[u], c0, r, nb);
       }
-      *reinterpret_cast<float4*>(Vc + (size_t)r * ldv + c0) = make_float4(a[0], a[1], a[2], a[3]);
+    }
+  } else {
+    for (int it = 0; it < nsweeps; ++it) {
+      const int r = rg + QR_ROWS_PER_SWEEP * it;
+      if (r < rows) {
+        const float4 a = panel_load(A + (size_t)r * lda, c0, nb, vec);
+        *reinterpret_cast<float4*>(Vc + (size_t)r * ldv + c0) = clean_v(a, c0, r, nb);
+      }
     }
   }
 }
@@ -304,7 +410,12 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, int batch,
     return hipErrorInvalidValue;
   int vec = (lda % 4 == 0);
   for (int i = 0; i < batch && vec; ++i) vec = ((reinterpret_cast<uintptr_t>(p.A[i]) & 15u) == 0);
-  hipLaunchKernelGGL(br::br_qr_panel, dim3(batch), dim3(br::QR_THREADS), 0, s, p, rows, nb, lda, vec, ldv, pre_rows);
+  if (rows <= br::QR_RESIDENT_SWEEPS * br::QR_ROWS_PER_SWEEP)
+    hipLaunchKernelGGL((br::br_qr_panel<br::QR_RESIDENT_SWEEPS, true>), dim3(batch), dim3(br::QR_THREADS), 0, s, p, rows, nb,
+                       lda, vec, ldv, pre_rows);
+  else
+    hipLaunchKernelGGL((br::br_qr_panel<br::QR_STREAM_SWEEPS, false>), dim3(batch), dim3(br::QR_THREADS), 0, s, p, rows, nb,
+                       lda, vec, ldv, pre_rows);
   return hipGetLastError();
 }
 
