@@ -1,0 +1,235 @@
+"""Parity at the benchmark configurations' full sizes, in the launch configuration bench.py times.
+
+The oracle cannot run a whole 634 M-parameter stage in seconds, so the GPU runs the full set of
+matrices (same batching and chunking as the benchmark) while the oracle follows a SAMPLE of them
+from the same inputs: every distinct shape, and matrices from different launch chunks.  At
+orders 2560-6912 the oracle's own Householder loop would take minutes, so its QR step is LAPACK's
+(a library routine) with the same sign convention; the orthogonal factor is unique, and the two
+QR routines are pinned against each other in the CPU tests.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import br_oracle as oc
+from oracle.metrics import misalignment, orthogonality_defect, rel_err
+from paper_2602_03515_amd import synth
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+TOL = 1e-4
+
+
+def lapack_qr(P):
+    q, r = np.linalg.qr(P)
+    d = np.where(np.diag(r) < 0, -1.0, 1.0)
+    return q * d[None, :], r * d[:, None]
+
+
+@pytest.fixture(scope="module")
+def h():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_harness
+    return gpu_harness
+
+
+def _floor(W, dW):
+    s = np.abs(dW).max()
+    return float(2.0 ** -23 * np.abs(W).max() / s) if s > 0 else 0.0
+
+
+def _young_moment_floor(hp, G):
+    """While the second moment is young (the first steps), Adam's quotient m / sqrt(s + eps) has
+    slope (1 - beta1) / sqrt(eps) at entries whose rotated gradient is near zero, so the FP32
+    rounding of a rotated-gradient entry (a length-K dot product: about 2^-24 times the row norm of
+    G as a standard deviation) is amplified by that slope.  Relative to
+    max|X| = (1 - beta1) / sqrt(1 - beta2) this adds 2^-24 * max_row_norm(G) * sqrt(1 - beta2) / sqrt(eps)
+    per standard deviation; the maximum over ~1e8 entries sits at 4-5 standard deviations: factor 4."""
+    row = float(np.sqrt((np.asarray(G, dtype=np.float64) ** 2).sum(axis=1)).max())
+    return 4.0 * 2.0 ** -24 * row * np.sqrt(1.0 - hp.beta2) / np.sqrt(hp.eps)
+
+
+def _follow(h, opt, B, params, grads_per_step, sample, hp, freq, lr, w0_host, check_q=True, tol=TOL,
+            young_moment=False):
+    """Drive all matrices on the GPU; the oracle follows the matrices in `sample`."""
+    states = {i: oc.MatrixState(w0_host[i].shape[0], w0_host[i].shape[1], hp) for i in sample}
+    W_ref = {i: w0_host[i].astype(np.float64) for i in sample}
+    for t, grads in enumerate(grads_per_step, 1):
+        opt.step(grads, lr)
+        prev = {i: W_ref[i].copy() for i in sample}
+        for i in sample:
+            g = grads[i].detach().to(torch.float32).cpu().numpy().astype(np.float64)
+            W_ref[i] = oc.optimizer_step(states[i], W_ref[i], g, lr, hp, freq, lapack_qr)
+        torch.cuda.synchronize()
+        for i in sample:
+            got = h.to_np(params[i]) if params[i].dtype == torch.float32 else h.to_np(opt.state(i, B.BR_STATE_MASTER))
+            e = rel_err(got - w0_host[i], W_ref[i] - w0_host[i])
+            lim = tol + _floor(W_ref[i], W_ref[i] - w0_host[i])
+            if young_moment:
+                lim += _young_moment_floor(hp, grads[i].detach().float().cpu().numpy())
+            assert e <= lim, f"step {t} matrix {i} {w0_host[i].shape}: cumulative update rel err {e:.3e} > {lim:.3e}"
+    worst = {}
+    for i in sample:
+        st = states[i]
+        pairs = [("M", B.BR_STATE_M, st.M), ("S", B.BR_STATE_S, st.S)]
+        if st.L is not None:
+            pairs.append(("L", B.BR_STATE_L, st.L))
+        if st.R is not None:
+            pairs.append(("R", B.BR_STATE_R, st.R))
+        if check_q and st.QL is not None:
+            pairs.append(("QL", B.BR_STATE_QL, st.QL))
+        if check_q and st.QR is not None:
+            pairs.append(("QR", B.BR_STATE_QR, st.QR))
+        for name, kind, ref in pairs:
+            e = rel_err(h.to_np(opt.state(i, kind)), ref)
+            worst[name] = max(worst.get(name, 0.0), e)
+            assert e <= tol, f"matrix {i} {name}: rel err {e:.3e}"
+        for kind, Q in ((B.BR_STATE_QL, st.QL), (B.BR_STATE_QR, st.QR)):
+            if Q is not None:
+                q = opt.state(i, kind).double()
+                defect = float((q.T @ q - torch.eye(q.shape[0], device=q.device, dtype=q.dtype)).abs().max())
+                assert defect < 1e-5, f"matrix {i}: ||Q^T Q - I||_max = {defect:.2e}"
+    return worst
+
+
+def test_stage_3b_bilateral_sampled_matrices(h):
+    """The 56-matrix 3B-class stage exactly as bench.py builds it (device-side seeded inputs,
+    FP32, bilateral, 4-slot gradient ring), refresh every 4 steps so that five steps cover plain
+    steps, a refresh step and a cached-rotated-moment step (four gradients are the fewest that make
+    the 6912 x 6912 statistics of a 2560 x 6912 matrix full rank and well conditioned: 4 x 2560
+    rows).  The oracle follows one matrix of each shape plus a square one from the last launch
+    chunk."""
+    import bench
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+    dev = torch.device("cuda:0")
+    shapes = list(synth.STAGE_3B)
+    params, ring = bench.make_inputs(shapes, bench.TAU + 1, seed=2, device=dev)
+    sample = [0, 4, 6, 52]
+    w0 = {i: params[i].cpu().numpy().copy() for i in sample}
+    hp = oc.Hyper().rounded_to_f32()
+    lr = float(np.float32(1e-3))
+    opt = BasisRotationAdam(params, freq=4, lr=lr)
+    steps = [ring[t % (bench.TAU + 1)] for t in range(1, 6)]
+    worst = _follow(h, opt, B, params, steps, sample, hp, 4, lr, w0)
+    print("stage sample worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
+    # every matrix of the stage: finite weights and orthogonal bases (properties that need no oracle)
+    for i in range(len(shapes)):
+        assert torch.isfinite(params[i]).all()
+    for i in (1, 5, 20, 41, 55):
+        for kind in (B.BR_STATE_QL, B.BR_STATE_QR):
+            q = opt.state(i, kind).double()
+            assert float((q.T @ q - torch.eye(q.shape[0], device=dev, dtype=q.dtype)).abs().max()) < 1e-5
+
+
+def test_llama_layer_2048_bf16_config(h):
+    """One Llama-style layer at hidden 2048, BF16 parameters and gradients, FP32 master/state,
+    refresh every 10 steps, 12 steps.  All seven matrices run on the GPU; the oracle follows one
+    attention matrix for all 12 steps (the rectangular shapes are followed at full size in FP32 by
+    the stage test and in BF16 at hidden 256 by the small-size suite)."""
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+    shapes = list(synth.LLAMA_LAYER_2048)
+    hp = oc.Hyper().rounded_to_f32()
+    lr = float(np.float32(1e-3))
+    W0s, seqs = [], []
+    for k, (m, n) in enumerate(shapes):
+        steps = 12 if k == 0 else 2          # only matrix 0 needs 12 distinct host gradients
+        W0, grads = synth.lowrank_gradients(seed=2000 + k, m=m, n=n, steps=steps, rank=64, sigma=0.01, bf16=True)
+        W0s.append(W0)
+        seqs.append(grads)
+    params = [h.to_dev(W, bf16=True) for W in W0s]
+    dev_grads = [[h.to_dev(g, bf16=True) for g in seq] for seq in seqs]
+    opt = BasisRotationAdam(params, freq=10, lr=lr, grad_dtype=torch.bfloat16)
+    per_step = [[dev_grads[k][t % len(dev_grads[k])] for k in range(len(shapes))] for t in range(12)]
+    w0 = {0: W0s[0]}
+    worst = _follow(h, opt, B, params, per_step, [0], hp, 10, lr, w0)
+    print("hidden-2048 BF16 worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
+    master = opt.state(0, B.BR_STATE_MASTER)
+    assert torch.equal(master.to(torch.bfloat16), params[0])
+    for i in range(1, len(shapes)):
+        assert torch.isfinite(params[i].float()).all()
+        for kind in (B.BR_STATE_QL, B.BR_STATE_QR):
+            q = opt.state(i, kind).double()
+            assert float((q.T @ q - torch.eye(q.shape[0], device=q.device, dtype=q.dtype)).abs().max()) < 1e-5
+
+
+def test_stage_plus_embedding_unilateral_refresh_every_step(h):
+    """Refresh-heavy configuration: one layer of the stage plus the 32000 x 2560 embedding shard,
+    unilateral rotation (every factor is 2560 x 2560), refresh EVERY step with two power iterations
+    and one QR.  The oracle follows the embedding and one 6912 x 2560 matrix for three steps."""
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+    import bench
+    dev = torch.device("cuda:0")
+    shapes = list(synth.STAGE_3B_LAYER) + [synth.EMBEDDING_SHARD]
+    params, ring = bench.make_inputs(shapes, 3, seed=5, device=dev)
+    sample = [6, 7]
+    w0 = {i: params[i].cpu().numpy().copy() for i in sample}
+    hp = oc.Hyper(geometry="unilateral", power_iters=2).rounded_to_f32()
+    lr = float(np.float32(1e-3))
+    opt = BasisRotationAdam(params, freq=1, lr=lr, geometry=B.BR_UNILATERAL, power_iters=2)
+    assert not opt.has_state(7, B.BR_STATE_QL) and opt.state(7, B.BR_STATE_QR).shape == (2560, 2560)
+    # FP32 state of the refresh-heavy configuration: 2 m n + 2 min(m,n)^2 floats per matrix (+ cache)
+    closed = sum(4 * (2 * m * n + 2 * min(m, n) ** 2) for m, n in shapes)
+    assert 0 <= opt.state_bytes - closed - 4 * sum(m * n for m, n in shapes) <= 4096 * len(shapes)
+    worst = _follow(h, opt, B, params, [ring[t % 3] for t in range(1, 4)], sample, hp, 1, lr, w0,
+                    young_moment=True)
+    print("unilateral refresh-every-step worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
+
+
+@pytest.mark.parametrize("geometry", ["bilateral", "unilateral"])
+@pytest.mark.parametrize("tau", [0, 3, 7])
+def test_quadratic_with_delay_512x128(h, geometry, tau):
+    """Quadratic with a Kronecker-structured Hessian, 512 x 128, 500 steps under delay tau.  The
+    oracle runs the delayed trajectory; the GPU consumes the SAME gradient sequence (so that both
+    sides compute the same function of the same inputs) and is compared at steps 1, 10, 100, 500.
+
+    Tolerance: the left statistics of this problem are ill-conditioned by construction (eigenvalues of
+    the Hessian span three decades; cond(L) is about 1.5e4 at the first refresh), and the FP32 QR
+    resolves the basis only to about cond * 2^-24, so bases and updates are compared at
+    1e-4 + 8 * cond * 2^-24 with cond the largest condition number the oracle saw at a refresh."""
+    from paper_2602_03515_amd import binding as B
+    prob = synth.quadratic_problem(seed=1, m=512, n=128, noise_std=0.01)
+    hp_kw = dict(geometry=0 if geometry == "bilateral" else 1)
+    lr = 1e-2
+    checkpoints = {}
+    conds = [1.0]
+
+    def rec(t, st, W):
+        if t % 10 == 0:
+            for A in (st.L, st.R):
+                if A is not None:
+                    conds.append(float(np.linalg.cond(A)))
+        if t in (1, 10, 100, 500):
+            checkpoints[t] = (W.copy(), None if st.QL is None else st.QL.copy(), None if st.QR is None else st.QR.copy(),
+                              st.M.copy(), st.S.copy(), max(conds))
+
+    hp = h.oracle_hyper(**hp_kw)
+    st, W_end, consumed = oc.run_delayed(prob.gradient, prob.W0, hp, float(np.float32(lr)), 10, tau, 500,
+                                         qr=lapack_qr, record=rec)
+    sb = h.SideBySide([prob.W0], freq=10, lr=lr, **hp_kw)
+    w0 = prob.W0.astype(np.float64)
+    for t, g in enumerate(consumed, 1):
+        sb.opt.step([h.to_dev(g)], sb.lr)
+        if t in checkpoints:
+            W_ref, QL, QR, M, S, cond = checkpoints[t]
+            tol = TOL + 8 * cond * 2.0 ** -24
+            got = h.to_np(sb.params[0])
+            e = rel_err(got - w0, W_ref - w0)
+            assert e <= tol + _floor(W_ref, W_ref - w0), f"t={t}: update err {e:.3e} (cond {cond:.1e})"
+            assert rel_err(h.to_np(sb.opt.state(0, B.BR_STATE_M)), M) <= TOL
+            assert rel_err(h.to_np(sb.opt.state(0, B.BR_STATE_S)), S) <= tol
+            for kind, Q in ((B.BR_STATE_QL, QL), (B.BR_STATE_QR, QR)):
+                if Q is not None:
+                    q = h.to_np(sb.opt.state(0, kind))
+                    assert orthogonality_defect(q) < 1e-5
+                    eq = rel_err(q, Q)
+                    assert eq <= tol, f"t={t}: basis err {eq:.3e} > {tol:.3e}"
+    # the trajectory did optimise, and the estimated right basis is better aligned with the Hessian
+    # factor than the identity (bilateral: both sides)
+    assert prob.loss(h.to_np(sb.params[0])) < 0.5 * prob.loss(prob.W0)
+    qr_gpu = h.to_np(sb.opt.state(0, B.BR_STATE_QR))
+    assert misalignment(qr_gpu, prob.H_R) < misalignment(np.eye(128), prob.H_R)
+    assert abs(misalignment(qr_gpu, prob.H_R) - misalignment(st.QR, prob.H_R)) <= 1e-2 * misalignment(st.QR, prob.H_R)
