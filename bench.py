@@ -89,6 +89,23 @@ def cpu_baseline(seconds_hint=20.0):
                       f"float64 numpy, {t_total:.1f} s"}
 
 
+def counter_traffic(workload_name):
+    """HBM bytes per launch of the dominant kernel, from the hardware-counter runs summarised in
+    profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size).  Counters cannot be
+    read from inside this process; the value is the one measured for the same library and launch
+    shapes by the commands that file lists.  None when no such measurement exists."""
+    if workload_name != "stage3b":
+        return None
+    path = os.path.join(ROOT, "profiles", "gemm_f32_mfma_stage3b_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if "traffic_bytes_per_launch" in line:
+                return float(line.rsplit("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,7 +168,9 @@ def main():
         avg_ms = dom["ms"] / dom["launches"]
         achieved = dom["flops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": achieved, "peak": PEAK_TFLOPS["f32"],
-                    "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS["f32"], "traffic": None,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS["f32"],
+                    "traffic": counter_traffic(args.workload) if dom["kernel"].endswith("<nn>") else None,
+                    "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
                     "launches": dom["launches"], "avg_launch_ms": avg_ms}
     breakdown = {p["kernel"]: {"launches": p["launches"], "ms_per_step": p["ms"] / args.steps,
                                "tflops": (p["flops"] / (p["ms"] * 1e-3) / 1e12) if p["ms"] > 0 else None,

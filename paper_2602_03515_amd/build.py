@@ -60,6 +60,15 @@ def build_library(verbose: bool = False) -> str:
         print(res.stdout, file=sys.stderr)
         raise RuntimeError("link failed")
     os.replace(tmp, LIB_PATH)
+    # stand-alone C driver of the ABI (used for hardware-counter runs)
+    exe = os.path.join(HERE, "br_native_bench")
+    cmd = [hipcc, *HIPCC_FLAGS, os.path.join(CSRC, "br_native_bench.hip"), "-o", exe + ".tmp",
+           f"-L{HERE}", "-lbr_hip", "-Wl,-rpath,$ORIGIN"]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        print(res.stdout, file=sys.stderr)
+        raise RuntimeError("native driver build failed")
+    os.replace(exe + ".tmp", exe)
     return LIB_PATH
 
 

@@ -42,15 +42,31 @@ __global__ __launch_bounds__(256) void br_ema_first_moment(BrPtrBatch p, int64_t
   const float w = 1.0f - beta1;
   const int64_t n4 = count >> 2;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-    float4 g = load_grad4(G, i, grad_bf16);
-    float4 m = reinterpret_cast<float4*>(M)[i];
-    m.x = beta1 * m.x + w * g.x;
-    m.y = beta1 * m.y + w * g.y;
-    m.z = beta1 * m.z + w * g.z;
-    m.w = beta1 * m.w + w * g.w;
-    reinterpret_cast<float4*>(M)[i] = m;
-    if (G32) reinterpret_cast<float4*>(G32)[i] = g;
+  // two independent 16-byte triples in flight per lane
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += 2 * stride) {
+    const int64_t j = i + stride;
+    const bool two = j < n4;
+    float4 g0 = load_grad4(G, i, grad_bf16);
+    float4 m0 = reinterpret_cast<float4*>(M)[i];
+    float4 g1 = g0, m1 = m0;
+    if (two) {
+      g1 = load_grad4(G, j, grad_bf16);
+      m1 = reinterpret_cast<float4*>(M)[j];
+    }
+    m0.x = beta1 * m0.x + w * g0.x;
+    m0.y = beta1 * m0.y + w * g0.y;
+    m0.z = beta1 * m0.z + w * g0.z;
+    m0.w = beta1 * m0.w + w * g0.w;
+    reinterpret_cast<float4*>(M)[i] = m0;
+    if (G32) reinterpret_cast<float4*>(G32)[i] = g0;
+    if (two) {
+      m1.x = beta1 * m1.x + w * g1.x;
+      m1.y = beta1 * m1.y + w * g1.y;
+      m1.z = beta1 * m1.z + w * g1.z;
+      m1.w = beta1 * m1.w + w * g1.w;
+      reinterpret_cast<float4*>(M)[j] = m1;
+      if (G32) reinterpret_cast<float4*>(G32)[j] = g1;
+    }
   }
   if (blockIdx.x == 0) {
     for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
@@ -87,10 +103,7 @@ __global__ __launch_bounds__(256) void br_adam_rotated(BrAdamBatch p, int64_t co
   const int64_t n4 = count >> 2;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   float sg = 0.f, sx = 0.f;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-    float4 g = reinterpret_cast<const float4*>(GX)[i];
-    float4 s = reinterpret_cast<float4*>(S)[i];
-    float4 m = reinterpret_cast<float4*>(Mr)[i];
+  auto body = [&](float4 g, float4 s, float4 m, int64_t i) {
     if (upd) {
       m.x = a.beta1 * m.x + w1 * g.x;
       m.y = a.beta1 * m.y + w1 * g.y;
@@ -109,6 +122,22 @@ __global__ __launch_bounds__(256) void br_adam_rotated(BrAdamBatch p, int64_t co
       sg += g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
       sx += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
     }
+  };
+  // two independent 16-byte triples in flight per lane
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += 2 * stride) {
+    const int64_t j = i + stride;
+    const bool two = j < n4;
+    float4 g0 = reinterpret_cast<const float4*>(GX)[i];
+    float4 s0 = reinterpret_cast<float4*>(S)[i];
+    float4 m0 = reinterpret_cast<float4*>(Mr)[i];
+    float4 g1 = g0, s1 = s0, m1 = m0;
+    if (two) {
+      g1 = reinterpret_cast<const float4*>(GX)[j];
+      s1 = reinterpret_cast<float4*>(S)[j];
+      m1 = reinterpret_cast<float4*>(Mr)[j];
+    }
+    body(g0, s0, m0, i);
+    if (two) body(g1, s1, m1, j);
   }
   if (blockIdx.x == 0) {
     for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
@@ -207,9 +236,9 @@ __global__ __launch_bounds__(256) void br_bf16_to_f32(const uint16_t* __restrict
 }
 
 static inline int grid_for(int64_t work_items, int batch) {
-  // ~8 workgroups of 256 per compute unit across the whole launch, at least one per matrix
+  // ~16 workgroups of 256 per compute unit across the whole launch, at least one per matrix
   int64_t blocks = (work_items + 255) / 256;
-  int64_t cap = (256 * 8 + batch - 1) / batch;
+  int64_t cap = (256 * 16 + batch - 1) / batch;
   if (cap < 1) cap = 1;
   if (blocks > cap) blocks = cap;
   if (blocks < 1) blocks = 1;

@@ -23,6 +23,7 @@ constexpr int BN = 128;
 constexpr int BK = 16;
 constexpr int LDS_LD = 132;  // 128 + 4: keeps float4 rows 16-byte aligned, shifts banks by 4 per k
 constexpr int NUM_XCD = 8;
+constexpr int GROUP_M = 8;
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -69,21 +70,24 @@ __device__ __forceinline__ float4 load4(const float* __restrict__ base, int row,
 // tile dimension as its row index and is transposed while being written to LDS.
 template <bool KMAJOR, bool VEC>
 struct TileLoader {
-  float4 r[2];
+  static constexpr int PASSES = BK / 8;       // 16-byte loads per thread for one BK x 128 tile
+  static constexpr int TPR = BK / 4;          // threads per stored row of a k-minor operand
+  static constexpr int RPP = 256 / TPR;       // rows per pass of a k-minor operand
+  float4 r[PASSES];
   __device__ __forceinline__ void fetch(const float* __restrict__ base, int ld, int d0, int k0,
                                         int D, int K, int tid) {
     if (KMAJOR) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < PASSES; ++i) {
         int k = (tid >> 5) + 8 * i;
         int d = (tid & 31) * 4;
         r[i] = load4<VEC>(base, k0 + k, d0 + d, ld, K, D);
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        int d = (tid >> 2) + 64 * i;
-        int k = (tid & 3) * 4;
+      for (int i = 0; i < PASSES; ++i) {
+        int d = tid / TPR + RPP * i;
+        int k = (tid % TPR) * 4;
         r[i] = load4<VEC>(base, d0 + d, k0 + k, ld, D, K);
       }
     }
@@ -91,16 +95,16 @@ struct TileLoader {
   __device__ __forceinline__ void stash(float (*lds)[LDS_LD], int tid) const {
     if (KMAJOR) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < PASSES; ++i) {
         int k = (tid >> 5) + 8 * i;
         int d = (tid & 31) * 4;
         *reinterpret_cast<float4*>(&lds[k][d]) = r[i];
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        int d = (tid >> 2) + 64 * i;
-        int k = (tid & 3) * 4;
+      for (int i = 0; i < PASSES; ++i) {
+        int d = tid / TPR + RPP * i;
+        int k = (tid % TPR) * 4;
         lds[k + 0][d] = r[i].x;
         lds[k + 1][d] = r[i].y;
         lds[k + 2][d] = r[i].z;
@@ -120,7 +124,7 @@ namespace br {
 // `splitk` K ranges and the partial product goes to `partial`, summed in a fixed order by
 // br_splitk_reduce (deterministic, no atomics).
 template <bool TA, bool TB, bool VEC, bool SPLIT>
-__global__ __launch_bounds__(256) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBatch batch) {
+__global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBatch batch) {
   __shared__ __attribute__((aligned(16))) float As[2][BK][LDS_LD];
   __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDS_LD];
 
@@ -148,8 +152,16 @@ __global__ __launch_bounds__(256) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBa
       tm = r;
       tn = t - r * (r + 1) / 2;
     } else {
-      tm = t / g.tiles_n;
-      tn = t - tm * g.tiles_n;
+      // Grouped order: GROUP_M tile rows at a time, column by column inside the group, so that the
+      // ~128 tiles in flight on one XCD form an 8 x 16 patch (24 operand panels) instead of
+      // two and a half tile rows (50+ panels): fewer distinct panels stream through its L2.
+      const int group = GROUP_M * g.tiles_n;
+      const int grp = t / group;
+      const int first_m = grp * GROUP_M;
+      const int gm = min(GROUP_M, g.tiles_m - first_m);
+      const int r = t - grp * group;
+      tn = r / gm;
+      tm = first_m + (r - tn * gm);
     }
   }
   const float* __restrict__ A = batch.A[mat];
