@@ -74,6 +74,32 @@ struct TileLoader {
   static constexpr int TPR = BK / 4;          // threads per stored row of a k-minor operand
   static constexpr int RPP = 256 / TPR;       // rows per pass of a k-minor operand
   float4 r[PASSES];
+  const float* fp[PASSES];  // per-thread source pointers of the unguarded path
+  size_t fstep;             // their advance per K tile
+  // Unguarded path for tiles that lie wholly inside the operands (and K a multiple of BK):
+  // plain 16-byte loads through pointers that advance by a constant, no bounds logic.
+  __device__ __forceinline__ void init_fast(const float* __restrict__ base, int ld, int d0, int k0, int tid) {
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      if (KMAJOR) {
+        int k = (tid >> 5) + 8 * i;
+        int d = (tid & 31) * 4;
+        fp[i] = base + (size_t)(k0 + k) * (size_t)ld + d0 + d;
+      } else {
+        int d = tid / TPR + RPP * i;
+        int k = (tid % TPR) * 4;
+        fp[i] = base + (size_t)(d0 + d) * (size_t)ld + k0 + k;
+      }
+    }
+    fstep = KMAJOR ? (size_t)BK * (size_t)ld : (size_t)BK;
+  }
+  __device__ __forceinline__ void fetch_fast() {
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+      r[i] = *reinterpret_cast<const float4*>(fp[i]);
+      fp[i] += fstep;
+    }
+  }
   __device__ __forceinline__ void fetch(const float* __restrict__ base, int ld, int d0, int k0,
                                         int D, int K, int tid) {
     if (KMAJOR) {
@@ -192,20 +218,9 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
     kt0 = split * g.kt_per_split;
     nkt = min(nkt, kt0 + g.kt_per_split);
   }
-  la.fetch(A, g.lda, m0, kt0 * BK, g.M, g.K, tid);
-  lb.fetch(B, g.ldb, n0, kt0 * BK, g.N, g.K, tid);
-  la.stash(As[0], tid);
-  lb.stash(Bs[0], tid);
-  __syncthreads();
-
   const int lk = lane >> 5;  // which of the two k of an MFMA this lane feeds
   const int li = lane & 31;  // row of A / column of B inside the 32-wide MFMA tile
-  for (int kt = kt0; kt < nkt; ++kt) {
-    const int cur = (kt - kt0) & 1;
-    if (kt + 1 < nkt) {
-      la.fetch(A, g.lda, m0, (kt + 1) * BK, g.M, g.K, tid);
-      lb.fetch(B, g.ldb, n0, (kt + 1) * BK, g.N, g.K, tid);
-    }
+  auto mfma_tile = [&](int cur) {
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
       float a0 = As[cur][kk + lk][wm * 64 + li];
@@ -217,15 +232,47 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
     }
-    if (kt + 1 < nkt) {
+  };
+  const bool interior = VEC && (m0 + BM <= g.M) && (n0 + BN <= g.N) && (g.K % BK == 0);
+  if (interior) {
+    la.init_fast(A, g.lda, m0, kt0 * BK, tid);
+    lb.init_fast(B, g.ldb, n0, kt0 * BK, tid);
+    la.fetch_fast();
+    lb.fetch_fast();
+    la.stash(As[0], tid);
+    lb.stash(Bs[0], tid);
+    __syncthreads();
+    for (int kt = kt0; kt < nkt - 1; ++kt) {
+      const int cur = (kt - kt0) & 1;
+      la.fetch_fast();
+      lb.fetch_fast();
+      mfma_tile(cur);
       la.stash(As[cur ^ 1], tid);
       lb.stash(Bs[cur ^ 1], tid);
+      __syncthreads();
     }
+    if (nkt > kt0) mfma_tile((nkt - 1 - kt0) & 1);
+  } else {
+    la.fetch(A, g.lda, m0, kt0 * BK, g.M, g.K, tid);
+    lb.fetch(B, g.ldb, n0, kt0 * BK, g.N, g.K, tid);
+    la.stash(As[0], tid);
+    lb.stash(Bs[0], tid);
     __syncthreads();
+    for (int kt = kt0; kt < nkt; ++kt) {
+      const int cur = (kt - kt0) & 1;
+      if (kt + 1 < nkt) {
+        la.fetch(A, g.lda, m0, (kt + 1) * BK, g.M, g.K, tid);
+        lb.fetch(B, g.ldb, n0, (kt + 1) * BK, g.N, g.K, tid);
+      }
+      mfma_tile(cur);
+      if (kt + 1 < nkt) {
+        la.stash(As[cur ^ 1], tid);
+        lb.stash(Bs[cur ^ 1], tid);
+      }
+      __syncthreads();
+    }
   }
 
-  // Epilogue.  Accumulator register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4 and
-  // column l%32 of its 32 x 32 tile.
   if (SPLIT && g.splitk > 1) {
     float* __restrict__ P = g.partial + ((size_t)mat * g.splitk + split) * (size_t)g.M * g.N;
 #pragma unroll

@@ -3,7 +3,12 @@
 // optimizer steps.  It exists for hardware-counter runs (a profiler attaches to a plain
 // executable) and as a C usage example of include/br.h.
 //
-//   br_native_bench [--layers N] [--steps K] [--freq F] [--copy-calibration]
+//   br_native_bench [--layers N] [--steps K] [--freq F] [--copy-calibration] [--mfma-peak]
+//
+// --mfma-peak runs br_mfma_peak instead of the optimizer: a register-only loop of
+// v_mfma_f32_32x32x2_f32 on every SIMD, once as a ~25 ms burst and once sustained for ~0.5 s,
+// which gives the FP32 matrix-core rate this machine actually holds (clocks drop under
+// sustained load), the practical ceiling for the contraction kernel.
 //
 // --copy-calibration additionally launches br_plain_copy on 1 GiB (reads 1 GiB, writes 1 GiB),
 // the known-traffic kernel against which HBM byte counters are scaled.
@@ -40,6 +45,53 @@ __global__ void br_plain_copy(const float4* __restrict__ src, float4* __restrict
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
 }
 
+typedef float br_floatx16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void br_mfma_peak(float* out, int iters) {
+  br_floatx16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  unsigned x = (threadIdx.x + 1 + blockIdx.x * 977) * 2654435761u;
+  x ^= x >> 15; x *= 0x2c1b3c6du; x ^= x >> 12;
+  float a0 = (float)(x & 0xffff) / 65536.f - 0.5f, a1 = (float)(x >> 16) / 65536.f - 0.5f;
+  x *= 0x297a2d39u; x ^= x >> 15;
+  float b0 = (float)(x & 0xffff) / 65536.f - 0.5f, b1 = (float)(x >> 16) / 65536.f - 0.5f;
+  for (int i = 0; i < iters; i += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, c1, 0, 0, 0);
+      c2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, c2, 0, 0, 0);
+      c3 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, c3, 0, 0, 0);
+    }
+  }
+  float s = 0.f;
+  for (int v = 0; v < 16; ++v) s += c0[v] + c1[v] + c2[v] + c3[v];
+  if (s == 12345.f) out[threadIdx.x] = s;  // keeps the loop alive
+}
+
+static int mfma_peak() {
+  float* d = nullptr;
+  CHECK_HIP(hipMalloc(&d, 4096));
+  hipEvent_t e0, e1;
+  CHECK_HIP(hipEventCreate(&e0));
+  CHECK_HIP(hipEventCreate(&e1));
+  const int grid = 256 * 4;  // four workgroups of four waves per compute unit
+  const int iters_list[2] = {50000, 1000000};
+  for (int k = 0; k < 2; ++k) {
+    hipLaunchKernelGGL(br_mfma_peak, dim3(grid), dim3(256), 0, 0, d, 1000);
+    CHECK_HIP(hipDeviceSynchronize());
+    CHECK_HIP(hipEventRecord(e0, 0));
+    hipLaunchKernelGGL(br_mfma_peak, dim3(grid), dim3(256), 0, 0, d, iters_list[k]);
+    CHECK_HIP(hipEventRecord(e1, 0));
+    CHECK_HIP(hipEventSynchronize(e1));
+    float ms = 0.f;
+    CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+    double flops = (double)grid * 4 * iters_list[k] * 4.0 * 4096.0;
+    std::printf("br_mfma_peak %s: %.1f ms, %.1f TFLOP/s FP32 MFMA\n", k ? "sustained" : "burst", ms, flops / (ms * 1e-3) / 1e12);
+  }
+  CHECK_HIP(hipFree(d));
+  return 0;
+}
+
 int main(int argc, char** argv) {
   int layers = 8, steps = 2, freq = 10, calib = 0;
   for (int i = 1; i < argc; ++i) {
@@ -47,6 +99,7 @@ int main(int argc, char** argv) {
     else if (!std::strcmp(argv[i], "--steps") && i + 1 < argc) steps = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--freq") && i + 1 < argc) freq = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--copy-calibration")) calib = 1;
+    else if (!std::strcmp(argv[i], "--mfma-peak")) return mfma_peak();
     else { std::fprintf(stderr, "unknown argument %s\n", argv[i]); return 2; }
   }
   const int64_t layer_shapes[7][2] = {{2560, 2560}, {2560, 2560}, {2560, 2560}, {2560, 2560},
