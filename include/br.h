@@ -153,6 +153,19 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
 br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_mats);
 
 /*
+ * Global-norm gradient clipping over all matrices of the context (the training recipe of the
+ * experimental-details appendix clips at 1.0): norm = sqrt(sum of squares of every gradient
+ * entry); every gradient is multiplied IN PLACE by min(1, max_norm / (norm + 1e-6)).  Call it
+ * before br_accumulate_stats.  Nothing is copied to the host: the norm and the factor stay in
+ * device memory (br_get_clip_result).  BF16 gradients are rescaled with round-to-nearest-even.
+ * `grads`: host array of n_mats device pointers (writable).
+ */
+br_status br_clip_gradients(br_ctx* ctx, void* const* grads, int32_t n_mats, float max_norm);
+
+/* Device pointer to two floats: the global norm and the factor of the latest br_clip_gradients. */
+br_status br_get_clip_result(br_ctx* ctx, void** dev_ptr);
+
+/*
  * Eigenbasis-Estimation for every rotated side (Algorithm 2 lines 3, 6 and
  * Section 3.2): P <- A^power_iters Q with A = L or R (first-order source: M M^T,
  * M^T M), then Q <- the orthogonal factor of the Householder QR of P with

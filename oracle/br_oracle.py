@@ -268,3 +268,29 @@ def extra_state_floats(m: int, n: int, geometry: str, source: str) -> int:
     left, right = rotated_sides(m, n, geometry)
     rot = (m * m if left else 0) + (n * n if right else 0)
     return rot * (2 if source == "second" else 1)
+
+
+def clip_by_global_norm(grads, max_norm: float):
+    """Global-norm gradient clipping as used in the paper's training recipe (experimental details:
+    clipping value 1.0): every gradient is multiplied by min(1, max_norm / (norm + 1e-6)) with
+    norm the 2-norm of all entries of all gradients.  Returns (scaled gradients, norm, factor)."""
+    total = 0.0
+    for g in grads:
+        g64 = np.asarray(g, dtype=np.float64)
+        total += float(np.sum(g64 * g64))
+    norm = float(np.sqrt(total))
+    factor = min(1.0, max_norm / (norm + 1e-6))
+    return [np.asarray(g, dtype=np.float64) * factor for g in grads], norm, factor
+
+
+def stage_refresh_periods(delays, base_period: int):
+    """Stage-aware refresh allocation (Section 4.3, "Stage-aware" paragraph): the refresh budget
+    of a stage, 1 / period, is proportional to its gradient delay, and the total budget equals
+    that of a uniform schedule with `base_period` on every stage.  A stage without delay gets no
+    refreshes (period 0 = never).  Periods are real numbers here; callers round."""
+    delays = [float(d) for d in delays]
+    total = sum(delays)
+    if total <= 0:
+        return [float(base_period)] * len(delays)
+    budget = len(delays) / float(base_period)
+    return [0.0 if d <= 0 else total / (budget * d) for d in delays]

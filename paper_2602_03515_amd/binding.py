@@ -62,6 +62,10 @@ _lib.br_init.argtypes = [C.POINTER(_ctx_p), C.POINTER(br_matrix_desc), C.c_int32
 _lib.br_init.restype = C.c_int
 _lib.br_accumulate_stats.argtypes = [_ctx_p, C.POINTER(C.c_void_p), C.c_int32]
 _lib.br_accumulate_stats.restype = C.c_int
+_lib.br_clip_gradients.argtypes = [_ctx_p, C.POINTER(C.c_void_p), C.c_int32, C.c_float]
+_lib.br_clip_gradients.restype = C.c_int
+_lib.br_get_clip_result.argtypes = [_ctx_p, C.POINTER(C.c_void_p)]
+_lib.br_get_clip_result.restype = C.c_int
 _lib.br_refresh_basis.argtypes = [_ctx_p]
 _lib.br_refresh_basis.restype = C.c_int
 _lib.br_step.argtypes = [_ctx_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_float]
@@ -86,7 +90,7 @@ _lib.br_version.restype = C.c_char_p
 _lib.br_destroy.argtypes = [_ctx_p]
 _lib.br_destroy.restype = None
 
-EXPORTED = ["br_workspace_bytes", "br_init", "br_accumulate_stats", "br_refresh_basis", "br_step", "br_get_state",
+EXPORTED = ["br_workspace_bytes", "br_init", "br_clip_gradients", "br_get_clip_result", "br_accumulate_stats", "br_refresh_basis", "br_step", "br_get_state",
             "br_notify_state_written", "br_get_step_count", "br_set_step_count", "br_profile_begin", "br_profile_end", "br_last_error",
             "br_version", "br_destroy"]
 
@@ -156,6 +160,16 @@ def br_init(descs, hp: br_hparams, dev_workspace: int, workspace_bytes: int, hip
 
 def br_accumulate_stats(ctx, grads: Sequence[int]):
     _check(_lib.br_accumulate_stats(ctx, _ptr_array(grads), len(grads)), "br_accumulate_stats", ctx)
+
+
+def br_clip_gradients(ctx, grads: Sequence[int], max_norm: float):
+    _check(_lib.br_clip_gradients(ctx, _ptr_array(grads), len(grads), max_norm), "br_clip_gradients", ctx)
+
+
+def br_get_clip_result(ctx) -> int:
+    p = C.c_void_p()
+    _check(_lib.br_get_clip_result(ctx, C.byref(p)), "br_get_clip_result", ctx)
+    return p.value
 
 
 def br_refresh_basis(ctx):

@@ -15,8 +15,8 @@
 
 namespace {
 
-constexpr int kStepChunk = 16;     // matrices per batched step launch ([G|M] doubles it to BR_MAXB)
-constexpr int kRefreshChunk = 32;  // factor matrices per batched refresh launch
+constexpr int kStepChunk = 32;     // matrices per batched step launch ([G|M] doubles it to BR_MAXB)
+constexpr int kRefreshChunk = 64;  // factor matrices per batched refresh launch
 constexpr int64_t kMaxDim = 1 << 24;
 constexpr size_t kNormPartialBytes = (size_t)BR_MAXB * 2 * BR_NORM_BLOCKS * sizeof(float);
 constexpr size_t kSplitKBytes = (size_t)64 << 20;  // partial products of the QR's split-K contractions
@@ -63,6 +63,7 @@ struct br_ctx {
   Layout lay;
   hipStream_t stream = nullptr;
   char* scratch = nullptr;
+  float* clip_result = nullptr;  // 2 floats at the end of the state region
   int64_t t = 0;
   bool stats_fresh = false;
   bool mrot_valid = true;  // cached M~ equals Q_L^T M Q_R (true at t = 0: both are zero)
@@ -190,6 +191,7 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
     size_t chunk = std::min<size_t>(kv.second.size(), kRefreshChunk);
     scratch = std::max(scratch, chunk * refresh_scratch(kv.first, hp).total + kSplitKBytes);
   }
+  state += 256;  // global gradient norm and clipping factor
   lay->state_bytes = state;
   lay->scratch_bytes = scratch + kNormPartialBytes;
 }
@@ -312,6 +314,7 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
     if ((m.rot_l || m.rot_r) && c->hp.cache_rotated_moment) m.Mrot = take(mn);
     m.norms = take(256);
   }
+  c->clip_result = reinterpret_cast<float*>(p);
   c->scratch = reinterpret_cast<char*>(dev_workspace) + c->lay.state_bytes;
   // zero state, identity bases
   if (!hip_ok(c, hipMemsetAsync(dev_workspace, 0, c->lay.state_bytes, c->stream), "state clear")) {
@@ -396,6 +399,49 @@ static br_status check_call(br_ctx* ctx, const void* const* a, const void* const
     if (!a[i] || (need_b && !b[i])) return fail(ctx, BR_ERR_INVALID_ARG, "null device pointer for matrix " + std::to_string(i));
     if ((reinterpret_cast<uintptr_t>(a[i]) & 15u) || (need_b && (reinterpret_cast<uintptr_t>(b[i]) & 15u)))
       return fail(ctx, BR_ERR_INVALID_ARG, "device pointers must be 16-byte aligned (matrix " + std::to_string(i) + ")");
+  }
+  return BR_OK;
+}
+
+br_status br_get_clip_result(br_ctx* ctx, void** dev_ptr) {
+  if (!ctx || !dev_ptr) return BR_ERR_INVALID_ARG;
+  *dev_ptr = ctx->clip_result;
+  return BR_OK;
+}
+
+br_status br_clip_gradients(br_ctx* ctx, void* const* grads, int32_t n_mats, float max_norm) {
+  br_status st = check_call(ctx, reinterpret_cast<const void* const*>(grads), nullptr, false, n_mats);
+  if (st != BR_OK) return st;
+  br_ctx* c = ctx;
+  if (!(max_norm > 0.f)) return fail(c, BR_ERR_INVALID_ARG, "max_norm must be positive");
+  if (c->stats_fresh) return fail(c, BR_ERR_STATE, "clip the gradients before br_accumulate_stats");
+  if ((size_t)n_mats * BR_CLIP_BLOCKS * sizeof(float) > kNormPartialBytes)
+    return fail(c, BR_ERR_UNSUPPORTED, "too many matrices for the clipping reduction");
+  float* partials = reinterpret_cast<float*>(c->scratch);
+  for (int pass = 0; pass < 2; ++pass) {
+    int slot = 0;
+    for (const Group& g : c->lay.groups) {
+      const int64_t count = g.m * g.n;
+      for (size_t off = 0; off < g.idx.size(); off += BR_MAXB) {
+        const int B = (int)std::min<size_t>(BR_MAXB, g.idx.size() - off);
+        BrPtrBatch pb;
+        std::memset(&pb, 0, sizeof(pb));
+        for (int i = 0; i < B; ++i) {
+          pb.in0[i] = grads[g.idx[off + i]];
+          pb.out0[i] = grads[g.idx[off + i]];
+        }
+        const double gbytes = (double)count * B * (g.gdt == BR_BF16 ? 2.0 : 4.0);
+        if (pass == 0) {
+          Timed tm(c, "br_grad_sumsq", 2.0 * count * B, gbytes);
+          if (!hip_ok(c, br_launch_sumsq(c->stream, pb, B, count, g.gdt == BR_BF16, partials, slot), "sumsq launch")) return BR_ERR_HIP;
+        } else {
+          Timed tm(c, "br_scale_inplace", 1.0 * count * B, 2.0 * gbytes);
+          if (!hip_ok(c, br_launch_scale_inplace(c->stream, pb, B, count, g.gdt == BR_BF16, c->clip_result), "scale launch")) return BR_ERR_HIP;
+        }
+        slot += B * BR_CLIP_BLOCKS;
+      }
+    }
+    if (pass == 0 && !hip_ok(c, br_launch_clip_finalize(c->stream, partials, slot, max_norm, c->clip_result), "clip finalize launch")) return BR_ERR_HIP;
   }
   return BR_OK;
 }

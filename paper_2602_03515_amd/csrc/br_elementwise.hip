@@ -214,6 +214,68 @@ __global__ __launch_bounds__(256) void br_adam_plain(BrPtrBatch p, ShadowPtrs sh
   }
 }
 
+// in0 = gradient (f32 or bf16); one partial per workgroup at partials[slot0 + blockIdx.y * gridDim.x + blockIdx.x]
+__global__ __launch_bounds__(256) void br_grad_sumsq(BrPtrBatch p, int64_t count, int grad_bf16, float* partials, int slot0) {
+  __shared__ float red[4];
+  const void* __restrict__ G = p.in0[blockIdx.y];
+  const int64_t n4 = count >> 2;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  float s = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    float4 g = load_grad4(G, i, grad_bf16);
+    s += (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w);
+  }
+  if (blockIdx.x == 0) {
+    for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
+      float g = load_grad1(G, i, grad_bf16);
+      s += g * g;
+    }
+  }
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) partials[slot0 + blockIdx.y * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void br_clip_finalize(const float* __restrict__ partials, int n, float max_norm,
+                                                        float* __restrict__ result) {
+  __shared__ float red[4];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += partials[i];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float norm = sqrtf((red[0] + red[1]) + (red[2] + red[3]));
+    const float f = max_norm / (norm + 1e-6f);
+    result[0] = norm;
+    result[1] = f < 1.0f ? f : 1.0f;
+  }
+}
+
+__global__ __launch_bounds__(256) void br_scale_inplace(BrPtrBatch p, int64_t count, int grad_bf16,
+                                                        const float* __restrict__ result) {
+  const float f = result[1];
+  if (f >= 1.0f) return;  // nothing to clip: leave the gradients untouched
+  void* G = p.out0[blockIdx.y];
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  if (grad_bf16) {
+    uint16_t* g = reinterpret_cast<uint16_t*>(G);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
+      g[i] = f32_to_bf16_rne(f * bf16_bits_to_f32(g[i]));
+  } else {
+    float* g = reinterpret_cast<float*>(G);
+    const int64_t n4 = count >> 2;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+      float4 v = reinterpret_cast<float4*>(g)[i];
+      v.x *= f; v.y *= f; v.z *= f; v.w *= f;
+      reinterpret_cast<float4*>(g)[i] = v;
+    }
+    if (blockIdx.x == 0)
+      for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) g[i] *= f;
+  }
+}
+
 struct MatPtrs {
   float* p[BR_MAXB];
 };
@@ -274,6 +336,26 @@ hipError_t br_launch_adam_plain(hipStream_t s, const BrPtrBatch& p, uint16_t* co
   for (int i = 0; i < BR_MAXB; ++i) sh.p[i] = (i < batch) ? shadow[i] : nullptr;
   dim3 grid(br::grid_for(count, batch), batch);
   hipLaunchKernelGGL(br::br_adam_plain, grid, dim3(256), 0, s, p, sh, count, a);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_sumsq(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16, float* partials,
+                           int slot0) {
+  if (batch <= 0 || count <= 0) return hipSuccess;
+  hipLaunchKernelGGL(br::br_grad_sumsq, dim3(BR_CLIP_BLOCKS, batch), dim3(256), 0, s, p, count, grad_bf16, partials, slot0);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_clip_finalize(hipStream_t s, const float* partials, int n_partials, float max_norm, float* result) {
+  hipLaunchKernelGGL(br::br_clip_finalize, dim3(1), dim3(256), 0, s, partials, n_partials, max_norm, result);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_scale_inplace(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16,
+                                   const float* result) {
+  if (batch <= 0 || count <= 0) return hipSuccess;
+  dim3 grid(br::grid_for(grad_bf16 ? count : count / 4 + 1, batch), batch);
+  hipLaunchKernelGGL(br::br_scale_inplace, grid, dim3(256), 0, s, p, count, grad_bf16, result);
   return hipGetLastError();
 }
 

@@ -6,7 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#define BR_MAXB 32  // matrices handled by one batched launch (pointers travel as kernel arguments)
+#define BR_MAXB 64  // matrices handled by one batched launch (pointers travel as kernel arguments)
 
 // ---- batched GEMM on FP32 matrix cores -------------------------------------------------
 // C_b = alpha * op(A_b) * op(B_b) + beta * C_b,  b = 0..batch-1, all row-major.
@@ -75,6 +75,15 @@ struct BrPlainArgs {
 hipError_t br_launch_adam_plain(hipStream_t s, const BrPtrBatch& p, uint16_t* const* shadow, int batch,
                                 int64_t count, const BrPlainArgs& a);
 
+// Global-norm clipping.  sumsq: per-(matrix, block) partial sums of squares into partials[slot0 + b*blocks + x];
+// finalize: fixed-order sum of n_partials values -> result[0] = norm, result[1] = min(1, max_norm/(norm+1e-6));
+// scale: G <- result[1] * G in place (no-op pass when the factor is 1).
+#define BR_CLIP_BLOCKS 64
+hipError_t br_launch_sumsq(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16, float* partials,
+                           int slot0);
+hipError_t br_launch_clip_finalize(hipStream_t s, const float* partials, int n_partials, float max_norm, float* result);
+hipError_t br_launch_scale_inplace(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16,
+                                   const float* result);
 hipError_t br_launch_set_identity(hipStream_t s, float* const* mats, int batch, int n);
 hipError_t br_launch_bf16_to_f32(hipStream_t s, const uint16_t* src, float* dst, int64_t count);
 

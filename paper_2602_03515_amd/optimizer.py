@@ -42,6 +42,16 @@ class BasisRotationAdam:
         self._check_grads(grads)
         B.br_accumulate_stats(self.ctx, [g.data_ptr() for g in grads])
 
+    def clip_gradients(self, grads: Sequence[torch.Tensor], max_norm: float) -> None:
+        """Global-norm clipping of the stage's gradients, in place, on the device."""
+        self._check_grads(grads)
+        B.br_clip_gradients(self.ctx, [g.data_ptr() for g in grads], float(max_norm))
+
+    def clip_result(self) -> torch.Tensor:
+        """Device tensor [global norm, applied factor] of the latest clip_gradients call."""
+        off = B.br_get_clip_result(self.ctx) - self.workspace.data_ptr()
+        return self.workspace[off:off + 8].view(torch.float32)
+
     def refresh_basis(self) -> None:
         B.br_refresh_basis(self.ctx)
 
@@ -50,8 +60,11 @@ class BasisRotationAdam:
         B.br_step(self.ctx, [p.data_ptr() for p in self.params], [g.data_ptr() for g in grads],
                   self.lr if lr is None else float(lr))
 
-    def step(self, grads: Sequence[torch.Tensor], lr: Optional[float] = None) -> None:
+    def step(self, grads: Sequence[torch.Tensor], lr: Optional[float] = None,
+             max_grad_norm: Optional[float] = None) -> None:
         t = self.step_count + 1
+        if max_grad_norm is not None:
+            self.clip_gradients(grads, max_grad_norm)
         self.accumulate_stats(grads)
         if self.freq > 0 and t % self.freq == 0:
             self.refresh_basis()

@@ -44,7 +44,7 @@ def test_workspace_state_bytes_follow_memory_table(B):
                             cache_rotated_moment=0)
         for shape, printed in (((4096, 4096), float(attn)), ((4096, 14336), float(mlp))):
             state, scratch = B.br_workspace_bytes(B.make_descs([shape]), hp)
-            extra = state - 2 * shape[0] * shape[1] * 4 - 256
+            extra = state - 2 * shape[0] * shape[1] * 4 - 512
             assert abs(extra / 2 ** 30 - printed) <= 0.0051, (source, geometry, shape, extra / 2 ** 30)
             assert scratch > 0
     # transposed MLP shape under unilateral rotation keeps the 4096-side factor
@@ -55,7 +55,7 @@ def test_workspace_state_bytes_follow_memory_table(B):
     # BF16 parameters add an FP32 master copy; unrotated tensors add nothing beyond Adam
     s32, _ = B.br_workspace_bytes(B.make_descs([(512, 256, B.BR_F32, B.BR_F32, 0)]), uni)
     s16, _ = B.br_workspace_bytes(B.make_descs([(512, 256, B.BR_BF16, B.BR_BF16, 0)]), uni)
-    assert s32 == 2 * 512 * 256 * 4 + 256 and s16 == 3 * 512 * 256 * 4 + 256
+    assert s32 == 2 * 512 * 256 * 4 + 512 and s16 == 3 * 512 * 256 * 4 + 512
     # the optional cache of the rotated first moment costs one more m x n buffer per rotated matrix
     on, _ = B.br_workspace_bytes(B.make_descs([(512, 256)]), B.make_hparams(cache_rotated_moment=1))
     off, _ = B.br_workspace_bytes(B.make_descs([(512, 256)]), B.make_hparams(cache_rotated_moment=0))
@@ -67,7 +67,7 @@ def test_stage_state_bytes_3b_class():
     state, scratch = B.br_workspace_bytes(B.make_descs(synth.STAGE_3B), B.make_hparams(cache_rotated_moment=0))
     closed_form = sum(4 * (2 * m * n + 2 * m * m + 2 * n * n) for m, n in synth.STAGE_3B)
     assert abs(closed_form - 18.86e9) < 0.01e9
-    assert 0 <= state - closed_form <= 56 * 256 * 8
+    assert 0 <= state - closed_form <= 56 * 256 * 8 + 256
     cached, _ = B.br_workspace_bytes(B.make_descs(synth.STAGE_3B), B.make_hparams(cache_rotated_moment=1))
     assert cached - state == 4 * sum(m * n for m, n in synth.STAGE_3B)
 
@@ -135,3 +135,22 @@ def test_delay_ring_indexing():
     assert r0.stale() == "W1"
     with pytest.raises(ValueError):
         GradientRing(-1)
+
+
+def test_stage_aware_refresh_periods_keep_the_budget():
+    """Budgets proportional to the delay, same total as the uniform schedule."""
+    from oracle import br_oracle as oc
+    from paper_2602_03515_amd.schedule import refresh_due, stage_refresh_periods
+    P, f0 = 8, 10
+    delays = [P - 1 - k for k in range(P)]            # stage k waits K - k updates
+    exact = oc.stage_refresh_periods(delays, f0)
+    assert abs(sum(1.0 / p for p in exact if p > 0) - P / f0) < 1e-12
+    ratios = [(1.0 / exact[k]) / delays[k] for k in range(P) if delays[k] > 0]
+    assert max(ratios) - min(ratios) < 1e-12
+    got = stage_refresh_periods(delays, f0)
+    assert got[-1] == 0 and all(g >= 1 for g in got[:-1])
+    assert got == [0 if e == 0 else max(1, round(e)) for e in exact]
+    assert got == sorted(got[:-1]) + [0]             # longer delay, shorter period
+    assert stage_refresh_periods([3, 3, 3], 10) == [10, 10, 10]
+    assert stage_refresh_periods([0, 0], 7) == [7, 7]
+    assert [t for t in range(1, 13) if refresh_due(t, 4)] == [4, 8, 12] and not refresh_due(5, 0)

@@ -309,3 +309,41 @@ def test_error_paths_leave_kernels_unlaunched(harness):
     B.br_step(opt.ctx, [W.data_ptr()], [g.data_ptr()], 1e-3)
     torch.cuda.synchronize()
     assert torch.isfinite(W).all() and opt.step_count == 1
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_global_norm_clipping(harness, bf16):
+    """Clipping before the step: norm and factor against the oracle, gradients rescaled in place,
+    and the clipped trajectory follows the oracle fed with the oracle's clipped gradients."""
+    shapes = [(96, 64), (64, 96), (33, 17), (96, 64)]
+    W0s, seqs = [], []
+    for k, (m, n) in enumerate(shapes):
+        W0, grads = synth.spiked_gradients(seed=300 + k, m=m, n=n, steps=3, noise_std=0.1)
+        if bf16:
+            W0, grads = synth.to_bf16_f32(W0), [synth.to_bf16_f32(g) for g in grads]
+        W0s.append(W0)
+        seqs.append(grads)
+    sb = harness.SideBySide(W0s, freq=2, lr=1e-3, bf16_params=bf16, bf16_grads=bf16)
+    for t in range(3):
+        host = [seqs[k][t] for k in range(len(shapes))]
+        max_norm = 1.0 if t < 2 else 1e4                       # last step: nothing to clip
+        ref, norm, factor = oc.clip_by_global_norm(host, max_norm)
+        if bf16:
+            ref = [oc.bf16_round(r) for r in ref]
+        dev = [harness.to_dev(g, bf16) for g in host]
+        sb.opt.clip_gradients(dev, max_norm)
+        res = harness.to_np(sb.opt.clip_result())
+        assert abs(res[0] - norm) <= 1e-5 * norm and abs(res[1] - factor) <= 1e-5
+        for d, r, h0 in zip(dev, ref, host):
+            got = harness.to_np(d)
+            if t == 2:
+                assert np.array_equal(got, np.asarray(h0, dtype=np.float64))   # factor 1: untouched
+            elif bf16:
+                assert np.abs(got - r).max() <= 2.0 ** -7 * np.abs(r).max() and (got != r).mean() < 0.01
+            else:
+                assert rel_err(got, r) <= 1e-6
+        sb.opt.step(dev, sb.lr)
+        torch.cuda.synchronize()
+        for i, st in enumerate(sb.states):
+            sb.W_ref[i] = oc.optimizer_step(st, sb.W_ref[i], harness.to_np(dev[i]), sb.lr, sb.hp, sb.freq, sb.qr)
+    sb.compare_state(TOL)

@@ -379,3 +379,18 @@ def test_first_moment_source_uses_momentum_gram():
         G = 3.0 * np.outer(u, v) + 0.01 * rng.standard_normal((9, 6))
         W = oc.optimizer_step(st, W, G, 1e-3, hp, freq=2)
     assert abs(st.QL[:, 0] @ u) > 0.999 and abs(st.QR[:, 0] @ v) > 0.999
+
+
+def test_global_norm_clipping_matches_torch():
+    rng = np.random.default_rng(90)
+    grads = [rng.standard_normal((5, 7)), rng.standard_normal((3, 2)) * 4.0]
+    for max_norm in (1.0, 1e3):
+        params = [torch.nn.Parameter(torch.zeros(g.shape, dtype=torch.float64)) for g in grads]
+        for p, g in zip(params, grads):
+            p.grad = torch.tensor(g)
+        total = torch.nn.utils.clip_grad_norm_(params, max_norm)
+        out, norm, factor = oc.clip_by_global_norm(grads, max_norm)
+        assert abs(norm - float(total)) < 1e-12
+        for p, o in zip(params, out):
+            assert np.abs(p.grad.numpy() - o).max() < 1e-14
+        assert (factor < 1.0) == (max_norm == 1.0)
