@@ -18,7 +18,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"f32": 157.3}   # MI355X dense FP32 matrix-core peak
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # MI355X dense matrix-core peaks (FP32, BF16)
+MATH = {"f32": 0, "bf16": 1, "bf16x3": 2}
 PEAK_HBM_GBS = 8000.0
 TAU = 3
 FREQ = 10
@@ -112,6 +113,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="stage3b")
+    ap.add_argument("--math", default="f32", choices=sorted(MATH),
+                    help="input precision of the step's contractions: f32 (FP32 MFMA, default), "
+                         "bf16x3 (hi+lo BF16 split, same 1e-4 bar), bf16 (2e-2 bar)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that HBM byte counters "
@@ -133,7 +137,7 @@ def main():
     shapes, desc = workload(args.workload)
     n_params = sum(m * n for m, n in shapes)
     params, ring = make_inputs(shapes, TAU + 1, seed=2, device=dev)
-    opt = BasisRotationAdam(params, freq=FREQ, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8)
+    opt = BasisRotationAdam(params, freq=FREQ, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, math=MATH[args.math])
     torch.cuda.synchronize()
 
     if args.copy_calibration:
@@ -167,8 +171,9 @@ def main():
     if dom:
         avg_ms = dom["ms"] / dom["launches"]
         achieved = dom["flops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": achieved, "peak": PEAK_TFLOPS["f32"],
-                    "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS["f32"],
+        peak = PEAK_TFLOPS["bf16" if "bf16" in dom["kernel"] else "f32"]
+        roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": achieved, "peak": peak,
+                    "unit": "TFLOP/s", "frac": achieved / peak,
                     "traffic": counter_traffic(args.workload) if dom["kernel"].endswith("<nn>") else None,
                     "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
                     "launches": dom["launches"], "avg_launch_ms": avg_ms}
@@ -183,11 +188,11 @@ def main():
         "steps_per_s": args.steps / elapsed,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": args.math, "data": "synthetic",
         "config": {"workload": f"{args.workload}: {desc}", "params": n_params, "geometry": "bilateral",
                    "source": "second", "refresh_every": FREQ, "refreshes_in_timed_region": refreshes,
                    "power_iters": 1, "delay_tau": TAU, "param_dtype": "f32", "grad_dtype": "f32",
-                   "math": "fp32 MFMA", "state_bytes": opt.state_bytes, "scratch_bytes": opt.scratch_bytes},
+                   "math": {"f32": "fp32 MFMA", "bf16": "bf16 MFMA", "bf16x3": "bf16 MFMA, hi+lo split (3 products)"}[args.math], "state_bytes": opt.state_bytes, "scratch_bytes": opt.scratch_bytes},
         "roofline": roofline,
         "kernels": breakdown,
     }

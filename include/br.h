@@ -70,7 +70,11 @@ typedef enum { BR_BILATERAL = 0, BR_UNILATERAL = 1 } br_geometry;
  * M M^T and M^T M at refresh time and keeps no statistics buffers (lines 11-19). */
 typedef enum { BR_SRC_SECOND = 0, BR_SRC_FIRST = 1 } br_source;
 
-/* Input precision of the matrix-core contractions.  F32 issues FP32 MFMA. */
+/* Input precision of the step's matrix-core contractions (statistics, rotations, rotate-back).
+ * F32 issues FP32 MFMA.  BF16 rounds both operands to BF16 (parity bar 2e-2).  BF16X3 splits
+ * each FP32 operand into hi + lo BF16 parts and adds the products hi*hi + hi*lo + lo*hi in FP32:
+ * 16-bit mantissa inputs, same 1e-4 bar as F32, about a fifth of the matrix-core time.  The
+ * refresh (L Q product and the QR) always runs in FP32. */
 typedef enum { BR_MATH_F32 = 0, BR_MATH_BF16 = 1, BR_MATH_BF16X3 = 2 } br_math;
 
 /* Which buffer br_get_state returns. */

@@ -16,7 +16,8 @@
 namespace {
 
 constexpr int kStepChunk = 32;     // matrices per batched step launch ([G|M] doubles it to BR_MAXB)
-constexpr int kRefreshChunk = 64;  // factor matrices per batched refresh launch
+constexpr int kRefreshChunk = 64;
+constexpr int kLowpChunk = 16;     // matrices per batched step launch in the BF16 math modes  // factor matrices per batched refresh launch
 constexpr int64_t kMaxDim = 1 << 24;
 constexpr size_t kNormPartialBytes = (size_t)BR_MAXB * 2 * BR_NORM_BLOCKS * sizeof(float);
 constexpr size_t kSplitKBytes = (size_t)64 << 20;  // partial products of the QR's split-K contractions
@@ -102,7 +103,6 @@ br_status validate(const br_matrix_desc* descs, int32_t n_mats, const br_hparams
   if (hp->geometry != BR_BILATERAL && hp->geometry != BR_UNILATERAL) { *why = "unknown geometry"; return BR_ERR_INVALID_ARG; }
   if (hp->source != BR_SRC_SECOND && hp->source != BR_SRC_FIRST) { *why = "unknown source"; return BR_ERR_INVALID_ARG; }
   if (hp->math != BR_MATH_F32 && hp->math != BR_MATH_BF16 && hp->math != BR_MATH_BF16X3) { *why = "unknown math mode"; return BR_ERR_INVALID_ARG; }
-  if (hp->math != BR_MATH_F32) { *why = "only BR_MATH_F32 is implemented"; return BR_ERR_UNSUPPORTED; }
   if (hp->power_iters < 1 || hp->power_iters > 8) { *why = "power_iters must be in 1..8"; return BR_ERR_INVALID_ARG; }
   if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f)) { *why = "beta1/beta2 must be in [0,1)"; return BR_ERR_INVALID_ARG; }
   if (!(hp->stat_beta < 1.f)) { *why = "stat_beta must be below 1 (negative selects beta2)"; return BR_ERR_INVALID_ARG; }
@@ -127,6 +127,29 @@ int step_buffers(const Group& g, const br_hparams& hp) {
   else if (g.rot_l || g.rot_r) nb = hp.cache_rotated_moment ? 1 : 2;
   if (g.gdt == BR_BF16 && (g.rot_l || g.rot_r)) nb += 1;
   return nb;
+}
+
+// Scratch of one matrix during a step in the BF16 math modes.  Eleven slots, each large enough for
+// an m x n FP32 matrix or for a pair of BF16 planes of it (either orientation, rows padded to a
+// multiple of 8), followed by the planes of the bases in both orientations.
+inline int ldp8(int64_t k) { return (int)((k + 7) & ~(int64_t)7); }
+enum { LS_GP = 0, LS_GTP, LS_T1, LS_T1P, LS_GX, LS_XP, LS_MP, LS_T2, LS_T2P, LS_MROT, LS_G32, LS_COUNT };
+struct LowpLayout {
+  size_t slot, qlp, qlt, qrp, qrt, per_mat;
+};
+LowpLayout lowp_layout(const Group& g) {
+  LowpLayout l;
+  const size_t a = (size_t)g.m * ldp8(g.n), b = (size_t)g.n * ldp8(g.m);
+  l.slot = align256(4 * std::max(a, b));
+  size_t off = LS_COUNT * l.slot;
+  const size_t ql = g.rot_l ? align256(4 * (size_t)g.m * ldp8(g.m)) : 0;
+  const size_t qr = g.rot_r ? align256(4 * (size_t)g.n * ldp8(g.n)) : 0;
+  l.qlp = off; off += ql;
+  l.qlt = off; off += ql;
+  l.qrp = off; off += qr;
+  l.qrt = off; off += qr;
+  l.per_mat = off;
+  return l;
 }
 
 struct RefreshScratch {
@@ -185,6 +208,8 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
   for (auto& g : lay->groups) {
     size_t chunk = std::min<size_t>(g.idx.size(), kStepChunk);
     size_t need = chunk * step_buffers(g, hp) * align256((size_t)g.m * g.n * 4);
+    if (hp.math != BR_MATH_F32 && (g.rot_l || g.rot_r))
+      need = std::min<size_t>(g.idx.size(), kLowpChunk) * lowp_layout(g).per_mat;
     scratch = std::max(scratch, need);
   }
   for (auto& kv : lay->refresh) {
@@ -250,6 +275,154 @@ bool gemm(br_ctx* c, BrGemmArgs a, const BrGemmBatch& b, bool step = true, float
 
 inline float* scratch_buf(br_ctx* c, size_t per_mat_bufs, size_t bytes_each, int mat_in_chunk, int which) {
   return reinterpret_cast<float*>(c->scratch + kNormPartialBytes + ((size_t)mat_in_chunk * per_mat_bufs + which) * bytes_each);
+}
+
+
+// ---- BF16 math modes: operand planes and contractions -------------------------------------------
+struct LowpCtx {
+  br_ctx* c;
+  const Group* g;
+  LowpLayout lay;
+  int B;
+  int nprod;
+  char* base;  // scratch of this chunk
+  uint16_t* slot16(int i, int s) const { return reinterpret_cast<uint16_t*>(base + (size_t)i * lay.per_mat + (size_t)s * lay.slot); }
+  float* slot32(int i, int s) const { return reinterpret_cast<float*>(base + (size_t)i * lay.per_mat + (size_t)s * lay.slot); }
+  uint16_t* qplane(int i, size_t off) const { return reinterpret_cast<uint16_t*>(base + (size_t)i * lay.per_mat + off); }
+};
+
+// planes of the R x C matrices src[i] (row stride C), optionally transposed
+bool lowp_split(const LowpCtx& x, const float* const* src, int R, int Ccols, bool transpose, uint16_t* const* dst) {
+  const int ldp = transpose ? ldp8(R) : ldp8(Ccols);
+  const size_t plane = (size_t)(transpose ? Ccols : R) * ldp;
+  Timed tm(x.c, "br_split_planes", 0.0, (double)R * Ccols * x.B * (4.0 + (x.nprod == 3 ? 4.0 : 2.0)));
+  return hip_ok(x.c, br_launch_split_planes(x.c->stream, src, dst, x.B, R, Ccols, Ccols, transpose ? 1 : 0, ldp, plane,
+                                            x.nprod == 3 ? 1 : 0), "plane split launch");
+}
+
+// C_i = alpha A_i B_i^T + beta C_i with A_i: M x K planes, B_i: N x K planes
+bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp, int N, int K, float* const* C, int ldc,
+               float alpha, float beta, uint16_t* const* shadow, bool mirror, int nprod = 0) {
+  if (nprod == 0) nprod = x.nprod;
+  BrLowpBatch b;
+  std::memset(&b, 0, sizeof(b));
+  for (int i = 0; i < x.B; ++i) {
+    b.A[i] = A[i];
+    b.B[i] = Bp[i];
+    b.C[i] = C[i];
+    b.shadow[i] = shadow ? shadow[i] : nullptr;
+  }
+  const int ldk = ldp8(K);
+  BrLowpArgs a{M, N, ldk, ldk, ldk, ldc, (size_t)M * ldk, (size_t)N * ldk, alpha, beta, x.B, mirror ? 1 : 0, nprod};
+  double flops = 2.0 * M * N * (double)K * x.B;
+  if (mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (M + 127) / 128));
+  const char* name = nullptr;
+  (void)br_launch_gemm_lowp(nullptr, BrLowpArgs{0, 0, 0, 8, 8, 0, 0, 0, 0.f, 0.f, 0, 0, nprod}, b, &name);
+  Timed tm(x.c, name, flops, 0.0);
+  return hip_ok(x.c, br_launch_gemm_lowp(x.c->stream, a, b, nullptr), "bf16 gemm launch");
+}
+
+// a2 in the BF16 modes for one chunk: L <- b L + (1-b) G G^T, R <- b R + (1-b) G^T G
+bool lowp_stats(const LowpCtx& x, const float* const* G32, size_t off) {
+  const Group& g = *x.g;
+  const br_hparams& hp = x.c->hp;
+  const int m = (int)g.m, n = (int)g.n;
+  uint16_t* pl[BR_MAXB];
+  float* out[BR_MAXB];
+  if (g.rot_l) {
+    for (int i = 0; i < x.B; ++i) { pl[i] = x.slot16(i, LS_GP); out[i] = x.c->mats[g.idx[off + i]].L; }
+    if (!lowp_split(x, G32, m, n, false, pl)) return false;
+    if (!lowp_gemm(x, pl, m, pl, m, n, out, m, 1.0f - hp.stat_beta, hp.stat_beta, nullptr, true, x.nprod == 3 ? 4 : 1)) return false;
+  }
+  if (g.rot_r) {
+    for (int i = 0; i < x.B; ++i) { pl[i] = x.slot16(i, LS_GTP); out[i] = x.c->mats[g.idx[off + i]].R; }
+    if (!lowp_split(x, G32, m, n, true, pl)) return false;
+    if (!lowp_gemm(x, pl, n, pl, n, m, out, n, 1.0f - hp.stat_beta, hp.stat_beta, nullptr, true, x.nprod == 3 ? 4 : 1)) return false;
+  }
+  return true;
+}
+
+// a4-a6 in the BF16 modes for one chunk.  Every contraction is A B^T on planes with k contiguous;
+// the transposed operands come from the split kernel.
+bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* const* Wp, uint16_t* const* shadow,
+               float* const* Mt, bool advance, const BrAdamArgs& aa, float lr, float decay, float* partials) {
+  br_ctx* c = x.c;
+  const Group& g = *x.g;
+  const int m = (int)g.m, n = (int)g.n, B = x.B;
+  const int64_t count = g.m * g.n;
+  uint16_t *QLp[BR_MAXB], *QLt[BR_MAXB], *QRp[BR_MAXB], *QRt[BR_MAXB];
+  uint16_t *P0[BR_MAXB], *P1[BR_MAXB];
+  const float* src[BR_MAXB];
+  float* dst[BR_MAXB];
+  float* GX[BR_MAXB];
+  for (int i = 0; i < B; ++i) {
+    QLp[i] = x.qplane(i, x.lay.qlp); QLt[i] = x.qplane(i, x.lay.qlt);
+    QRp[i] = x.qplane(i, x.lay.qrp); QRt[i] = x.qplane(i, x.lay.qrt);
+    GX[i] = x.slot32(i, LS_GX);
+  }
+  if (g.rot_l) {
+    for (int i = 0; i < B; ++i) src[i] = c->mats[g.idx[off + i]].QL;
+    if (!lowp_split(x, src, m, m, false, QLp) || !lowp_split(x, src, m, m, true, QLt)) return false;
+  }
+  if (g.rot_r) {
+    for (int i = 0; i < B; ++i) src[i] = c->mats[g.idx[off + i]].QR;
+    if (!lowp_split(x, src, n, n, false, QRp) || !lowp_split(x, src, n, n, true, QRt)) return false;
+  }
+  // rotate one m x n matrix (FP32 sources `in`) into `out`
+  auto rotate_in = [&](const float* const* in, float* const* out, int s_t, int s_tp, int s_plane) -> bool {
+    if (g.rot_l && g.rot_r) {
+      for (int i = 0; i < B; ++i) { P0[i] = x.slot16(i, s_plane); dst[i] = x.slot32(i, s_t); }
+      if (!lowp_split(x, in, m, n, true, P0)) return false;                                   // in^T planes [n][m]
+      if (!lowp_gemm(x, QLt, m, P0, n, m, dst, n, 1.f, 0.f, nullptr, false)) return false;     // T = Q_L^T in
+      for (int i = 0; i < B; ++i) { P1[i] = x.slot16(i, s_tp); src[i] = x.slot32(i, s_t); }
+      if (!lowp_split(x, src, m, n, false, P1)) return false;                                 // T planes [m][n]
+      return lowp_gemm(x, P1, m, QRt, n, n, out, n, 1.f, 0.f, nullptr, false);                // out = T Q_R
+    }
+    if (g.rot_l) {
+      for (int i = 0; i < B; ++i) P0[i] = x.slot16(i, s_plane);
+      if (!lowp_split(x, in, m, n, true, P0)) return false;
+      return lowp_gemm(x, QLt, m, P0, n, m, out, n, 1.f, 0.f, nullptr, false);                // out = Q_L^T in
+    }
+    for (int i = 0; i < B; ++i) P0[i] = x.slot16(i, s_plane);
+    if (!lowp_split(x, in, m, n, false, P0)) return false;
+    return lowp_gemm(x, P0, m, QRt, n, n, out, n, 1.f, 0.f, nullptr, false);                  // out = in Q_R
+  };
+  if (!rotate_in(G32, GX, LS_T1, LS_T1P, g.rot_l ? LS_GTP : LS_GP)) return false;
+  if (!advance) {
+    for (int i = 0; i < B; ++i) src[i] = c->mats[g.idx[off + i]].M;
+    const float* msrc[BR_MAXB];
+    for (int i = 0; i < B; ++i) msrc[i] = src[i];
+    if (!rotate_in(msrc, Mt, LS_T2, LS_T2P, LS_MP)) return false;
+  }
+  {
+    BrAdamBatch ab;
+    std::memset(&ab, 0, sizeof(ab));
+    for (int i = 0; i < B; ++i) {
+      const MatState& ms = c->mats[g.idx[off + i]];
+      ab.GX[i] = GX[i];
+      ab.S[i] = ms.S;
+      ab.Mrot[i] = Mt[i];
+      ab.norms[i] = ms.norms;
+    }
+    Timed tm(c, "br_adam_rotated", 8.0 * count * B, (advance ? 24.0 : 20.0) * count * B);
+    if (!hip_ok(c, br_launch_adam_rotated(c->stream, ab, B, count, aa, partials), "rotated adam launch")) return false;
+  }
+  // rotate back and apply: W <- decay W - lr Q_L X Q_R^T
+  for (int i = 0; i < B; ++i) { src[i] = GX[i]; P0[i] = x.slot16(i, LS_XP); }
+  if (g.rot_l && g.rot_r) {
+    if (!lowp_split(x, src, m, n, true, P0)) return false;                                    // X^T planes [n][m]
+    for (int i = 0; i < B; ++i) dst[i] = x.slot32(i, LS_T1);
+    if (!lowp_gemm(x, QLp, m, P0, n, m, dst, n, 1.f, 0.f, nullptr, false)) return false;       // Y = Q_L X
+    for (int i = 0; i < B; ++i) { src[i] = x.slot32(i, LS_T1); P1[i] = x.slot16(i, LS_T1P); }
+    if (!lowp_split(x, src, m, n, false, P1)) return false;
+    return lowp_gemm(x, P1, m, QRp, n, n, Wp, n, -lr, decay, shadow, false);                  // W -= lr Y Q_R^T
+  }
+  if (g.rot_l) {
+    if (!lowp_split(x, src, m, n, true, P0)) return false;
+    return lowp_gemm(x, QLp, m, P0, n, m, Wp, n, -lr, decay, shadow, false);                  // W -= lr Q_L X
+  }
+  if (!lowp_split(x, src, m, n, false, P0)) return false;
+  return lowp_gemm(x, P0, m, QRp, n, n, Wp, n, -lr, decay, shadow, false);                    // W -= lr X Q_R^T
 }
 
 }  // namespace
@@ -458,8 +631,12 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
     const int nbuf = step_buffers(g, hp);
     const bool rotated = g.rot_l || g.rot_r;
     const bool need_g32 = rotated && g.gdt == BR_BF16;
-    for (size_t off = 0; off < g.idx.size(); off += kStepChunk) {
-      const int B = (int)std::min<size_t>(kStepChunk, g.idx.size() - off);
+    const bool lowp = rotated && hp.math != BR_MATH_F32;
+    const size_t chunk = lowp ? kLowpChunk : kStepChunk;
+    for (size_t off = 0; off < g.idx.size(); off += chunk) {
+      const int B = (int)std::min<size_t>(chunk, g.idx.size() - off);
+      LowpCtx lx{c, &g, lowp ? lowp_layout(g) : LowpLayout{}, B, hp.math == BR_MATH_BF16X3 ? 3 : 1,
+                 c->scratch + kNormPartialBytes};
       BrPtrBatch pb;
       std::memset(&pb, 0, sizeof(pb));
       const float* g32[kStepChunk];
@@ -467,7 +644,7 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
         const MatState& m = c->mats[g.idx[off + i]];
         pb.in0[i] = grads[g.idx[off + i]];
         pb.out0[i] = m.M;
-        pb.out1[i] = need_g32 ? scratch_buf(c, nbuf, mn, i, nbuf - 1) : nullptr;
+        pb.out1[i] = !need_g32 ? nullptr : (lowp ? lx.slot32(i, LS_G32) : scratch_buf(c, nbuf, mn, i, nbuf - 1));
         g32[i] = need_g32 ? reinterpret_cast<const float*>(pb.out1[i]) : reinterpret_cast<const float*>(grads[g.idx[off + i]]);
       }
       {
@@ -476,6 +653,10 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
         if (!hip_ok(c, br_launch_ema(c->stream, pb, B, count, g.gdt == BR_BF16, hp.beta1), "first-moment launch")) return BR_ERR_HIP;
       }
       if (hp.source != BR_SRC_SECOND || !rotated) continue;
+      if (lowp) {
+        if (!lowp_stats(lx, g32, off)) return BR_ERR_HIP;
+        continue;
+      }
       BrGemmBatch gb;
       std::memset(&gb, 0, sizeof(gb));
       if (g.rot_l) {  // L <- b L + (1-b) G G^T
@@ -680,8 +861,12 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
     const int m = (int)g.m, n = (int)g.n;
     // scratch slots
     const int sT1 = 0, sGt = bilateral ? 1 : 0, sT2 = 2, sMt = bilateral ? 3 : 1;
-    for (size_t off = 0; off < g.idx.size(); off += kStepChunk) {
-      const int B = (int)std::min<size_t>(kStepChunk, g.idx.size() - off);
+    const bool lowp = rotated && hp.math != BR_MATH_F32;
+    const size_t chunk = lowp ? kLowpChunk : kStepChunk;
+    for (size_t off = 0; off < g.idx.size(); off += chunk) {
+      const int B = (int)std::min<size_t>(chunk, g.idx.size() - off);
+      LowpCtx lx{c, &g, lowp ? lowp_layout(g) : LowpLayout{}, B, hp.math == BR_MATH_BF16X3 ? 3 : 1,
+                 c->scratch + kNormPartialBytes};
       float* Wp[kStepChunk];         // FP32 weights that receive the update
       uint16_t* shadow[kStepChunk];  // BF16 parameter image, or null
       const float* G32[kStepChunk];
@@ -720,12 +905,18 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
       for (int i = 0; i < B; ++i) {
         const void* gp = grads[g.idx[off + i]];
         if (g.gdt == BR_BF16) {
-          float* dst = scratch_buf(c, nbuf, mn, i, nbuf - 1);
+          float* dst = lowp ? lx.slot32(i, LS_G32) : scratch_buf(c, nbuf, mn, i, nbuf - 1);
           if (!hip_ok(c, br_launch_bf16_to_f32(c->stream, reinterpret_cast<const uint16_t*>(gp), dst, count), "gradient widen")) return BR_ERR_HIP;
           G32[i] = dst;
         } else {
           G32[i] = reinterpret_cast<const float*>(gp);
         }
+      }
+      if (lowp) {
+        float* Mtl[kStepChunk];
+        for (int i = 0; i < B; ++i) Mtl[i] = cached ? c->mats[g.idx[off + i]].Mrot : lx.slot32(i, LS_MROT);
+        if (!lowp_step(lx, off, G32, Wp, shadow, Mtl, advance, aa, lr, decay, partials)) return BR_ERR_HIP;
+        continue;
       }
       BrGemmBatch gb;
       std::memset(&gb, 0, sizeof(gb));

@@ -36,6 +36,29 @@ struct BrGemmArgs {
 
 hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch& b, const char** kernel_name);
 
+// ---- BF16 matrix-core contractions on pre-split operand planes ----------------------------
+// C_b = alpha * A_b B_b^T + beta * C_b with A_b: M x Kp, B_b: N x Kp BF16 "planes" (hi plane at the
+// pointer, lo plane `a_plane`/`b_plane` elements further), k contiguous, row strides lda/ldb
+// (multiples of 8).  nprod = 1 uses the hi planes only, nprod = 3 adds the two hi*lo cross terms.
+struct BrLowpBatch {
+  const uint16_t* A[BR_MAXB];
+  const uint16_t* B[BR_MAXB];
+  float* C[BR_MAXB];
+  uint16_t* shadow[BR_MAXB];
+};
+struct BrLowpArgs {
+  int M, N, Kp;
+  int lda, ldb, ldc;
+  size_t a_plane, b_plane;
+  float alpha, beta;
+  int batch, mirror, nprod;
+};
+hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name);
+// hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src); transpose != 0 writes
+// the planes of the transposed matrix.  Rows of the planes are padded with zeros to ldp (multiple of 8).
+hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
+                                  int ld_src, int transpose, int ldp, size_t plane, int want_lo);
+
 // ---- elementwise ----------------------------------------------------------------------
 struct BrPtrBatch {
   const void* in0[BR_MAXB];

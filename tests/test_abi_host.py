@@ -81,7 +81,7 @@ def test_stage_state_bytes_3b_class():
     (dict(shapes=[(4, 4)], power_iters=0), "BR_ERR_INVALID_ARG"),
     (dict(shapes=[(4, 4)], beta1=1.0), "BR_ERR_INVALID_ARG"),
     (dict(shapes=[(4, 4)], eps=-1.0), "BR_ERR_INVALID_ARG"),
-    (dict(shapes=[(4, 4)], math=1), "BR_ERR_UNSUPPORTED"),
+    (dict(shapes=[(4, 4)], math=7), "BR_ERR_INVALID_ARG"),
     (dict(shapes=[(4, 4)], cache_rotated_moment=2), "BR_ERR_INVALID_ARG"),
     (dict(shapes=[]), "BR_ERR_INVALID_ARG"),
 ])
