@@ -131,8 +131,8 @@ int step_buffers(const Group& g, const br_hparams& hp) {
 
 // Scratch of one matrix during a step in the BF16 math modes.  Eleven slots, each large enough for
 // an m x n FP32 matrix or for a pair of BF16 planes of it (either orientation, rows padded to a
-// multiple of 8), followed by the planes of the bases in both orientations.
-inline int ldp8(int64_t k) { return (int)((k + 7) & ~(int64_t)7); }
+// multiple of 32), followed by the planes of the bases in both orientations.
+inline int ldp8(int64_t k) { return (int)((k + 31) & ~(int64_t)31); }  // planes pad k to whole 32-blocks
 enum { LS_GP = 0, LS_GTP, LS_T1, LS_T1P, LS_GX, LS_XP, LS_MP, LS_T2, LS_T2P, LS_MROT, LS_G32, LS_COUNT };
 struct LowpLayout {
   size_t slot, qlp, qlt, qrp, qrt, per_mat;
@@ -313,11 +313,11 @@ bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp,
     b.shadow[i] = shadow ? shadow[i] : nullptr;
   }
   const int ldk = ldp8(K);
-  BrLowpArgs a{M, N, ldk, ldk, ldk, ldc, (size_t)M * ldk, (size_t)N * ldk, alpha, beta, x.B, mirror ? 1 : 0, nprod};
+  BrLowpArgs a{M, N, ldk, ldc, (size_t)M * ldk, (size_t)N * ldk, alpha, beta, x.B, mirror ? 1 : 0, nprod};
   double flops = 2.0 * M * N * (double)K * x.B;
   if (mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (M + 127) / 128));
   const char* name = nullptr;
-  (void)br_launch_gemm_lowp(nullptr, BrLowpArgs{0, 0, 0, 8, 8, 0, 0, 0, 0.f, 0.f, 0, 0, nprod}, b, &name);
+  (void)br_launch_gemm_lowp(nullptr, BrLowpArgs{0, 0, 0, 0, 0, 0, 0.f, 0.f, 0, 0, nprod}, b, &name);
   Timed tm(x.c, name, flops, 0.0);
   return hip_ok(x.c, br_launch_gemm_lowp(x.c->stream, a, b, nullptr), "bf16 gemm launch");
 }

@@ -38,8 +38,8 @@ hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch&
 
 // ---- BF16 matrix-core contractions on pre-split operand planes ----------------------------
 // C_b = alpha * A_b B_b^T + beta * C_b with A_b: M x Kp, B_b: N x Kp BF16 "planes" (hi plane at the
-// pointer, lo plane `a_plane`/`b_plane` elements further), k contiguous, row strides lda/ldb
-// (multiples of 8).  nprod = 1 uses the hi planes only, nprod = 3 adds the two hi*lo cross terms.
+// pointer, lo plane `a_plane`/`b_plane` elements further) in K-blocked layout: element (row, k) of an
+// R-row plane at ((k / 32) * R + row) * 32 + k % 32, Kp a multiple of 32 (zero padded).  nprod = 1 uses the hi planes only, nprod = 3 adds the two hi*lo cross terms.
 struct BrLowpBatch {
   const uint16_t* A[BR_MAXB];
   const uint16_t* B[BR_MAXB];
@@ -48,14 +48,14 @@ struct BrLowpBatch {
 };
 struct BrLowpArgs {
   int M, N, Kp;
-  int lda, ldb, ldc;
+  int ldc;
   size_t a_plane, b_plane;
   float alpha, beta;
   int batch, mirror, nprod;
 };
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name);
 // hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src); transpose != 0 writes
-// the planes of the transposed matrix.  Rows of the planes are padded with zeros to ldp (multiple of 8).
+// the planes of the transposed matrix.  k is padded with zeros to ldp (multiple of 32).
 hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
                                   int ld_src, int transpose, int ldp, size_t plane, int want_lo);
 

@@ -4,6 +4,9 @@
 //
 // Operands are first rewritten as BF16 "planes" by br_split_planes:
 //     hi = bf16(x),  lo = bf16(x - hi)            (round to nearest even)
+// stored K-BLOCKED: element (row, k) of an R-row plane sits at ((k / 32) * R + row) * 32 + k % 32,
+// so the 128 rows x 32 k that one workgroup needs per iteration are one contiguous 8 KB run of
+// whole cache lines (a row-major plane would touch half of 128 different lines instead).
 // optionally transposed, so that EVERY contraction has the form C[i][j] = sum_k A[i][k] B[j][k]
 // with k contiguous in memory for both operands: the MFMA operand of a lane (8 consecutive k of
 // one row) is then a single 16-byte load from LDS and no transposition happens in the kernel.
@@ -30,8 +33,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 struct LowpKernArgs {
-  int M, N, Kp;          // Kp: padded K (multiple of 8), the planes' logical row length
-  int lda, ldb, ldc;     // lda, ldb in BF16 elements (multiples of 8)
+  int M, N, Kp;          // Kp: padded K (multiple of 32)
+  int ldc;
   size_t a_plane, b_plane;  // distance from the hi plane to the lo plane, in elements
   float alpha, beta;
   int tiles_m, tiles_n, total_tiles, mirror;
@@ -64,8 +67,9 @@ struct Stage {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int ra = m0 + lrow + 64 * i, rb = n0 + lrow + 64 * i;
-        a[p][i] = load_chunk(Ah + p * g.a_plane + (size_t)ra * g.lda + k, ra < g.M && k < g.Kp);
-        b[p][i] = load_chunk(Bh + p * g.b_plane + (size_t)rb * g.ldb + k, rb < g.N && k < g.Kp);
+        // K-blocked plane: element (row, k) at ((k / 32) * rows + row) * 32 + k % 32
+        a[p][i] = load_chunk(Ah + p * g.a_plane + ((size_t)(k0 >> 5) * g.M + ra) * 32 + lchunk * 8, ra < g.M && k < g.Kp);
+        b[p][i] = load_chunk(Bh + p * g.b_plane + ((size_t)(k0 >> 5) * g.N + rb) * 32 + lchunk * 8, rb < g.N && k < g.Kp);
       }
     }
   }
@@ -163,15 +167,26 @@ __global__ __launch_bounds__(256, 2) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
     }
   };
 
+  // Two K tiles are in flight from global memory (one register stage each) while a third is being
+  // multiplied out of LDS: at BF16 matrix-core speed one tile of lookahead does not cover the
+  // memory latency.
   const int nkt = (g.Kp + LBK - 1) / LBK;
+  Stage<NPLANES> stg2;
   stg.fetch(Ah, Bh, g, m0, n0, 0, lrow, lchunk);
+  if (nkt > 1) stg2.fetch(Ah, Bh, g, m0, n0, LBK, lrow, lchunk);
   stg.stash(lds[0], lrow, lchunk);
   __syncthreads();
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nkt) stg.fetch(Ah, Bh, g, m0, n0, (kt + 1) * LBK, lrow, lchunk);
-    mfma_tile(cur);
-    if (kt + 1 < nkt) stg.stash(lds[cur ^ 1], lrow, lchunk);
+  for (int kt = 0; kt < nkt; kt += 2) {
+    // even tile kt: LDS stage 0; tile kt+1 waits in stg2; fetch kt+2 into stg
+    if (kt + 2 < nkt) stg.fetch(Ah, Bh, g, m0, n0, (kt + 2) * LBK, lrow, lchunk);
+    mfma_tile(0);
+    if (kt + 1 < nkt) stg2.stash(lds[1], lrow, lchunk);
+    __syncthreads();
+    if (kt + 1 >= nkt) break;
+    // odd tile kt+1: LDS stage 1; tile kt+2 waits in stg; fetch kt+3 into stg2
+    if (kt + 3 < nkt) stg2.fetch(Ah, Bh, g, m0, n0, (kt + 3) * LBK, lrow, lchunk);
+    mfma_tile(1);
+    if (kt + 2 < nkt) stg.stash(lds[0], lrow, lchunk);
     __syncthreads();
   }
 
@@ -204,7 +219,7 @@ struct SplitArgs {
   uint16_t* dst[BR_MAXB];  // hi plane; the lo plane follows at +plane elements
 };
 
-// Same orientation: dst[r][c] for an R x C source, rows padded with zeros to ldp (multiple of 8).
+// Same orientation: plane rows = source rows, k = source column, padded with zeros to ldp (multiple of 32).
 __global__ __launch_bounds__(256) void br_split_planes(SplitArgs a, int R, int Ccols, int lds_, int ldp, size_t plane,
                                                        int want_lo) {
   const float* __restrict__ X = a.src[blockIdx.y];
@@ -234,13 +249,13 @@ __global__ __launch_bounds__(256) void br_split_planes(SplitArgs a, int R, int C
       const uint16_t l1 = f32_to_bf16_rne(x[2 * e + 1] - bf16_to_f32(h1));
       lo[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
     }
-    const size_t o = (size_t)r * ldp + c0;
+    const size_t o = ((size_t)(c0 >> 5) * R + r) * 32 + (c0 & 31);
     *reinterpret_cast<uint4*>(H + o) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
     if (want_lo) *reinterpret_cast<uint4*>(H + plane + o) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
   }
 }
 
-// Transposed: dst[c][r] for an R x C source, rows of dst padded with zeros to ldp (multiple of 8).
+// Transposed: plane rows = source columns, k = source row, padded with zeros to ldp (multiple of 32).
 // 64 x 64 tiles through LDS; blockIdx.x enumerates tiles.
 __global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int Ccols, int lds_, int ldp, size_t plane,
                                                          int want_lo) {
@@ -272,7 +287,7 @@ __global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int
         const uint16_t l0 = f32_to_bf16_rne(x0 - bf16_to_f32(h0)), l1 = f32_to_bf16_rne(x1 - bf16_to_f32(h1));
         lo[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
       }
-      const size_t o = (size_t)c * ldp + rbase;
+      const size_t o = ((size_t)(rbase >> 5) * Ccols + c) * 32 + (rbase & 31);
       *reinterpret_cast<uint4*>(H + o) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
       if (want_lo) *reinterpret_cast<uint4*>(H + plane + o) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
     }
@@ -284,7 +299,7 @@ __global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int
 hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
                                   int ld_src, int transpose, int ldp, size_t plane, int want_lo) {
   if (batch <= 0 || R <= 0 || Ccols <= 0) return hipSuccess;
-  if (batch > BR_MAXB || (ldp & 7) || ldp < (transpose ? R : Ccols)) return hipErrorInvalidValue;
+  if (batch > BR_MAXB || (ldp & 31) || ldp < (transpose ? R : Ccols)) return hipErrorInvalidValue;
   br::SplitArgs a;
   for (int i = 0; i < BR_MAXB; ++i) {
     a.src[i] = (i < batch) ? src[i] : nullptr;
@@ -308,11 +323,11 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
   if (kernel_name)
     *kernel_name = (a.nprod == 4) ? "br_gemm_bf16_mfma<4>" : (a.nprod == 3) ? "br_gemm_bf16_mfma<3>" : "br_gemm_bf16_mfma<1>";
   if (a.batch <= 0 || a.M <= 0 || a.N <= 0) return hipSuccess;
-  if (a.batch > BR_MAXB || (a.Kp & 7) || (a.lda & 7) || (a.ldb & 7) || a.lda < a.Kp || a.ldb < a.Kp) return hipErrorInvalidValue;
+  if (a.batch > BR_MAXB || (a.Kp & 31)) return hipErrorInvalidValue;
   if (a.mirror && a.M != a.N) return hipErrorInvalidValue;
   LowpKernArgs k;
   k.M = a.M; k.N = a.N; k.Kp = a.Kp;
-  k.lda = a.lda; k.ldb = a.ldb; k.ldc = a.ldc;
+  k.ldc = a.ldc;
   k.a_plane = a.a_plane; k.b_plane = a.b_plane;
   k.alpha = a.alpha; k.beta = a.beta;
   k.tiles_m = (a.M + LBM - 1) / LBM;
