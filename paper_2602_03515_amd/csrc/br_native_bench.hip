@@ -3,7 +3,7 @@
 // optimizer steps.  It exists for hardware-counter runs (a profiler attaches to a plain
 // executable) and as a C usage example of include/br.h.
 //
-//   br_native_bench [--layers N] [--steps K] [--freq F] [--copy-calibration] [--mfma-peak]
+//   br_native_bench [--layers N] [--steps K] [--freq F] [--math 0|1|2] [--copy-calibration] [--mfma-peak]
 //
 // --mfma-peak runs br_mfma_peak instead of the optimizer: a register-only loop of
 // v_mfma_f32_32x32x2_f32 on every SIMD, once as a ~25 ms burst and once sustained for ~0.5 s,
@@ -93,12 +93,13 @@ static int mfma_peak() {
 }
 
 int main(int argc, char** argv) {
-  int layers = 8, steps = 2, freq = 10, calib = 0;
+  int layers = 8, steps = 2, freq = 10, calib = 0, math = BR_MATH_F32;
   for (int i = 1; i < argc; ++i) {
     if (!std::strcmp(argv[i], "--layers") && i + 1 < argc) layers = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--steps") && i + 1 < argc) steps = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--freq") && i + 1 < argc) freq = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--copy-calibration")) calib = 1;
+    else if (!std::strcmp(argv[i], "--math") && i + 1 < argc) math = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--mfma-peak")) return mfma_peak();
     else { std::fprintf(stderr, "unknown argument %s\n", argv[i]); return 2; }
   }
@@ -110,7 +111,7 @@ int main(int argc, char** argv) {
   br_hparams hp;
   std::memset(&hp, 0, sizeof(hp));
   hp.beta1 = 0.9f; hp.beta2 = 0.95f; hp.eps = 1e-8f; hp.stat_beta = -1.f;
-  hp.geometry = BR_BILATERAL; hp.source = BR_SRC_SECOND; hp.power_iters = 1; hp.math = BR_MATH_F32;
+  hp.geometry = BR_BILATERAL; hp.source = BR_SRC_SECOND; hp.power_iters = 1; hp.math = math;
   hp.cache_rotated_moment = 1;
   size_t state = 0, scratch = 0;
   if (br_workspace_bytes(descs.data(), (int32_t)descs.size(), &hp, &state, &scratch) != BR_OK) {
