@@ -130,20 +130,19 @@ int step_buffers(const Group& g, const br_hparams& hp) {
 }
 
 // Scratch of one matrix during a step in the BF16 math modes.  Eleven slots, each large enough for
-// an m x n FP32 matrix or for a pair of BF16 planes of it (either orientation, rows padded to a
-// multiple of 32), followed by the planes of the bases in both orientations.
-inline int ldp8(int64_t k) { return (int)((k + 31) & ~(int64_t)31); }  // planes pad k to whole 32-blocks
+// an m x n FP32 matrix or for a pair of BF16 planes of it (either orientation, padded as
+// br_plane_layout says), followed by the planes of the bases in both orientations.
 enum { LS_GP = 0, LS_GTP, LS_T1, LS_T1P, LS_GX, LS_XP, LS_MP, LS_T2, LS_T2P, LS_MROT, LS_G32, LS_COUNT };
 struct LowpLayout {
   size_t slot, qlp, qlt, qrp, qrt, per_mat;
 };
 LowpLayout lowp_layout(const Group& g) {
   LowpLayout l;
-  const size_t a = (size_t)g.m * ldp8(g.n), b = (size_t)g.n * ldp8(g.m);
-  l.slot = align256(4 * std::max(a, b));
+  const size_t a = br_plane_layout(g.m, g.n).elems, b = br_plane_layout(g.n, g.m).elems;
+  l.slot = align256(4 * std::max(a, b));  // two BF16 planes, or (rows and k only grow by padding) an FP32 m x n matrix
   size_t off = LS_COUNT * l.slot;
-  const size_t ql = g.rot_l ? align256(4 * (size_t)g.m * ldp8(g.m)) : 0;
-  const size_t qr = g.rot_r ? align256(4 * (size_t)g.n * ldp8(g.n)) : 0;
+  const size_t ql = g.rot_l ? align256(4 * br_plane_layout(g.m, g.m).elems) : 0;
+  const size_t qr = g.rot_r ? align256(4 * br_plane_layout(g.n, g.n).elems) : 0;
   l.qlp = off; off += ql;
   l.qlt = off; off += ql;
   l.qrp = off; off += qr;
@@ -293,10 +292,8 @@ struct LowpCtx {
 
 // planes of the R x C matrices src[i] (row stride C), optionally transposed
 bool lowp_split(const LowpCtx& x, const float* const* src, int R, int Ccols, bool transpose, uint16_t* const* dst) {
-  const int ldp = transpose ? ldp8(R) : ldp8(Ccols);
-  const size_t plane = (size_t)(transpose ? Ccols : R) * ldp;
   Timed tm(x.c, "br_split_planes", 0.0, (double)R * Ccols * x.B * (4.0 + (x.nprod == 3 ? 4.0 : 2.0)));
-  return hip_ok(x.c, br_launch_split_planes(x.c->stream, src, dst, x.B, R, Ccols, Ccols, transpose ? 1 : 0, ldp, plane,
+  return hip_ok(x.c, br_launch_split_planes(x.c->stream, src, dst, x.B, R, Ccols, Ccols, transpose ? 1 : 0,
                                             x.nprod == 3 ? 1 : 0), "plane split launch");
 }
 
@@ -312,12 +309,11 @@ bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp,
     b.C[i] = C[i];
     b.shadow[i] = shadow ? shadow[i] : nullptr;
   }
-  const int ldk = ldp8(K);
-  BrLowpArgs a{M, N, ldk, ldc, (size_t)M * ldk, (size_t)N * ldk, alpha, beta, x.B, mirror ? 1 : 0, nprod};
+  BrLowpArgs a{M, N, K, ldc, alpha, beta, x.B, mirror ? 1 : 0, nprod};
   double flops = 2.0 * M * N * (double)K * x.B;
   if (mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (M + 127) / 128));
   const char* name = nullptr;
-  (void)br_launch_gemm_lowp(nullptr, BrLowpArgs{0, 0, 0, 0, 0, 0, 0.f, 0.f, 0, 0, nprod}, b, &name);
+  (void)br_launch_gemm_lowp(nullptr, BrLowpArgs{0, 0, 0, 0, 0.f, 0.f, 0, 0, nprod}, b, &name);
   Timed tm(x.c, name, flops, 0.0);
   return hip_ok(x.c, br_launch_gemm_lowp(x.c->stream, a, b, nullptr), "bf16 gemm launch");
 }

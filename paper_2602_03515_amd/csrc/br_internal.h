@@ -37,9 +37,28 @@ struct BrGemmArgs {
 hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch& b, const char** kernel_name);
 
 // ---- BF16 matrix-core contractions on pre-split operand planes ----------------------------
-// C_b = alpha * A_b B_b^T + beta * C_b with A_b: M x Kp, B_b: N x Kp BF16 "planes" (hi plane at the
-// pointer, lo plane `a_plane`/`b_plane` elements further) in K-blocked layout: element (row, k) of an
-// R-row plane at ((k / 32) * R + row) * 32 + k % 32, Kp a multiple of 32 (zero padded).  nprod = 1 uses the hi planes only, nprod = 3 adds the two hi*lo cross terms.
+// A plane holds an R x K operand as BF16 in the order the contraction kernel wants its LDS tiles:
+// rows padded to a multiple of BR_PLANE_ROW_PAD, k to a multiple of BR_PLANE_K_PAD (zeros),
+// k-blocked by 16, and the two 16-byte halves of each 32-byte (row, k-block) run swapped on every
+// other group of 8 rows:
+//   element (row, k) at ((k / 16) * rows_p + row) * 16 + ((((k % 16) / 8) ^ ((row / 8) % 2)) * 8) + k % 8.
+// The lo plane (when there is one) follows the hi plane at +elems elements.
+#define BR_PLANE_ROW_PAD 256
+#define BR_PLANE_K_PAD 64
+struct BrPlaneLayout {
+  int64_t rows_p, k_p;
+  size_t elems;  // elements of one plane
+};
+inline BrPlaneLayout br_plane_layout(int64_t rows, int64_t k) {
+  BrPlaneLayout l;
+  l.rows_p = (rows + BR_PLANE_ROW_PAD - 1) / BR_PLANE_ROW_PAD * BR_PLANE_ROW_PAD;
+  l.k_p = (k + BR_PLANE_K_PAD - 1) / BR_PLANE_K_PAD * BR_PLANE_K_PAD;
+  l.elems = (size_t)l.rows_p * (size_t)l.k_p;
+  return l;
+}
+// C_b = alpha * A_b B_b^T + beta * C_b with A_b the planes of an M x K operand and B_b those of an
+// N x K operand (16-byte aligned).  nprod = 1 uses the hi planes only, nprod = 3 adds the two
+// hi*lo cross terms, nprod = 4 also lo*lo.
 struct BrLowpBatch {
   const uint16_t* A[BR_MAXB];
   const uint16_t* B[BR_MAXB];
@@ -47,17 +66,17 @@ struct BrLowpBatch {
   uint16_t* shadow[BR_MAXB];
 };
 struct BrLowpArgs {
-  int M, N, Kp;
+  int M, N, K;
   int ldc;
-  size_t a_plane, b_plane;
   float alpha, beta;
   int batch, mirror, nprod;
 };
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name);
-// hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src); transpose != 0 writes
-// the planes of the transposed matrix.  k is padded with zeros to ldp (multiple of 32).
+// hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src) into planes of
+// br_plane_layout(R, C); transpose != 0 writes the planes of the transposed matrix,
+// br_plane_layout(C, R).  The padding is written too (zeros).
 hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
-                                  int ld_src, int transpose, int ldp, size_t plane, int want_lo);
+                                  int ld_src, int transpose, int want_lo);
 
 // ---- elementwise ----------------------------------------------------------------------
 struct BrPtrBatch {

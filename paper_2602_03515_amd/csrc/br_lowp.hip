@@ -4,12 +4,16 @@
 //
 // Operands are first rewritten as BF16 "planes" by br_split_planes:
 //     hi = bf16(x),  lo = bf16(x - hi)            (round to nearest even)
-// stored K-BLOCKED: element (row, k) of an R-row plane sits at ((k / 32) * R + row) * 32 + k % 32,
-// so the 128 rows x 32 k that one workgroup needs per iteration are one contiguous 8 KB run of
-// whole cache lines (a row-major plane would touch half of 128 different lines instead).
 // optionally transposed, so that EVERY contraction has the form C[i][j] = sum_k A[i][k] B[j][k]
-// with k contiguous in memory for both operands: the MFMA operand of a lane (8 consecutive k of
-// one row) is then a single 16-byte load from LDS and no transposition happens in the kernel.
+// with k contiguous for both operands.  A plane is stored as the IMAGE OF THE LDS TILES the
+// contraction kernel works on (BrPlaneLayout in br_internal.h): rows padded to a multiple of
+// 256, k padded to a multiple of 64 (zeros), k-blocked by 16, and the two 16-byte halves of each
+// 32-byte (row, k-block) run swapped on every other group of 8 rows.  The 256 rows x 16 k that
+// one workgroup needs from one operand per k-block are therefore one contiguous 8 KB run of
+// memory whose byte order is exactly the order wanted in LDS: the kernel moves it with
+// global_load_lds_dwordx4 (memory -> LDS without passing through registers, each wave 1 KB per
+// instruction), and the matrix-core operand of a lane (8 consecutive k of one row) is a single
+// conflict-free ds_read_b128.
 //   NPROD = 1: C = A_hi B_hi^T                                  (plain BF16 inputs)
 //   NPROD = 3: C = A_hi B_hi^T + A_hi B_lo^T + A_lo B_hi^T      (16-bit mantissa inputs, FP32
 //              accumulation: a product term is off by about 2^-16, the dropped lo*lo term)
@@ -17,23 +21,35 @@
 //              otherwise carry the systematic bias sum_k lo_k^2, and whose error the refresh
 //              amplifies by the condition number of the statistics.
 //
-// Kernel: 128 x 128 output tile per 256-thread workgroup, four wave64s in 2 x 2, each 64 x 64 =
-// four v_mfma_f32_32x32x16_bf16 accumulators; K advances 32 per iteration through double-buffered
-// LDS; LDS rows are 64 data bytes + 16 pad, which makes the 16-byte operand reads conflict-free.
+// Kernel: one 512-thread workgroup (eight wave64s, 2 x 4, each 128 x 64 = eight
+// v_mfma_f32_32x32x16_bf16 accumulators) per compute unit and 256 x 256 output tile.  Operands
+// stream through a ring of five 32 KB LDS stages (all 160 KB): a stage is 32 k of A and B
+// (NPROD = 1) or 16 k of A_hi, A_lo, B_hi, B_lo (NPROD >= 3).  Four stages are always in flight
+// from memory.  What bounds the kernel is the rate at which one compute unit can pull lines out
+// of L2 (about 20 bytes per clock measured), so the tile is as large as the register file allows:
+// 128 flop per operand byte for NPROD = 1, three and four times that for the split products.
+// There is ONE workgroup barrier per stage and it sits between two groups of the stage's matrix
+// instructions: operands are fetched from LDS one group ahead of their use, so the matrix pipe
+// keeps running across the barrier.
 #include "br_internal.h"
 
 namespace {
 
-constexpr int LBM = 128, LBN = 128, LBK = 32;
-constexpr int ROW_CHUNKS = 5;  // uint4 per LDS row: 4 data (32 bf16) + 1 pad
+constexpr int TILE = BR_PLANE_ROW_PAD;  // 256 x 256 output tile; planes pad their rows to it
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;
+constexpr int SUB_U4 = TILE * 2;        // uint4 per sub-tile: 256 rows x 16 k of one plane (8 KB)
+constexpr int STAGE_U4 = 4 * SUB_U4;    // four sub-tiles per stage (32 KB)
+constexpr int STAGES = 5;
+constexpr int LOADS = 4;                // 1 KB loads per wave and stage (one per sub-tile)
+constexpr int FM = 4, FN = 2;           // 32 x 32 accumulators per wave (wave tile 128 x 64)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 struct LowpKernArgs {
-  int M, N, Kp;          // Kp: padded K (multiple of 32)
+  int M, N;              // logical output extent
+  int Mp, Np, Kp;        // padded operand extents (rows to 256, k to 64)
   int ldc;
   size_t a_plane, b_plane;  // distance from the hi plane to the lo plane, in elements
   float alpha, beta;
@@ -49,50 +65,33 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
-__device__ __forceinline__ uint4 load_chunk(const uint16_t* __restrict__ p, bool ok) {
-  uint4 v = make_uint4(0u, 0u, 0u, 0u);
-  if (ok) v = *reinterpret_cast<const uint4*>(p);
-  return v;
-}
+// The 16-byte half h (8 k) of row r inside a k-block sits at position h ^ swz(r).  The operand
+// reads of a wave touch 32 consecutive rows at one logical half: with the swap, any 8 or 16
+// consecutive rows spread over all LDS banks.
+__device__ __forceinline__ int swz(int row) { return (row >> 3) & 1; }
 
-// Registers that carry the next K tile from global memory to LDS.
-template <int NPLANES>
-struct Stage {
-  uint4 a[NPLANES][2], b[NPLANES][2];
-  __device__ __forceinline__ void fetch(const uint16_t* __restrict__ Ah, const uint16_t* __restrict__ Bh,
-                                        const LowpKernArgs& g, int m0, int n0, int k0, int lrow, int lchunk) {
-    const int k = k0 + lchunk * 8;
-#pragma unroll
-    for (int p = 0; p < NPLANES; ++p) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int ra = m0 + lrow + 64 * i, rb = n0 + lrow + 64 * i;
-        // K-blocked plane: element (row, k) at ((k / 32) * rows + row) * 32 + k % 32
-        a[p][i] = load_chunk(Ah + p * g.a_plane + ((size_t)(k0 >> 5) * g.M + ra) * 32 + lchunk * 8, ra < g.M && k < g.Kp);
-        b[p][i] = load_chunk(Bh + p * g.b_plane + ((size_t)(k0 >> 5) * g.N + rb) * 32 + lchunk * 8, rb < g.N && k < g.Kp);
-      }
-    }
-  }
-  __device__ __forceinline__ void stash(uint4 (*st)[128][ROW_CHUNKS], int lrow, int lchunk) const {
-#pragma unroll
-    for (int p = 0; p < NPLANES; ++p) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        st[p][lrow + 64 * i][lchunk] = a[p][i];
-        st[2 + p][lrow + 64 * i][lchunk] = b[p][i];
-      }
-    }
-  }
-};
+// s_waitcnt immediate (gfx9 encoding) that waits on vmcnt only.
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+// ... and one that waits for lgkmcnt(0) only (LDS reads returned).
+constexpr int waitcnt_lgkm0() { return 15 | (3 << 14) | (7 << 4) | (0 << 8); }
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
 }  // namespace
 
 namespace br {
 
 template <int NPROD>
-__global__ __launch_bounds__(256, 2) void br_gemm_bf16_mfma(LowpKernArgs g, BrLowpBatch batch) {
-  // [stage][plane: A_hi, A_lo, B_hi, B_lo][row][chunk]
-  __shared__ uint4 lds[2][4][128][ROW_CHUNKS];
+__global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLowpBatch batch) {
+  constexpr bool SPLIT = NPROD > 1;
+  constexpr int KS = SPLIT ? 1 : 2;   // k-steps (16 k) per stage
+  constexpr int G = SPLIT ? 4 : 2;    // groups of matrix instructions per k-step
+  constexpr int MPG = FM / G;         // accumulator rows per group
+  constexpr int U = KS * G;           // groups per stage
+  constexpr int S = STAGES, LPT = LOADS;
+  static_assert(U % 2 == 0, "operand double buffering assumes an even number of groups per stage");
+  __shared__ uint4 lds[S * STAGE_U4];
 
   int bid = blockIdx.x;
   const int per = gridDim.x / NUM_XCD;
@@ -115,98 +114,168 @@ __global__ __launch_bounds__(256, 2) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
     tn = r / gm;
     tm = first_m + (r - tn * gm);
   }
-  const uint16_t* __restrict__ Ah = batch.A[mat];
-  const uint16_t* __restrict__ Bh = batch.B[mat];
+  const uint4* __restrict__ Ap = reinterpret_cast<const uint4*>(batch.A[mat]);
+  const uint4* __restrict__ Bp = reinterpret_cast<const uint4*>(batch.B[mat]);
   float* __restrict__ C = batch.C[mat];
   uint16_t* __restrict__ shadow = batch.shadow[mat];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = tm * LBM, n0 = tn * LBN;
-  constexpr int NPLANES = (NPROD == 1) ? 1 : 2;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
+  const int m0 = tm * TILE, n0 = tn * TILE;
+  const int lk = lane >> 5, li = lane & 31;
 
-  floatx16 acc[2][2];
+  floatx16 acc[FM][FN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // per-thread load slots: rows (tid >> 2) and (tid >> 2) + 64, 16-byte chunk (tid & 3) of the K tile
-  const int lrow = tid >> 2, lchunk = tid & 3;
-  Stage<NPLANES> stg;
-  const int lk = lane >> 5, li = lane & 31;
-  auto mfma_tile = [&](int st) {
-#pragma unroll
-    for (int s = 0; s < LBK / 16; ++s) {
-      bf16x8 a_hi[2], b_hi[2], a_lo[2], b_lo[2];
-#pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        a_hi[q] = __builtin_bit_cast(bf16x8, lds[st][0][wm * 64 + q * 32 + li][s * 2 + lk]);
-        b_hi[q] = __builtin_bit_cast(bf16x8, lds[st][2][wn * 64 + q * 32 + li][s * 2 + lk]);
-        if (NPROD >= 3) {
-          a_lo[q] = __builtin_bit_cast(bf16x8, lds[st][1][wm * 64 + q * 32 + li][s * 2 + lk]);
-          b_lo[q] = __builtin_bit_cast(bf16x8, lds[st][3][wn * 64 + q * 32 + li][s * 2 + lk]);
-        }
-      }
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-          if (NPROD == 4)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[mi], b_lo[ni], acc[mi][ni], 0, 0, 0);
-          if (NPROD >= 3) {
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[mi], b_hi[ni], acc[mi][ni], 0, 0, 0);
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[mi], b_lo[ni], acc[mi][ni], 0, 0, 0);
-          }
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[mi], b_hi[ni], acc[mi][ni], 0, 0, 0);
-        }
+  // uint4 strides: one k-block (16 k) of a plane = rows * 2, one plane = elements / 8.  Wave w
+  // moves the w-th KB of each sub-tile: source and destination are both linear, 64 lanes x 16 bytes.
+  const size_t a_kb = (size_t)g.Mp * 2, b_kb = (size_t)g.Np * 2;
+  const size_t a_pl = g.a_plane >> 3, b_pl = g.b_plane >> 3;
+  const uint4* __restrict__ a_src = Ap + (size_t)m0 * 2 + wave * 64 + lane;
+  const uint4* __restrict__ b_src = Bp + (size_t)n0 * 2 + wave * 64 + lane;
+  auto load1k = [&](const uint4* src, int dst_u4) {
+    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)&lds[dst_u4], 16, 0, 0);
+  };
+  // Sub-tiles of a stage.  NPROD = 1: A(k-step 0), B(0), A(1), B(1).  Split: A_hi, A_lo, B_hi, B_lo.
+  auto issue = [&](int st, int kt) {
+    const int base = st * STAGE_U4 + wave * 64;
+    if (!SPLIT) {
+      const uint4* a = a_src + (size_t)(2 * kt) * a_kb;
+      const uint4* b = b_src + (size_t)(2 * kt) * b_kb;
+      load1k(a, base);
+      load1k(b, base + SUB_U4);
+      load1k(a + a_kb, base + 2 * SUB_U4);
+      load1k(b + b_kb, base + 3 * SUB_U4);
+    } else {
+      const uint4* a = a_src + (size_t)kt * a_kb;
+      const uint4* b = b_src + (size_t)kt * b_kb;
+      load1k(a, base);
+      load1k(a + a_pl, base + SUB_U4);
+      load1k(b, base + 2 * SUB_U4);
+      load1k(b + b_pl, base + 3 * SUB_U4);
     }
   };
 
-  // Two K tiles are in flight from global memory (one register stage each) while a third is being
-  // multiplied out of LDS: at BF16 matrix-core speed one tile of lookahead does not cover the
-  // memory latency.
-  const int nkt = (g.Kp + LBK - 1) / LBK;
-  Stage<NPLANES> stg2;
-  stg.fetch(Ah, Bh, g, m0, n0, 0, lrow, lchunk);
-  if (nkt > 1) stg2.fetch(Ah, Bh, g, m0, n0, LBK, lrow, lchunk);
-  stg.stash(lds[0], lrow, lchunk);
-  __syncthreads();
-  for (int kt = 0; kt < nkt; kt += 2) {
-    // even tile kt: LDS stage 0; tile kt+1 waits in stg2; fetch kt+2 into stg
-    if (kt + 2 < nkt) stg.fetch(Ah, Bh, g, m0, n0, (kt + 2) * LBK, lrow, lchunk);
-    mfma_tile(0);
-    if (kt + 1 < nkt) stg2.stash(lds[1], lrow, lchunk);
-    __syncthreads();
-    if (kt + 1 >= nkt) break;
-    // odd tile kt+1: LDS stage 1; tile kt+2 waits in stg; fetch kt+3 into stg2
-    if (kt + 3 < nkt) stg2.fetch(Ah, Bh, g, m0, n0, (kt + 3) * LBK, lrow, lchunk);
-    mfma_tile(1);
-    if (kt + 2 < nkt) stg.stash(lds[0], lrow, lchunk);
-    __syncthreads();
-  }
+  struct AFrag { bf16x8 hi[MPG], lo[MPG]; };
+  struct BFrag { bf16x8 hi[FN], lo[FN]; };
+  const int half = lk ^ swz(li);  // wave tile rows start at multiples of 32: swz(row) == swz(li)
+  const int a_row = (wm * FM * 32 + li) * 2 + half, b_row = (wn * FN * 32 + li) * 2 + half;
+  auto fetch_a = [&](AFrag& f, int st, int ks, int grp) {
+    const int base = st * STAGE_U4 + (SPLIT ? 0 : 2 * ks * SUB_U4) + a_row + grp * MPG * 64;
+#pragma unroll
+    for (int q = 0; q < MPG; ++q) {
+      f.hi[q] = __builtin_bit_cast(bf16x8, lds[base + q * 64]);
+      if (SPLIT) f.lo[q] = __builtin_bit_cast(bf16x8, lds[base + SUB_U4 + q * 64]);
+    }
+  };
+  auto fetch_b = [&](BFrag& f, int st, int ks) {
+    const int base = st * STAGE_U4 + (SPLIT ? 2 * SUB_U4 : (2 * ks + 1) * SUB_U4) + b_row;
+#pragma unroll
+    for (int q = 0; q < FN; ++q) {
+      f.hi[q] = __builtin_bit_cast(bf16x8, lds[base + q * 64]);
+      if (SPLIT) f.lo[q] = __builtin_bit_cast(bf16x8, lds[base + SUB_U4 + q * 64]);
+    }
+  };
+  auto multiply = [&](const AFrag& a, const BFrag& b, int grp) {
+#pragma unroll
+    for (int q = 0; q < MPG; ++q) {
+      const int mi = grp * MPG + q;
+#pragma unroll
+      for (int ni = 0; ni < FN; ++ni) {
+        if (NPROD == 4)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo[q], b.lo[ni], acc[mi][ni], 0, 0, 0);
+        if (NPROD >= 3) {
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo[q], b.hi[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi[q], b.lo[ni], acc[mi][ni], 0, 0, 0);
+        }
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi[q], b.hi[ni], acc[mi][ni], 0, 0, 0);
+      }
+    }
+  };
+
+  // The ring always holds S stages: past the end of k the LAST one is loaded again into the
+  // stage that has just been freed (nobody reads it), which keeps the loop free of branches and
+  // the number of loads in flight constant.
+  const int nkt = g.Kp / (16 * KS);
+#pragma unroll
+  for (int p = 0; p < S; ++p) issue(p, min(p, nkt - 1));
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm((S - 1) * LPT));  // this wave's share of stage 0 has landed
+  // Bare barriers: __syncthreads() would add a fence that waits for ALL outstanding loads, the
+  // ones of the later stages included, and serialise the pipeline.
+  __builtin_amdgcn_s_barrier();
+  AFrag af[2];
+  BFrag bf[2];
+  fetch_b(bf[0], 0, 0);
+  fetch_a(af[0], 0, 0, 0);
+  int st = 0;
+  // One stage = U groups of matrix instructions; group u's operands are fetched during group u - 1.
+  auto stage = [&](int kt, bool last) {
+    const int nst = (st + 1 == S) ? 0 : st + 1;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ks = u / G, grp = u % G;
+      if (u + 1 < U) {
+        const int nks = (u + 1) / G, ngrp = (u + 1) % G;
+        if (ngrp == 0) fetch_b(bf[nks & 1], st, nks);
+        fetch_a(af[(u + 1) & 1], st, nks, ngrp);
+      } else if (!last) {
+        __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());            // this wave is done reading stage st
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm((S - 2) * LPT));  // its share of stage kt + 1 has landed
+        __builtin_amdgcn_s_barrier();                           // ... everybody's; and stage st is free
+        issue(st, min(kt + S, nkt - 1));
+        fetch_b(bf[KS & 1], nst, 0);
+        fetch_a(af[0], nst, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(af[u & 1], bf[ks & 1], grp);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (KS & 1) bf[0] = bf[1];  // odd k-steps per stage: the next stage's B operands were fetched into bf[1]
+    st = nst;
+  };
+  for (int kt = 0; kt + 1 < nkt; ++kt) stage(kt, false);
+  stage(nkt - 1, true);
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // the surplus loads of the last iterations
 
   const bool use_beta = (g.beta != 0.0f);
   const bool off_diag = g.mirror && (tm != tn);
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi) {
+  for (int mi = 0; mi < FM; ++mi) {
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-      const int col = n0 + wn * 64 + ni * 32 + li;
+    for (int ni = 0; ni < FN; ++ni) {
+      const int col = n0 + (wn * FN + ni) * 32 + li;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-        if (row < g.M && col < g.N) {
-          size_t off = (size_t)row * (size_t)g.ldc + col;
-          float val = g.alpha * acc[mi][ni][v];
-          if (use_beta) val += g.beta * C[off];
-          C[off] = val;
-          if (shadow) shadow[off] = f32_to_bf16_rne(val);
-          if (off_diag) C[(size_t)col * (size_t)g.ldc + row] = val;
+      for (int vg = 0; vg < 4; ++vg) {
+        const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;
+        float val[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int row = row0 + e;
+          val[e] = g.alpha * acc[mi][ni][vg * 4 + e];
+          if (row < g.M && col < g.N) {
+            const size_t off = (size_t)row * (size_t)g.ldc + col;
+            if (use_beta) val[e] += g.beta * C[off];
+            C[off] = val[e];
+            if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
+          }
+        }
+        if (off_diag && col < g.N) {
+          // transposed copy of a symmetric result: this lane's four rows are four consecutive columns there
+          float* dst = C + (size_t)col * (size_t)g.ldc + row0;
+          if (row0 + 3 < g.M && ((g.ldc & 3) == 0)) {
+            *reinterpret_cast<float4*>(dst) = make_float4(val[0], val[1], val[2], val[3]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (row0 + e < g.M) dst[e] = val[e];
+          }
         }
       }
     }
@@ -219,102 +288,112 @@ struct SplitArgs {
   uint16_t* dst[BR_MAXB];  // hi plane; the lo plane follows at +plane elements
 };
 
-// Same orientation: plane rows = source rows, k = source column, padded with zeros to ldp (multiple of 32).
-__global__ __launch_bounds__(256) void br_split_planes(SplitArgs a, int R, int Ccols, int lds_, int ldp, size_t plane,
+__device__ __forceinline__ void split8(const float* x, uint4* hi4, uint4* lo4) {
+  uint32_t hi[4], lo[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const uint16_t h0 = f32_to_bf16_rne(x[2 * e]), h1 = f32_to_bf16_rne(x[2 * e + 1]);
+    hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+    const uint16_t l0 = f32_to_bf16_rne(x[2 * e] - bf16_to_f32(h0));
+    const uint16_t l1 = f32_to_bf16_rne(x[2 * e + 1] - bf16_to_f32(h1));
+    lo[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+  }
+  *hi4 = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+  *lo4 = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+
+// Same orientation: plane rows = source rows, k = source column.  One thread per 16-byte chunk
+// of the padded plane, chunk index within 32 k fastest, then row, then 32-k group: a wave reads
+// 16 whole 128-byte lines of the source and writes two contiguous 512-byte runs of plane.
+__global__ __launch_bounds__(256) void br_split_planes(SplitArgs a, int R, int Ccols, int ld_src, int Rp, int Kp, size_t plane,
                                                        int want_lo) {
   const float* __restrict__ X = a.src[blockIdx.y];
   uint16_t* __restrict__ H = a.dst[blockIdx.y];
-  const int chunks_per_row = ldp >> 3;
-  const int64_t total = (int64_t)R * chunks_per_row;
+  const int64_t total = (int64_t)Rp * (Kp >> 3);
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const bool vec = ((ld_src & 3) == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0);
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-    const int r = (int)(i / chunks_per_row);
-    const int c0 = (int)(i - (int64_t)r * chunks_per_row) * 8;
+    const int c = (int)(i & 3);
+    const int64_t rr = i >> 2;
+    const int kb32 = (int)(rr / Rp);
+    const int r = (int)(rr - (int64_t)kb32 * Rp);
+    const int c0 = kb32 * 32 + c * 8;
     float x[8];
-    const float* row = X + (size_t)r * lds_;
-    if (c0 + 7 < Ccols && ((lds_ & 3) == 0)) {
+    if (r < R && c0 + 7 < Ccols && vec) {
+      const float* row = X + (size_t)r * ld_src;
       float4 u = *reinterpret_cast<const float4*>(row + c0);
       float4 w = *reinterpret_cast<const float4*>(row + c0 + 4);
       x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w; x[4] = w.x; x[5] = w.y; x[6] = w.z; x[7] = w.w;
     } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = (c0 + e < Ccols) ? row[c0 + e] : 0.f;
+      for (int e = 0; e < 8; ++e) x[e] = (r < R && c0 + e < Ccols) ? X[(size_t)r * ld_src + c0 + e] : 0.f;
     }
-    uint32_t hi[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint16_t h0 = f32_to_bf16_rne(x[2 * e]), h1 = f32_to_bf16_rne(x[2 * e + 1]);
-      hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-      const uint16_t l0 = f32_to_bf16_rne(x[2 * e] - bf16_to_f32(h0));
-      const uint16_t l1 = f32_to_bf16_rne(x[2 * e + 1] - bf16_to_f32(h1));
-      lo[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-    }
-    const size_t o = ((size_t)(c0 >> 5) * R + r) * 32 + (c0 & 31);
-    *reinterpret_cast<uint4*>(H + o) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    if (want_lo) *reinterpret_cast<uint4*>(H + plane + o) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    uint4 hi4, lo4;
+    split8(x, &hi4, &lo4);
+    const size_t o = (((size_t)(c0 >> 4) * Rp + r) * 2 + (((c0 >> 3) & 1) ^ swz(r))) * 8;
+    *reinterpret_cast<uint4*>(H + o) = hi4;
+    if (want_lo) *reinterpret_cast<uint4*>(H + plane + o) = lo4;
   }
 }
 
-// Transposed: plane rows = source columns, k = source row, padded with zeros to ldp (multiple of 32).
-// 64 x 64 tiles through LDS; blockIdx.x enumerates tiles.
-__global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int Ccols, int lds_, int ldp, size_t plane,
+// Transposed: plane rows = source columns, k = source row.  64 x 64 tiles through LDS;
+// blockIdx.x enumerates tiles over the PADDED plane (Kp / 64 along k, Rp / 64 along rows), so
+// the zero padding is written by the same pass.
+__global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int Ccols, int ld_src, int Rp, int Kp, size_t plane,
                                                          int want_lo) {
   __shared__ float tile[64][65];
   const float* __restrict__ X = a.src[blockIdx.y];
   uint16_t* __restrict__ H = a.dst[blockIdx.y];
-  const int tiles_c = (Ccols + 63) >> 6;
+  const int tiles_c = Rp >> 6;
   const int tr = blockIdx.x / tiles_c, tc = blockIdx.x - tr * tiles_c;
-  const int r0 = tr * 64, c0 = tc * 64;
+  const int r0 = tr * 64, c0 = tc * 64;  // source row (= k) and source column (= plane row) origin
   const int tid = threadIdx.x;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int rr = i * 4 + (tid >> 6), cc = tid & 63;
     const int r = r0 + rr, c = c0 + cc;
-    tile[rr][cc] = (r < R && c < Ccols) ? X[(size_t)r * lds_ + c] : 0.f;
+    tile[rr][cc] = (r < R && c < Ccols) ? X[(size_t)r * ld_src + c] : 0.f;
   }
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int cc = (tid >> 3) + 32 * i, rch = tid & 7;
-    const int c = c0 + cc, rbase = r0 + rch * 8;
-    if (c < Ccols && rbase < ldp) {
-      uint32_t hi[4], lo[4];
+    const int prow = c0 + cc, k0 = r0 + rch * 8;
+    float x[8];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float x0 = tile[rch * 8 + 2 * e][cc], x1 = tile[rch * 8 + 2 * e + 1][cc];
-        const uint16_t h0 = f32_to_bf16_rne(x0), h1 = f32_to_bf16_rne(x1);
-        hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        const uint16_t l0 = f32_to_bf16_rne(x0 - bf16_to_f32(h0)), l1 = f32_to_bf16_rne(x1 - bf16_to_f32(h1));
-        lo[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-      }
-      const size_t o = ((size_t)(rbase >> 5) * Ccols + c) * 32 + (rbase & 31);
-      *reinterpret_cast<uint4*>(H + o) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-      if (want_lo) *reinterpret_cast<uint4*>(H + plane + o) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    }
+    for (int e = 0; e < 8; ++e) x[e] = tile[rch * 8 + e][cc];
+    uint4 hi4, lo4;
+    split8(x, &hi4, &lo4);
+    const size_t o = (((size_t)(k0 >> 4) * Rp + prow) * 2 + (((k0 >> 3) & 1) ^ swz(prow))) * 8;
+    *reinterpret_cast<uint4*>(H + o) = hi4;
+    if (want_lo) *reinterpret_cast<uint4*>(H + plane + o) = lo4;
   }
 }
 
 }  // namespace br
 
 hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
-                                  int ld_src, int transpose, int ldp, size_t plane, int want_lo) {
+                                  int ld_src, int transpose, int want_lo) {
   if (batch <= 0 || R <= 0 || Ccols <= 0) return hipSuccess;
-  if (batch > BR_MAXB || (ldp & 31) || ldp < (transpose ? R : Ccols)) return hipErrorInvalidValue;
+  if (batch > BR_MAXB || ld_src < Ccols) return hipErrorInvalidValue;
   br::SplitArgs a;
   for (int i = 0; i < BR_MAXB; ++i) {
     a.src[i] = (i < batch) ? src[i] : nullptr;
     a.dst[i] = (i < batch) ? dst[i] : nullptr;
   }
+  const BrPlaneLayout pl = transpose ? br_plane_layout(Ccols, R) : br_plane_layout(R, Ccols);
+  if (pl.rows_p > 0x7fffffffLL || pl.k_p > 0x7fffffffLL) return hipErrorInvalidValue;
   if (!transpose) {
-    int64_t blocks = ((int64_t)R * (ldp >> 3) + 255) / 256;
-    int64_t cap = (4096 + batch - 1) / batch;
+    int64_t blocks = (pl.rows_p * (pl.k_p >> 3) + 255) / 256;
+    int64_t cap = (8192 + batch - 1) / batch;
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(br::br_split_planes, dim3((int)blocks, batch), dim3(256), 0, s, a, R, Ccols, ld_src, ldp, plane, want_lo);
+    hipLaunchKernelGGL(br::br_split_planes, dim3((int)blocks, batch), dim3(256), 0, s, a, R, Ccols, ld_src, (int)pl.rows_p,
+                       (int)pl.k_p, pl.elems, want_lo);
   } else {
-    // the padded tail r in [R, ldp) is covered because tiles extend to multiples of 64 >= ldp
-    int64_t tiles = (int64_t)((R + 63) / 64) * ((Ccols + 63) / 64);
+    int64_t tiles = (pl.k_p >> 6) * (pl.rows_p >> 6);
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(br::br_split_planes_t, dim3((int)tiles, batch), dim3(256), 0, s, a, R, Ccols, ld_src, ldp, plane, want_lo);
+    hipLaunchKernelGGL(br::br_split_planes_t, dim3((int)tiles, batch), dim3(256), 0, s, a, R, Ccols, ld_src, (int)pl.rows_p,
+                       (int)pl.k_p, pl.elems, want_lo);
   }
   return hipGetLastError();
 }
@@ -322,25 +401,30 @@ hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name) {
   if (kernel_name)
     *kernel_name = (a.nprod == 4) ? "br_gemm_bf16_mfma<4>" : (a.nprod == 3) ? "br_gemm_bf16_mfma<3>" : "br_gemm_bf16_mfma<1>";
-  if (a.batch <= 0 || a.M <= 0 || a.N <= 0) return hipSuccess;
-  if (a.batch > BR_MAXB || (a.Kp & 31)) return hipErrorInvalidValue;
+  if (a.batch <= 0 || a.M <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
+  if (a.batch > BR_MAXB) return hipErrorInvalidValue;
   if (a.mirror && a.M != a.N) return hipErrorInvalidValue;
+  const BrPlaneLayout pa = br_plane_layout(a.M, a.K), pb = br_plane_layout(a.N, a.K);
+  if (pa.rows_p > 0x7fffffffLL || pb.rows_p > 0x7fffffffLL || pa.k_p > 0x7fffffffLL) return hipErrorInvalidValue;
+  for (int i = 0; i < a.batch; ++i)
+    if ((reinterpret_cast<uintptr_t>(b.A[i]) & 15u) || (reinterpret_cast<uintptr_t>(b.B[i]) & 15u)) return hipErrorInvalidValue;
   LowpKernArgs k;
-  k.M = a.M; k.N = a.N; k.Kp = a.Kp;
+  k.M = a.M; k.N = a.N;
+  k.Mp = (int)pa.rows_p; k.Np = (int)pb.rows_p; k.Kp = (int)pa.k_p;
   k.ldc = a.ldc;
-  k.a_plane = a.a_plane; k.b_plane = a.b_plane;
+  k.a_plane = pa.elems; k.b_plane = pb.elems;
   k.alpha = a.alpha; k.beta = a.beta;
-  k.tiles_m = (a.M + LBM - 1) / LBM;
-  k.tiles_n = (a.N + LBN - 1) / LBN;
+  k.tiles_m = k.Mp / TILE;
+  k.tiles_n = k.Np / TILE;
   k.mirror = a.mirror ? 1 : 0;
   k.total_tiles = k.mirror ? k.tiles_m * (k.tiles_m + 1) / 2 : k.tiles_m * k.tiles_n;
   long long grid = (long long)k.total_tiles * a.batch;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (a.nprod == 4)
-    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<4>), dim3((int)grid), dim3(256), 0, s, k, b);
+    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<4>), dim3((int)grid), dim3(512), 0, s, k, b);
   else if (a.nprod == 3)
-    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<3>), dim3((int)grid), dim3(256), 0, s, k, b);
+    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<3>), dim3((int)grid), dim3(512), 0, s, k, b);
   else
-    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<1>), dim3((int)grid), dim3(256), 0, s, k, b);
+    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<1>), dim3((int)grid), dim3(512), 0, s, k, b);
   return hipGetLastError();
 }

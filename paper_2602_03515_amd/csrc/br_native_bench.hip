@@ -4,11 +4,19 @@
 // executable) and as a C usage example of include/br.h.
 //
 //   br_native_bench [--layers N] [--steps K] [--freq F] [--math 0|1|2] [--copy-calibration] [--mfma-peak]
+//   br_native_bench --lowp-gemm M N K BATCH NPROD MIRROR
+//
+// --lowp-gemm checks and times the BF16 matrix-core contraction alone: BATCH products
+// C = A B^T (A: M x K, B: N x K, FP32 noise split into BF16 planes by the library's own split
+// kernel; MIRROR = 1 computes A A^T on the lower tiles only), compared on a strided sample of
+// the output with a plain one-thread-per-element kernel that forms the same BF16 products in
+// FP64, then timed over 10 launches.
 //
 // --mfma-peak runs br_mfma_peak instead of the optimizer: a register-only loop of
 // v_mfma_f32_32x32x2_f32 on every SIMD, once as a ~25 ms burst and once sustained for ~0.5 s,
 // which gives the FP32 matrix-core rate this machine actually holds (clocks drop under
-// sustained load), the practical ceiling for the contraction kernel.
+// sustained load), the practical ceiling for the contraction kernel; then the same for
+// v_mfma_f32_32x32x16_bf16 (br_mfma_peak_bf16).
 //
 // --copy-calibration additionally launches br_plain_copy on 1 GiB (reads 1 GiB, writes 1 GiB),
 // the known-traffic kernel against which HBM byte counters are scaled.
@@ -21,6 +29,7 @@
 #include <vector>
 
 #include "../../include/br.h"
+#include "br_internal.h"
 
 #define CHECK_HIP(x)                                                                  \
   do {                                                                                \
@@ -68,6 +77,38 @@ __global__ __launch_bounds__(256) void br_mfma_peak(float* out, int iters) {
   if (s == 12345.f) out[threadIdx.x] = s;  // keeps the loop alive
 }
 
+typedef __bf16 br_bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned br_uintx4 __attribute__((ext_vector_type(4)));
+
+// Same register-only loop on v_mfma_f32_32x32x16_bf16 with pseudo-random BF16 operands.
+__global__ __launch_bounds__(256) void br_mfma_peak_bf16(float* out, int iters) {
+  br_floatx16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  unsigned x = (threadIdx.x + 1 + blockIdx.x * 977) * 2654435761u;
+  br_uintx4 ua, ub, uc, ud;
+  for (int e = 0; e < 4; ++e) {
+    x ^= x >> 15; x *= 0x2c1b3c6du; x ^= x >> 12;
+    ua[e] = (x & 0x807f807fu) | 0x3f003f00u;  // two BF16 values of magnitude 0.5 .. 1, random signs
+    x *= 0x297a2d39u; x ^= x >> 15;
+    ub[e] = (x & 0x807f807fu) | 0x3f003f00u;
+    uc[e] = ua[e] ^ 0x80000000u;
+    ud[e] = ub[e] ^ 0x00008000u;
+  }
+  const br_bf16x8 a0 = __builtin_bit_cast(br_bf16x8, ua), a1 = __builtin_bit_cast(br_bf16x8, uc);
+  const br_bf16x8 b0 = __builtin_bit_cast(br_bf16x8, ub), b1 = __builtin_bit_cast(br_bf16x8, ud);
+  for (int i = 0; i < iters; i += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, c1, 0, 0, 0);
+      c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, c2, 0, 0, 0);
+      c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, c3, 0, 0, 0);
+    }
+  }
+  float s = 0.f;
+  for (int v = 0; v < 16; ++v) s += c0[v] + c1[v] + c2[v] + c3[v];
+  if (s == 12345.f) out[threadIdx.x] = s;  // keeps the loop alive
+}
+
 static int mfma_peak() {
   float* d = nullptr;
   CHECK_HIP(hipMalloc(&d, 4096));
@@ -88,11 +129,129 @@ static int mfma_peak() {
     double flops = (double)grid * 4 * iters_list[k] * 4.0 * 4096.0;
     std::printf("br_mfma_peak %s: %.1f ms, %.1f TFLOP/s FP32 MFMA\n", k ? "sustained" : "burst", ms, flops / (ms * 1e-3) / 1e12);
   }
+  for (int waves = 1; waves <= 2; ++waves) {  // waves per SIMD
+    for (int k = 0; k < 2; ++k) {
+      const int g2 = 256 * waves;
+      hipLaunchKernelGGL(br_mfma_peak_bf16, dim3(g2), dim3(256), 0, 0, d, 1000);
+      CHECK_HIP(hipDeviceSynchronize());
+      CHECK_HIP(hipEventRecord(e0, 0));
+      hipLaunchKernelGGL(br_mfma_peak_bf16, dim3(g2), dim3(256), 0, 0, d, iters_list[k] / waves);
+      CHECK_HIP(hipEventRecord(e1, 0));
+      CHECK_HIP(hipEventSynchronize(e1));
+      float ms = 0.f;
+      CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+      double flops = (double)g2 * 4 * (iters_list[k] / waves) * 4.0 * 32768.0;
+      std::printf("br_mfma_peak_bf16 %s, %d wave(s) per SIMD: %.1f ms, %.1f TFLOP/s BF16 MFMA\n", k ? "sustained" : "burst", waves, ms,
+                  flops / (ms * 1e-3) / 1e12);
+    }
+  }
   CHECK_HIP(hipFree(d));
   return 0;
 }
 
+// ---- --lowp-gemm ---------------------------------------------------------------------------
+__device__ inline float nb_bf16_round(float f) {
+  unsigned u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return __uint_as_float(u & 0xffff0000u);
+}
+
+// ref[s] for sample s = (i, j) on a strided grid; err[0] = max |C - ref|, err[1] = max |ref| (as uint bits of floats)
+__global__ void br_lowp_reference(const float* A, const float* B, const float* C, int M, int N, int K, int nprod, int si, int sj,
+                                  int mirror, float alpha, unsigned* err) {
+  const int ni = (M + si - 1) / si, nj = (N + sj - 1) / sj;
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= ni * nj) return;
+  const int i = (s / nj) * si, j = (s % nj) * sj;
+  double acc = 0.0;
+  for (int k = 0; k < K; ++k) {
+    const float a = A[(size_t)i * K + k], b = B[(size_t)j * K + k];
+    const float ah = nb_bf16_round(a), bh = nb_bf16_round(b);
+    const float al = nb_bf16_round(a - ah), bl = nb_bf16_round(b - bh);
+    double p = (double)ah * bh;
+    if (nprod >= 3) p += (double)ah * bl + (double)al * bh;
+    if (nprod == 4) p += (double)al * bl;
+    acc += p;
+  }
+  (void)mirror;
+  const float ref = (float)(alpha * acc);
+  const float d = fabsf(C[(size_t)i * N + j] - ref);
+  atomicMax(&err[0], __float_as_uint(d));
+  atomicMax(&err[1], __float_as_uint(fabsf(ref)));
+}
+
+static int lowp_gemm_bench(int M, int N, int K, int batch, int nprod, int mirror) {
+  if (M <= 0 || N <= 0 || K <= 0 || batch < 1 || batch > BR_MAXB || (nprod != 1 && nprod != 3 && nprod != 4) || (mirror && M != N)) {
+    std::fprintf(stderr, "bad --lowp-gemm arguments\n");
+    return 2;
+  }
+  const BrPlaneLayout pa = br_plane_layout(M, K), pb = br_plane_layout(N, K);
+  std::vector<float*> A(batch), B(batch), C(batch);
+  std::vector<uint16_t*> Ap(batch), Bp(batch);
+  for (int i = 0; i < batch; ++i) {
+    CHECK_HIP(hipMalloc(&A[i], (size_t)M * K * 4));
+    CHECK_HIP(hipMalloc(&C[i], (size_t)M * N * 4));
+    CHECK_HIP(hipMalloc(&Ap[i], pa.elems * 4));
+    hipLaunchKernelGGL(br_fill_noise, dim3(2048), dim3(256), 0, 0, A[i], (size_t)M * K, 101u + i, 1.0f);
+    if (mirror) {
+      B[i] = A[i];
+      Bp[i] = Ap[i];
+    } else {
+      CHECK_HIP(hipMalloc(&B[i], (size_t)N * K * 4));
+      CHECK_HIP(hipMalloc(&Bp[i], pb.elems * 4));
+      hipLaunchKernelGGL(br_fill_noise, dim3(2048), dim3(256), 0, 0, B[i], (size_t)N * K, 7001u + i, 1.0f);
+    }
+    CHECK_HIP(hipMemset(C[i], 0xff, (size_t)M * N * 4));  // NaN pattern: unwritten outputs are caught
+  }
+  const int want_lo = nprod > 1;
+  CHECK_HIP(br_launch_split_planes(0, A.data(), Ap.data(), batch, M, K, K, 0, want_lo));
+  if (!mirror) CHECK_HIP(br_launch_split_planes(0, B.data(), Bp.data(), batch, N, K, K, 0, want_lo));
+  BrLowpBatch lb;
+  std::memset(&lb, 0, sizeof(lb));
+  for (int i = 0; i < batch; ++i) { lb.A[i] = Ap[i]; lb.B[i] = Bp[i]; lb.C[i] = C[i]; }
+  const float alpha = 0.5f;
+  BrLowpArgs la{M, N, K, N, alpha, 0.f, batch, mirror, nprod};
+  const char* name = nullptr;
+  CHECK_HIP(br_launch_gemm_lowp(0, la, lb, &name));
+  CHECK_HIP(hipDeviceSynchronize());
+  unsigned* err;
+  CHECK_HIP(hipMalloc(&err, 8));
+  const int si = M <= 512 ? 1 : 7, sj = N <= 512 ? 1 : 5;
+  const int samples = ((M + si - 1) / si) * ((N + sj - 1) / sj);
+  double worst = 0.0;
+  for (int i = 0; i < batch; i += (batch > 2 ? batch - 1 : 1)) {
+    CHECK_HIP(hipMemset(err, 0, 8));
+    hipLaunchKernelGGL(br_lowp_reference, dim3((samples + 255) / 256), dim3(256), 0, 0, A[i], B[i], C[i], M, N, K, nprod, si, sj,
+                       mirror, alpha, err);
+    unsigned h[2];
+    CHECK_HIP(hipMemcpy(h, err, 8, hipMemcpyDeviceToHost));
+    float d, r;
+    std::memcpy(&d, &h[0], 4);
+    std::memcpy(&r, &h[1], 4);
+    std::printf("matrix %d: max |C - ref| = %.3e, max |ref| = %.3e, ratio %.3e\n", i, d, r, d / r);
+    if (!(d / r < 1e-4)) worst = 1.0;
+    if (d / r > worst) worst = d / r;
+  }
+  hipEvent_t e0, e1;
+  CHECK_HIP(hipEventCreate(&e0));
+  CHECK_HIP(hipEventCreate(&e1));
+  const int reps = 10;
+  CHECK_HIP(hipEventRecord(e0, 0));
+  for (int r = 0; r < reps; ++r) CHECK_HIP(br_launch_gemm_lowp(0, la, lb, nullptr));
+  CHECK_HIP(hipEventRecord(e1, 0));
+  CHECK_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+  double flops = 2.0 * M * N * (double)K * batch * (mirror ? 0.5 : 1.0);
+  std::printf("%s M=%d N=%d K=%d batch=%d mirror=%d: %.3f ms/launch, %.1f TFLOP/s (algorithmic), check %s\n", name, M, N, K, batch,
+              mirror, ms / reps, flops / (ms / reps * 1e-3) / 1e12, worst < 1e-4 ? "OK" : "FAILED");
+  return worst < 1e-4 ? 0 : 1;
+}
+
 int main(int argc, char** argv) {
+  if (argc == 8 && !std::strcmp(argv[1], "--lowp-gemm"))
+    return lowp_gemm_bench(std::atoi(argv[2]), std::atoi(argv[3]), std::atoi(argv[4]), std::atoi(argv[5]), std::atoi(argv[6]),
+                           std::atoi(argv[7]));
   int layers = 8, steps = 2, freq = 10, calib = 0, math = BR_MATH_F32;
   for (int i = 1; i < argc; ++i) {
     if (!std::strcmp(argv[i], "--layers") && i + 1 < argc) layers = std::atoi(argv[++i]);
