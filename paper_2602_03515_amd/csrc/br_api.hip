@@ -16,8 +16,8 @@
 namespace {
 
 constexpr int kStepChunk = 32;     // matrices per batched step launch ([G|M] doubles it to BR_MAXB)
-constexpr int kRefreshChunk = 64;
-constexpr int kLowpChunk = 16;     // matrices per batched step launch in the BF16 math modes  // factor matrices per batched refresh launch
+constexpr int kRefreshChunk = 64;   // factor matrices per batched refresh launch
+constexpr int kLowpChunk = 16;      // matrices per batched step launch in the BF16 math modes
 constexpr int64_t kMaxDim = 1 << 24;
 constexpr size_t kNormPartialBytes = (size_t)BR_MAXB * 2 * BR_NORM_BLOCKS * sizeof(float);
 constexpr size_t kSplitKBytes = (size_t)64 << 20;  // partial products of the QR's split-K contractions
@@ -50,10 +50,19 @@ struct ProfRec {
   double flops, bytes;
 };
 
+// Factor matrices of one order that are refreshed by the same batched launches, one unit after
+// the other on the caller's stream.  (Running units concurrently on several streams was tried and
+// is slower: the 1024-thread panel workgroups are not placed while any contraction is running.)
+struct RefreshUnit {
+  int64_t k;
+  std::vector<RefreshJob> jobs;
+};
+
 struct Layout {
   size_t state_bytes = 0, scratch_bytes = 0;
   std::vector<Group> groups;
   std::map<int64_t, std::vector<RefreshJob>> refresh;  // factor order -> jobs
+  std::vector<RefreshUnit> units;
 };
 
 }  // namespace
@@ -152,7 +161,7 @@ LowpLayout lowp_layout(const Group& g) {
 }
 
 struct RefreshScratch {
-  size_t P0, P1, gram, V, Y, W, T, Tp, G, diag, total;
+  size_t P0, P1, gram, V, Y, W, T, Tp, G, diag, xch, cnt, planesA, planesB, total;
 };
 
 RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
@@ -170,6 +179,12 @@ RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   r.Tp = off; off += align256((size_t)(BR_QR_NBO / BR_QR_NB) * BR_QR_NB * BR_QR_NB * 4);
   r.G = off; off += align256((size_t)BR_QR_NBO * BR_QR_NBO * 4);
   r.diag = off; off += align256((size_t)k * 4);
+  r.xch = off; off += align256(br_qr_panel_xch_floats((int)k) * 4);            // cluster exchange of one panel launch ...
+  r.cnt = off; off += align256((size_t)((k + BR_QR_NB - 1) / BR_QR_NB) * 4);  // ... and one arrival counter per panel
+  // BF16 math mode: hi + lo planes of the statistics and of the transposed basis for the power iteration
+  const size_t pl = (hp.math == BR_MATH_BF16) ? align256(4 * br_plane_layout(k, k).elems) : 0;
+  r.planesA = off; off += pl;
+  r.planesB = off; off += pl;
   r.total = off;
   return r;
 }
@@ -211,10 +226,22 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
       need = std::min<size_t>(g.idx.size(), kLowpChunk) * lowp_layout(g).per_mat;
     scratch = std::max(scratch, need);
   }
+  // Refresh units: every order's jobs in chunks of at most kRefreshChunk, evenly sized.
+  lay->units.clear();
+  size_t refresh_bytes = 0;
   for (auto& kv : lay->refresh) {
-    size_t chunk = std::min<size_t>(kv.second.size(), kRefreshChunk);
-    scratch = std::max(scratch, chunk * refresh_scratch(kv.first, hp).total + kSplitKBytes);
+    const size_t n = kv.second.size();
+    const size_t chunks = (n + kRefreshChunk - 1) / kRefreshChunk;
+    for (size_t ci = 0; ci < chunks; ++ci) {
+      const size_t lo = n * ci / chunks, hi = n * (ci + 1) / chunks;
+      RefreshUnit u;
+      u.k = kv.first;
+      u.jobs.assign(kv.second.begin() + lo, kv.second.begin() + hi);
+      refresh_bytes = std::max(refresh_bytes, align256(u.jobs.size() * refresh_scratch(u.k, hp).total + kSplitKBytes));
+      lay->units.push_back(u);
+    }
   }
+  scratch = std::max(scratch, refresh_bytes);
   state += 256;  // global gradient norm and clipping factor
   lay->state_bytes = state;
   lay->scratch_bytes = scratch + kNormPartialBytes;
@@ -254,12 +281,13 @@ struct Timed {  // brackets one launch (or a region) with events while profiling
 
 // step = true: one of the optimizer step's contractions (timed individually while profiling).
 // step = false: a contraction inside the QR (split-K capable variant, timed as part of the region).
-bool gemm(br_ctx* c, BrGemmArgs a, const BrGemmBatch& b, bool step = true, float* partial = nullptr) {
+bool gemm(br_ctx* c, BrGemmArgs a, const BrGemmBatch& b, bool step = true, float* partial = nullptr,
+          hipStream_t qr_stream = nullptr) {
   if (!step) {
     a.qr_role = 1;
     a.partial = partial;
     a.partial_floats = partial ? kSplitKBytes / sizeof(float) : 0;
-    return hip_ok(c, br_launch_gemm(c->stream, a, b, nullptr), "gemm launch");
+    return hip_ok(c, br_launch_gemm(qr_stream ? qr_stream : c->stream, a, b, nullptr), "gemm launch");
   }
   if (c->prof_on) {
     const char* name = nullptr;
@@ -459,7 +487,7 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
   plan(descs, n_mats, c->hp, &c->lay);
   if (workspace_bytes < c->lay.state_bytes + c->lay.scratch_bytes) {
     g_static_err = "workspace too small: need " + std::to_string(c->lay.state_bytes + c->lay.scratch_bytes) + " bytes";
-    delete c;
+    br_destroy(c);
     return BR_ERR_WORKSPACE;
   }
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -487,7 +515,7 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
   c->scratch = reinterpret_cast<char*>(dev_workspace) + c->lay.state_bytes;
   // zero state, identity bases
   if (!hip_ok(c, hipMemsetAsync(dev_workspace, 0, c->lay.state_bytes, c->stream), "state clear")) {
-    g_static_err = c->err; delete c; return BR_ERR_HIP;
+    g_static_err = c->err; br_destroy(c); return BR_ERR_HIP;
   }
   for (auto& kv : c->lay.refresh) {
     const auto& jobs = kv.second;
@@ -499,7 +527,7 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
         ptrs[i] = jobs[off + i].left ? m.QL : m.QR;
       }
       if (!hip_ok(c, br_launch_set_identity(c->stream, ptrs, b, (int)kv.first), "identity init")) {
-        g_static_err = c->err; delete c; return BR_ERR_HIP;
+        g_static_err = c->err; br_destroy(c); return BR_ERR_HIP;
       }
     }
   }
@@ -672,12 +700,12 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 }
 
 // Blocked Householder QR of the k x k matrices P (in place) for a batch of jobs, orthogonal
-// factor written to Q with the sign convention diag(R) >= 0.  Two-level blocking: inner panels
-// of BR_QR_NB columns are factorised by the panel kernel and applied inside their outer block
-// of BR_QR_NBO columns; the outer block's reflectors are then merged into one compact-WY factor
-// and applied to the trailing matrix with K = BR_QR_NBO contractions.
-static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs, char* base,
-                     size_t stride, float* partial) {
+// factor written to Q with the sign convention diag(R) >= 0, everything on stream s.  Two-level
+// blocking: inner panels of BR_QR_NB columns are factorised by the panel kernel and applied
+// inside their outer block of BR_QR_NBO columns; the outer block's reflectors are then merged
+// into one compact-WY factor and applied to the trailing matrix with K = BR_QR_NBO contractions.
+static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs,
+                     char* base, size_t stride, float* partial) {
   const int NB = BR_QR_NB, NBO = BR_QR_NBO;
   const int nblocks = (k + NBO - 1) / NBO;
   auto V = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.V); };
@@ -687,8 +715,16 @@ static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, 
   auto Tp = [&](int i, int pnl) { return reinterpret_cast<float*>(base + i * stride + rs.Tp) + (size_t)pnl * NB * NB; };
   auto G = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.G); };
   auto D = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.diag); };
+  auto Cnt = [&](int i) { return reinterpret_cast<int*>(base + i * stride + rs.cnt); };
+  auto mm = [&](const BrGemmArgs& a, const BrGemmBatch& gb) { return gemm(c, a, gb, false, partial, s); };
   BrQrPanelBatch pb;
+  BrQrClusterBatch cb;
   BrGemmBatch gb;
+  {
+    int* cp[BR_MAXB];
+    for (int i = 0; i < B; ++i) cp[i] = Cnt(i);
+    if (!hip_ok(c, br_launch_zero_ints(s, cp, B, (k + NB - 1) / NB), "counter clear launch")) return false;
+  }
   for (int blk = 0; blk < nblocks; ++blk) {
     const int J0 = blk * NBO;
     const int nbo = std::min(NBO, k - J0);  // columns of this outer block
@@ -699,25 +735,28 @@ static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, 
       const int nb = std::min(NB, k - j0);
       const int prow = k - j0;
       std::memset(&pb, 0, sizeof(pb));
+      std::memset(&cb, 0, sizeof(cb));
       for (int i = 0; i < B; ++i) {
         pb.A[i] = P[i] + (size_t)j0 * k + j0;
         pb.Vc[i] = V(i) + (size_t)(pnl * NB) * NBO + pnl * NB;
         pb.T[i] = Tp(i, pnl);
         pb.diag[i] = D(i) + j0;
+        cb.xch[i] = reinterpret_cast<float*>(base + i * stride + rs.xch);
+        cb.cnt[i] = Cnt(i) + j0 / NB;
       }
-      if (!hip_ok(c, br_launch_qr_panel(c->stream, pb, B, prow, nb, k, NBO, pnl * NB), "qr panel launch")) return false;
+      if (!hip_ok(c, br_launch_qr_panel(s, pb, cb, B, prow, nb, k, NBO, pnl * NB), "qr panel launch")) return false;
       const int nin = J0 + nbo - (j0 + nb);  // columns of the outer block still to the right
       if (nin <= 0) continue;
       std::memset(&gb, 0, sizeof(gb));
       // Yt = Vp Tp^T  (prow x NB), Vp = this panel's slice of V
       for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = Tp(i, pnl); gb.C[i] = Y(i); }
-      if (!gemm(c, BrGemmArgs{prow, NB, NB, NBO, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
+      if (!mm(BrGemmArgs{prow, NB, NB, NBO, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
       // W = Vp^T C, C = the outer block's remaining columns in the panel's rows
       for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
-      if (!gemm(c, BrGemmArgs{NB, nin, prow, NBO, k, NBO, 1, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
+      if (!mm(BrGemmArgs{NB, nin, prow, NBO, k, NBO, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
       // C <- C - Yt W
       for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)j0 * k + j0 + nb; }
-      if (!gemm(c, BrGemmArgs{prow, nin, NB, NB, NBO, k, 0, 0, -1.f, 1.f, B, 0}, gb, false, partial)) return false;
+      if (!mm(BrGemmArgs{prow, nin, NB, NB, NBO, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
     }
     // Merge the panels' factors: G = V^T V, then T_blk from the inner factors and G.
     const float* gp[BR_MAXB];
@@ -726,24 +765,24 @@ static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, 
     std::memset(&gb, 0, sizeof(gb));
     if (npanels > 1) {
       for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = V(i); gb.C[i] = G(i); }
-      if (!gemm(c, BrGemmArgs{NBO, NBO, rows, NBO, NBO, NBO, 1, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
+      if (!mm(BrGemmArgs{NBO, NBO, rows, NBO, NBO, NBO, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
     }
     for (int i = 0; i < B; ++i) { gp[i] = G(i); tpp[i] = Tp(i, 0); tb[i] = T(i, blk); }
-    if (!hip_ok(c, br_launch_qr_build_t(c->stream, gp, tpp, tb, B, npanels), "qr factor merge launch")) return false;
+    if (!hip_ok(c, br_launch_qr_build_t(s, gp, tpp, tb, B, npanels), "qr factor merge launch")) return false;
     const int nt = k - J0 - nbo;
     if (nt <= 0) continue;
     // Yt = V T^T ; W = V^T C ; C <- C - Yt W   on the trailing columns
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
-    if (!gemm(c, BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 1, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
+    if (!mm(BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = P[i] + (size_t)J0 * k + J0 + nbo; gb.C[i] = W(i); }
-    if (!gemm(c, BrGemmArgs{NBO, nt, rows, NBO, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
+    if (!mm(BrGemmArgs{NBO, nt, rows, NBO, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
     for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)J0 * k + J0 + nbo; }
-    if (!gemm(c, BrGemmArgs{rows, nt, NBO, NBO, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb, false, partial)) return false;
+    if (!mm(BrGemmArgs{rows, nt, NBO, NBO, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
   }
   // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before block blk is
   // applied, Q differs from the identity only in Q[J1:, J1:] with J1 the next block's offset,
   // so only the columns from J0 on change.
-  if (!hip_ok(c, br_launch_set_identity(c->stream, Q, B, k), "identity launch")) return false;
+  if (!hip_ok(c, br_launch_set_identity(s, Q, B, k), "identity launch")) return false;
   for (int blk = nblocks - 1; blk >= 0; --blk) {
     const int J0 = blk * NBO;
     const int nbo = std::min(NBO, k - J0);
@@ -753,19 +792,19 @@ static bool qr_batch(br_ctx* c, int B, int k, float* const* P, float* const* Q, 
       pb.A[i] = P[i] + (size_t)J0 * k + J0;
       pb.Vc[i] = V(i);
     }
-    if (!hip_ok(c, br_launch_qr_extract_v(c->stream, pb, B, rows, nbo, k, NBO), "qr extract launch")) return false;
+    if (!hip_ok(c, br_launch_qr_extract_v(s, pb, B, rows, nbo, k, NBO), "qr extract launch")) return false;
     std::memset(&gb, 0, sizeof(gb));
     // Y = V T ; W = V^T Qsub ; Qsub <- Qsub - Y W,  Qsub = Q[J0:, J0:]
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
-    if (!gemm(c, BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
+    if (!mm(BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Q[i] + (size_t)J0 * k + J0; gb.C[i] = W(i); }
-    if (!gemm(c, BrGemmArgs{NBO, rows, rows, NBO, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb, false, partial)) return false;
+    if (!mm(BrGemmArgs{NBO, rows, rows, NBO, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
     for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Q[i] + (size_t)J0 * k + J0; }
-    if (!gemm(c, BrGemmArgs{rows, rows, NBO, NBO, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb, false, partial)) return false;
+    if (!mm(BrGemmArgs{rows, rows, NBO, NBO, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
   }
   const float* dg[BR_MAXB];
   for (int i = 0; i < B; ++i) dg[i] = D(i);
-  return hip_ok(c, br_launch_qr_fix_signs(c->stream, Q, dg, B, k), "sign fix launch");
+  return hip_ok(c, br_launch_qr_fix_signs(s, Q, dg, B, k), "sign fix launch");
 }
 
 br_status br_refresh_basis(br_ctx* ctx) {
@@ -775,50 +814,66 @@ br_status br_refresh_basis(br_ctx* ctx) {
   const br_hparams& hp = c->hp;
   char* base = c->scratch + kNormPartialBytes;
   c->mrot_valid = false;  // the bases change: M~ must be rebuilt from M at the next step
-  for (auto& kv : c->lay.refresh) {
-    const int k = (int)kv.first;
-    const auto& jobs = kv.second;
+  for (const RefreshUnit& u : c->lay.units) {
+    const int k = (int)u.k;
+    const int B = (int)u.jobs.size();
     const RefreshScratch rs = refresh_scratch(k, hp);
-    for (size_t off = 0; off < jobs.size(); off += kRefreshChunk) {
-      const int B = (int)std::min<size_t>(kRefreshChunk, jobs.size() - off);
-      float* Q[BR_MAXB];
-      float* P0[BR_MAXB];
-      float* P1[BR_MAXB];
-      const float* A[BR_MAXB];
-      BrGemmBatch gb;
-      std::memset(&gb, 0, sizeof(gb));
-      for (int i = 0; i < B; ++i) {
-        const RefreshJob& j = jobs[off + i];
-        const MatState& m = c->mats[j.mat];
-        Q[i] = j.left ? m.QL : m.QR;
-        P0[i] = reinterpret_cast<float*>(base + i * rs.total + rs.P0);
-        P1[i] = reinterpret_cast<float*>(base + i * rs.total + rs.P1);
-        if (hp.source == BR_SRC_SECOND) {
-          A[i] = j.left ? m.L : m.R;
-        } else {  // first-order source: Gram matrix of the first moment (Algorithm 2 lines 12, 14)
-          float* gram = reinterpret_cast<float*>(base + i * rs.total + rs.gram);
-          A[i] = gram;
-          BrGemmBatch one;
-          std::memset(&one, 0, sizeof(one));
-          one.A[0] = m.M; one.B[0] = m.M; one.C[0] = gram;
-          BrGemmArgs a = j.left ? BrGemmArgs{k, k, (int)m.d.n, (int)m.d.n, (int)m.d.n, k, 0, 1, 1.f, 0.f, 1, 1}
-                                : BrGemmArgs{k, k, (int)m.d.m, (int)m.d.n, (int)m.d.n, k, 1, 0, 1.f, 0.f, 1, 1};
-          if (!gemm(c, a, one)) return BR_ERR_HIP;
-        }
+    float* Q[BR_MAXB];
+    float* P0[BR_MAXB];
+    float* P1[BR_MAXB];
+    const float* A[BR_MAXB];
+    BrGemmBatch gb;
+    std::memset(&gb, 0, sizeof(gb));
+    for (int i = 0; i < B; ++i) {
+      const RefreshJob& j = u.jobs[i];
+      const MatState& m = c->mats[j.mat];
+      Q[i] = j.left ? m.QL : m.QR;
+      P0[i] = reinterpret_cast<float*>(base + i * rs.total + rs.P0);
+      P1[i] = reinterpret_cast<float*>(base + i * rs.total + rs.P1);
+      if (hp.source == BR_SRC_SECOND) {
+        A[i] = j.left ? m.L : m.R;
+      } else {  // first-order source: Gram matrix of the first moment (Algorithm 2 lines 12, 14)
+        float* gram = reinterpret_cast<float*>(base + i * rs.total + rs.gram);
+        A[i] = gram;
+        BrGemmBatch one;
+        std::memset(&one, 0, sizeof(one));
+        one.A[0] = m.M; one.B[0] = m.M; one.C[0] = gram;
+        BrGemmArgs a = j.left ? BrGemmArgs{k, k, (int)m.d.n, (int)m.d.n, (int)m.d.n, k, 0, 1, 1.f, 0.f, 1, 1}
+                              : BrGemmArgs{k, k, (int)m.d.m, (int)m.d.n, (int)m.d.n, k, 1, 0, 1.f, 0.f, 1, 1};
+        if (!gemm(c, a, one)) return BR_ERR_HIP;
       }
-      // P <- A^iters Q
-      float** src = Q;
-      float** dst = P0;
-      for (int it = 0; it < hp.power_iters; ++it) {
+    }
+    // P <- A^iters Q.  In the BF16 math mode the product runs on the BF16 matrix cores with both
+    // operands split into hi + lo planes and all four partial products (16-bit mantissa inputs);
+    // BF16X3 keeps FP32 here: the QR amplifies an input error by the condition number of A, and
+    // 2^-17 per entry is already too much for that mode's 1e-4 bar.
+    float** src = Q;
+    float** dst = P0;
+    const bool lowp = hp.math == BR_MATH_BF16;
+    LowpCtx lx{c, nullptr, LowpLayout{}, B, 3, nullptr};
+    uint16_t *plA[BR_MAXB], *plB[BR_MAXB];
+    for (int i = 0; i < B && lowp; ++i) {
+      plA[i] = reinterpret_cast<uint16_t*>(base + i * rs.total + rs.planesA);
+      plB[i] = reinterpret_cast<uint16_t*>(base + i * rs.total + rs.planesB);
+    }
+    if (lowp && !lowp_split(lx, A, k, k, false, plA)) return BR_ERR_HIP;
+    for (int it = 0; it < hp.power_iters; ++it) {
+      if (lowp) {
+        const float* s32[BR_MAXB];
+        for (int i = 0; i < B; ++i) s32[i] = src[i];
+        if (!lowp_split(lx, s32, k, k, true, plB)) return BR_ERR_HIP;  // planes of src^T: B[j][l] = src[l][j]
+        if (!lowp_gemm(lx, plA, k, plB, k, k, dst, k, 1.f, 0.f, nullptr, false, 4)) return BR_ERR_HIP;
+      } else {
         for (int i = 0; i < B; ++i) { gb.A[i] = A[i]; gb.B[i] = src[i]; gb.C[i] = dst[i]; }
         if (!gemm(c, BrGemmArgs{k, k, k, k, k, k, 0, 0, 1.f, 0.f, B, 0}, gb)) return BR_ERR_HIP;
-        src = dst;
-        dst = (dst == P0) ? P1 : P0;
       }
-      {
-        Timed tm(c, "qr_householder(region)", (8.0 / 3.0) * (double)k * k * k * B, 0.0);
-        if (!qr_batch(c, B, k, src, Q, rs, base, rs.total, reinterpret_cast<float*>(base + (size_t)B * rs.total))) return BR_ERR_HIP;
-      }
+      src = dst;
+      dst = (dst == P0) ? P1 : P0;
+    }
+    {
+      Timed tm(c, "qr_householder(region)", (8.0 / 3.0) * (double)k * k * k * B, 0.0);
+      float* part = reinterpret_cast<float*>(base + (size_t)B * rs.total);
+      if (!qr_batch(c, c->stream, B, k, src, Q, rs, base, rs.total, part)) return BR_ERR_HIP;
     }
   }
   return BR_OK;

@@ -139,12 +139,24 @@ struct BrQrPanelBatch {
   float* T[BR_MAXB];     // BR_QR_NB x BR_QR_NB upper-triangular block-reflector factor
   float* diag[BR_MAXB];  // nb diagonal entries of R for this panel
 };
+// Panels taller than one workgroup's register capacity are factorised by a cluster of
+// br_qr_panel_cluster(rows) workgroups per matrix, which exchange partial sums through xch
+// (br_qr_panel_xch_floats(rows) floats per matrix) and meet on the counter cnt (one int per
+// matrix and launch, ZERO before the launch; never reused without being cleared).
+#define BR_QR_MAX_RESIDENT 192  // workgroups of one panel launch: all of them must fit on the chip at once
+struct BrQrClusterBatch {
+  float* xch[BR_MAXB];
+  int* cnt[BR_MAXB];
+};
+int br_qr_panel_cluster(int rows);
+size_t br_qr_panel_xch_floats(int rows);
 // Householder-factorise the rows x nb panel in place (reflectors below the diagonal, R on and
-// above), one workgroup per matrix.
+// above).
 // Vc points at this panel's first row and first column inside a reflector block of row stride
 // ldv; the pre_rows rows of that block above it are zero-filled in the panel's columns.
-hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda, int ldv,
-                              int pre_rows);
+hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQrClusterBatch& cb, int batch, int rows, int nb,
+                              int lda, int ldv, int pre_rows);
+hipError_t br_launch_zero_ints(hipStream_t s, int* const* ptrs, int batch, int n);
 // Copy the reflectors of an already factorised block of nb columns out into Vc (rows x width).
 hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda,
                                   int width);

@@ -3,8 +3,11 @@
 //
 // The factorisation is blocked (panel width BR_QR_NB = 32) in compact-WY form:
 //   H_1 H_2 ... H_nb = I - V T V^T,  V unit lower trapezoidal, T upper triangular.
-// This file holds the panel kernel (one 1024-thread workgroup per matrix of the batch);
-// the trailing-matrix and Q-forming updates are GEMMs issued by the host logic.
+// This file holds the panel kernel; the trailing-matrix and Q-forming updates are GEMMs issued
+// by the host logic.  A panel is held ENTIRELY IN REGISTERS from its first load to its final
+// store: a 1024-thread workgroup keeps up to 2304 rows, and a taller panel is shared by a cluster
+// of workgroups (gridDim.y, one slab of rows each) that combine their partial dot products
+// through global memory once per column.
 //
 // Panel kernel (br_qr_panel), one pass per column.  A panel row is 32 floats = one 128-byte line; it
 // is owned by 8 adjacent lanes (4 columns each), so every wave64 access touches 8 whole
@@ -19,8 +22,10 @@ namespace br {
 constexpr int QR_THREADS = 1024;
 constexpr int QR_ROWS_PER_SWEEP = QR_THREADS / 8;  // 128
 constexpr int QR_WAVES = QR_THREADS / 64;          // 16
-constexpr int QR_RESIDENT_SWEEPS = 18;             // panels of up to 2304 rows live in registers
-constexpr int QR_STREAM_SWEEPS = 8;                // taller panels stream through, 8 loads in flight
+constexpr int QR_RESIDENT_SWEEPS = 18;             // a workgroup keeps up to 18 x 128 = 2304 rows in registers
+constexpr int QR_MAX_SLAB = QR_RESIDENT_SWEEPS * QR_ROWS_PER_SWEEP;
+constexpr int QR_XCH_FLOATS = 64;                  // per (step, workgroup): 32 partial sums + the next pivot row
+constexpr unsigned QR_SPIN_LIMIT = 1u << 26;       // polls before a cluster gives up and poisons its result
 
 // One lane's four columns of a panel row travel as a float4 VALUE (never through a pointer), so
 // that groups of rows stay in registers.
@@ -86,6 +91,49 @@ __device__ __forceinline__ void panel_reduce(float4 acc, float (*red)[32], float
   __syncthreads();
 }
 
+// Cluster part of the reduction (gridDim.y > 1): every workgroup publishes its 32 partial sums
+// (workgroup 0 also the pivot row of the next pass), announces it on the panel's counter and
+// waits until all have; then each sums the partials in workgroup order, so that all of them
+// hold bit-identical values.  Exchange slots are per step: nothing is ever overwritten.
+// The wait is bounded: a cluster that never becomes complete poisons its sums with NaN (which
+// reaches the basis and the weights) instead of hanging.
+struct Cluster {
+  float* xch;   // [step][workgroup][QR_XCH_FLOATS] of this matrix
+  int* cnt;     // this panel's arrival counter (zero before the launch)
+  int w, nw;
+};
+
+__device__ __forceinline__ void cluster_combine(const Cluster& cl, int step, float* comb, float* pivnext, int tid) {
+  if (cl.nw == 1) return;
+  float* mine = cl.xch + ((size_t)step * cl.nw + cl.w) * QR_XCH_FLOATS;
+  if (tid < 32) {
+    mine[tid] = comb[tid];
+    if (cl.w == 0) mine[32 + tid] = pivnext[tid];
+  }
+  __syncthreads();
+  __shared__ int gave_up;
+  if (tid == 0) {
+    gave_up = 0;
+    __hip_atomic_fetch_add(cl.cnt, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    const int target = cl.nw * (step + 1);
+    unsigned spins = 0;
+    while (__hip_atomic_load(cl.cnt, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if (++spins > QR_SPIN_LIMIT) { gave_up = 1; break; }
+      __builtin_amdgcn_s_sleep(2);
+    }
+  }
+  __syncthreads();
+  if (tid < 32) {
+    const float* base = cl.xch + (size_t)step * cl.nw * QR_XCH_FLOATS;
+    float s = 0.f;
+    for (int ww = 0; ww < cl.nw; ++ww)
+      s += __hip_atomic_load(base + (size_t)ww * QR_XCH_FLOATS + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    comb[tid] = gave_up ? __builtin_nanf("") : s;
+    if (cl.w != 0) pivnext[tid] = __hip_atomic_load(base + 32 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+}
+
 // State shared by all rows during pass j.
 struct PassParams {
   int j, jn;          // current column, owner column of the next one
@@ -139,12 +187,11 @@ __device__ __forceinline__ float4 fma4(float s, float4 a, float4 acc) {
   return make_float4(acc.x + s * a.x, acc.y + s * a.y, acc.z + s * a.z, acc.w + s * a.w);
 }
 
-// U: rows are processed in groups of U sweeps (U * 128 rows) so that U independent 16-byte
-// loads are in flight per lane.  RESIDENT: the whole panel (rows <= U * 128) stays in
-// registers from the first load to the final store; the passes touch no memory at all.
-template <int U, bool RESIDENT>
+// U sweeps of 128 rows per workgroup, all in registers; the passes touch no memory at all.
+// Workgroup (x, y) holds rows [y * slab, min(rows, (y + 1) * slab)) of panel x.
+template <int U>
 __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int rows, int nb, int lda, int vec_ok,
-                                                          int ldv, int pre_rows) {
+                                                          int ldv, int pre_rows, int slab, BrQrClusterBatch cb) {
   __shared__ float red[QR_WAVES][32];
   __shared__ float comb[32];
   __shared__ __attribute__((aligned(16))) float dvec[32];
@@ -157,14 +204,22 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   float* __restrict__ Tg = p.T[blockIdx.x];
   float* __restrict__ diag = p.diag[blockIdx.x];
   const bool vec = vec_ok != 0;
+  Cluster cl;
+  cl.xch = cb.xch[blockIdx.x];
+  cl.cnt = cb.cnt[blockIdx.x];
+  cl.w = blockIdx.y;
+  cl.nw = gridDim.y;
+  const bool first = (cl.w == 0);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int sub = tid & 7;
-  const int rg = tid >> 3;
   const int c0 = sub * 4;
   const int group_base = lane & ~7;
-  const int nsweeps = (rows + QR_ROWS_PER_SWEEP - 1) / QR_ROWS_PER_SWEEP;
+  const int row0 = cl.w * slab;                  // first row of this workgroup's slab
+  const int rend = min(rows, row0 + slab);       // one past its last row
+  const int rg = row0 + (tid >> 3);              // this thread's row in sweep 0
+  const int nsweeps = (rend - row0 + QR_ROWS_PER_SWEEP - 1) / QR_ROWS_PER_SWEEP;
 
   for (int i = tid; i < 32 * 33; i += QR_THREADS) (&Tl[0][0])[i] = 0.f;
   if (tid < 32) {
@@ -173,50 +228,28 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   }
   __syncthreads();
 
-  float4 ra[RESIDENT ? U : 1];
+  float4 ra[U];
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (RESIDENT) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int r = rg + QR_ROWS_PER_SWEEP * u;
-      ra[u] = zero4;
-      if (r < rows) ra[u] = panel_load(A + (size_t)r * lda, c0, nb, vec);
-    }
+  for (int u = 0; u < U; ++u) {
+    const int r = rg + QR_ROWS_PER_SWEEP * u;
+    ra[u] = zero4;
+    if (r < rend) ra[u] = panel_load(A + (size_t)r * lda, c0, nb, vec);
   }
 
   // Pre-pass: dot products of column 0 with every column; stash row 0.
   float4 acc = zero4;
-  if (RESIDENT) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int r = rg + QR_ROWS_PER_SWEEP * u;
-      const float x0 = __shfl(ra[u].x, group_base, 64);
-      if (r < rows) {
-        acc = fma4(x0, ra[u], acc);
-        if (r == 0) *reinterpret_cast<float4*>(&pivrow[0][c0]) = ra[u];
-      }
-    }
-  } else {
-    for (int it0 = 0; it0 < nsweeps; it0 += U) {
-      float4 a[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
-        a[u] = zero4;
-        if (r < rows) a[u] = panel_load(A + (size_t)r * lda, c0, nb, vec);
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
-        const float x0 = __shfl(a[u].x, group_base, 64);
-        if (r < rows) {
-          acc = fma4(x0, a[u], acc);
-          if (r == 0) *reinterpret_cast<float4*>(&pivrow[0][c0]) = a[u];
-        }
-      }
+  for (int u = 0; u < U; ++u) {
+    const int r = rg + QR_ROWS_PER_SWEEP * u;
+    const float x0 = __shfl(ra[u].x, group_base, 64);
+    if (r < rend) {
+      acc = fma4(x0, ra[u], acc);
+      if (r == 0) *reinterpret_cast<float4*>(&pivrow[0][c0]) = ra[u];
     }
   }
   panel_reduce(acc, red, comb, tid);
+  cluster_combine(cl, 0, comb, pivrow[0], tid);
   if (tid < 32) dvec[tid] = comb[tid];
   __syncthreads();
 
@@ -245,37 +278,16 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
       pp.w.w = (c0 + 3 > j && c0 + 3 < nb) ? tau * (pr.w + pp.scale * (dv.w - alpha * pr.w)) : 0.f;
     }
     acc = zero4;
-    if (RESIDENT) {
-      const int u0 = j / QR_ROWS_PER_SWEEP;
+    const int u0 = first ? j / QR_ROWS_PER_SWEEP : 0;  // sweeps above row j are finished
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (u >= u0 && u < nsweeps) {  // uniform across the workgroup
-          const int r = rg + QR_ROWS_PER_SWEEP * u;
-          pass_row(ra[u], r, (r >= j) && (r < rows), pp, c0, group_base, acc, pivrow[cur ^ 1]);
-        }
-      }
-    } else {
-      for (int it0 = j / QR_ROWS_PER_SWEEP; it0 < nsweeps; it0 += U) {
-        float4 a[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
-          a[u] = zero4;
-          if ((r >= j) && (r < rows)) a[u] = panel_load(A + (size_t)r * lda, c0, nb, vec);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
-          pass_row(a[u], r, (r >= j) && (r < rows), pp, c0, group_base, acc, pivrow[cur ^ 1]);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int r = rg + QR_ROWS_PER_SWEEP * (it0 + u);
-          if ((r >= j) && (r < rows)) panel_store(A + (size_t)r * lda, c0, nb, vec, a[u]);
-        }
+    for (int u = 0; u < U; ++u) {
+      if (u >= u0 && u < nsweeps) {  // uniform across the workgroup
+        const int r = rg + QR_ROWS_PER_SWEEP * u;
+        pass_row(ra[u], r, (r >= j) && (r < rend), pp, c0, group_base, acc, pivrow[cur ^ 1]);
       }
     }
     panel_reduce(acc, red, comb, tid);
+    cluster_combine(cl, j + 1, comb, pivrow[cur ^ 1], tid);
     if (tid < 32) {
       if (tid > j) dvec[tid] = comb[tid];
       else if (tid < j) zl[tid] = comb[tid];
@@ -287,39 +299,33 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
       Tl[tid][j] = -tau * s;
     } else if (tid == j) {
       Tl[j][j] = tau;
-      diag[j] = pp.beta;
+      if (first) diag[j] = pp.beta;
     }
     __syncthreads();
   }
 
-  // Block-reflector factor, zero padded to BR_QR_NB x BR_QR_NB.
-  for (int i = tid; i < BR_QR_NB * BR_QR_NB; i += QR_THREADS) {
-    const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
-    Tg[i] = (r < nb && c < nb) ? Tl[r][c] : 0.f;
-  }
-  // Clean copy of the reflectors: unit diagonal, zeros above it and right of column nb.  The
-  // copy is a 32-column slice of a wider reflector block (row stride ldv); the pre_rows rows of
-  // that block above this panel's first row are zero in these columns.
-  for (int i = tid; i < pre_rows * BR_QR_NB; i += QR_THREADS) {
-    const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
-    Vc[-(ptrdiff_t)(r + 1) * ldv + c] = 0.f;
-  }
-  if (RESIDENT) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int r = rg + QR_ROWS_PER_SWEEP * u;
-      if (r < rows) {
-        panel_store(A + (size_t)r * lda, c0, nb, vec, ra[u]);
-        *reinterpret_cast<float4*>(Vc + (size_t)r * ldv + c0) = clean_v(ra[u], c0, r, nb);
-      }
+  if (first) {
+    // Block-reflector factor, zero padded to BR_QR_NB x BR_QR_NB.
+    for (int i = tid; i < BR_QR_NB * BR_QR_NB; i += QR_THREADS) {
+      const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
+      Tg[i] = (r < nb && c < nb) ? Tl[r][c] : 0.f;
     }
-  } else {
-    for (int it = 0; it < nsweeps; ++it) {
-      const int r = rg + QR_ROWS_PER_SWEEP * it;
-      if (r < rows) {
-        const float4 a = panel_load(A + (size_t)r * lda, c0, nb, vec);
-        *reinterpret_cast<float4*>(Vc + (size_t)r * ldv + c0) = clean_v(a, c0, r, nb);
-      }
+    // The clean copy of the reflectors (below) is a 32-column slice of a wider reflector block
+    // (row stride ldv); the pre_rows rows of that block above this panel's first row are zero
+    // in these columns.
+    for (int i = tid; i < pre_rows * BR_QR_NB; i += QR_THREADS) {
+      const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
+      Vc[-(ptrdiff_t)(r + 1) * ldv + c] = 0.f;
+    }
+  }
+  // Factorised panel back to the matrix, and the clean copy: unit diagonal, zeros above it and
+  // right of column nb.
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int r = rg + QR_ROWS_PER_SWEEP * u;
+    if (r < rend) {
+      panel_store(A + (size_t)r * lda, c0, nb, vec, ra[u]);
+      *reinterpret_cast<float4*>(Vc + (size_t)r * ldv + c0) = clean_v(ra[u], c0, r, nb);
     }
   }
 }
@@ -385,6 +391,15 @@ __global__ __launch_bounds__(256) void br_qr_build_t(BuildTArgs a, int npanels) 
   for (int i = tid; i < BR_QR_NBO * BR_QR_NBO; i += 256) Tout[i] = T[i / BR_QR_NBO][i % BR_QR_NBO];
 }
 
+struct ZeroArgs {
+  int* ptr[BR_MAXB];
+};
+
+__global__ __launch_bounds__(256) void br_zero_ints(ZeroArgs a, int n) {
+  int* __restrict__ p = a.ptr[blockIdx.y];
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+
 struct SignArgs {
   float* Q[BR_MAXB];
   const float* diag[BR_MAXB];
@@ -403,20 +418,46 @@ __global__ __launch_bounds__(256) void br_qr_fix_signs(SignArgs a, int n) {
 
 }  // namespace br
 
-hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda, int ldv,
-                              int pre_rows) {
+int br_qr_panel_cluster(int rows) { return (rows + br::QR_MAX_SLAB - 1) / br::QR_MAX_SLAB; }
+
+size_t br_qr_panel_xch_floats(int rows) {
+  return (size_t)(BR_QR_NB + 1) * br_qr_panel_cluster(rows) * br::QR_XCH_FLOATS;
+}
+
+hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQrClusterBatch& cb, int batch, int rows, int nb,
+                              int lda, int ldv, int pre_rows) {
   if (batch <= 0) return hipSuccess;
   if (batch > BR_MAXB || rows < nb || nb < 1 || nb > BR_QR_NB || lda < nb || ldv < BR_QR_NB || (ldv & 3) || pre_rows < 0)
     return hipErrorInvalidValue;
   int vec = (lda % 4 == 0);
   for (int i = 0; i < batch && vec; ++i) vec = ((reinterpret_cast<uintptr_t>(p.A[i]) & 15u) == 0);
-  if (rows <= br::QR_RESIDENT_SWEEPS * br::QR_ROWS_PER_SWEEP)
-    hipLaunchKernelGGL((br::br_qr_panel<br::QR_RESIDENT_SWEEPS, true>), dim3(batch), dim3(br::QR_THREADS), 0, s, p, rows, nb,
-                       lda, vec, ldv, pre_rows);
-  else
-    hipLaunchKernelGGL((br::br_qr_panel<br::QR_STREAM_SWEEPS, false>), dim3(batch), dim3(br::QR_THREADS), 0, s, p, rows, nb,
-                       lda, vec, ldv, pre_rows);
-  return hipGetLastError();
+  const int nw = br_qr_panel_cluster(rows);
+  // balanced slabs, whole sweeps
+  int slab = (rows + nw - 1) / nw;
+  slab = (slab + br::QR_ROWS_PER_SWEEP - 1) / br::QR_ROWS_PER_SWEEP * br::QR_ROWS_PER_SWEEP;
+  // A cluster waits for all of its workgroups: every workgroup of a launch must be resident at
+  // the same time (one 1024-thread workgroup per compute unit), so large batches go in pieces.
+  const int per_launch = BR_QR_MAX_RESIDENT / nw;
+  if (per_launch < 1) return hipErrorInvalidValue;
+  for (int off = 0; off < batch; off += per_launch) {
+    const int b = (batch - off < per_launch) ? batch - off : per_launch;
+    BrQrPanelBatch pp;
+    BrQrClusterBatch cc;
+    for (int i = 0; i < BR_MAXB; ++i) {
+      const bool live = i < b;
+      pp.A[i] = live ? p.A[off + i] : nullptr;
+      pp.Vc[i] = live ? p.Vc[off + i] : nullptr;
+      pp.T[i] = live ? p.T[off + i] : nullptr;
+      pp.diag[i] = live ? p.diag[off + i] : nullptr;
+      cc.xch[i] = live ? cb.xch[off + i] : nullptr;
+      cc.cnt[i] = live ? cb.cnt[off + i] : nullptr;
+    }
+    hipLaunchKernelGGL((br::br_qr_panel<br::QR_RESIDENT_SWEEPS>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda,
+                       vec, ldv, pre_rows, slab, cc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda,
@@ -441,6 +482,15 @@ hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const floa
     a.T[i] = (i < batch) ? T[i] : nullptr;
   }
   hipLaunchKernelGGL(br::br_qr_build_t, dim3(batch), dim3(256), 0, s, a, npanels);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_zero_ints(hipStream_t s, int* const* ptrs, int batch, int n) {
+  if (batch <= 0 || n <= 0) return hipSuccess;
+  if (batch > BR_MAXB) return hipErrorInvalidValue;
+  br::ZeroArgs a;
+  for (int i = 0; i < BR_MAXB; ++i) a.ptr[i] = (i < batch) ? ptrs[i] : nullptr;
+  hipLaunchKernelGGL(br::br_zero_ints, dim3((n + 255) / 256, batch), dim3(256), 0, s, a, n);
   return hipGetLastError();
 }
 
