@@ -161,7 +161,7 @@ LowpLayout lowp_layout(const Group& g) {
 }
 
 struct RefreshScratch {
-  size_t P0, P1, gram, V, Y, W, T, Tp, G, diag, xch, cnt, planesA, planesB, total;
+  size_t P0, P1, gram, V, Y, W, T, Tp, Tm, G, X, Z, diag, xch, cnt, planesA, planesB, total;
 };
 
 RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
@@ -176,8 +176,11 @@ RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   r.Y = off; off += align256((size_t)k * BR_QR_NBO * 4);       // V T or V T^T
   r.W = off; off += align256((size_t)k * BR_QR_NBO * 4);       // V^T C
   r.T = off; off += align256(blocks * BR_QR_NBO * BR_QR_NBO * 4);  // one factor per outer block
-  r.Tp = off; off += align256((size_t)(BR_QR_NBO / BR_QR_NB) * BR_QR_NB * BR_QR_NB * 4);
-  r.G = off; off += align256((size_t)BR_QR_NBO * BR_QR_NBO * 4);
+  r.Tp = off; off += align256((size_t)(BR_QR_NBM / BR_QR_NB) * BR_QR_NB * BR_QR_NB * 4);  // panel factors of a middle block
+  r.Tm = off; off += align256((size_t)(BR_QR_NBO / BR_QR_NBM) * BR_QR_NBM * BR_QR_NBM * 4);  // middle factors of an outer block
+  r.G = off; off += align256((size_t)BR_QR_NBM * BR_QR_NBM * 4);  // Gram matrix of a middle block's reflectors
+  r.X = off; off += align256((size_t)BR_QR_NBM * BR_QR_NBM * 4);  // V_0^T V_1
+  r.Z = off; off += align256((size_t)BR_QR_NBM * BR_QR_NBM * 4);  // T_0 (V_0^T V_1)
   r.diag = off; off += align256((size_t)k * 4);
   r.xch = off; off += align256(br_qr_panel_xch_floats((int)k) * 4);            // cluster exchange of one panel launch ...
   r.cnt = off; off += align256((size_t)((k + BR_QR_NB - 1) / BR_QR_NB) * 4);  // ... and one arrival counter per panel
@@ -700,26 +703,31 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 }
 
 // Blocked Householder QR of the k x k matrices P (in place) for a batch of jobs, orthogonal
-// factor written to Q with the sign convention diag(R) >= 0, everything on stream s.  Two-level
-// blocking: inner panels of BR_QR_NB columns are factorised by the panel kernel and applied
-// inside their outer block of BR_QR_NBO columns; the outer block's reflectors are then merged
-// into one compact-WY factor and applied to the trailing matrix with K = BR_QR_NBO contractions.
+// factor written to Q with the sign convention diag(R) >= 0, everything on stream s.
+// Three-level blocking.  Panels of BR_QR_NB columns are factorised by the panel kernel and
+// applied inside their middle block of BR_QR_NBM columns, whose reflectors are merged into one
+// compact-WY factor in LDS.  Two middle blocks form an outer block of BR_QR_NBO columns:
+//   T = [ T_0  -T_0 (V_0^T V_1) T_1 ]
+//       [ 0     T_1                 ]
+// which is applied to the trailing matrix, and later to Q, with K = BR_QR_NBO contractions.
 static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs,
                      char* base, size_t stride, float* partial) {
-  const int NB = BR_QR_NB, NBO = BR_QR_NBO;
+  const int NB = BR_QR_NB, NBM = BR_QR_NBM, NBO = BR_QR_NBO;
   const int nblocks = (k + NBO - 1) / NBO;
-  auto V = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.V); };
-  auto Y = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.Y); };
-  auto W = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.W); };
-  auto T = [&](int i, int blk) { return reinterpret_cast<float*>(base + i * stride + rs.T) + (size_t)blk * NBO * NBO; };
-  auto Tp = [&](int i, int pnl) { return reinterpret_cast<float*>(base + i * stride + rs.Tp) + (size_t)pnl * NB * NB; };
-  auto G = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.G); };
-  auto D = [&](int i) { return reinterpret_cast<float*>(base + i * stride + rs.diag); };
+  auto F = [&](int i, size_t off) { return reinterpret_cast<float*>(base + i * stride + off); };
+  auto V = [&](int i) { return F(i, rs.V); };
+  auto Y = [&](int i) { return F(i, rs.Y); };
+  auto W = [&](int i) { return F(i, rs.W); };
+  auto T = [&](int i, int blk) { return F(i, rs.T) + (size_t)blk * NBO * NBO; };
+  auto Tp = [&](int i, int pnl) { return F(i, rs.Tp) + (size_t)pnl * NB * NB; };
+  auto Tm = [&](int i, int mid) { return F(i, rs.Tm) + (size_t)mid * NBM * NBM; };
+  auto D = [&](int i) { return F(i, rs.diag); };
   auto Cnt = [&](int i) { return reinterpret_cast<int*>(base + i * stride + rs.cnt); };
   auto mm = [&](const BrGemmArgs& a, const BrGemmBatch& gb) { return gemm(c, a, gb, false, partial, s); };
   BrQrPanelBatch pb;
   BrQrClusterBatch cb;
   BrGemmBatch gb;
+  std::memset(&gb, 0, sizeof(gb));
   {
     int* cp[BR_MAXB];
     for (int i = 0; i < B; ++i) cp[i] = Cnt(i);
@@ -729,46 +737,83 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     const int J0 = blk * NBO;
     const int nbo = std::min(NBO, k - J0);  // columns of this outer block
     const int rows = k - J0;                // rows of this outer block
-    const int npanels = (nbo + NB - 1) / NB;
-    for (int pnl = 0; pnl < npanels; ++pnl) {
-      const int j0 = J0 + pnl * NB;
-      const int nb = std::min(NB, k - j0);
-      const int prow = k - j0;
-      std::memset(&pb, 0, sizeof(pb));
-      std::memset(&cb, 0, sizeof(cb));
-      for (int i = 0; i < B; ++i) {
-        pb.A[i] = P[i] + (size_t)j0 * k + j0;
-        pb.Vc[i] = V(i) + (size_t)(pnl * NB) * NBO + pnl * NB;
-        pb.T[i] = Tp(i, pnl);
-        pb.diag[i] = D(i) + j0;
-        cb.xch[i] = reinterpret_cast<float*>(base + i * stride + rs.xch);
-        cb.cnt[i] = Cnt(i) + j0 / NB;
+    const int nmid = (nbo + NBM - 1) / NBM;
+    if (nbo < NBO) {  // the reflector block of a narrow last outer block: unused columns must read as zero
+      int* vp[BR_MAXB];
+      for (int i = 0; i < B; ++i) vp[i] = reinterpret_cast<int*>(V(i));
+      if (!hip_ok(c, br_launch_zero_ints(s, vp, B, rows * NBO), "reflector clear launch")) return false;
+    }
+    for (int mid = 0; mid < nmid; ++mid) {
+      const int M0 = J0 + mid * NBM;
+      const int nbm = std::min(NBM, k - M0);  // columns of this middle block
+      const int mrows = k - M0;
+      const int npanels = (nbm + NB - 1) / NB;
+      if (mid > 0) {
+        // apply middle block 0 to this middle block's columns: Yt = V_0 T_0^T ; W = V_0^T C ; C <- C - Yt W
+        for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Tm(i, 0); gb.C[i] = Y(i); }
+        if (!mm(BrGemmArgs{rows, NBM, NBM, NBO, NBM, NBM, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
+        for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = P[i] + (size_t)J0 * k + M0; gb.C[i] = W(i); }
+        if (!mm(BrGemmArgs{NBM, nbm, rows, NBO, k, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+        for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)J0 * k + M0; }
+        if (!mm(BrGemmArgs{rows, nbm, NBM, NBM, NBM, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
       }
-      if (!hip_ok(c, br_launch_qr_panel(s, pb, cb, B, prow, nb, k, NBO, pnl * NB), "qr panel launch")) return false;
-      const int nin = J0 + nbo - (j0 + nb);  // columns of the outer block still to the right
-      if (nin <= 0) continue;
-      std::memset(&gb, 0, sizeof(gb));
-      // Yt = Vp Tp^T  (prow x NB), Vp = this panel's slice of V
-      for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = Tp(i, pnl); gb.C[i] = Y(i); }
-      if (!mm(BrGemmArgs{prow, NB, NB, NBO, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
-      // W = Vp^T C, C = the outer block's remaining columns in the panel's rows
-      for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
-      if (!mm(BrGemmArgs{NB, nin, prow, NBO, k, NBO, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
-      // C <- C - Yt W
-      for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)j0 * k + j0 + nb; }
-      if (!mm(BrGemmArgs{prow, nin, NB, NB, NBO, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
+      for (int pnl = 0; pnl < npanels; ++pnl) {
+        const int j0 = M0 + pnl * NB;
+        const int nb = std::min(NB, k - j0);
+        const int prow = k - j0;
+        const int voff = j0 - J0;  // this panel's first row and first column inside the reflector block
+        std::memset(&pb, 0, sizeof(pb));
+        std::memset(&cb, 0, sizeof(cb));
+        for (int i = 0; i < B; ++i) {
+          pb.A[i] = P[i] + (size_t)j0 * k + j0;
+          pb.Vc[i] = V(i) + (size_t)voff * NBO + voff;
+          pb.T[i] = Tp(i, pnl);
+          pb.diag[i] = D(i) + j0;
+          cb.xch[i] = F(i, rs.xch);
+          cb.cnt[i] = Cnt(i) + j0 / NB;
+        }
+        if (!hip_ok(c, br_launch_qr_panel(s, pb, cb, B, prow, nb, k, NBO, voff), "qr panel launch")) return false;
+        const int nin = M0 + nbm - (j0 + nb);  // columns of the middle block still to the right
+        if (nin <= 0) continue;
+        // Yt = Vp Tp^T  (prow x NB), Vp = this panel's slice of V
+        for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = Tp(i, pnl); gb.C[i] = Y(i); }
+        if (!mm(BrGemmArgs{prow, NB, NB, NBO, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
+        // W = Vp^T C, C = the middle block's remaining columns in the panel's rows
+        for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
+        if (!mm(BrGemmArgs{NB, nin, prow, NBO, k, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+        // C <- C - Yt W
+        for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)j0 * k + j0 + nb; }
+        if (!mm(BrGemmArgs{prow, nin, NB, NB, NBM, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
+      }
+      // Merge the panels' factors: G = V_mid^T V_mid, then T_mid from the panel factors and G.
+      const float* gp[BR_MAXB];
+      const float* tpp[BR_MAXB];
+      float* tb[BR_MAXB];
+      if (npanels > 1) {
+        for (int i = 0; i < B; ++i) {
+          gb.A[i] = V(i) + (size_t)(mid * NBM) * NBO + mid * NBM;
+          gb.B[i] = gb.A[i];
+          gb.C[i] = F(i, rs.G);
+        }
+        if (!mm(BrGemmArgs{NBM, NBM, mrows, NBO, NBO, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+      }
+      for (int i = 0; i < B; ++i) { gp[i] = F(i, rs.G); tpp[i] = Tp(i, 0); tb[i] = Tm(i, mid); }
+      if (!hip_ok(c, br_launch_qr_build_t(s, gp, tpp, tb, B, npanels), "qr factor merge launch")) return false;
     }
-    // Merge the panels' factors: G = V^T V, then T_blk from the inner factors and G.
-    const float* gp[BR_MAXB];
-    const float* tpp[BR_MAXB];
-    float* tb[BR_MAXB];
-    std::memset(&gb, 0, sizeof(gb));
-    if (npanels > 1) {
-      for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = V(i); gb.C[i] = G(i); }
-      if (!mm(BrGemmArgs{NBO, NBO, rows, NBO, NBO, NBO, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+    {  // outer factor: diagonal blocks, then the coupling block -T_0 (V_0^T V_1) T_1
+      const float* tmp[BR_MAXB];
+      float* tb[BR_MAXB];
+      for (int i = 0; i < B; ++i) { tmp[i] = Tm(i, 0); tb[i] = T(i, blk); }
+      if (!hip_ok(c, br_launch_qr_assemble_t(s, tmp, tb, B, nmid), "qr outer factor launch")) return false;
+      if (nmid > 1) {
+        for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = V(i) + NBM; gb.C[i] = F(i, rs.X); }
+        if (!mm(BrGemmArgs{NBM, NBM, rows, NBO, NBO, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+        for (int i = 0; i < B; ++i) { gb.A[i] = Tm(i, 0); gb.B[i] = F(i, rs.X); gb.C[i] = F(i, rs.Z); }
+        if (!mm(BrGemmArgs{NBM, NBM, NBM, NBM, NBM, NBM, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
+        for (int i = 0; i < B; ++i) { gb.A[i] = F(i, rs.Z); gb.B[i] = Tm(i, 1); gb.C[i] = T(i, blk) + NBM; }
+        if (!mm(BrGemmArgs{NBM, NBM, NBM, NBM, NBM, NBO, 0, 0, -1.f, 0.f, B, 0}, gb)) return false;
+      }
     }
-    for (int i = 0; i < B; ++i) { gp[i] = G(i); tpp[i] = Tp(i, 0); tb[i] = T(i, blk); }
-    if (!hip_ok(c, br_launch_qr_build_t(s, gp, tpp, tb, B, npanels), "qr factor merge launch")) return false;
     const int nt = k - J0 - nbo;
     if (nt <= 0) continue;
     // Yt = V T^T ; W = V^T C ; C <- C - Yt W   on the trailing columns
@@ -793,7 +838,6 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       pb.Vc[i] = V(i);
     }
     if (!hip_ok(c, br_launch_qr_extract_v(s, pb, B, rows, nbo, k, NBO), "qr extract launch")) return false;
-    std::memset(&gb, 0, sizeof(gb));
     // Y = V T ; W = V^T Qsub ; Qsub <- Qsub - Y W,  Qsub = Q[J0:, J0:]
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
     if (!mm(BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;

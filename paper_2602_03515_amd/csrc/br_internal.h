@@ -131,7 +131,8 @@ hipError_t br_launch_bf16_to_f32(hipStream_t s, const uint16_t* src, float* dst,
 
 // ---- QR ---------------------------------------------------------------------------------
 #define BR_QR_NB 32    // inner panel width of the blocked Householder factorisation
-#define BR_QR_NBO 128  // outer block width: four inner panels share one trailing-matrix update
+#define BR_QR_NBM 128  // middle block: four panels, merged into one block reflector inside LDS
+#define BR_QR_NBO 256  // outer block: two middle blocks share one trailing-matrix update (K = 256 contractions)
 
 struct BrQrPanelBatch {
   float* A[BR_MAXB];     // top-left corner of the panel inside the matrix being factorised
@@ -160,10 +161,13 @@ hipError_t br_launch_zero_ints(hipStream_t s, int* const* ptrs, int batch, int n
 // Copy the reflectors of an already factorised block of nb columns out into Vc (rows x width).
 hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda,
                                   int width);
-// Assemble the BR_QR_NBO-wide block-reflector factor from npanels inner factors and the Gram
+// Assemble the BR_QR_NBM-wide block-reflector factor from npanels inner factors and the Gram
 // matrix of the block's reflectors.
 hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const float* const* Tp, float* const* T, int batch,
                                 int npanels);
+// Diagonal blocks of an outer block's factor T (BR_QR_NBO x BR_QR_NBO) from its nmid middle
+// factors (consecutive BR_QR_NBM x BR_QR_NBM matrices); everything else zero.
+hipError_t br_launch_qr_assemble_t(hipStream_t s, const float* const* Tm, float* const* T, int batch, int nmid);
 // Q[:, j] *= sign(diag[j]) (zero counts as +).
 hipError_t br_launch_qr_fix_signs(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n);
 

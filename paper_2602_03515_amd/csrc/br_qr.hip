@@ -1,7 +1,8 @@
 // Householder QR building blocks for the basis refresh (Section 3.2: "power iteration
 // followed by QR decomposition"; Algorithm 2 lines 3 and 6).
 //
-// The factorisation is blocked (panel width BR_QR_NB = 32) in compact-WY form:
+// The factorisation is blocked on three levels (panels of BR_QR_NB = 32 columns, middle blocks of
+// BR_QR_NBM = 128, outer blocks of BR_QR_NBO = 256) in compact-WY form:
 //   H_1 H_2 ... H_nb = I - V T V^T,  V unit lower trapezoidal, T upper triangular.
 // This file holds the panel kernel; the trailing-matrix and Q-forming updates are GEMMs issued
 // by the host logic.  A panel is held ENTIRELY IN REGISTERS from its first load to its final
@@ -345,25 +346,25 @@ __global__ __launch_bounds__(256) void br_qr_extract_v(BrQrPanelBatch p, int row
   }
 }
 
-// Merge the 32-wide block-reflector factors of one outer block into its BR_QR_NBO-wide factor:
+// Merge the 32-wide block-reflector factors of one middle block into its BR_QR_NBM-wide factor:
 //   T = [ T_a  -T_a (V_a^T V_b) T_b ]
 //       [ 0     T_b             ]      applied panel by panel,
-// with the cross products V_a^T V_b read from the Gram matrix G = V^T V of the outer block.
+// with the cross products V_a^T V_b read from the Gram matrix G = V^T V of the middle block.
 // One 256-thread workgroup per matrix; everything lives in LDS.
 struct BuildTArgs {
-  const float* G[BR_MAXB];   // BR_QR_NBO x BR_QR_NBO
+  const float* G[BR_MAXB];   // BR_QR_NBM x BR_QR_NBM
   const float* Tp[BR_MAXB];  // npanels consecutive BR_QR_NB x BR_QR_NB factors
-  float* T[BR_MAXB];         // BR_QR_NBO x BR_QR_NBO output
+  float* T[BR_MAXB];         // BR_QR_NBM x BR_QR_NBM output
 };
 
 __global__ __launch_bounds__(256) void br_qr_build_t(BuildTArgs a, int npanels) {
-  __shared__ float T[BR_QR_NBO][BR_QR_NBO + 1];
-  __shared__ float Z[BR_QR_NBO][BR_QR_NB + 1];
+  __shared__ float T[BR_QR_NBM][BR_QR_NBM + 1];
+  __shared__ float Z[BR_QR_NBM][BR_QR_NB + 1];
   const float* __restrict__ G = a.G[blockIdx.x];
   const float* __restrict__ Tp = a.Tp[blockIdx.x];
   float* __restrict__ Tout = a.T[blockIdx.x];
   const int tid = threadIdx.x;
-  for (int i = tid; i < BR_QR_NBO * BR_QR_NBO; i += 256) T[i / BR_QR_NBO][i % BR_QR_NBO] = 0.f;
+  for (int i = tid; i < BR_QR_NBM * BR_QR_NBM; i += 256) T[i / BR_QR_NBM][i % BR_QR_NBM] = 0.f;
   __syncthreads();
   for (int pnl = 0; pnl < npanels; ++pnl) {
     const int o = pnl * BR_QR_NB;
@@ -375,7 +376,7 @@ __global__ __launch_bounds__(256) void br_qr_build_t(BuildTArgs a, int npanels) 
     for (int i = tid; i < o * BR_QR_NB; i += 256) {
       const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
       float s = 0.f;
-      for (int l = r; l < o; ++l) s += T[r][l] * G[(size_t)l * BR_QR_NBO + o + c];
+      for (int l = r; l < o; ++l) s += T[r][l] * G[(size_t)l * BR_QR_NBM + o + c];
       Z[r][c] = s;
     }
     __syncthreads();
@@ -388,7 +389,27 @@ __global__ __launch_bounds__(256) void br_qr_build_t(BuildTArgs a, int npanels) 
     }
     __syncthreads();
   }
-  for (int i = tid; i < BR_QR_NBO * BR_QR_NBO; i += 256) Tout[i] = T[i / BR_QR_NBO][i % BR_QR_NBO];
+  for (int i = tid; i < BR_QR_NBM * BR_QR_NBM; i += 256) Tout[i] = T[i / BR_QR_NBM][i % BR_QR_NBM];
+}
+
+// T of an outer block (BR_QR_NBO wide) from its middle blocks' factors: the diagonal blocks are
+// copied here, the rest is zeroed; the coupling block -T_0 (V_0^T V_1) T_1 is then written over
+// the upper right corner by two small contractions.
+struct AssembleTArgs {
+  const float* Tm[BR_MAXB];  // nmid consecutive BR_QR_NBM x BR_QR_NBM factors
+  float* T[BR_MAXB];         // BR_QR_NBO x BR_QR_NBO output
+};
+
+__global__ __launch_bounds__(256) void br_qr_assemble_t(AssembleTArgs a, int nmid) {
+  const float* __restrict__ Tm = a.Tm[blockIdx.y];
+  float* __restrict__ T = a.T[blockIdx.y];
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < BR_QR_NBO * BR_QR_NBO; i += gridDim.x * 256) {
+    const int r = i / BR_QR_NBO, c = i - r * BR_QR_NBO;
+    const int mb = r / BR_QR_NBM;
+    float v = 0.f;
+    if (c / BR_QR_NBM == mb && mb < nmid) v = Tm[(size_t)mb * BR_QR_NBM * BR_QR_NBM + (r % BR_QR_NBM) * BR_QR_NBM + c % BR_QR_NBM];
+    T[i] = v;
+  }
 }
 
 struct ZeroArgs {
@@ -474,7 +495,7 @@ hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int ba
 hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const float* const* Tp, float* const* T, int batch,
                                 int npanels) {
   if (batch <= 0) return hipSuccess;
-  if (batch > BR_MAXB || npanels < 1 || npanels * BR_QR_NB > BR_QR_NBO) return hipErrorInvalidValue;
+  if (batch > BR_MAXB || npanels < 1 || npanels * BR_QR_NB > BR_QR_NBM) return hipErrorInvalidValue;
   br::BuildTArgs a;
   for (int i = 0; i < BR_MAXB; ++i) {
     a.G[i] = (i < batch) ? G[i] : nullptr;
@@ -482,6 +503,18 @@ hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const floa
     a.T[i] = (i < batch) ? T[i] : nullptr;
   }
   hipLaunchKernelGGL(br::br_qr_build_t, dim3(batch), dim3(256), 0, s, a, npanels);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_qr_assemble_t(hipStream_t s, const float* const* Tm, float* const* T, int batch, int nmid) {
+  if (batch <= 0) return hipSuccess;
+  if (batch > BR_MAXB || nmid < 1 || nmid * BR_QR_NBM > BR_QR_NBO) return hipErrorInvalidValue;
+  br::AssembleTArgs a;
+  for (int i = 0; i < BR_MAXB; ++i) {
+    a.Tm[i] = (i < batch) ? Tm[i] : nullptr;
+    a.T[i] = (i < batch) ? T[i] : nullptr;
+  }
+  hipLaunchKernelGGL(br::br_qr_assemble_t, dim3(16, batch), dim3(256), 0, s, a, nmid);
   return hipGetLastError();
 }
 
