@@ -70,7 +70,9 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
-__device__ __forceinline__ void panel_reduce(float4 acc, float (*red)[32], float* comb, int tid) {
+// The value for column tid is also returned to threads tid < 32; comb[] is only synchronised
+// when `publish` is set (the cluster exchange reads it from other threads).
+__device__ __forceinline__ float panel_reduce(float4 acc, float (*red)[32], float* comb, int tid, bool publish) {
   const int lane = tid & 63, wave = tid >> 6, sub = tid & 7;
   acc.x = group_sum(acc.x);
   acc.y = group_sum(acc.y);
@@ -83,13 +85,14 @@ __device__ __forceinline__ void panel_reduce(float4 acc, float (*red)[32], float
     red[wave][sub * 4 + 3] = acc.w;
   }
   __syncthreads();
+  float s = 0.f;
   if (tid < 32) {
-    float s = 0.f;
 #pragma unroll
     for (int w = 0; w < QR_WAVES; ++w) s += red[w][tid];
     comb[tid] = s;
   }
-  __syncthreads();
+  if (publish) __syncthreads();
+  return s;
 }
 
 // Cluster part of the reduction (gridDim.y > 1): every workgroup publishes its 32 partial sums
@@ -188,7 +191,8 @@ __device__ __forceinline__ float4 fma4(float s, float4 a, float4 acc) {
   return make_float4(acc.x + s * a.x, acc.y + s * a.y, acc.z + s * a.z, acc.w + s * a.w);
 }
 
-// U sweeps of 128 rows per workgroup, all in registers; the passes touch no memory at all.
+// U sweeps of 128 rows per workgroup (U * 128 >= slab), all in registers; the passes touch no
+// memory at all.
 // Workgroup (x, y) holds rows [y * slab, min(rows, (y + 1) * slab)) of panel x.
 template <int U>
 __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int rows, int nb, int lda, int vec_ok,
@@ -196,9 +200,10 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   __shared__ float red[QR_WAVES][32];
   __shared__ float comb[32];
   __shared__ __attribute__((aligned(16))) float dvec[32];
-  __shared__ float zl[32];
   __shared__ __attribute__((aligned(16))) float pivrow[2][32];
-  __shared__ float Tl[32][33];
+  __shared__ float Sl[32][33];  // Sl[l][j] = v_l^T v_j for l < j: the strict upper triangle of V^T V
+  __shared__ float Xl[32][33];  // columns of T while they are being solved for
+  __shared__ float taus[32];
 
   float* __restrict__ A = p.A[blockIdx.x];
   float* __restrict__ Vc = p.Vc[blockIdx.x];
@@ -220,10 +225,13 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   const int row0 = cl.w * slab;                  // first row of this workgroup's slab
   const int rend = min(rows, row0 + slab);       // one past its last row
   const int rg = row0 + (tid >> 3);              // this thread's row in sweep 0
-  const int nsweeps = (rend - row0 + QR_ROWS_PER_SWEEP - 1) / QR_ROWS_PER_SWEEP;
 
-  for (int i = tid; i < 32 * 33; i += QR_THREADS) (&Tl[0][0])[i] = 0.f;
+  for (int i = tid; i < 32 * 33; i += QR_THREADS) {
+    (&Sl[0][0])[i] = 0.f;
+    (&Xl[0][0])[i] = 0.f;
+  }
   if (tid < 32) {
+    taus[tid] = 0.f;
     pivrow[0][tid] = 0.f;
     pivrow[1][tid] = 0.f;
   }
@@ -249,10 +257,16 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
       if (r == 0) *reinterpret_cast<float4*>(&pivrow[0][c0]) = ra[u];
     }
   }
-  panel_reduce(acc, red, comb, tid);
-  cluster_combine(cl, 0, comb, pivrow[0], tid);
-  if (tid < 32) dvec[tid] = comb[tid];
-  __syncthreads();
+  {
+    const bool multi = cl.nw > 1;
+    float sum = panel_reduce(acc, red, comb, tid, multi);
+    if (multi) {
+      cluster_combine(cl, 0, comb, pivrow[0], tid);
+      if (tid < 32) sum = comb[tid];
+    }
+    if (tid < 32) dvec[tid] = sum;
+    __syncthreads();
+  }
 
   for (int j = 0; j < nb; ++j) {
     const int cur = j & 1;
@@ -279,37 +293,55 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
       pp.w.w = (c0 + 3 > j && c0 + 3 < nb) ? tau * (pr.w + pp.scale * (dv.w - alpha * pr.w)) : 0.f;
     }
     acc = zero4;
-    const int u0 = first ? j / QR_ROWS_PER_SWEEP : 0;  // sweeps above row j are finished
+    // Every sweep, unconditionally: the loop body is free of branches, so the cross-lane reads of
+    // different sweeps overlap.  Rows past the slab hold zeros and stay zero; rows above row j are
+    // finished and whatever the pass does to them is masked out of the sums and of the reflectors.
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (u >= u0 && u < nsweeps) {  // uniform across the workgroup
-        const int r = rg + QR_ROWS_PER_SWEEP * u;
-        pass_row(ra[u], r, (r >= j) && (r < rend), pp, c0, group_base, acc, pivrow[cur ^ 1]);
+      const int r = rg + QR_ROWS_PER_SWEEP * u;
+      pass_row(ra[u], r, (r >= j) && (r < rend), pp, c0, group_base, acc, pivrow[cur ^ 1]);
+    }
+    {
+      // Column sums of this pass: for c > j the dot products of the next pass, for c < j the entries
+      // v_c^T v_j of the Gram matrix of the reflectors.
+      const bool multi = cl.nw > 1;
+      float sum = panel_reduce(acc, red, comb, tid, multi);
+      if (multi) {
+        cluster_combine(cl, j + 1, comb, pivrow[cur ^ 1], tid);
+        if (tid < 32) sum = comb[tid];
       }
+      if (tid < 32) {
+        if (tid > j) dvec[tid] = sum;
+        else if (tid < j) Sl[tid][j] = sum;
+        else {
+          taus[j] = tau;
+          if (first) diag[j] = pp.beta;
+        }
+      }
+      __syncthreads();
     }
-    panel_reduce(acc, red, comb, tid);
-    cluster_combine(cl, j + 1, comb, pivrow[cur ^ 1], tid);
-    if (tid < 32) {
-      if (tid > j) dvec[tid] = comb[tid];
-      else if (tid < j) zl[tid] = comb[tid];
-    }
-    __syncthreads();
-    if (tid < j) {
-      float s = 0.f;
-      for (int l = tid; l < j; ++l) s += Tl[tid][l] * zl[l];
-      Tl[tid][j] = -tau * s;
-    } else if (tid == j) {
-      Tl[j][j] = tau;
-      if (first) diag[j] = pp.beta;
-    }
-    __syncthreads();
   }
+
+  // Block-reflector factor.  H_1 ... H_nb = I - V T V^T with T^-1 = diag(1 / tau) + strict upper
+  // triangle of V^T V: thread t solves for column t of T by back substitution.  A reflector with
+  // tau = 0 is the identity; its row and column of T are zero.
+  if (first && tid < 32) {
+    const int t = tid;
+    const float tt = (t < nb) ? taus[t] : 0.f;
+    Xl[t][t] = tt;
+    for (int r = t - 1; r >= 0; --r) {
+      float sacc = 0.f;
+      for (int l = r + 1; l <= t; ++l) sacc += Sl[r][l] * Xl[l][t];
+      Xl[r][t] = (tt != 0.f) ? -taus[r] * sacc : 0.f;
+    }
+  }
+  __syncthreads();
 
   if (first) {
     // Block-reflector factor, zero padded to BR_QR_NB x BR_QR_NB.
     for (int i = tid; i < BR_QR_NB * BR_QR_NB; i += QR_THREADS) {
       const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
-      Tg[i] = (r < nb && c < nb) ? Tl[r][c] : 0.f;
+      Tg[i] = (r < nb && c < nb && r <= c) ? Xl[r][c] : 0.f;
     }
     // The clean copy of the reflectors (below) is a 32-column slice of a wider reflector block
     // (row stride ldv); the pre_rows rows of that block above this panel's first row are zero
@@ -473,8 +505,16 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
       cc.xch[i] = live ? cb.xch[off + i] : nullptr;
       cc.cnt[i] = live ? cb.cnt[off + i] : nullptr;
     }
-    hipLaunchKernelGGL((br::br_qr_panel<br::QR_RESIDENT_SWEEPS>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda,
-                       vec, ldv, pre_rows, slab, cc);
+    const int sweeps = slab / br::QR_ROWS_PER_SWEEP;
+    if (sweeps <= 5)
+      hipLaunchKernelGGL((br::br_qr_panel<5>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda, vec, ldv, pre_rows,
+                         slab, cc);
+    else if (sweeps <= 10)
+      hipLaunchKernelGGL((br::br_qr_panel<10>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda, vec, ldv, pre_rows,
+                         slab, cc);
+    else
+      hipLaunchKernelGGL((br::br_qr_panel<br::QR_RESIDENT_SWEEPS>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda,
+                         vec, ldv, pre_rows, slab, cc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
