@@ -29,6 +29,9 @@ struct MatState {
   bool rot_l = false, rot_r = false;
   float *M = nullptr, *S = nullptr, *L = nullptr, *R = nullptr, *QL = nullptr, *QR = nullptr;
   float *master = nullptr, *norms = nullptr, *Mrot = nullptr;
+  // BF16 math modes: operand planes of the bases in both orientations (state region, rebuilt when
+  // the bases change) and of this step's gradient (scratch, valid from br_accumulate_stats to br_step)
+  uint16_t *qlp = nullptr, *qlt = nullptr, *qrp = nullptr, *qrt = nullptr, *gp = nullptr, *gtp = nullptr;
   bool master_ready = false;
 };
 
@@ -60,6 +63,7 @@ struct RefreshUnit {
 
 struct Layout {
   size_t state_bytes = 0, scratch_bytes = 0;
+  size_t gplane_bytes = 0;  // gradient planes of all rotated matrices, ahead of the per-phase scratch
   std::vector<Group> groups;
   std::map<int64_t, std::vector<RefreshJob>> refresh;  // factor order -> jobs
   std::vector<RefreshUnit> units;
@@ -73,6 +77,8 @@ struct br_ctx {
   Layout lay;
   hipStream_t stream = nullptr;
   char* scratch = nullptr;
+  char* phase = nullptr;  // scratch shared by the phases of a step (after the norm partials and the gradient planes)
+  bool qplanes_valid = false;  // BF16 math modes: the bases' operand planes match the bases
   float* clip_result = nullptr;  // 2 floats at the end of the state region
   int64_t t = 0;
   bool stats_fresh = false;
@@ -138,26 +144,23 @@ int step_buffers(const Group& g, const br_hparams& hp) {
   return nb;
 }
 
-// Scratch of one matrix during a step in the BF16 math modes.  Eleven slots, each large enough for
-// an m x n FP32 matrix or for a pair of BF16 planes of it (either orientation, padded as
-// br_plane_layout says), followed by the planes of the bases in both orientations.
-enum { LS_GP = 0, LS_GTP, LS_T1, LS_T1P, LS_GX, LS_XP, LS_MP, LS_T2, LS_T2P, LS_MROT, LS_G32, LS_COUNT };
+// Scratch of one matrix during a step in the BF16 math modes.  Slots, each large enough for an
+// m x n FP32 matrix or for a pair of BF16 planes of it (either orientation, padded as
+// br_plane_layout says).
+enum { LS_T1 = 0, LS_T1P, LS_GX, LS_XP, LS_YP, LS_MP, LS_T2, LS_T2P, LS_MROT, LS_G32, LS_COUNT };
 struct LowpLayout {
-  size_t slot, qlp, qlt, qrp, qrt, per_mat;
+  size_t slot, per_mat;
 };
 LowpLayout lowp_layout(const Group& g) {
   LowpLayout l;
   const size_t a = br_plane_layout(g.m, g.n).elems, b = br_plane_layout(g.n, g.m).elems;
   l.slot = align256(4 * std::max(a, b));  // two BF16 planes, or (rows and k only grow by padding) an FP32 m x n matrix
-  size_t off = LS_COUNT * l.slot;
-  const size_t ql = g.rot_l ? align256(4 * br_plane_layout(g.m, g.m).elems) : 0;
-  const size_t qr = g.rot_r ? align256(4 * br_plane_layout(g.n, g.n).elems) : 0;
-  l.qlp = off; off += ql;
-  l.qlt = off; off += ql;
-  l.qrp = off; off += qr;
-  l.qrt = off; off += qr;
-  l.per_mat = off;
+  l.per_mat = LS_COUNT * l.slot;
   return l;
+}
+// bytes of the operand planes (hi, or hi + lo) of a rows x k matrix
+inline size_t plane_bytes(int64_t rows, int64_t k, const br_hparams& hp) {
+  return align256((hp.math == BR_MATH_BF16X3 ? 4 : 2) * br_plane_layout(rows, k).elems);
 }
 
 struct RefreshScratch {
@@ -195,6 +198,7 @@ RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
 void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Layout* lay) {
   lay->groups.clear();
   lay->refresh.clear();
+  lay->gplane_bytes = 0;
   size_t state = 0, scratch = 0;
   for (int i = 0; i < n_mats; ++i) {
     const br_matrix_desc& d = descs[i];
@@ -210,6 +214,11 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
     if (r) state += align256((size_t)d.n * d.n * 4);
     if (d.param_dtype == BR_BF16) state += mn;
     if ((l || r) && hp.cache_rotated_moment) state += mn;
+    if (hp.math != BR_MATH_F32) {
+      if (l) state += 2 * plane_bytes(d.m, d.m, hp);
+      if (r) state += 2 * plane_bytes(d.n, d.n, hp);
+      if (l || r) lay->gplane_bytes += plane_bytes(d.m, d.n, hp) + plane_bytes(d.n, d.m, hp);
+    }
     state += 256;  // norms
     Group* g = nullptr;
     for (auto& c : lay->groups)
@@ -247,7 +256,7 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
   scratch = std::max(scratch, refresh_bytes);
   state += 256;  // global gradient norm and clipping factor
   lay->state_bytes = state;
-  lay->scratch_bytes = scratch + kNormPartialBytes;
+  lay->scratch_bytes = scratch + kNormPartialBytes + lay->gplane_bytes;
 }
 
 // ---- launch bookkeeping ------------------------------------------------------------------
@@ -304,7 +313,7 @@ bool gemm(br_ctx* c, BrGemmArgs a, const BrGemmBatch& b, bool step = true, float
 }
 
 inline float* scratch_buf(br_ctx* c, size_t per_mat_bufs, size_t bytes_each, int mat_in_chunk, int which) {
-  return reinterpret_cast<float*>(c->scratch + kNormPartialBytes + ((size_t)mat_in_chunk * per_mat_bufs + which) * bytes_each);
+  return reinterpret_cast<float*>(c->phase + ((size_t)mat_in_chunk * per_mat_bufs + which) * bytes_each);
 }
 
 
@@ -318,7 +327,6 @@ struct LowpCtx {
   char* base;  // scratch of this chunk
   uint16_t* slot16(int i, int s) const { return reinterpret_cast<uint16_t*>(base + (size_t)i * lay.per_mat + (size_t)s * lay.slot); }
   float* slot32(int i, int s) const { return reinterpret_cast<float*>(base + (size_t)i * lay.per_mat + (size_t)s * lay.slot); }
-  uint16_t* qplane(int i, size_t off) const { return reinterpret_cast<uint16_t*>(base + (size_t)i * lay.per_mat + off); }
 };
 
 // planes of the R x C matrices src[i] (row stride C), optionally transposed
@@ -328,98 +336,149 @@ bool lowp_split(const LowpCtx& x, const float* const* src, int R, int Ccols, boo
                                             x.nprod == 3 ? 1 : 0), "plane split launch");
 }
 
-// C_i = alpha A_i B_i^T + beta C_i with A_i: M x K planes, B_i: N x K planes
+// C_i = alpha A_i B_i^T + beta C_i with A_i: M x K planes, B_i: N x K planes.  With an epilogue other
+// than BR_EPI_F32 the transposed result leaves as planes in out16 (see BrLowpArgs).
 bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp, int N, int K, float* const* C, int ldc,
-               float alpha, float beta, uint16_t* const* shadow, bool mirror, int nprod = 0) {
+               float alpha, float beta, uint16_t* const* out16, bool mirror, int nprod = 0, int epilogue = BR_EPI_F32,
+               const BrAdamArgs* adam = nullptr, float* const* S = nullptr, float* const* Mrot = nullptr) {
   if (nprod == 0) nprod = x.nprod;
   BrLowpBatch b;
   std::memset(&b, 0, sizeof(b));
   for (int i = 0; i < x.B; ++i) {
     b.A[i] = A[i];
     b.B[i] = Bp[i];
-    b.C[i] = C[i];
-    b.shadow[i] = shadow ? shadow[i] : nullptr;
+    b.C[i] = C ? C[i] : nullptr;
+    b.shadow[i] = out16 ? out16[i] : nullptr;
+    b.S[i] = S ? S[i] : nullptr;
+    b.Mrot[i] = Mrot ? Mrot[i] : nullptr;
   }
   BrLowpArgs a{M, N, K, ldc, alpha, beta, x.B, mirror ? 1 : 0, nprod};
+  a.epilogue = epilogue;
+  a.out_lo = (x.nprod == 3) ? 1 : 0;
+  if (adam) a.adam = *adam;
   double flops = 2.0 * M * N * (double)K * x.B;
-  if (mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (M + 127) / 128));
+  if (mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (M + 255) / 256));
   const char* name = nullptr;
   (void)br_launch_gemm_lowp(nullptr, BrLowpArgs{0, 0, 0, 0, 0.f, 0.f, 0, 0, nprod}, b, &name);
   Timed tm(x.c, name, flops, 0.0);
   return hip_ok(x.c, br_launch_gemm_lowp(x.c->stream, a, b, nullptr), "bf16 gemm launch");
 }
 
-// a2 in the BF16 modes for one chunk: L <- b L + (1-b) G G^T, R <- b R + (1-b) G^T G
-bool lowp_stats(const LowpCtx& x, const float* const* G32, size_t off) {
+// Operand planes of this step's gradients in both orientations (kept until br_step), and a2 in the
+// BF16 modes for one chunk: L <- b L + (1-b) G G^T, R <- b R + (1-b) G^T G.
+bool lowp_stats(const LowpCtx& x, const float* const* G32, size_t off, bool with_stats) {
   const Group& g = *x.g;
   const br_hparams& hp = x.c->hp;
   const int m = (int)g.m, n = (int)g.n;
-  uint16_t* pl[BR_MAXB];
+  uint16_t *gp[BR_MAXB], *gtp[BR_MAXB];
   float* out[BR_MAXB];
+  for (int i = 0; i < x.B; ++i) {
+    gp[i] = x.c->mats[g.idx[off + i]].gp;
+    gtp[i] = x.c->mats[g.idx[off + i]].gtp;
+  }
+  if (!lowp_split(x, G32, m, n, false, gp) || !lowp_split(x, G32, m, n, true, gtp)) return false;
+  if (!with_stats) return true;
   if (g.rot_l) {
-    for (int i = 0; i < x.B; ++i) { pl[i] = x.slot16(i, LS_GP); out[i] = x.c->mats[g.idx[off + i]].L; }
-    if (!lowp_split(x, G32, m, n, false, pl)) return false;
-    if (!lowp_gemm(x, pl, m, pl, m, n, out, m, 1.0f - hp.stat_beta, hp.stat_beta, nullptr, true, x.nprod == 3 ? 4 : 1)) return false;
+    for (int i = 0; i < x.B; ++i) out[i] = x.c->mats[g.idx[off + i]].L;
+    if (!lowp_gemm(x, gp, m, gp, m, n, out, m, 1.0f - hp.stat_beta, hp.stat_beta, nullptr, true, x.nprod == 3 ? 4 : 1)) return false;
   }
   if (g.rot_r) {
-    for (int i = 0; i < x.B; ++i) { pl[i] = x.slot16(i, LS_GTP); out[i] = x.c->mats[g.idx[off + i]].R; }
-    if (!lowp_split(x, G32, m, n, true, pl)) return false;
-    if (!lowp_gemm(x, pl, n, pl, n, m, out, n, 1.0f - hp.stat_beta, hp.stat_beta, nullptr, true, x.nprod == 3 ? 4 : 1)) return false;
+    for (int i = 0; i < x.B; ++i) out[i] = x.c->mats[g.idx[off + i]].R;
+    if (!lowp_gemm(x, gtp, n, gtp, n, m, out, n, 1.0f - hp.stat_beta, hp.stat_beta, nullptr, true, x.nprod == 3 ? 4 : 1)) return false;
   }
   return true;
 }
 
-// a4-a6 in the BF16 modes for one chunk.  Every contraction is A B^T on planes with k contiguous;
-// the transposed operands come from the split kernel.
+// a4-a6 in the BF16 modes for one chunk.  Every contraction is A B^T on planes with k contiguous.
+// Fused form (bilateral, or left factor only; no norms requested): no intermediate exists in FP32.
+// Each contraction hands its result to the next one as operand planes straight from its
+// accumulators, which emit the TRANSPOSE of what they hold; so the chain alternates between a
+// product and its transpose:
+//   (Q_L^T G)^T = G^T Q_L          -> planes of T = Q_L^T G
+//   G~ = T Q_R, Adam in the epilogue (moments advanced in place)  -> planes of X^T
+//   (Q_L X)^T = X^T Q_L^T          -> planes of Y = Q_L X
+//   W <- decay W - lr Y Q_R^T      (FP32 epilogue)
+// Otherwise every product is stored in FP32 and split again (rotate_in / rotate back below).
 bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* const* Wp, uint16_t* const* shadow,
                float* const* Mt, bool advance, const BrAdamArgs& aa, float lr, float decay, float* partials) {
   br_ctx* c = x.c;
   const Group& g = *x.g;
   const int m = (int)g.m, n = (int)g.n, B = x.B;
   const int64_t count = g.m * g.n;
-  uint16_t *QLp[BR_MAXB], *QLt[BR_MAXB], *QRp[BR_MAXB], *QRt[BR_MAXB];
+  uint16_t *QLp[BR_MAXB], *QLt[BR_MAXB], *QRp[BR_MAXB], *QRt[BR_MAXB], *GP[BR_MAXB], *GTP[BR_MAXB];
   uint16_t *P0[BR_MAXB], *P1[BR_MAXB];
   const float* src[BR_MAXB];
   float* dst[BR_MAXB];
   float* GX[BR_MAXB];
+  float* Sp[BR_MAXB];
   for (int i = 0; i < B; ++i) {
-    QLp[i] = x.qplane(i, x.lay.qlp); QLt[i] = x.qplane(i, x.lay.qlt);
-    QRp[i] = x.qplane(i, x.lay.qrp); QRt[i] = x.qplane(i, x.lay.qrt);
+    const MatState& ms = c->mats[g.idx[off + i]];
+    QLp[i] = ms.qlp; QLt[i] = ms.qlt; QRp[i] = ms.qrp; QRt[i] = ms.qrt;
+    GP[i] = ms.gp; GTP[i] = ms.gtp;
     GX[i] = x.slot32(i, LS_GX);
+    Sp[i] = ms.S;
   }
-  if (g.rot_l) {
-    for (int i = 0; i < B; ++i) src[i] = c->mats[g.idx[off + i]].QL;
-    if (!lowp_split(x, src, m, m, false, QLp) || !lowp_split(x, src, m, m, true, QLt)) return false;
-  }
-  if (g.rot_r) {
-    for (int i = 0; i < B; ++i) src[i] = c->mats[g.idx[off + i]].QR;
-    if (!lowp_split(x, src, n, n, false, QRp) || !lowp_split(x, src, n, n, true, QRt)) return false;
-  }
-  // rotate one m x n matrix (FP32 sources `in`) into `out`
-  auto rotate_in = [&](const float* const* in, float* const* out, int s_t, int s_tp, int s_plane) -> bool {
-    if (g.rot_l && g.rot_r) {
-      for (int i = 0; i < B; ++i) { P0[i] = x.slot16(i, s_plane); dst[i] = x.slot32(i, s_t); }
-      if (!lowp_split(x, in, m, n, true, P0)) return false;                                   // in^T planes [n][m]
-      if (!lowp_gemm(x, QLt, m, P0, n, m, dst, n, 1.f, 0.f, nullptr, false)) return false;     // T = Q_L^T in
-      for (int i = 0; i < B; ++i) { P1[i] = x.slot16(i, s_tp); src[i] = x.slot32(i, s_t); }
-      if (!lowp_split(x, src, m, n, false, P1)) return false;                                 // T planes [m][n]
-      return lowp_gemm(x, P1, m, QRt, n, n, out, n, 1.f, 0.f, nullptr, false);                // out = T Q_R
-    }
+  if (!c->qplanes_valid) {  // the bases changed (or this is the first step): rebuild their operand planes
     if (g.rot_l) {
-      for (int i = 0; i < B; ++i) P0[i] = x.slot16(i, s_plane);
-      if (!lowp_split(x, in, m, n, true, P0)) return false;
-      return lowp_gemm(x, QLt, m, P0, n, m, out, n, 1.f, 0.f, nullptr, false);                // out = Q_L^T in
+      for (int i = 0; i < B; ++i) src[i] = c->mats[g.idx[off + i]].QL;
+      if (!lowp_split(x, src, m, m, false, QLp) || !lowp_split(x, src, m, m, true, QLt)) return false;
     }
-    for (int i = 0; i < B; ++i) P0[i] = x.slot16(i, s_plane);
-    if (!lowp_split(x, in, m, n, false, P0)) return false;
-    return lowp_gemm(x, P0, m, QRt, n, n, out, n, 1.f, 0.f, nullptr, false);                  // out = in Q_R
+    if (g.rot_r) {
+      for (int i = 0; i < B; ++i) src[i] = c->mats[g.idx[off + i]].QR;
+      if (!lowp_split(x, src, n, n, false, QRp) || !lowp_split(x, src, n, n, true, QRt)) return false;
+    }
+  }
+  const bool bilateral = g.rot_l && g.rot_r;
+  if (!aa.compute_norms && g.rot_l) {
+    uint16_t *T1P[BR_MAXB], *XTP[BR_MAXB], *YP[BR_MAXB];
+    for (int i = 0; i < B; ++i) { T1P[i] = x.slot16(i, LS_T1P); XTP[i] = x.slot16(i, LS_XP); YP[i] = x.slot16(i, LS_YP); }
+    if (!advance) {  // M~ = Q_L^T M Q_R from the first moment itself
+      for (int i = 0; i < B; ++i) { src[i] = c->mats[g.idx[off + i]].M; P0[i] = x.slot16(i, LS_MP); P1[i] = x.slot16(i, LS_T2P); }
+      if (!lowp_split(x, src, m, n, true, P0)) return false;  // planes of M^T
+      if (bilateral) {
+        if (!lowp_gemm(x, P0, n, QLt, m, m, nullptr, 0, 1.f, 0.f, P1, false, 0, BR_EPI_PLANES)) return false;  // planes of Q_L^T M
+        if (!lowp_gemm(x, P1, m, QRt, n, n, Mt, n, 1.f, 0.f, nullptr, false)) return false;                   // M~
+      } else {
+        if (!lowp_gemm(x, QLt, m, P0, n, m, Mt, n, 1.f, 0.f, nullptr, false)) return false;                   // M~ = Q_L^T M
+      }
+    }
+    if (bilateral) {
+      if (!lowp_gemm(x, GTP, n, QLt, m, m, nullptr, 0, 1.f, 0.f, T1P, false, 0, BR_EPI_PLANES)) return false;            // T
+      if (!lowp_gemm(x, T1P, m, QRt, n, n, nullptr, n, 1.f, 0.f, XTP, false, 0, BR_EPI_ADAM, &aa, Sp, Mt)) return false;  // X^T
+      if (!lowp_gemm(x, XTP, n, QLp, m, m, nullptr, 0, 1.f, 0.f, YP, false, 0, BR_EPI_PLANES)) return false;             // Y
+      return lowp_gemm(x, YP, m, QRp, n, n, Wp, n, -lr, decay, shadow, false);                                          // W
+    }
+    if (!lowp_gemm(x, QLt, m, GTP, n, m, nullptr, n, 1.f, 0.f, XTP, false, 0, BR_EPI_ADAM, &aa, Sp, Mt)) return false;    // X^T
+    return lowp_gemm(x, QLp, m, XTP, n, m, Wp, n, -lr, decay, shadow, false);                                            // W -= lr Q_L X
+  }
+  // rotate one m x n matrix into `out`; its planes are given (gradient) or made here from `in` (first moment)
+  auto rotate_in = [&](const float* const* in, uint16_t* const* in_p, uint16_t* const* in_tp, float* const* out, int s_t,
+                       int s_tp, int s_plane) -> bool {
+    uint16_t* made[BR_MAXB];
+    for (int i = 0; i < B; ++i) made[i] = x.slot16(i, s_plane);
+    if (g.rot_l) {  // needs the planes of in^T ([n][m])
+      if (!in_tp) {
+        if (!lowp_split(x, in, m, n, true, made)) return false;
+        in_tp = made;
+      }
+      if (!bilateral) return lowp_gemm(x, QLt, m, in_tp, n, m, out, n, 1.f, 0.f, nullptr, false);  // out = Q_L^T in
+      for (int i = 0; i < B; ++i) dst[i] = x.slot32(i, s_t);
+      if (!lowp_gemm(x, QLt, m, in_tp, n, m, dst, n, 1.f, 0.f, nullptr, false)) return false;       // T = Q_L^T in
+      for (int i = 0; i < B; ++i) { P1[i] = x.slot16(i, s_tp); src[i] = x.slot32(i, s_t); }
+      if (!lowp_split(x, src, m, n, false, P1)) return false;                                       // T planes [m][n]
+      return lowp_gemm(x, P1, m, QRt, n, n, out, n, 1.f, 0.f, nullptr, false);                      // out = T Q_R
+    }
+    if (!in_p) {
+      if (!lowp_split(x, in, m, n, false, made)) return false;
+      in_p = made;
+    }
+    return lowp_gemm(x, in_p, m, QRt, n, n, out, n, 1.f, 0.f, nullptr, false);                      // out = in Q_R
   };
-  if (!rotate_in(G32, GX, LS_T1, LS_T1P, g.rot_l ? LS_GTP : LS_GP)) return false;
+  if (!rotate_in(G32, GP, GTP, GX, LS_T1, LS_T1P, LS_MP)) return false;
   if (!advance) {
-    for (int i = 0; i < B; ++i) src[i] = c->mats[g.idx[off + i]].M;
     const float* msrc[BR_MAXB];
-    for (int i = 0; i < B; ++i) msrc[i] = src[i];
-    if (!rotate_in(msrc, Mt, LS_T2, LS_T2P, LS_MP)) return false;
+    for (int i = 0; i < B; ++i) msrc[i] = c->mats[g.idx[off + i]].M;
+    if (!rotate_in(msrc, nullptr, nullptr, Mt, LS_T2, LS_T2P, LS_MP)) return false;
   }
   {
     BrAdamBatch ab;
@@ -436,7 +495,7 @@ bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* con
   }
   // rotate back and apply: W <- decay W - lr Q_L X Q_R^T
   for (int i = 0; i < B; ++i) { src[i] = GX[i]; P0[i] = x.slot16(i, LS_XP); }
-  if (g.rot_l && g.rot_r) {
+  if (bilateral) {
     if (!lowp_split(x, src, m, n, true, P0)) return false;                                    // X^T planes [n][m]
     for (int i = 0; i < B; ++i) dst[i] = x.slot32(i, LS_T1);
     if (!lowp_gemm(x, QLp, m, P0, n, m, dst, n, 1.f, 0.f, nullptr, false)) return false;       // Y = Q_L X
@@ -512,10 +571,25 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
     if (m.rot_r) m.QR = take(align256((size_t)m.d.n * m.d.n * 4));
     if (m.d.param_dtype == BR_BF16) m.master = take(mn);
     if ((m.rot_l || m.rot_r) && c->hp.cache_rotated_moment) m.Mrot = take(mn);
+    if (c->hp.math != BR_MATH_F32) {
+      auto take16 = [&](size_t bytes) { return reinterpret_cast<uint16_t*>(take(bytes)); };
+      if (m.rot_l) { m.qlp = take16(plane_bytes(m.d.m, m.d.m, c->hp)); m.qlt = take16(plane_bytes(m.d.m, m.d.m, c->hp)); }
+      if (m.rot_r) { m.qrp = take16(plane_bytes(m.d.n, m.d.n, c->hp)); m.qrt = take16(plane_bytes(m.d.n, m.d.n, c->hp)); }
+    }
     m.norms = take(256);
+  }
+  {
+    char* gp = reinterpret_cast<char*>(dev_workspace) + c->lay.state_bytes + kNormPartialBytes;
+    for (int i = 0; i < n_mats && c->hp.math != BR_MATH_F32; ++i) {
+      MatState& m = c->mats[i];
+      if (!m.rot_l && !m.rot_r) continue;
+      m.gp = reinterpret_cast<uint16_t*>(gp); gp += plane_bytes(m.d.m, m.d.n, c->hp);
+      m.gtp = reinterpret_cast<uint16_t*>(gp); gp += plane_bytes(m.d.n, m.d.m, c->hp);
+    }
   }
   c->clip_result = reinterpret_cast<float*>(p);
   c->scratch = reinterpret_cast<char*>(dev_workspace) + c->lay.state_bytes;
+  c->phase = c->scratch + kNormPartialBytes + c->lay.gplane_bytes;
   // zero state, identity bases
   if (!hip_ok(c, hipMemsetAsync(dev_workspace, 0, c->lay.state_bytes, c->stream), "state clear")) {
     g_static_err = c->err; br_destroy(c); return BR_ERR_HIP;
@@ -561,6 +635,7 @@ br_status br_set_step_count(br_ctx* ctx, int64_t t) {
 br_status br_notify_state_written(br_ctx* ctx) {
   if (!ctx) return BR_ERR_INVALID_ARG;
   ctx->mrot_valid = false;
+  ctx->qplanes_valid = false;
   return BR_OK;
 }
 
@@ -662,8 +737,7 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
     const size_t chunk = lowp ? kLowpChunk : kStepChunk;
     for (size_t off = 0; off < g.idx.size(); off += chunk) {
       const int B = (int)std::min<size_t>(chunk, g.idx.size() - off);
-      LowpCtx lx{c, &g, lowp ? lowp_layout(g) : LowpLayout{}, B, hp.math == BR_MATH_BF16X3 ? 3 : 1,
-                 c->scratch + kNormPartialBytes};
+      LowpCtx lx{c, &g, lowp ? lowp_layout(g) : LowpLayout{}, B, hp.math == BR_MATH_BF16X3 ? 3 : 1, c->phase};
       BrPtrBatch pb;
       std::memset(&pb, 0, sizeof(pb));
       const float* g32[kStepChunk];
@@ -679,11 +753,11 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
         Timed tm(c, "br_ema_first_moment", 2.0 * count * B, bytes);
         if (!hip_ok(c, br_launch_ema(c->stream, pb, B, count, g.gdt == BR_BF16, hp.beta1), "first-moment launch")) return BR_ERR_HIP;
       }
-      if (hp.source != BR_SRC_SECOND || !rotated) continue;
       if (lowp) {
-        if (!lowp_stats(lx, g32, off)) return BR_ERR_HIP;
+        if (!lowp_stats(lx, g32, off, hp.source == BR_SRC_SECOND)) return BR_ERR_HIP;
         continue;
       }
+      if (hp.source != BR_SRC_SECOND || !rotated) continue;
       BrGemmBatch gb;
       std::memset(&gb, 0, sizeof(gb));
       if (g.rot_l) {  // L <- b L + (1-b) G G^T
@@ -856,8 +930,9 @@ br_status br_refresh_basis(br_ctx* ctx) {
   if (ctx->dead) return BR_ERR_HIP;
   br_ctx* c = ctx;
   const br_hparams& hp = c->hp;
-  char* base = c->scratch + kNormPartialBytes;
+  char* base = c->phase;
   c->mrot_valid = false;  // the bases change: M~ must be rebuilt from M at the next step
+  c->qplanes_valid = false;
   for (const RefreshUnit& u : c->lay.units) {
     const int k = (int)u.k;
     const int B = (int)u.jobs.size();
@@ -960,8 +1035,7 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
     const size_t chunk = lowp ? kLowpChunk : kStepChunk;
     for (size_t off = 0; off < g.idx.size(); off += chunk) {
       const int B = (int)std::min<size_t>(chunk, g.idx.size() - off);
-      LowpCtx lx{c, &g, lowp ? lowp_layout(g) : LowpLayout{}, B, hp.math == BR_MATH_BF16X3 ? 3 : 1,
-                 c->scratch + kNormPartialBytes};
+      LowpCtx lx{c, &g, lowp ? lowp_layout(g) : LowpLayout{}, B, hp.math == BR_MATH_BF16X3 ? 3 : 1, c->phase};
       float* Wp[kStepChunk];         // FP32 weights that receive the update
       uint16_t* shadow[kStepChunk];  // BF16 parameter image, or null
       const float* G32[kStepChunk];
@@ -1094,6 +1168,7 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
     }
   }
   c->mrot_valid = true;
+  c->qplanes_valid = true;
   c->t = t;
   c->stats_fresh = false;
   return BR_OK;

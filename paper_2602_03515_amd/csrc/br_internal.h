@@ -36,6 +36,14 @@ struct BrGemmArgs {
 
 hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch& b, const char** kernel_name);
 
+struct BrAdamArgs {
+  float beta1, beta2, eps;
+  float c1, c2;     // bias-correction multipliers for the first/second moment (1 when disabled)
+  int eps_outside;
+  int compute_norms;
+  int update_mrot;  // 1: M~ <- beta1 M~ + (1-beta1) G~ before it is used (cached rotated moment)
+};
+
 // ---- BF16 matrix-core contractions on pre-split operand planes ----------------------------
 // A plane holds an R x K operand as BF16 in the order the contraction kernel wants its LDS tiles:
 // rows padded to a multiple of BR_PLANE_ROW_PAD, k to a multiple of BR_PLANE_K_PAD (zeros),
@@ -59,17 +67,29 @@ inline BrPlaneLayout br_plane_layout(int64_t rows, int64_t k) {
 // C_b = alpha * A_b B_b^T + beta * C_b with A_b the planes of an M x K operand and B_b those of an
 // N x K operand (16-byte aligned).  nprod = 1 uses the hi planes only, nprod = 3 adds the two
 // hi*lo cross terms, nprod = 4 also lo*lo.
+// Epilogues.  BR_EPI_F32: C as above (shadow = optional BF16 image of C).  BR_EPI_PLANES: no FP32
+// store; the TRANSPOSE of alpha A B^T is written to shadow as operand planes of
+// br_plane_layout(N, M) (hi, plus lo when out_lo), padding included.  BR_EPI_ADAM: the product is a
+// rotated gradient; S and Mrot (m x n FP32, row stride ldc) are advanced in place as
+// br_adam_rotated does and X leaves as planes like BR_EPI_PLANES.  The last two need beta = 0
+// and no mirroring.
+enum { BR_EPI_F32 = 0, BR_EPI_PLANES = 1, BR_EPI_ADAM = 2 };
 struct BrLowpBatch {
   const uint16_t* A[BR_MAXB];
   const uint16_t* B[BR_MAXB];
   float* C[BR_MAXB];
   uint16_t* shadow[BR_MAXB];
+  float* S[BR_MAXB];
+  float* Mrot[BR_MAXB];
 };
 struct BrLowpArgs {
   int M, N, K;
   int ldc;
   float alpha, beta;
   int batch, mirror, nprod;
+  int epilogue = BR_EPI_F32;
+  int out_lo = 0;
+  BrAdamArgs adam = {};
 };
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name);
 // hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src) into planes of
@@ -90,13 +110,6 @@ struct BrPtrBatch {
 hipError_t br_launch_ema(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16,
                          float beta1);
 
-struct BrAdamArgs {
-  float beta1, beta2, eps;
-  float c1, c2;     // bias-correction multipliers for the first/second moment (1 when disabled)
-  int eps_outside;
-  int compute_norms;
-  int update_mrot;  // 1: M~ <- beta1 M~ + (1-beta1) G~ before it is used (cached rotated moment)
-};
 struct BrAdamBatch {
   float* GX[BR_MAXB];     // G~ on entry, X = M~ / sqrt(S~ + eps) on exit
   float* S[BR_MAXB];      // second moment in the rotated basis, updated in place

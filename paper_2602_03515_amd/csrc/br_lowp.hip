@@ -54,7 +54,14 @@ struct LowpKernArgs {
   size_t a_plane, b_plane;  // distance from the hi plane to the lo plane, in elements
   float alpha, beta;
   int tiles_m, tiles_n, total_tiles, mirror;
+  // plane-emitting epilogues: the result's transpose as operand planes (rows = N index, k = M index)
+  int out_kp;            // padded k extent of the emitted planes (M to a multiple of 64)
+  size_t out_plane;      // elements from their hi plane to their lo plane
+  int out_lo;            // also emit the lo plane
+  BrAdamArgs adam;       // EPI_ADAM
 };
+
+enum { EPI_F32 = 0, EPI_PLANES = 1, EPI_ADAM = 2 };
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
@@ -82,7 +89,16 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 namespace br {
 
-template <int NPROD>
+// EPI selects what happens to the 256 x 256 tile of alpha A B^T:
+//   EPI_F32     C = tile + beta C in FP32 (optionally mirrored, optional BF16 image);
+//   EPI_PLANES  nothing is stored in FP32: the TRANSPOSE of the result is written as BF16 operand
+//               planes (hi, and lo when out_lo) ready to be the A or B operand of the next
+//               contraction.  An accumulator lane holds 4 consecutive M indices of one N index,
+//               i.e. 4 consecutive k of one plane row: an 8-byte store, two lanes per 16-byte chunk;
+//   EPI_ADAM    the tile is a rotated gradient G~: Adam's moments are advanced in place
+//               (S~ <- b2 S~ + (1-b2) G~ G~, and M~ <- b1 M~ + (1-b1) G~ when adam.update_mrot;
+//               Algorithm 1 lines 9-11) and X = M~ / sqrt(S~ + eps) leaves as planes like above.
+template <int NPROD, int EPI>
 __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLowpBatch batch) {
   constexpr bool SPLIT = NPROD > 1;
   constexpr int KS = SPLIT ? 1 : 2;   // k-steps (16 k) per stage
@@ -244,37 +260,94 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
   stage(nkt - 1, true);
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // the surplus loads of the last iterations
 
-  const bool use_beta = (g.beta != 0.0f);
-  const bool off_diag = g.mirror && (tm != tn);
+  if (EPI == EPI_F32) {
+    const bool use_beta = (g.beta != 0.0f);
+    const bool off_diag = g.mirror && (tm != tn);
 #pragma unroll
-  for (int mi = 0; mi < FM; ++mi) {
+    for (int mi = 0; mi < FM; ++mi) {
 #pragma unroll
-    for (int ni = 0; ni < FN; ++ni) {
-      const int col = n0 + (wn * FN + ni) * 32 + li;
+      for (int ni = 0; ni < FN; ++ni) {
+        const int col = n0 + (wn * FN + ni) * 32 + li;
 #pragma unroll
-      for (int vg = 0; vg < 4; ++vg) {
-        const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;
-        float val[4];
+        for (int vg = 0; vg < 4; ++vg) {
+          const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;
+          float val[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int row = row0 + e;
-          val[e] = g.alpha * acc[mi][ni][vg * 4 + e];
-          if (row < g.M && col < g.N) {
-            const size_t off = (size_t)row * (size_t)g.ldc + col;
-            if (use_beta) val[e] += g.beta * C[off];
-            C[off] = val[e];
-            if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
+          for (int e = 0; e < 4; ++e) {
+            const int row = row0 + e;
+            val[e] = g.alpha * acc[mi][ni][vg * 4 + e];
+            if (row < g.M && col < g.N) {
+              const size_t off = (size_t)row * (size_t)g.ldc + col;
+              if (use_beta) val[e] += g.beta * C[off];
+              C[off] = val[e];
+              if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
+            }
+          }
+          if (off_diag && col < g.N) {
+            // transposed copy of a symmetric result: this lane's four rows are four consecutive columns there
+            float* dst = C + (size_t)col * (size_t)g.ldc + row0;
+            if (row0 + 3 < g.M && ((g.ldc & 3) == 0)) {
+              *reinterpret_cast<float4*>(dst) = make_float4(val[0], val[1], val[2], val[3]);
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (row0 + e < g.M) dst[e] = val[e];
+            }
           }
         }
-        if (off_diag && col < g.N) {
-          // transposed copy of a symmetric result: this lane's four rows are four consecutive columns there
-          float* dst = C + (size_t)col * (size_t)g.ldc + row0;
-          if (row0 + 3 < g.M && ((g.ldc & 3) == 0)) {
-            *reinterpret_cast<float4*>(dst) = make_float4(val[0], val[1], val[2], val[3]);
-          } else {
+      }
+    }
+  } else {
+    uint16_t* __restrict__ Pout = shadow;  // the emitted planes travel in the batch's 16-bit output slot
+    float* __restrict__ S = batch.S[mat];
+    float* __restrict__ Mr = batch.Mrot[mat];
+    const BrAdamArgs ad = g.adam;
+    const float w1 = 1.0f - ad.beta1, w2 = 1.0f - ad.beta2;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (row0 + e < g.M) dst[e] = val[e];
+    for (int mi = 0; mi < FM; ++mi) {
+#pragma unroll
+      for (int ni = 0; ni < FN; ++ni) {
+        const int col = n0 + (wn * FN + ni) * 32 + li;  // plane row; below Np by construction
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+          const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;  // plane k of val[0]
+          float val[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            val[e] = g.alpha * acc[mi][ni][vg * 4 + e];  // exactly zero in the padding: the operands are zero there
+            if (EPI == EPI_ADAM) {
+              const int row = row0 + e;
+              float x = 0.f;
+              if (row < g.M && col < g.N) {
+                const size_t off = (size_t)row * (size_t)g.ldc + col;
+                const float gt = val[e];
+                float mt = Mr[off];
+                if (ad.update_mrot) {
+                  mt = ad.beta1 * mt + w1 * gt;
+                  Mr[off] = mt;
+                }
+                const float st2 = ad.beta2 * S[off] + w2 * (gt * gt);
+                S[off] = st2;
+                const float num = mt * ad.c1, den = st2 * ad.c2;
+                x = ad.eps_outside ? num / (sqrtf(den) + ad.eps) : num / sqrtf(den + ad.eps);
+              }
+              val[e] = x;
+            }
+          }
+          if (row0 < g.out_kp) {  // out_kp is a multiple of 64 and row0 of 4: all four or none
+            const size_t o = (((size_t)(row0 >> 4) * g.Np + col) * 2 + (((row0 >> 3) & 1) ^ swz(col))) * 8 + (row0 & 7);
+            uint16_t h[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16_rne(val[e]);
+            *reinterpret_cast<uint2*>(Pout + o) =
+                make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+            if (g.out_lo) {
+              uint16_t l[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) l[e] = f32_to_bf16_rne(val[e] - bf16_to_f32(h[e]));
+              *reinterpret_cast<uint2*>(Pout + g.out_plane + o) =
+                  make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+            }
           }
         }
       }
@@ -398,16 +471,33 @@ hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16
   return hipGetLastError();
 }
 
+namespace {
+template <int EPI>
+void launch_lowp(hipStream_t s, int nprod, int grid, const LowpKernArgs& k, const BrLowpBatch& b) {
+  if (nprod == 4)
+    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<4, EPI>), dim3(grid), dim3(512), 0, s, k, b);
+  else if (nprod == 3)
+    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<3, EPI>), dim3(grid), dim3(512), 0, s, k, b);
+  else
+    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<1, EPI>), dim3(grid), dim3(512), 0, s, k, b);
+}
+}  // namespace
+
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name) {
   if (kernel_name)
     *kernel_name = (a.nprod == 4) ? "br_gemm_bf16_mfma<4>" : (a.nprod == 3) ? "br_gemm_bf16_mfma<3>" : "br_gemm_bf16_mfma<1>";
   if (a.batch <= 0 || a.M <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
   if (a.batch > BR_MAXB) return hipErrorInvalidValue;
   if (a.mirror && a.M != a.N) return hipErrorInvalidValue;
+  if (a.epilogue != BR_EPI_F32 && (a.mirror || a.beta != 0.f)) return hipErrorInvalidValue;
+  if (a.epilogue != BR_EPI_F32 && a.epilogue != BR_EPI_PLANES && a.epilogue != BR_EPI_ADAM) return hipErrorInvalidValue;
   const BrPlaneLayout pa = br_plane_layout(a.M, a.K), pb = br_plane_layout(a.N, a.K);
   if (pa.rows_p > 0x7fffffffLL || pb.rows_p > 0x7fffffffLL || pa.k_p > 0x7fffffffLL) return hipErrorInvalidValue;
-  for (int i = 0; i < a.batch; ++i)
+  for (int i = 0; i < a.batch; ++i) {
     if ((reinterpret_cast<uintptr_t>(b.A[i]) & 15u) || (reinterpret_cast<uintptr_t>(b.B[i]) & 15u)) return hipErrorInvalidValue;
+    if (a.epilogue != BR_EPI_F32 && (!b.shadow[i] || (reinterpret_cast<uintptr_t>(b.shadow[i]) & 15u))) return hipErrorInvalidValue;
+    if (a.epilogue == BR_EPI_ADAM && (!b.S[i] || !b.Mrot[i])) return hipErrorInvalidValue;
+  }
   LowpKernArgs k;
   k.M = a.M; k.N = a.N;
   k.Mp = (int)pa.rows_p; k.Np = (int)pb.rows_p; k.Kp = (int)pa.k_p;
@@ -418,13 +508,15 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
   k.tiles_n = k.Np / TILE;
   k.mirror = a.mirror ? 1 : 0;
   k.total_tiles = k.mirror ? k.tiles_m * (k.tiles_m + 1) / 2 : k.tiles_m * k.tiles_n;
+  const BrPlaneLayout po = br_plane_layout(a.N, a.M);  // planes of the transposed result
+  k.out_kp = (int)po.k_p;
+  k.out_plane = po.elems;
+  k.out_lo = a.out_lo ? 1 : 0;
+  k.adam = a.adam;
   long long grid = (long long)k.total_tiles * a.batch;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  if (a.nprod == 4)
-    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<4>), dim3((int)grid), dim3(512), 0, s, k, b);
-  else if (a.nprod == 3)
-    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<3>), dim3((int)grid), dim3(512), 0, s, k, b);
-  else
-    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<1>), dim3((int)grid), dim3(512), 0, s, k, b);
+  if (a.epilogue == BR_EPI_ADAM) launch_lowp<EPI_ADAM>(s, a.nprod, (int)grid, k, b);
+  else if (a.epilogue == BR_EPI_PLANES) launch_lowp<EPI_PLANES>(s, a.nprod, (int)grid, k, b);
+  else launch_lowp<EPI_F32>(s, a.nprod, (int)grid, k, b);
   return hipGetLastError();
 }
