@@ -381,3 +381,51 @@ def test_bf16_math_mode_meets_the_2e2_bar(harness, geometry):
     sb, worst = _run(harness, [W0], [[g] for g in grads], freq=4, lr=1e-3, geometry=geometry, math=1, tol=2e-2,
                      check_q=False)
     print("bf16 worst:", {k: f"{v:.2e}" for k, v in worst.items()})
+
+
+@pytest.mark.parametrize("math", [1, 2])
+def test_bf16_modes_injected_basis_midway(harness, math):
+    """BF16 math modes keep operand planes of the bases between steps; overwriting the bases
+    (br_notify_state_written) must rebuild them, and the cached rotated first moment with them."""
+    m, n = 200, 328
+    rng = np.random.default_rng(16)
+    A32 = synth.haar_orthogonal(rng, m).astype(np.float32)
+    B32 = synth.haar_orthogonal(rng, n).astype(np.float32)
+    W0, grads = synth.spiked_gradients(seed=31, m=m, n=n, steps=6, noise_std=0.1)
+    tol = TOL if math == 2 else 2e-2
+    sb = harness.SideBySide([W0], freq=0, lr=1e-2, math=math)
+    w0 = sb.W_ref[0].copy()
+    for t, g in enumerate(grads, 1):
+        if t == 4:
+            sb.opt.state(0, sb.B.BR_STATE_QL).copy_(torch.from_numpy(A32))
+            sb.opt.state(0, sb.B.BR_STATE_QR).copy_(torch.from_numpy(B32))
+            sb.B.br_notify_state_written(sb.opt.ctx)
+            sb.states[0].QL, sb.states[0].QR = A32.astype(np.float64), B32.astype(np.float64)
+        sb.step([g])
+    assert rel_err(sb.gpu_weights(0) - w0, sb.W_ref[0] - w0) <= tol + _storage_floor(sb.W_ref[0], sb.W_ref[0] - w0)
+    sb.compare_state(tol)
+
+
+@pytest.mark.parametrize("geometry", [0, 1])
+def test_bf16x3_fused_and_unfused_chains_agree(harness, geometry):
+    """With per-matrix norms requested the BF16 modes store every product in FP32 and split it
+    again; without, products travel as operand planes and Adam runs in an epilogue.  Same result."""
+    shapes = [(264, 136), (136, 264), (200, 200)]
+    W0s, seqs = [], []
+    for k, (m, n) in enumerate(shapes):
+        W0, grads = synth.spiked_gradients(seed=40 + k, m=m, n=n, steps=7, noise_std=0.1)
+        W0s.append(W0)
+        seqs.append(grads)
+    steps = [[seqs[k][t] for k in range(len(shapes))] for t in range(7)]
+    out = []
+    for norms in (0, 1):
+        sb, _ = _run(harness, W0s, steps, freq=3, lr=1e-3, geometry=geometry, math=2, compute_norms=norms)
+        out.append([sb.gpu_weights(i) for i in range(len(shapes))])
+    for i, W0 in enumerate(W0s):
+        w0 = np.asarray(W0, dtype=np.float64)
+        assert rel_err(out[0][i] - w0, out[1][i] - w0) <= 2e-5 + _storage_floor(out[1][i], out[1][i] - w0)
+
+
+def test_bf16x3_first_moment_source(harness):
+    W0, grads = synth.spiked_gradients(seed=33, m=136, n=264, steps=6, noise_std=0.1)
+    _run(harness, [W0], [[g] for g in grads], freq=3, lr=1e-3, geometry=1, math=2, source=1)
