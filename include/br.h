@@ -167,6 +167,18 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
  */
 br_status br_clip_gradients(br_ctx* ctx, void* const* grads, int32_t n_mats, float max_norm);
 
+/*
+ * Delay Compensation of stale gradients (appendix "Experiments for Other Baselines", first-order
+ * Taylor formula): for every matrix, IN PLACE,
+ *     G <- G + lambda * G . G . (W_now - W_stale)
+ * with W_stale the weights the gradient was taken at and W_now the current ones, both in the
+ * matrix's param_dtype, G in its grad_dtype (BF16 results rounded to nearest even).  Call it
+ * before br_clip_gradients / br_accumulate_stats.  All three arrays: n_mats device pointers.
+ * lambda must lie in [0, 1].
+ */
+br_status br_delay_compensate(br_ctx* ctx, void* const* grads, const void* const* params_now,
+                              const void* const* params_stale, int32_t n_mats, float lambda);
+
 /* Device pointer to two floats: the global norm and the factor of the latest br_clip_gradients. */
 br_status br_get_clip_result(br_ctx* ctx, void** dev_ptr);
 

@@ -283,6 +283,15 @@ def clip_by_global_norm(grads, max_norm: float):
     return [np.asarray(g, dtype=np.float64) * factor for g in grads], norm, factor
 
 
+def delay_compensate(G, W_now, W_stale, lam: float):
+    """Delay Compensation (appendix "Experiments for Other Baselines", the displayed first-order
+    Taylor formula): the gradient taken at the stale weights is corrected towards the current
+    weights with the diagonal empirical Fisher as the Hessian,
+        g <- g + lam * g . g . (w_now - w_stale),     lam in [0, 1]."""
+    g = np.asarray(G, dtype=np.float64)
+    return g + lam * g * g * (np.asarray(W_now, dtype=np.float64) - np.asarray(W_stale, dtype=np.float64))
+
+
 def stage_refresh_periods(delays, base_period: int):
     """Stage-aware refresh allocation (Section 4.3, "Stage-aware" paragraph): the refresh budget
     of a stage, 1 / period, is proportional to its gradient delay, and the total budget equals

@@ -64,6 +64,9 @@ _lib.br_accumulate_stats.argtypes = [_ctx_p, C.POINTER(C.c_void_p), C.c_int32]
 _lib.br_accumulate_stats.restype = C.c_int
 _lib.br_clip_gradients.argtypes = [_ctx_p, C.POINTER(C.c_void_p), C.c_int32, C.c_float]
 _lib.br_clip_gradients.restype = C.c_int
+_lib.br_delay_compensate.argtypes = [_ctx_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32,
+                                     C.c_float]
+_lib.br_delay_compensate.restype = C.c_int
 _lib.br_get_clip_result.argtypes = [_ctx_p, C.POINTER(C.c_void_p)]
 _lib.br_get_clip_result.restype = C.c_int
 _lib.br_refresh_basis.argtypes = [_ctx_p]
@@ -90,7 +93,7 @@ _lib.br_version.restype = C.c_char_p
 _lib.br_destroy.argtypes = [_ctx_p]
 _lib.br_destroy.restype = None
 
-EXPORTED = ["br_workspace_bytes", "br_init", "br_clip_gradients", "br_get_clip_result", "br_accumulate_stats", "br_refresh_basis", "br_step", "br_get_state",
+EXPORTED = ["br_workspace_bytes", "br_init", "br_delay_compensate", "br_clip_gradients", "br_get_clip_result", "br_accumulate_stats", "br_refresh_basis", "br_step", "br_get_state",
             "br_notify_state_written", "br_get_step_count", "br_set_step_count", "br_profile_begin", "br_profile_end", "br_last_error",
             "br_version", "br_destroy"]
 
@@ -164,6 +167,11 @@ def br_accumulate_stats(ctx, grads: Sequence[int]):
 
 def br_clip_gradients(ctx, grads: Sequence[int], max_norm: float):
     _check(_lib.br_clip_gradients(ctx, _ptr_array(grads), len(grads), max_norm), "br_clip_gradients", ctx)
+
+
+def br_delay_compensate(ctx, grads: Sequence[int], params_now: Sequence[int], params_stale: Sequence[int], lam: float):
+    _check(_lib.br_delay_compensate(ctx, _ptr_array(grads), _ptr_array(params_now), _ptr_array(params_stale), len(grads), lam),
+           "br_delay_compensate", ctx)
 
 
 def br_get_clip_result(ctx) -> int:

@@ -684,6 +684,35 @@ br_status br_get_clip_result(br_ctx* ctx, void** dev_ptr) {
   return BR_OK;
 }
 
+br_status br_delay_compensate(br_ctx* ctx, void* const* grads, const void* const* params_now,
+                              const void* const* params_stale, int32_t n_mats, float lambda) {
+  br_status st = check_call(ctx, reinterpret_cast<const void* const*>(grads), params_now, true, n_mats);
+  if (st == BR_OK) st = check_call(ctx, params_stale, nullptr, false, n_mats);
+  if (st != BR_OK) return st;
+  br_ctx* c = ctx;
+  if (!(lambda >= 0.f && lambda <= 1.f)) return fail(c, BR_ERR_INVALID_ARG, "lambda must lie in [0, 1]");
+  if (c->stats_fresh) return fail(c, BR_ERR_STATE, "compensate the gradients before br_accumulate_stats");
+  for (const Group& g : c->lay.groups) {
+    const int64_t count = g.m * g.n;
+    for (size_t off = 0; off < g.idx.size(); off += BR_MAXB) {
+      const int B = (int)std::min<size_t>(BR_MAXB, g.idx.size() - off);
+      BrPtrBatch pb;
+      std::memset(&pb, 0, sizeof(pb));
+      for (int i = 0; i < B; ++i) {
+        pb.in0[i] = params_now[g.idx[off + i]];
+        pb.in1[i] = params_stale[g.idx[off + i]];
+        pb.out0[i] = grads[g.idx[off + i]];
+      }
+      const double gb = (g.gdt == BR_BF16 ? 2.0 : 4.0), wb = (g.pdt == BR_BF16 ? 2.0 : 4.0);
+      Timed tm(c, "br_delay_compensate", 5.0 * count * B, (double)count * B * (2.0 * gb + 2.0 * wb));
+      if (!hip_ok(c, br_launch_delay_compensate(c->stream, pb, B, count, g.gdt == BR_BF16, g.pdt == BR_BF16, lambda),
+                  "delay compensation launch"))
+        return BR_ERR_HIP;
+    }
+  }
+  return BR_OK;
+}
+
 br_status br_clip_gradients(br_ctx* ctx, void* const* grads, int32_t n_mats, float max_norm) {
   br_status st = check_call(ctx, reinterpret_cast<const void* const*>(grads), nullptr, false, n_mats);
   if (st != BR_OK) return st;

@@ -309,6 +309,41 @@ __global__ __launch_bounds__(256) void br_scale_inplace(BrPtrBatch p, int64_t co
   }
 }
 
+// Delay Compensation: G <- G + lambda G.G.(Wn - Ws).  Four entries per lane; every workgroup walks
+// one contiguous range of its matrix.
+__global__ __launch_bounds__(256) void br_delay_compensate(BrPtrBatch p, int64_t count, int grad_bf16, int param_bf16,
+                                                           float lambda) {
+  const void* __restrict__ Wn = p.in0[blockIdx.y];
+  const void* __restrict__ Ws = p.in1[blockIdx.y];
+  void* __restrict__ G = p.out0[blockIdx.y];
+  const int64_t n4 = count >> 2;
+  int64_t lo, hi;
+  block_range(n4, &lo, &hi);
+  for (int64_t i = lo + threadIdx.x; i < hi; i += 256) {
+    float4 g = nt_load_grad4(G, i, grad_bf16);
+    const float4 a = nt_load_grad4(Wn, i, param_bf16), b = nt_load_grad4(Ws, i, param_bf16);
+    g.x += lambda * g.x * g.x * (a.x - b.x);
+    g.y += lambda * g.y * g.y * (a.y - b.y);
+    g.z += lambda * g.z * g.z * (a.z - b.z);
+    g.w += lambda * g.w * g.w * (a.w - b.w);
+    if (grad_bf16) {
+      const u2v o = {(uint32_t)f32_to_bf16_rne(g.x) | ((uint32_t)f32_to_bf16_rne(g.y) << 16),
+                     (uint32_t)f32_to_bf16_rne(g.z) | ((uint32_t)f32_to_bf16_rne(g.w) << 16)};
+      __builtin_nontemporal_store(o, reinterpret_cast<u2v*>(G) + i);
+    } else {
+      nt_store4(reinterpret_cast<float*>(G), i, g);
+    }
+  }
+  if (blockIdx.x == 0) {
+    for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
+      float g = load_grad1(G, i, grad_bf16);
+      g += lambda * g * g * (load_grad1(Wn, i, param_bf16) - load_grad1(Ws, i, param_bf16));
+      if (grad_bf16) reinterpret_cast<uint16_t*>(G)[i] = f32_to_bf16_rne(g);
+      else reinterpret_cast<float*>(G)[i] = g;
+    }
+  }
+}
+
 struct MatPtrs {
   float* p[BR_MAXB];
 };
@@ -389,6 +424,14 @@ hipError_t br_launch_scale_inplace(hipStream_t s, const BrPtrBatch& p, int batch
   if (batch <= 0 || count <= 0) return hipSuccess;
   dim3 grid(br::grid_for(grad_bf16 ? count : count / 4 + 1, batch), batch);
   hipLaunchKernelGGL(br::br_scale_inplace, grid, dim3(256), 0, s, p, count, grad_bf16, result);
+  return hipGetLastError();
+}
+
+hipError_t br_launch_delay_compensate(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16,
+                                      int param_bf16, float lambda) {
+  if (batch <= 0 || count <= 0) return hipSuccess;
+  dim3 grid(br::grid_for(count / 4 + 1, batch), batch);
+  hipLaunchKernelGGL(br::br_delay_compensate, grid, dim3(256), 0, s, p, count, grad_bf16, param_bf16, lambda);
   return hipGetLastError();
 }
 

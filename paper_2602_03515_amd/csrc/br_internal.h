@@ -139,6 +139,9 @@ hipError_t br_launch_sumsq(hipStream_t s, const BrPtrBatch& p, int batch, int64_
 hipError_t br_launch_clip_finalize(hipStream_t s, const float* partials, int n_partials, float max_norm, float* result);
 hipError_t br_launch_scale_inplace(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16,
                                    const float* result);
+// G <- G + lambda G.G.(Wn - Ws): in0 = Wn, in1 = Ws (f32 or bf16 by param_bf16), out0 = G (f32 or bf16 by grad_bf16).
+hipError_t br_launch_delay_compensate(hipStream_t s, const BrPtrBatch& p, int batch, int64_t count, int grad_bf16,
+                                      int param_bf16, float lambda);
 hipError_t br_launch_set_identity(hipStream_t s, float* const* mats, int batch, int n);
 hipError_t br_launch_bf16_to_f32(hipStream_t s, const uint16_t* src, float* dst, int64_t count);
 

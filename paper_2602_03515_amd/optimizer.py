@@ -42,6 +42,11 @@ class BasisRotationAdam:
         self._check_grads(grads)
         B.br_accumulate_stats(self.ctx, [g.data_ptr() for g in grads])
 
+    def delay_compensate(self, grads: Sequence[torch.Tensor], stale_params: Sequence[torch.Tensor], lam: float) -> None:
+        """G <- G + lam G.G.(W - W_stale) in place, W the current parameters."""
+        B.br_delay_compensate(self.ctx, [g.data_ptr() for g in grads], [p.data_ptr() for p in self.params],
+                              [p.data_ptr() for p in stale_params], float(lam))
+
     def clip_gradients(self, grads: Sequence[torch.Tensor], max_norm: float) -> None:
         """Global-norm clipping of the stage's gradients, in place, on the device."""
         self._check_grads(grads)

@@ -429,3 +429,31 @@ def test_bf16x3_fused_and_unfused_chains_agree(harness, geometry):
 def test_bf16x3_first_moment_source(harness):
     W0, grads = synth.spiked_gradients(seed=33, m=136, n=264, steps=6, noise_std=0.1)
     _run(harness, [W0], [[g] for g in grads], freq=3, lr=1e-3, geometry=1, math=2, source=1)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_delay_compensation(harness, bf16):
+    """G <- G + lambda G.G.(W_now - W_stale) on the device against the oracle, ragged sizes included."""
+    shapes = [(96, 64), (33, 17), (5, 3), (257, 129)]
+    rng = np.random.default_rng(77)
+    W0s = [rng.standard_normal(s) for s in shapes]
+    stale = [w + 0.05 * rng.standard_normal(w.shape) for w in W0s]
+    grads = [rng.standard_normal(s) for s in shapes]
+    if bf16:
+        W0s, stale, grads = ([synth.to_bf16_f32(a) for a in x] for x in (W0s, stale, grads))
+    sb = harness.SideBySide(W0s, freq=0, lr=1e-3, bf16_params=bf16, bf16_grads=bf16)
+    dev_g = [harness.to_dev(g, bf16) for g in grads]
+    dev_s = [harness.to_dev(w, bf16) for w in stale]
+    lam = 0.5
+    sb.opt.delay_compensate(dev_g, dev_s, lam)
+    torch.cuda.synchronize()
+    for d, g, w, ws in zip(dev_g, grads, W0s, stale):
+        ref = oc.delay_compensate(g, w, ws, np.float32(lam))
+        got = harness.to_np(d)
+        if bf16:
+            r = oc.bf16_round(ref)
+            assert np.abs(got - r).max() <= 2.0 ** -7 * np.abs(r).max() and (got != r).mean() < 0.01
+        else:
+            assert rel_err(got, ref) <= 1e-6
+    with pytest.raises(Exception):
+        sb.opt.delay_compensate(dev_g, dev_s, 1.5)

@@ -394,3 +394,27 @@ def test_global_norm_clipping_matches_torch():
         for p, o in zip(params, out):
             assert np.abs(p.grad.numpy() - o).max() < 1e-14
         assert (factor < 1.0) == (max_norm == 1.0)
+
+
+def test_delay_compensation_is_exact_on_a_matched_quadratic():
+    """Per coordinate f(w) = h (w - w*)^2 / 2 has the gradient h (w - w*).  When lam * g_stale^2
+    equals h, the compensated stale gradient IS the fresh gradient; the choice below makes that
+    hold with lam = 0.5 on every coordinate.  A wrong sign of (w_now - w_stale), a missing square
+    or a compensation in the stale direction breaks the equality."""
+    rng = np.random.default_rng(3)
+    shape = (7, 5)
+    lam = 0.5
+    g_stale = rng.uniform(0.5, 1.4, size=shape) * rng.choice([-1.0, 1.0], size=shape)
+    h = lam * g_stale ** 2                                   # curvature seen through the empirical Fisher
+    w_star = rng.standard_normal(shape)
+    w_stale = w_star + g_stale / h
+    w_now = w_stale + 0.3 * rng.standard_normal(shape)
+    fresh = h * (w_now - w_star)
+    assert np.allclose(oc.delay_compensate(g_stale, w_now, w_stale, lam), fresh, rtol=1e-13, atol=1e-13)
+    assert not np.allclose(oc.delay_compensate(g_stale, w_stale, w_now, lam), fresh)
+    # lam = 0 and identical weights both leave the gradient alone; the correction is linear in lam
+    assert np.array_equal(oc.delay_compensate(g_stale, w_now, w_stale, 0.0), g_stale)
+    assert np.array_equal(oc.delay_compensate(g_stale, w_now, w_now, 1.0), g_stale)
+    d1 = oc.delay_compensate(g_stale, w_now, w_stale, 0.2) - g_stale
+    d2 = oc.delay_compensate(g_stale, w_now, w_stale, 0.4) - g_stale
+    assert np.allclose(2 * d1, d2, rtol=1e-13)
