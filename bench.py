@@ -90,21 +90,48 @@ def cpu_baseline(seconds_hint=20.0):
                       f"float64 numpy, {t_total:.1f} s"}
 
 
-def counter_traffic(workload_name):
+def counter_traffic(workload_name, kernel):
     """HBM bytes per launch of the dominant kernel, from the hardware-counter runs summarised in
     profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size).  Counters cannot be
     read from inside this process; the value is the one measured for the same library and launch
     shapes by the commands that file lists.  None when no such measurement exists."""
     if workload_name != "stage3b":
         return None
-    path = os.path.join(ROOT, "profiles", "gemm_f32_mfma_stage3b_hbm_traffic.txt")
+    name = "gemm_bf16_mfma_stage3b_hbm_traffic.txt" if "bf16" in kernel else "gemm_f32_mfma_stage3b_hbm_traffic.txt"
     try:
-        for line in open(path):
-            if "traffic_bytes_per_launch" in line:
+        for line in open(os.path.join(ROOT, "profiles", name)):
+            if line.startswith("traffic_bytes_per_launch") and f"[{kernel}]" in line:
                 return float(line.rsplit("=", 1)[1])
     except OSError:
         pass
     return None
+
+
+def run_mode(B, BasisRotationAdam, torch, params, ring, math, warmup, steps):
+    """Times `steps` optimizer steps in one math mode on copies of the parameters; returns
+    (elapsed seconds, profile entries, optimizer)."""
+    work = [p.clone() for p in params]
+    opt = BasisRotationAdam(work, freq=FREQ, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, math=MATH[math])
+    torch.cuda.synchronize()
+    t = 0
+    for _ in range(warmup):
+        t += 1
+        opt.step(ring[t % (TAU + 1)])          # the ring hands over the slot filled tau steps ago
+    torch.cuda.synchronize()
+    B.br_profile_begin(opt.ctx)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        t += 1
+        opt.step(ring[t % (TAU + 1)])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.br_profile_end(opt.ctx)
+    return elapsed, prof, opt
+
+
+def dominant_gemm(prof):
+    gemm = [p for p in prof if p["kernel"].startswith("br_gemm")]
+    return max(gemm, key=lambda p: p["ms"]) if gemm else None
 
 
 def main():
@@ -117,6 +144,8 @@ def main():
                     help="input precision of the step's contractions: f32 (FP32 MFMA, default), "
                          "bf16x3 (hi+lo BF16 split, same 1e-4 bar), bf16 (2e-2 bar)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-modes", action="store_true",
+                    help="after the timed run, also time the other math modes (10 steps each) and report them under 'modes'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that HBM byte counters "
                          "collected by a profiler can be scaled")
@@ -137,9 +166,6 @@ def main():
     shapes, desc = workload(args.workload)
     n_params = sum(m * n for m, n in shapes)
     params, ring = make_inputs(shapes, TAU + 1, seed=2, device=dev)
-    opt = BasisRotationAdam(params, freq=FREQ, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, math=MATH[args.math])
-    torch.cuda.synchronize()
-
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -148,25 +174,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    t = 0
-    for _ in range(args.warmup):
-        t += 1
-        opt.step(ring[t % (TAU + 1)])          # the ring hands over the slot filled tau steps ago
-    torch.cuda.synchronize()
-
-    B.br_profile_begin(opt.ctx)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        t += 1
-        opt.step(ring[t % (TAU + 1)])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof = B.br_profile_end(opt.ctx)
+    elapsed, prof, opt = run_mode(B, BasisRotationAdam, torch, params, ring, args.math, args.warmup, args.steps)
 
     ms_per_step = 1e3 * elapsed / args.steps
     refreshes = sum(1 for k in range(args.warmup + 1, args.warmup + args.steps + 1) if k % FREQ == 0)
-    gemm = [p for p in prof if p["kernel"].startswith("br_gemm")]
-    dom = max(gemm, key=lambda p: p["ms"]) if gemm else None
+    dom = dominant_gemm(prof)
     roofline = None
     if dom:
         avg_ms = dom["ms"] / dom["launches"]
@@ -174,7 +186,7 @@ def main():
         peak = PEAK_TFLOPS["bf16" if "bf16" in dom["kernel"] else "f32"]
         roofline = {"bound": "mfma", "kernel": dom["kernel"], "achieved": achieved, "peak": peak,
                     "unit": "TFLOP/s", "frac": achieved / peak,
-                    "traffic": counter_traffic(args.workload) if dom["kernel"].endswith("<nn>") else None,
+                    "traffic": counter_traffic(args.workload, dom["kernel"]),
                     "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
                     "launches": dom["launches"], "avg_launch_ms": avg_ms}
     breakdown = {p["kernel"]: {"launches": p["launches"], "ms_per_step": p["ms"] / args.steps,
@@ -192,10 +204,33 @@ def main():
         "config": {"workload": f"{args.workload}: {desc}", "params": n_params, "geometry": "bilateral",
                    "source": "second", "refresh_every": FREQ, "refreshes_in_timed_region": refreshes,
                    "power_iters": 1, "delay_tau": TAU, "param_dtype": "f32", "grad_dtype": "f32",
-                   "math": {"f32": "fp32 MFMA", "bf16": "bf16 MFMA", "bf16x3": "bf16 MFMA, hi+lo split (3 products)"}[args.math], "state_bytes": opt.state_bytes, "scratch_bytes": opt.scratch_bytes},
+                   "math": {"f32": "fp32 MFMA", "bf16": "bf16 MFMA", "bf16x3": "bf16 MFMA, hi+lo split (3 products)"}[args.math], "state_bytes": None, "scratch_bytes": None},
         "roofline": roofline,
         "kernels": breakdown,
     }
+    out["config"]["state_bytes"], out["config"]["scratch_bytes"] = opt.state_bytes, opt.scratch_bytes
+    # the HBM-bound part of the step: its busiest kernel against the 8 TB/s datasheet figure
+    ew = [p for p in prof if p["bytes"] > 0 and p["ms"] > 0]
+    if ew:
+        e = max(ew, key=lambda p: p["ms"])
+        gbs = e["bytes"] / (e["ms"] * 1e-3) / 1e9
+        out["roofline_elementwise"] = {"bound": "hbm", "kernel": e["kernel"], "achieved": gbs, "peak": PEAK_HBM_GBS,
+                                       "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "launches": e["launches"]}
+    del opt
+    if args.all_modes:
+        out["modes"] = {}
+        for math in sorted(MATH):
+            if math == args.math:
+                continue
+            torch.cuda.empty_cache()
+            el, pr, o2 = run_mode(B, BasisRotationAdam, torch, params, ring, math, 1, 10)
+            d2 = dominant_gemm(pr)
+            ach = d2["flops"] / (d2["ms"] * 1e-3) / 1e12
+            pk = PEAK_TFLOPS["bf16" if "bf16" in d2["kernel"] else "f32"]
+            out["modes"][math] = {"value": n_params * 10 / el, "unit": "params/s", "ms_per_step": 1e2 * el, "steps": 10,
+                                  "warmup": 1, "dominant_kernel": d2["kernel"], "achieved_tflops": ach, "frac": ach / pk,
+                                  "state_bytes": o2.state_bytes, "scratch_bytes": o2.scratch_bytes}
+            del o2
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

@@ -5,6 +5,7 @@
 //
 //   br_native_bench [--layers N] [--steps K] [--freq F] [--math 0|1|2] [--copy-calibration] [--mfma-peak]
 //   br_native_bench --lowp-gemm M N K BATCH NPROD MIRROR
+//   br_native_bench --stream-peak
 //
 // --lowp-gemm checks and times the BF16 matrix-core contraction alone: BATCH products
 // C = A B^T (A: M x K, B: N x K, FP32 noise split into BF16 planes by the library's own split
@@ -17,6 +18,11 @@
 // which gives the FP32 matrix-core rate this machine actually holds (clocks drop under
 // sustained load), the practical ceiling for the contraction kernel; then the same for
 // v_mfma_f32_32x32x16_bf16 (br_mfma_peak_bf16).
+//
+// --stream-peak measures what the memory system sustains for the access mixes of the elementwise
+// kernels on 1 GiB arrays of noise: reads only, writes only, a copy, and the 2-read 1-write mix of
+// the first-moment update, each workgroup walking one contiguous range (as the library's kernels
+// do) and, for comparison, the last one with a grid-stride loop.
 //
 // --copy-calibration additionally launches br_plain_copy on 1 GiB (reads 1 GiB, writes 1 GiB),
 // the known-traffic kernel against which HBM byte counters are scaled.
@@ -52,6 +58,54 @@ __global__ void br_fill_noise(float* dst, size_t n, unsigned seed, float scale) 
 __global__ void br_plain_copy(const float4* __restrict__ src, float4* __restrict__ dst, size_t n4) {
   size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
+}
+
+typedef float br_f4 __attribute__((ext_vector_type(4)));
+
+// mode 0: read, 1: write, 2: copy a -> b, 3: b = 0.9 b + 0.1 a; contiguous range per workgroup, or grid-stride
+__global__ __launch_bounds__(256) void br_stream(const br_f4* __restrict__ a, br_f4* __restrict__ b, size_t n4, int mode, int strided) {
+  size_t lo, hi, step;
+  if (strided) {
+    lo = (size_t)blockIdx.x * 256; hi = n4; step = (size_t)gridDim.x * 256;
+  } else {
+    const size_t per = (n4 + gridDim.x - 1) / gridDim.x;
+    lo = (size_t)blockIdx.x * per; hi = (lo + per < n4) ? lo + per : n4; step = 256;
+  }
+  br_f4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (size_t i = lo + threadIdx.x; i < hi; i += step) {
+    if (mode == 0) acc += __builtin_nontemporal_load(a + i);
+    else if (mode == 1) __builtin_nontemporal_store(br_f4{1.f, 2.f, 3.f, 4.f}, b + i);
+    else if (mode == 2) __builtin_nontemporal_store(__builtin_nontemporal_load(a + i), b + i);
+    else __builtin_nontemporal_store(0.9f * __builtin_nontemporal_load(b + i) + 0.1f * __builtin_nontemporal_load(a + i), b + i);
+  }
+  if (mode == 0 && acc.x == 1.2345f) b[0] = acc;
+}
+
+static int stream_peak() {
+  const size_t n4 = (size_t)1 << 26;  // 1 GiB per array
+  br_f4 *a, *b;
+  CHECK_HIP(hipMalloc(&a, n4 * 16));
+  CHECK_HIP(hipMalloc(&b, n4 * 16));
+  hipLaunchKernelGGL(br_fill_noise, dim3(4096), dim3(256), 0, 0, (float*)a, n4 * 4, 1u, 1.0f);
+  hipLaunchKernelGGL(br_fill_noise, dim3(4096), dim3(256), 0, 0, (float*)b, n4 * 4, 2u, 1.0f);
+  hipEvent_t e0, e1;
+  CHECK_HIP(hipEventCreate(&e0));
+  CHECK_HIP(hipEventCreate(&e1));
+  const char* names[5] = {"read", "write", "copy (1 read, 1 write)", "2 reads, 1 write", "2 reads, 1 write, grid-stride loop"};
+  const double arrays[5] = {1, 1, 2, 3, 3};
+  for (int k = 0; k < 5; ++k) {
+    const int mode = k < 4 ? k : 3, strided = k == 4;
+    hipLaunchKernelGGL(br_stream, dim3(2048), dim3(256), 0, 0, a, b, n4, mode, strided);
+    CHECK_HIP(hipDeviceSynchronize());
+    CHECK_HIP(hipEventRecord(e0, 0));
+    for (int r = 0; r < 5; ++r) hipLaunchKernelGGL(br_stream, dim3(2048), dim3(256), 0, 0, a, b, n4, mode, strided);
+    CHECK_HIP(hipEventRecord(e1, 0));
+    CHECK_HIP(hipEventSynchronize(e1));
+    float ms = 0.f;
+    CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+    std::printf("br_stream %-36s %7.3f ms  %6.0f GB/s\n", names[k], ms / 5, arrays[k] * n4 * 16 / (ms / 5 * 1e-3) / 1e9);
+  }
+  return 0;
 }
 
 typedef float br_floatx16 __attribute__((ext_vector_type(16)));
@@ -260,6 +314,7 @@ int main(int argc, char** argv) {
     else if (!std::strcmp(argv[i], "--copy-calibration")) calib = 1;
     else if (!std::strcmp(argv[i], "--math") && i + 1 < argc) math = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--mfma-peak")) return mfma_peak();
+    else if (!std::strcmp(argv[i], "--stream-peak")) return stream_peak();
     else { std::fprintf(stderr, "unknown argument %s\n", argv[i]); return 2; }
   }
   const int64_t layer_shapes[7][2] = {{2560, 2560}, {2560, 2560}, {2560, 2560}, {2560, 2560},
