@@ -296,15 +296,30 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
     for (int ni = 0; ni < 2; ++ni) {
       const int col = n0 + wn * 64 + ni * 32 + li;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-        if (row < g.M && col < g.N) {
-          size_t off = (size_t)row * (size_t)g.ldc + col;
-          float val = g.alpha * acc[mi][ni][v];
-          if (use_beta) val += g.beta * C[off];
-          C[off] = val;
-          if (shadow) shadow[off] = f32_to_bf16_rne(val);
-          if (off_diag) C[(size_t)col * (size_t)g.ldc + row] = val;
+      for (int vg = 0; vg < 4; ++vg) {
+        const int row0 = m0 + wm * 64 + mi * 32 + 8 * vg + 4 * lk;
+        float val[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int row = row0 + e;
+          val[e] = g.alpha * acc[mi][ni][vg * 4 + e];
+          if (row < g.M && col < g.N) {
+            size_t off = (size_t)row * (size_t)g.ldc + col;
+            if (use_beta) val[e] += g.beta * C[off];
+            C[off] = val[e];
+            if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
+          }
+        }
+        if (off_diag && col < g.N) {
+          // transposed copy of a symmetric result: this lane's four rows are four consecutive columns there
+          float* dst = C + (size_t)col * (size_t)g.ldc + row0;
+          if (VEC && row0 + 3 < g.M && ((g.ldc & 3) == 0)) {
+            *reinterpret_cast<float4*>(dst) = make_float4(val[0], val[1], val[2], val[3]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (row0 + e < g.M) dst[e] = val[e];
+          }
         }
       }
     }
@@ -378,7 +393,7 @@ hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch&
   long long grid = (long long)k.total_tiles * a.batch;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   bool vec = (a.lda % 4 == 0) && (a.ldb % 4 == 0);
-  for (int i = 0; i < a.batch && vec; ++i) vec = aligned16(b.A[i]) && aligned16(b.B[i]);
+  for (int i = 0; i < a.batch && vec; ++i) vec = aligned16(b.A[i]) && aligned16(b.B[i]) && (!a.mirror || aligned16(b.C[i]));
   if (!a.qr_role) return launch_any<false>(s, a, k, b, (int)grid, vec);
   // Split K when the launch would leave most of the 256 compute units idle.
   const int nkt = (a.K + BK - 1) / BK;

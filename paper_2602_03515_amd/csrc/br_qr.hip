@@ -6,7 +6,7 @@
 //   H_1 H_2 ... H_nb = I - V T V^T,  V unit lower trapezoidal, T upper triangular.
 // This file holds the panel kernel; the trailing-matrix and Q-forming updates are GEMMs issued
 // by the host logic.  A panel is held ENTIRELY IN REGISTERS from its first load to its final
-// store: a 1024-thread workgroup keeps up to 2304 rows, and a taller panel is shared by a cluster
+// store: a 1024-thread workgroup keeps up to 1536 rows, and a taller panel is shared by a cluster
 // of workgroups (gridDim.y, one slab of rows each) that combine their partial dot products
 // through global memory once per column.
 //
@@ -23,7 +23,7 @@ namespace br {
 constexpr int QR_THREADS = 1024;
 constexpr int QR_ROWS_PER_SWEEP = QR_THREADS / 8;  // 128
 constexpr int QR_WAVES = QR_THREADS / 64;          // 16
-constexpr int QR_RESIDENT_SWEEPS = 18;             // a workgroup keeps up to 18 x 128 = 2304 rows in registers
+constexpr int QR_RESIDENT_SWEEPS = 12;             // a workgroup keeps up to 12 x 128 = 1536 rows in registers
 constexpr int QR_MAX_SLAB = QR_RESIDENT_SWEEPS * QR_ROWS_PER_SWEEP;
 constexpr int QR_XCH_FLOATS = 64;                  // per (step, workgroup): 32 partial sums + the next pivot row
 constexpr unsigned QR_SPIN_LIMIT = 1u << 26;       // polls before a cluster gives up and poisons its result
@@ -143,39 +143,45 @@ struct PassParams {
   int j, jn;          // current column, owner column of the next one
   float scale, beta;  // v = x * scale below the diagonal; R_jj
   float4 w;           // tau * (v^T A[:, c]) for this lane's four columns (0 for c <= j)
+  float wn;           // the same for column j + 1 (0 when there is none)
 };
 
-__device__ __forceinline__ float apply_col(float a, int c, int r, float v, float w, const PassParams& pp) {
-  if (c > pp.j) return a - v * w;
-  if (c == pp.j) return (r == pp.j) ? pp.beta : v;
-  return a;
-}
-
-__device__ __forceinline__ float acc_col(float acc, float a, int c, int r, float v, float xn, int j) {
-  if (c < j) return acc + a * v;
-  if (c > j && r > j) return acc + xn * a;
-  return acc;
+__device__ __forceinline__ float4 fma4(float s, float4 a, float4 acc) {
+  return make_float4(acc.x + s * a.x, acc.y + s * a.y, acc.z + s * a.z, acc.w + s * a.w);
 }
 
 // Apply reflector j to one row (columns c0..c0+3 of row r, in `a`) and accumulate this row's
-// contribution to the dot products needed by pass j + 1 and by column j of T.
-__device__ __forceinline__ void pass_row(float4& a, int r, bool active, const PassParams& pp, int c0, int group_base,
-                                         float4& acc, float* pivnext) {
+// contribution to the dot products needed by pass j + 1 and by column j of V^T V.
+// Written for instruction count (the kernel is bound by vector-ALU issue): the update is one FMA per
+// entry because w is zero for the columns up to j; column j itself is patched by one select on a
+// per-lane mask that is fixed for the whole pass; both kinds of sums (entries times v for the columns
+// before j, entries times the new column j + 1 for those after) are accumulated for every column and
+// told apart once per pass, not per row.  Columns j and j + 1 are read BEFORE the update, so that the
+// two cross-lane reads do not depend on it: the updated entry of column j + 1 is a_old - v * w_next.
+struct PassMasks {
+  bool eq[4];  // this lane's entry k is column j
+};
+
+template <bool FIRST_SWEEP>
+__device__ __forceinline__ void pass_row(float4& a, int r, bool active, const PassParams& pp, const PassMasks& pm,
+                                         int c0, int group_base, float4& accv, float4& accx, float* pivnext) {
   const int j = pp.j;
   const float aj = __shfl(pick4(a, j & 3), group_base | (j >> 2), 64);
-  const float v = (r == j) ? 1.0f : aj * pp.scale;
-  a.x = apply_col(a.x, c0 + 0, r, v, pp.w.x, pp);
-  a.y = apply_col(a.y, c0 + 1, r, v, pp.w.y, pp);
-  a.z = apply_col(a.z, c0 + 2, r, v, pp.w.z, pp);
-  a.w = apply_col(a.w, c0 + 3, r, v, pp.w.w, pp);
-  const float xn = __shfl(pick4(a, pp.jn & 3), group_base | (pp.jn >> 2), 64);
-  if (active) {
-    acc.x = acc_col(acc.x, a.x, c0 + 0, r, v, xn, j);
-    acc.y = acc_col(acc.y, a.y, c0 + 1, r, v, xn, j);
-    acc.z = acc_col(acc.z, a.z, c0 + 2, r, v, xn, j);
-    acc.w = acc_col(acc.w, a.w, c0 + 3, r, v, xn, j);
-    if (r == j + 1) *reinterpret_cast<float4*>(pivnext + c0) = a;
-  }
+  const float an_old = __shfl(pick4(a, pp.jn & 3), group_base | (pp.jn >> 2), 64);
+  const bool piv = (r == j);
+  const float v = piv ? 1.0f : aj * pp.scale;
+  const float own = piv ? pp.beta : v;  // what column j keeps: R_jj in the pivot row, the reflector below it
+  a.x = pm.eq[0] ? own : fmaf(-v, pp.w.x, a.x);
+  a.y = pm.eq[1] ? own : fmaf(-v, pp.w.y, a.y);
+  a.z = pm.eq[2] ? own : fmaf(-v, pp.w.z, a.z);
+  a.w = pm.eq[3] ? own : fmaf(-v, pp.w.w, a.w);
+  const float xn = fmaf(-v, pp.wn, an_old);
+  const float va = active ? v : 0.f;
+  const float xa = (active && r > j) ? xn : 0.f;
+  accv = fma4(va, a, accv);
+  accx = fma4(xa, a, accx);
+  // the next pivot row (panel row j + 1 <= 32) can only sit in the first sweep: the others stay free of branches
+  if (FIRST_SWEEP && r == j + 1) *reinterpret_cast<float4*>(pivnext + c0) = a;
 }
 
 __device__ __forceinline__ float4 clean_v(float4 a, int c0, int r, int nb) {
@@ -185,10 +191,6 @@ __device__ __forceinline__ float4 clean_v(float4 a, int c0, int r, int nb) {
   o.z = (c0 + 2 >= nb || c0 + 2 > r) ? 0.f : ((c0 + 2 == r) ? 1.0f : a.z);
   o.w = (c0 + 3 >= nb || c0 + 3 > r) ? 0.f : ((c0 + 3 == r) ? 1.0f : a.w);
   return o;
-}
-
-__device__ __forceinline__ float4 fma4(float s, float4 a, float4 acc) {
-  return make_float4(acc.x + s * a.x, acc.y + s * a.y, acc.z + s * a.z, acc.w + s * a.w);
 }
 
 // U sweeps of 128 rows per workgroup (U * 128 >= slab), all in registers; the passes touch no
@@ -292,15 +294,29 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
       pp.w.z = (c0 + 2 > j && c0 + 2 < nb) ? tau * (pr.z + pp.scale * (dv.z - alpha * pr.z)) : 0.f;
       pp.w.w = (c0 + 3 > j && c0 + 3 < nb) ? tau * (pr.w + pp.scale * (dv.w - alpha * pr.w)) : 0.f;
     }
-    acc = zero4;
+    {
+      const int jn = pp.jn;
+      const float prn = pivrow[cur][jn], dvn = dvec[jn];
+      pp.wn = (j + 1 < nb) ? tau * (prn + pp.scale * (dvn - alpha * prn)) : 0.f;
+    }
+    PassMasks pm;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pm.eq[e] = (c0 + e == j);
     // Every sweep, unconditionally: the loop body is free of branches, so the cross-lane reads of
     // different sweeps overlap.  Rows past the slab hold zeros and stay zero; rows above row j are
     // finished and whatever the pass does to them is masked out of the sums and of the reflectors.
+    float4 accv = zero4, accx = zero4;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = rg + QR_ROWS_PER_SWEEP * u;
-      pass_row(ra[u], r, (r >= j) && (r < rend), pp, c0, group_base, acc, pivrow[cur ^ 1]);
+      if (u == 0) pass_row<true>(ra[u], r, (r >= j) && (r < rend), pp, pm, c0, group_base, accv, accx, pivrow[cur ^ 1]);
+      else pass_row<false>(ra[u], r, (r >= j) && (r < rend), pp, pm, c0, group_base, accv, accx, pivrow[cur ^ 1]);
+      if (u % 6 == 5) __builtin_amdgcn_sched_barrier(0);  // at most six sweeps' cross-lane values in registers at once
     }
+    acc.x = (c0 + 0 < j) ? accv.x : ((c0 + 0 > j) ? accx.x : 0.f);
+    acc.y = (c0 + 1 < j) ? accv.y : ((c0 + 1 > j) ? accx.y : 0.f);
+    acc.z = (c0 + 2 < j) ? accv.z : ((c0 + 2 > j) ? accx.z : 0.f);
+    acc.w = (c0 + 3 < j) ? accv.w : ((c0 + 3 > j) ? accx.w : 0.f);
     {
       // Column sums of this pass: for c > j the dot products of the next pass, for c < j the entries
       // v_c^T v_j of the Gram matrix of the reflectors.
