@@ -29,6 +29,10 @@ def workload(name):
     from paper_2602_03515_amd import synth
     if name == "stage3b":
         return list(synth.STAGE_3B), "3B-class pipeline stage: 8 layers x (4x 2560x2560, 2x 2560x6912, 1x 6912x2560) = 56 matrices"
+    if name == "stage3b_emb":
+        return (list(synth.STAGE_3B) + [synth.EMBEDDING_SHARD],
+                "refresh-heavy stress: the 56 stage matrices + the 32000x2560 embedding shard, unilateral rotation, "
+                "refresh every step with 2 power iterations + QR")
     if name == "layer3b":
         return list(synth.STAGE_3B_LAYER), "one layer of the 3B-class stage (7 matrices)"
     if name == "layer2048":
@@ -107,11 +111,11 @@ def counter_traffic(workload_name, kernel):
     return None
 
 
-def run_mode(B, BasisRotationAdam, torch, params, ring, math, warmup, steps):
+def run_mode(B, BasisRotationAdam, torch, params, ring, math, warmup, steps, freq=FREQ, **hparams):
     """Times `steps` optimizer steps in one math mode on copies of the parameters; returns
     (elapsed seconds, profile entries, optimizer)."""
     work = [p.clone() for p in params]
-    opt = BasisRotationAdam(work, freq=FREQ, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, math=MATH[math])
+    opt = BasisRotationAdam(work, freq=freq, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, math=MATH[math], **hparams)
     torch.cuda.synchronize()
     t = 0
     for _ in range(warmup):
@@ -174,10 +178,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    elapsed, prof, opt = run_mode(B, BasisRotationAdam, torch, params, ring, args.math, args.warmup, args.steps)
+    stress = args.workload == "stage3b_emb"
+    freq = 1 if stress else FREQ
+    extra = {"geometry": B.BR_UNILATERAL, "power_iters": 2} if stress else {}
+    elapsed, prof, opt = run_mode(B, BasisRotationAdam, torch, params, ring, args.math, args.warmup, args.steps, freq=freq, **extra)
 
     ms_per_step = 1e3 * elapsed / args.steps
-    refreshes = sum(1 for k in range(args.warmup + 1, args.warmup + args.steps + 1) if k % FREQ == 0)
+    refreshes = sum(1 for k in range(args.warmup + 1, args.warmup + args.steps + 1) if k % freq == 0)
     dom = dominant_gemm(prof)
     roofline = None
     if dom:
@@ -201,9 +208,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.math, "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {desc}", "params": n_params, "geometry": "bilateral",
-                   "source": "second", "refresh_every": FREQ, "refreshes_in_timed_region": refreshes,
-                   "power_iters": 1, "delay_tau": TAU, "param_dtype": "f32", "grad_dtype": "f32",
+        "config": {"workload": f"{args.workload}: {desc}", "params": n_params, "geometry": "unilateral" if stress else "bilateral",
+                   "source": "second", "refresh_every": freq, "refreshes_in_timed_region": refreshes,
+                   "power_iters": 2 if stress else 1, "delay_tau": TAU, "param_dtype": "f32", "grad_dtype": "f32",
                    "math": {"f32": "fp32 MFMA", "bf16": "bf16 MFMA", "bf16x3": "bf16 MFMA, hi+lo split (3 products)"}[args.math], "state_bytes": None, "scratch_bytes": None},
         "roofline": roofline,
         "kernels": breakdown,
@@ -216,6 +223,20 @@ def main():
         gbs = e["bytes"] / (e["ms"] * 1e-3) / 1e9
         out["roofline_elementwise"] = {"bound": "hbm", "kernel": e["kernel"], "achieved": gbs, "peak": PEAK_HBM_GBS,
                                        "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "launches": e["launches"]}
+    if stress:
+        # what the refresh-heavy configuration is for: QR throughput and the optimizer state's size
+        qr = next((p for p in prof if p["kernel"].startswith("qr_householder")), None)
+        orders = [min(m, n) for m, n in shapes]
+        closed = 4 * sum(2 * m * n + 2 * min(m, n) ** 2 for m, n in shapes)
+        out["refresh"] = {
+            "factor_orders": sorted(set(orders)), "qr_per_step": len(orders),
+            "qr_ms_per_step": qr["ms"] / args.steps if qr else None,
+            "qr_per_s": (len(orders) * args.steps / (qr["ms"] * 1e-3)) if qr else None,
+            "qr_tflops_nominal": (qr["flops"] / (qr["ms"] * 1e-3) / 1e12) if qr else None,
+            "state_bytes_closed_form": closed, "state_bytes": opt.state_bytes, "scratch_bytes": opt.scratch_bytes,
+            "peak_allocated_bytes": int(torch.cuda.max_memory_allocated(dev)),
+            "note": "closed form = 4 (2 mn + 2 min(m,n)^2) per matrix: M, S~ and the smaller side's statistic and basis; "
+                    "state_bytes adds the cached rotated moment and alignment; peak includes parameters and the gradient ring"}
     del opt
     if args.all_modes:
         out["modes"] = {}

@@ -930,7 +930,10 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
   // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before block blk is
   // applied, Q differs from the identity only in Q[J1:, J1:] with J1 the next block's offset,
   // so only the columns from J0 on change.
-  if (!hip_ok(c, br_launch_set_identity(s, Q, B, k), "identity launch")) return false;
+  // The identity carries the signs that make diag(R) >= 0 (a column of Q flips with its sign).
+  const float* dg[BR_MAXB];
+  for (int i = 0; i < B; ++i) dg[i] = D(i);
+  if (!hip_ok(c, br_launch_qr_signed_identity(s, Q, dg, B, k), "signed identity launch")) return false;
   for (int blk = nblocks - 1; blk >= 0; --blk) {
     const int J0 = blk * NBO;
     const int nbo = std::min(NBO, k - J0);
@@ -949,9 +952,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Q[i] + (size_t)J0 * k + J0; }
     if (!mm(BrGemmArgs{rows, rows, NBO, NBO, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
   }
-  const float* dg[BR_MAXB];
-  for (int i = 0; i < B; ++i) dg[i] = D(i);
-  return hip_ok(c, br_launch_qr_fix_signs(s, Q, dg, B, k), "sign fix launch");
+  return true;
 }
 
 br_status br_refresh_basis(br_ctx* ctx) {

@@ -295,6 +295,14 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
       const int col = n0 + wn * 64 + ni * 32 + li;
+      // The old values of this accumulator's sixteen outputs are fetched together, before any of
+      // them is stored: a load issued after a store to the same matrix would wait for that store.
+      float old[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+        old[v] = (use_beta && row < g.M && col < g.N) ? C[(size_t)row * (size_t)g.ldc + col] : 0.f;
+      }
 #pragma unroll
       for (int vg = 0; vg < 4; ++vg) {
         const int row0 = m0 + wm * 64 + mi * 32 + 8 * vg + 4 * lk;
@@ -303,9 +311,9 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
         for (int e = 0; e < 4; ++e) {
           const int row = row0 + e;
           val[e] = g.alpha * acc[mi][ni][vg * 4 + e];
+          if (use_beta) val[e] += g.beta * old[vg * 4 + e];
           if (row < g.M && col < g.N) {
             size_t off = (size_t)row * (size_t)g.ldc + col;
-            if (use_beta) val[e] += g.beta * C[off];
             C[off] = val[e];
             if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
           }
@@ -395,7 +403,8 @@ hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch&
   bool vec = (a.lda % 4 == 0) && (a.ldb % 4 == 0);
   for (int i = 0; i < a.batch && vec; ++i) vec = aligned16(b.A[i]) && aligned16(b.B[i]) && (!a.mirror || aligned16(b.C[i]));
   if (!a.qr_role) return launch_any<false>(s, a, k, b, (int)grid, vec);
-  // Split K when the launch would leave most of the 256 compute units idle.
+  // Split K when the launch would leave most of the 256 compute units idle.  (Splitting launches
+  // of a few tiles per compute unit as well, to shorten their tails, was measured and gained nothing.)
   const int nkt = (a.K + BK - 1) / BK;
   if (a.partial && !a.mirror && grid < 384 && nkt >= 32) {
     long long want = (768 + grid - 1) / grid;

@@ -185,6 +185,6 @@ hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const floa
 // factors (consecutive BR_QR_NBM x BR_QR_NBM matrices); everything else zero.
 hipError_t br_launch_qr_assemble_t(hipStream_t s, const float* const* Tm, float* const* T, int batch, int nmid);
 // Q[:, j] *= sign(diag[j]) (zero counts as +).
-hipError_t br_launch_qr_fix_signs(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n);
+hipError_t br_launch_qr_signed_identity(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n);
 
 #endif  // BR_INTERNAL_H_

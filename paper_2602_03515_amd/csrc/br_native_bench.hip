@@ -5,7 +5,12 @@
 //
 //   br_native_bench [--layers N] [--steps K] [--freq F] [--math 0|1|2] [--copy-calibration] [--mfma-peak]
 //   br_native_bench --lowp-gemm M N K BATCH NPROD MIRROR
+//   br_native_bench --f32-gemm M N K BATCH TA TB QR LDC BETA
 //   br_native_bench --stream-peak
+//
+// --f32-gemm times the FP32 matrix-core contraction alone at one shape (10 launches), e.g. the
+// trailing updates of the QR: QR = 1 selects the variant the factorisation uses, LDC > N updates
+// a block inside a wider matrix, BETA != 0 makes the kernel read C as well.
 //
 // --lowp-gemm checks and times the BF16 matrix-core contraction alone: BATCH products
 // C = A B^T (A: M x K, B: N x K, FP32 noise split into BF16 planes by the library's own split
@@ -302,7 +307,59 @@ static int lowp_gemm_bench(int M, int N, int K, int batch, int nprod, int mirror
   return worst < 1e-4 ? 0 : 1;
 }
 
+// ---- --f32-gemm ----------------------------------------------------------------------------
+// Times one batched FP32 contraction at a given shape: C (M x N, row stride LDC) <- beta C +
+// alpha op(A) op(B), the operands stored with their natural row strides.  QR = 1 runs the
+// variant used inside the QR factorisation.  Timing only (the parity tests cover the values).
+static int f32_gemm_bench(int M, int N, int K, int batch, int ta, int tb, int qr, int ldc, float beta) {
+  if (M <= 0 || N <= 0 || K <= 0 || batch < 1 || batch > BR_MAXB || ldc < N) {
+    std::fprintf(stderr, "bad --f32-gemm arguments\n");
+    return 2;
+  }
+  const size_t ea = (size_t)M * K, eb = (size_t)N * K, ec = (size_t)M * ldc;
+  BrGemmBatch gb;
+  std::memset(&gb, 0, sizeof(gb));
+  for (int i = 0; i < batch; ++i) {
+    float *a, *b, *c;
+    CHECK_HIP(hipMalloc(&a, ea * 4));
+    CHECK_HIP(hipMalloc(&b, eb * 4));
+    CHECK_HIP(hipMalloc(&c, ec * 4));
+    hipLaunchKernelGGL(br_fill_noise, dim3(2048), dim3(256), 0, 0, a, ea, 11u + i, 1.0f);
+    hipLaunchKernelGGL(br_fill_noise, dim3(2048), dim3(256), 0, 0, b, eb, 911u + i, 1.0f);
+    CHECK_HIP(hipMemset(c, 0, ec * 4));
+    gb.A[i] = a; gb.B[i] = b; gb.C[i] = c;
+  }
+  BrGemmArgs a{M, N, K, ta ? M : K, tb ? K : N, ldc, ta, tb, 1e-3f, beta, batch, 0};
+  a.qr_role = qr;
+  float* partial = nullptr;
+  if (qr) {
+    a.partial_floats = (size_t)16 << 20;
+    CHECK_HIP(hipMalloc(&partial, a.partial_floats * 4));
+    a.partial = partial;
+  }
+  const char* name = nullptr;
+  CHECK_HIP(br_launch_gemm(0, a, gb, &name));
+  CHECK_HIP(hipDeviceSynchronize());
+  hipEvent_t e0, e1;
+  CHECK_HIP(hipEventCreate(&e0));
+  CHECK_HIP(hipEventCreate(&e1));
+  const int reps = 10;
+  CHECK_HIP(hipEventRecord(e0, 0));
+  for (int r = 0; r < reps; ++r) CHECK_HIP(br_launch_gemm(0, a, gb, nullptr));
+  CHECK_HIP(hipEventRecord(e1, 0));
+  CHECK_HIP(hipEventSynchronize(e1));
+  float ms = 0.f;
+  CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+  const double flops = 2.0 * M * N * (double)K * batch;
+  std::printf("%s M=%d N=%d K=%d batch=%d ldc=%d beta=%g: %.3f ms/launch, %.1f TFLOP/s\n", name, M, N, K, batch, ldc, beta, ms / reps,
+              flops / (ms / reps * 1e-3) / 1e12);
+  return 0;
+}
+
 int main(int argc, char** argv) {
+  if (argc == 11 && !std::strcmp(argv[1], "--f32-gemm"))
+    return f32_gemm_bench(std::atoi(argv[2]), std::atoi(argv[3]), std::atoi(argv[4]), std::atoi(argv[5]), std::atoi(argv[6]),
+                          std::atoi(argv[7]), std::atoi(argv[8]), std::atoi(argv[9]), (float)std::atof(argv[10]));
   if (argc == 8 && !std::strcmp(argv[1], "--lowp-gemm"))
     return lowp_gemm_bench(std::atoi(argv[2]), std::atoi(argv[3]), std::atoi(argv[4]), std::atoi(argv[5]), std::atoi(argv[6]),
                            std::atoi(argv[7]));

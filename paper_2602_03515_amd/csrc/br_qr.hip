@@ -398,38 +398,46 @@ __global__ __launch_bounds__(256) void br_qr_extract_v(BrQrPanelBatch p, int row
 //   T = [ T_a  -T_a (V_a^T V_b) T_b ]
 //       [ 0     T_b             ]      applied panel by panel,
 // with the cross products V_a^T V_b read from the Gram matrix G = V^T V of the middle block.
-// One 256-thread workgroup per matrix; everything lives in LDS.
+// One 1024-thread workgroup per matrix; T, the panel's slice of G and the intermediate product
+// live in LDS.
 struct BuildTArgs {
   const float* G[BR_MAXB];   // BR_QR_NBM x BR_QR_NBM
   const float* Tp[BR_MAXB];  // npanels consecutive BR_QR_NB x BR_QR_NB factors
   float* T[BR_MAXB];         // BR_QR_NBM x BR_QR_NBM output
 };
 
-__global__ __launch_bounds__(256) void br_qr_build_t(BuildTArgs a, int npanels) {
+constexpr int BUILD_T_THREADS = 1024;
+
+__global__ __launch_bounds__(BUILD_T_THREADS) void br_qr_build_t(BuildTArgs a, int npanels) {
   __shared__ float T[BR_QR_NBM][BR_QR_NBM + 1];
   __shared__ float Z[BR_QR_NBM][BR_QR_NB + 1];
+  __shared__ float Gs[BR_QR_NBM][BR_QR_NB + 1];
   const float* __restrict__ G = a.G[blockIdx.x];
   const float* __restrict__ Tp = a.Tp[blockIdx.x];
   float* __restrict__ Tout = a.T[blockIdx.x];
   const int tid = threadIdx.x;
-  for (int i = tid; i < BR_QR_NBM * BR_QR_NBM; i += 256) T[i / BR_QR_NBM][i % BR_QR_NBM] = 0.f;
+  for (int i = tid; i < BR_QR_NBM * BR_QR_NBM; i += BUILD_T_THREADS) T[i / BR_QR_NBM][i % BR_QR_NBM] = 0.f;
   __syncthreads();
   for (int pnl = 0; pnl < npanels; ++pnl) {
     const int o = pnl * BR_QR_NB;
-    for (int i = tid; i < BR_QR_NB * BR_QR_NB; i += 256)
+    for (int i = tid; i < BR_QR_NB * BR_QR_NB; i += BUILD_T_THREADS)
       T[o + i / BR_QR_NB][o + i % BR_QR_NB] = Tp[(size_t)pnl * BR_QR_NB * BR_QR_NB + i];
+    for (int i = tid; i < o * BR_QR_NB; i += BUILD_T_THREADS) {
+      const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
+      Gs[r][c] = G[(size_t)r * BR_QR_NBM + o + c];
+    }
     __syncthreads();
     if (pnl == 0) continue;
     // Z = T[0:o, 0:o] * G[0:o, o:o+32]
-    for (int i = tid; i < o * BR_QR_NB; i += 256) {
+    for (int i = tid; i < o * BR_QR_NB; i += BUILD_T_THREADS) {
       const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
       float s = 0.f;
-      for (int l = r; l < o; ++l) s += T[r][l] * G[(size_t)l * BR_QR_NBM + o + c];
+      for (int l = r; l < o; ++l) s += T[r][l] * Gs[l][c];
       Z[r][c] = s;
     }
     __syncthreads();
     // T[0:o, o:o+32] = -Z * T_b
-    for (int i = tid; i < o * BR_QR_NB; i += 256) {
+    for (int i = tid; i < o * BR_QR_NB; i += BUILD_T_THREADS) {
       const int r = i / BR_QR_NB, c = i - r * BR_QR_NB;
       float s = 0.f;
       for (int l = 0; l <= c; ++l) s += Z[r][l] * T[o + l][o + c];
@@ -437,7 +445,7 @@ __global__ __launch_bounds__(256) void br_qr_build_t(BuildTArgs a, int npanels) 
     }
     __syncthreads();
   }
-  for (int i = tid; i < BR_QR_NBM * BR_QR_NBM; i += 256) Tout[i] = T[i / BR_QR_NBM][i % BR_QR_NBM];
+  for (int i = tid; i < BR_QR_NBM * BR_QR_NBM; i += BUILD_T_THREADS) Tout[i] = T[i / BR_QR_NBM][i % BR_QR_NBM];
 }
 
 // T of an outer block (BR_QR_NBO wide) from its middle blocks' factors: the diagonal blocks are
@@ -474,14 +482,18 @@ struct SignArgs {
   const float* diag[BR_MAXB];
 };
 
-__global__ __launch_bounds__(256) void br_qr_fix_signs(SignArgs a, int n) {
+// Q <- diag(sign(d)): the matrix the reflectors are applied to when the orthogonal factor is
+// formed.  (H_1 ... H_k) diag(s) equals (H_1 ... H_k I) with its columns' signs flipped, entry by
+// entry and bit for bit, so starting from the signed identity makes diag(R) >= 0 without a pass
+// over Q afterwards.
+__global__ __launch_bounds__(256) void br_qr_signed_identity(SignArgs a, int n) {
   float* __restrict__ Q = a.Q[blockIdx.y];
   const float* __restrict__ d = a.diag[blockIdx.y];
   const int64_t total = (int64_t)n * n;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-    const int c = (int)(i % n);
-    if (d[c] < 0.f) Q[i] = -Q[i];
+    const int r = (int)(i / n), c = (int)(i - (int64_t)r * n);
+    Q[i] = (r == c) ? ((d[c] < 0.f) ? -1.0f : 1.0f) : 0.0f;
   }
 }
 
@@ -558,7 +570,7 @@ hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const floa
     a.Tp[i] = (i < batch) ? Tp[i] : nullptr;
     a.T[i] = (i < batch) ? T[i] : nullptr;
   }
-  hipLaunchKernelGGL(br::br_qr_build_t, dim3(batch), dim3(256), 0, s, a, npanels);
+  hipLaunchKernelGGL(br::br_qr_build_t, dim3(batch), dim3(br::BUILD_T_THREADS), 0, s, a, npanels);
   return hipGetLastError();
 }
 
@@ -583,7 +595,7 @@ hipError_t br_launch_zero_ints(hipStream_t s, int* const* ptrs, int batch, int n
   return hipGetLastError();
 }
 
-hipError_t br_launch_qr_fix_signs(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n) {
+hipError_t br_launch_qr_signed_identity(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n) {
   if (batch <= 0) return hipSuccess;
   if (batch > BR_MAXB) return hipErrorInvalidValue;
   br::SignArgs a;
@@ -594,6 +606,6 @@ hipError_t br_launch_qr_fix_signs(hipStream_t s, float* const* Q, const float* c
   int64_t blocks = ((int64_t)n * n + 255) / 256;
   int64_t cap = (2048 + batch - 1) / batch;
   if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL(br::br_qr_fix_signs, dim3((int)blocks, batch), dim3(256), 0, s, a, n);
+  hipLaunchKernelGGL(br::br_qr_signed_identity, dim3((int)blocks, batch), dim3(256), 0, s, a, n);
   return hipGetLastError();
 }
