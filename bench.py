@@ -148,8 +148,9 @@ def main():
                     help="input precision of the step's contractions: f32 (FP32 MFMA, default), "
                          "bf16x3 (hi+lo BF16 split, same 1e-4 bar), bf16 (2e-2 bar)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all-modes", action="store_true",
-                    help="after the timed run, also time the other math modes (10 steps each) and report them under 'modes'")
+    ap.add_argument("--single-mode", action="store_true",
+                    help="skip the short runs of the other math modes (10 steps each, reported under 'modes') that "
+                         "otherwise follow the timed run")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that HBM byte counters "
                          "collected by a profiler can be scaled")
@@ -238,7 +239,7 @@ def main():
             "note": "closed form = 4 (2 mn + 2 min(m,n)^2) per matrix: M, S~ and the smaller side's statistic and basis; "
                     "state_bytes adds the cached rotated moment and alignment; peak includes parameters and the gradient ring"}
     del opt
-    if args.all_modes:
+    if not args.single_mode:
         out["modes"] = {}
         for math in sorted(MATH):
             if math == args.math:

@@ -268,6 +268,14 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
 #pragma unroll
       for (int ni = 0; ni < FN; ++ni) {
         const int col = n0 + (wn * FN + ni) * 32 + li;
+        // Old values of the accumulator's sixteen outputs first, then the stores: a load issued
+        // after a store to the same matrix would wait for it.
+        float old[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + (wm * FM + mi) * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+          old[v] = (use_beta && row < g.M && col < g.N) ? C[(size_t)row * (size_t)g.ldc + col] : 0.f;
+        }
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
           const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;
@@ -276,9 +284,9 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
           for (int e = 0; e < 4; ++e) {
             const int row = row0 + e;
             val[e] = g.alpha * acc[mi][ni][vg * 4 + e];
+            if (use_beta) val[e] += g.beta * old[vg * 4 + e];
             if (row < g.M && col < g.N) {
               const size_t off = (size_t)row * (size_t)g.ldc + col;
-              if (use_beta) val[e] += g.beta * C[off];
               C[off] = val[e];
               if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
             }
@@ -308,6 +316,19 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
 #pragma unroll
       for (int ni = 0; ni < FN; ++ni) {
         const int col = n0 + (wn * FN + ni) * 32 + li;  // plane row; below Np by construction
+        // EPI_ADAM: the moments of the accumulator's sixteen entries are fetched together, before any
+        // of them is stored (a load issued after a store to the same array would wait for it).
+        float mold[16], sold[16];
+        if (EPI == EPI_ADAM) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = m0 + (wm * FM + mi) * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+            const bool in = row < g.M && col < g.N;
+            const size_t off = (size_t)row * (size_t)g.ldc + col;
+            mold[v] = in ? Mr[off] : 0.f;
+            sold[v] = in ? S[off] : 0.f;
+          }
+        }
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
           const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;  // plane k of val[0]
@@ -321,12 +342,12 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
               if (row < g.M && col < g.N) {
                 const size_t off = (size_t)row * (size_t)g.ldc + col;
                 const float gt = val[e];
-                float mt = Mr[off];
+                float mt = mold[vg * 4 + e];
                 if (ad.update_mrot) {
                   mt = ad.beta1 * mt + w1 * gt;
                   Mr[off] = mt;
                 }
-                const float st2 = ad.beta2 * S[off] + w2 * (gt * gt);
+                const float st2 = ad.beta2 * sold[vg * 4 + e] + w2 * (gt * gt);
                 S[off] = st2;
                 const float num = mt * ad.c1, den = st2 * ad.c2;
                 x = ad.eps_outside ? num / (sqrtf(den) + ad.eps) : num / sqrtf(den + ad.eps);
