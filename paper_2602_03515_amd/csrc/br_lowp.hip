@@ -263,19 +263,27 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
   if (EPI == EPI_F32) {
     const bool use_beta = (g.beta != 0.0f);
     const bool off_diag = g.mirror && (tm != tn);
+    // Old values of an accumulator's sixteen outputs are fetched together, one accumulator ahead
+    // of the stores: a load issued after a store to the same matrix would wait for it.
+    float oldv[2][16];
+    auto fetch_old = [&](int a, float* dst) {
+      const int mi = a / FN, ni = a % FN;
+      const int col = n0 + (wn * FN + ni) * 32 + li;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + (wm * FM + mi) * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+        dst[v] = (use_beta && row < g.M && col < g.N) ? C[(size_t)row * (size_t)g.ldc + col] : 0.f;
+      }
+    };
+    fetch_old(0, oldv[0]);
 #pragma unroll
     for (int mi = 0; mi < FM; ++mi) {
 #pragma unroll
       for (int ni = 0; ni < FN; ++ni) {
         const int col = n0 + (wn * FN + ni) * 32 + li;
-        // Old values of the accumulator's sixteen outputs first, then the stores: a load issued
-        // after a store to the same matrix would wait for it.
-        float old[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = m0 + (wm * FM + mi) * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-          old[v] = (use_beta && row < g.M && col < g.N) ? C[(size_t)row * (size_t)g.ldc + col] : 0.f;
-        }
+        const int a = mi * FN + ni;
+        if (a + 1 < FM * FN) fetch_old(a + 1, oldv[(a + 1) & 1]);
+        const float* old = oldv[a & 1];
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
           const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;
@@ -311,24 +319,31 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
     float* __restrict__ Mr = batch.Mrot[mat];
     const BrAdamArgs ad = g.adam;
     const float w1 = 1.0f - ad.beta1, w2 = 1.0f - ad.beta2;
+    // EPI_ADAM: the moments of an accumulator's sixteen entries are fetched together, one accumulator
+    // ahead of the stores (a load issued after a store to the same array would wait for it).
+    float moldv[2][16], soldv[2][16];
+    auto fetch_moments = [&](int a, float* md, float* sd) {
+      const int mi = a / FN, ni = a % FN;
+      const int col = n0 + (wn * FN + ni) * 32 + li;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + (wm * FM + mi) * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+        const bool in = row < g.M && col < g.N;
+        const size_t off = (size_t)row * (size_t)g.ldc + col;
+        md[v] = in ? Mr[off] : 0.f;
+        sd[v] = in ? S[off] : 0.f;
+      }
+    };
+    if (EPI == EPI_ADAM) fetch_moments(0, moldv[0], soldv[0]);
 #pragma unroll
     for (int mi = 0; mi < FM; ++mi) {
 #pragma unroll
       for (int ni = 0; ni < FN; ++ni) {
         const int col = n0 + (wn * FN + ni) * 32 + li;  // plane row; below Np by construction
-        // EPI_ADAM: the moments of the accumulator's sixteen entries are fetched together, before any
-        // of them is stored (a load issued after a store to the same array would wait for it).
-        float mold[16], sold[16];
-        if (EPI == EPI_ADAM) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = m0 + (wm * FM + mi) * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-            const bool in = row < g.M && col < g.N;
-            const size_t off = (size_t)row * (size_t)g.ldc + col;
-            mold[v] = in ? Mr[off] : 0.f;
-            sold[v] = in ? S[off] : 0.f;
-          }
-        }
+        const int a = mi * FN + ni;
+        if (EPI == EPI_ADAM && a + 1 < FM * FN) fetch_moments(a + 1, moldv[(a + 1) & 1], soldv[(a + 1) & 1]);
+        const float* mold = moldv[a & 1];
+        const float* sold = soldv[a & 1];
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
           const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;  // plane k of val[0]
