@@ -17,7 +17,7 @@ namespace {
 
 constexpr int kStepChunk = 32;     // matrices per batched step launch ([G|M] doubles it to BR_MAXB)
 constexpr int kRefreshChunk = 64;   // factor matrices per batched refresh launch
-constexpr int kLowpChunk = 16;      // matrices per batched step launch in the BF16 math modes
+constexpr int kLowpChunk = 16;      // matrices per batched step launch in the BF16 math modes: what sizes their scratch
 constexpr int64_t kMaxDim = 1 << 24;
 constexpr size_t kNormPartialBytes = (size_t)BR_MAXB * 2 * BR_NORM_BLOCKS * sizeof(float);
 constexpr size_t kSplitKBytes = (size_t)64 << 20;  // partial products of the QR's split-K contractions
@@ -40,6 +40,7 @@ struct Group {  // matrices that can share a batched launch
   int pdt, gdt;
   bool rot_l, rot_r;
   std::vector<int> idx;
+  size_t lowp_chunk = 0;  // matrices per batched step launch in the BF16 math modes
 };
 
 struct RefreshJob {
@@ -231,12 +232,23 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
     if (l) lay->refresh[d.m].push_back(RefreshJob{i, true});
     if (r) lay->refresh[d.n].push_back(RefreshJob{i, false});
   }
+  size_t lowp_need = 0;
   for (auto& g : lay->groups) {
     size_t chunk = std::min<size_t>(g.idx.size(), kStepChunk);
     size_t need = chunk * step_buffers(g, hp) * align256((size_t)g.m * g.n * 4);
-    if (hp.math != BR_MATH_F32 && (g.rot_l || g.rot_r))
+    if (hp.math != BR_MATH_F32 && (g.rot_l || g.rot_r)) {
       need = std::min<size_t>(g.idx.size(), kLowpChunk) * lowp_layout(g).per_mat;
+      lowp_need = std::max(lowp_need, need);
+    }
     scratch = std::max(scratch, need);
+  }
+  // Groups of small matrices take more of them per launch, within the scratch the largest group needs
+  // anyway: a launch of 1600 tiles is 6.25 rounds on 256 compute units and pays for 7, one of 3200
+  // for 13 instead of 12.5 (8 % measured).
+  for (auto& g : lay->groups) {
+    if (hp.math == BR_MATH_F32 || !(g.rot_l || g.rot_r)) continue;
+    const size_t fit = lowp_need / lowp_layout(g).per_mat;
+    g.lowp_chunk = std::min<size_t>(std::min<size_t>(g.idx.size(), kStepChunk), std::max<size_t>(fit, 1));
   }
   // Refresh units: every order's jobs in chunks of at most kRefreshChunk, evenly sized.
   lay->units.clear();
@@ -763,7 +775,7 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
     const bool rotated = g.rot_l || g.rot_r;
     const bool need_g32 = rotated && g.gdt == BR_BF16;
     const bool lowp = rotated && hp.math != BR_MATH_F32;
-    const size_t chunk = lowp ? kLowpChunk : kStepChunk;
+    const size_t chunk = lowp ? g.lowp_chunk : kStepChunk;
     for (size_t off = 0; off < g.idx.size(); off += chunk) {
       const int B = (int)std::min<size_t>(chunk, g.idx.size() - off);
       LowpCtx lx{c, &g, lowp ? lowp_layout(g) : LowpLayout{}, B, hp.math == BR_MATH_BF16X3 ? 3 : 1, c->phase};
@@ -1062,7 +1074,7 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
     // scratch slots
     const int sT1 = 0, sGt = bilateral ? 1 : 0, sT2 = 2, sMt = bilateral ? 3 : 1;
     const bool lowp = rotated && hp.math != BR_MATH_F32;
-    const size_t chunk = lowp ? kLowpChunk : kStepChunk;
+    const size_t chunk = lowp ? g.lowp_chunk : kStepChunk;
     for (size_t off = 0; off < g.idx.size(); off += chunk) {
       const int B = (int)std::min<size_t>(chunk, g.idx.size() - off);
       LowpCtx lx{c, &g, lowp ? lowp_layout(g) : LowpLayout{}, B, hp.math == BR_MATH_BF16X3 ? 3 : 1, c->phase};
