@@ -352,7 +352,8 @@ bool lowp_split(const LowpCtx& x, const float* const* src, int R, int Ccols, boo
 // than BR_EPI_F32 the transposed result leaves as planes in out16 (see BrLowpArgs).
 bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp, int N, int K, float* const* C, int ldc,
                float alpha, float beta, uint16_t* const* out16, bool mirror, int nprod = 0, int epilogue = BR_EPI_F32,
-               const BrAdamArgs* adam = nullptr, float* const* S = nullptr, float* const* Mrot = nullptr) {
+               const BrAdamArgs* adam = nullptr, float* const* S = nullptr, float* const* Mrot = nullptr,
+               bool adam_transposed = false) {
   if (nprod == 0) nprod = x.nprod;
   BrLowpBatch b;
   std::memset(&b, 0, sizeof(b));
@@ -368,6 +369,7 @@ bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp,
   a.epilogue = epilogue;
   a.out_lo = (x.nprod == 3) ? 1 : 0;
   if (adam) a.adam = *adam;
+  a.adam_transposed = adam_transposed ? 1 : 0;
   double flops = 2.0 * M * N * (double)K * x.B;
   if (mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (M + 255) / 256));
   const char* name = nullptr;
@@ -402,7 +404,7 @@ bool lowp_stats(const LowpCtx& x, const float* const* G32, size_t off, bool with
 }
 
 // a4-a6 in the BF16 modes for one chunk.  Every contraction is A B^T on planes with k contiguous.
-// Fused form (bilateral, or left factor only; no norms requested): no intermediate exists in FP32.
+// Fused form (no norms requested): no intermediate exists in FP32.
 // Each contraction hands its result to the next one as operand planes straight from its
 // accumulators, which emit the TRANSPOSE of what they hold; so the chain alternates between a
 // product and its transpose:
@@ -410,6 +412,9 @@ bool lowp_stats(const LowpCtx& x, const float* const* G32, size_t off, bool with
 //   G~ = T Q_R, Adam in the epilogue (moments advanced in place)  -> planes of X^T
 //   (Q_L X)^T = X^T Q_L^T          -> planes of Y = Q_L X
 //   W <- decay W - lr Y Q_R^T      (FP32 epilogue)
+// Left factor only: X^T from Q_L^T G directly, then W <- decay W - lr Q_L X.  Right factor only: the
+// first contraction is taken transposed, G~^T = Q_R^T G^T, so that X itself leaves as planes for
+// W <- decay W - lr X Q_R^T.
 // Otherwise every product is stored in FP32 and split again (rotate_in / rotate back below).
 bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* const* Wp, uint16_t* const* shadow,
                float* const* Mt, bool advance, const BrAdamArgs& aa, float lr, float decay, float* partials) {
@@ -462,6 +467,17 @@ bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* con
     }
     if (!lowp_gemm(x, QLt, m, GTP, n, m, nullptr, n, 1.f, 0.f, XTP, false, 0, BR_EPI_ADAM, &aa, Sp, Mt)) return false;    // X^T
     return lowp_gemm(x, QLp, m, XTP, n, m, Wp, n, -lr, decay, shadow, false);                                            // W -= lr Q_L X
+  }
+  if (!aa.compute_norms && g.rot_r) {  // right factor only, fused: G~^T = Q_R^T G^T carries Adam, X leaves as planes
+    uint16_t* XP[BR_MAXB];
+    for (int i = 0; i < B; ++i) XP[i] = x.slot16(i, LS_XP);
+    if (!advance) {  // M~ = M Q_R from the first moment itself
+      for (int i = 0; i < B; ++i) { src[i] = c->mats[g.idx[off + i]].M; P0[i] = x.slot16(i, LS_MP); }
+      if (!lowp_split(x, src, m, n, false, P0)) return false;
+      if (!lowp_gemm(x, P0, m, QRt, n, n, Mt, n, 1.f, 0.f, nullptr, false)) return false;
+    }
+    if (!lowp_gemm(x, QRt, n, GP, m, n, nullptr, n, 1.f, 0.f, XP, false, 0, BR_EPI_ADAM, &aa, Sp, Mt, true)) return false;  // X
+    return lowp_gemm(x, XP, m, QRp, n, n, Wp, n, -lr, decay, shadow, false);                                              // W -= lr X Q_R^T
   }
   // rotate one m x n matrix into `out`; its planes are given (gradient) or made here from `in` (first moment)
   auto rotate_in = [&](const float* const* in, uint16_t* const* in_p, uint16_t* const* in_tp, float* const* out, int s_t,

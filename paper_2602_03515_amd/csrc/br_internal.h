@@ -90,6 +90,7 @@ struct BrLowpArgs {
   int epilogue = BR_EPI_F32;
   int out_lo = 0;
   BrAdamArgs adam = {};
+  int adam_transposed = 0;  // BR_EPI_ADAM: the product is G~^T; moments (row stride ldc) are indexed [col][row]
 };
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name);
 // hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src) into planes of

@@ -59,6 +59,7 @@ struct LowpKernArgs {
   size_t out_plane;      // elements from their hi plane to their lo plane
   int out_lo;            // also emit the lo plane
   BrAdamArgs adam;       // EPI_ADAM
+  int adam_t;            // EPI_ADAM: the tile is G~^T (row = column of G~): the moments are indexed [col][row]
 };
 
 enum { EPI_F32 = 0, EPI_PLANES = 1, EPI_ADAM = 2 };
@@ -98,6 +99,8 @@ namespace br {
 //   EPI_ADAM    the tile is a rotated gradient G~: Adam's moments are advanced in place
 //               (S~ <- b2 S~ + (1-b2) G~ G~, and M~ <- b1 M~ + (1-b1) G~ when adam.update_mrot;
 //               Algorithm 1 lines 9-11) and X = M~ / sqrt(S~ + eps) leaves as planes like above.
+//               With adam_t the tile is G~^T instead (right factor only: G~^T = Q_R^T G^T), the
+//               moments are indexed [col][row], and what leaves are the planes of X itself.
 template <int NPROD, int EPI>
 __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLowpBatch batch) {
   constexpr bool SPLIT = NPROD > 1;
@@ -329,7 +332,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + (wm * FM + mi) * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
         const bool in = row < g.M && col < g.N;
-        const size_t off = (size_t)row * (size_t)g.ldc + col;
+        const size_t off = g.adam_t ? (size_t)col * (size_t)g.ldc + row : (size_t)row * (size_t)g.ldc + col;
         md[v] = in ? Mr[off] : 0.f;
         sd[v] = in ? S[off] : 0.f;
       }
@@ -355,7 +358,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
               const int row = row0 + e;
               float x = 0.f;
               if (row < g.M && col < g.N) {
-                const size_t off = (size_t)row * (size_t)g.ldc + col;
+                const size_t off = g.adam_t ? (size_t)col * (size_t)g.ldc + row : (size_t)row * (size_t)g.ldc + col;
                 const float gt = val[e];
                 float mt = mold[vg * 4 + e];
                 if (ad.update_mrot) {
@@ -549,6 +552,7 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
   k.out_plane = po.elems;
   k.out_lo = a.out_lo ? 1 : 0;
   k.adam = a.adam;
+  k.adam_t = a.adam_transposed ? 1 : 0;
   long long grid = (long long)k.total_tiles * a.batch;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (a.epilogue == BR_EPI_ADAM) launch_lowp<EPI_ADAM>(s, a.nprod, (int)grid, k, b);

@@ -406,6 +406,31 @@ def test_bf16_modes_injected_basis_midway(harness, math):
     sb.compare_state(tol)
 
 
+@pytest.mark.parametrize("math", [1, 2])
+def test_bf16_modes_right_factor_only_chain(harness, math):
+    """Unilateral rotation of a tall matrix rotates the right side only.  In the BF16 modes that chain
+    takes its first contraction transposed (Adam's moments are indexed [col][row] in its epilogue);
+    a basis injected midway also forces the cached rotated moment to be rebuilt as M Q_R."""
+    m, n = 328, 200
+    rng = np.random.default_rng(17)
+    B32 = synth.haar_orthogonal(rng, n).astype(np.float32)
+    W0, grads = synth.spiked_gradients(seed=34, m=m, n=n, steps=7, noise_std=0.1)
+    tol = TOL if math == 2 else 2e-2
+    sb = harness.SideBySide([W0], freq=0, lr=1e-2, math=math, geometry=1)
+    w0 = sb.W_ref[0].copy()
+    for t, g in enumerate(grads, 1):
+        if t == 4:
+            sb.opt.state(0, sb.B.BR_STATE_QR).copy_(torch.from_numpy(B32))
+            sb.B.br_notify_state_written(sb.opt.ctx)
+            sb.states[0].QR = B32.astype(np.float64)
+        sb.step([g])
+    assert rel_err(sb.gpu_weights(0) - w0, sb.W_ref[0] - w0) <= tol + _storage_floor(sb.W_ref[0], sb.W_ref[0] - w0)
+    sb.compare_state(tol)
+    # and with the refresh running: tall and ragged
+    W0, grads = synth.spiked_gradients(seed=35, m=300, n=136, steps=8, noise_std=0.1)
+    _run(harness, [W0], [[g] for g in grads], freq=3, lr=1e-3, geometry=1, math=math, tol=tol, check_q=(math == 2))
+
+
 @pytest.mark.parametrize("geometry", [0, 1])
 def test_bf16x3_fused_and_unfused_chains_agree(harness, geometry):
     """With per-matrix norms requested the BF16 modes store every product in FP32 and split it
