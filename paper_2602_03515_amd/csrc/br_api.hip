@@ -5,6 +5,7 @@
 #include "br_internal.h"
 
 #include <algorithm>
+#include <functional>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -165,26 +166,39 @@ inline size_t plane_bytes(int64_t rows, int64_t k, const br_hparams& hp) {
 }
 
 struct RefreshScratch {
-  size_t P0, P1, gram, V, Y, W, T, Tp, Tm, G, X, Z, diag, xch, cnt, planesA, planesB, total;
+  size_t P0, P1, gram, V, Y, W, T, Tp, Tl, G, X, Z, diag, xch, cnt, planesA, planesB, total;
 };
+
+// Doubling levels of the QR's block-reflector merges above the LDS-merged middle block: level l
+// joins two factors of width BR_QR_NBM << l.  One level (top blocks of 256 columns) is what is
+// used: a second one (512) makes the K = 512 trailing updates 15 % faster and was measured to give
+// all of it back in the wider blocks' own merges and applies, for orders 2560 and 6912 alike.
+constexpr int kQrLevels = 1;
+static_assert((BR_QR_NBM << kQrLevels) == BR_QR_NBT, "top block = middle block doubled kQrLevels times");
+// floats before level l's pair of child factors in the Tl scratch
+inline size_t qr_level_offset(int l) {
+  size_t off = 0;
+  for (int i = 0; i < l; ++i) off += 2 * (size_t)(BR_QR_NBM << i) * (BR_QR_NBM << i);
+  return off;
+}
 
 RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   RefreshScratch r;
   size_t kk = align256((size_t)k * k * 4);
-  size_t blocks = (size_t)((k + BR_QR_NBO - 1) / BR_QR_NBO);
+  size_t blocks = (size_t)((k + BR_QR_NBT - 1) / BR_QR_NBT);
   size_t off = 0;
   r.P0 = off; off += kk;
   r.P1 = off; if (hp.power_iters > 1) off += kk;
   r.gram = off; if (hp.source == BR_SRC_FIRST) off += kk;
-  r.V = off; off += align256((size_t)k * BR_QR_NBO * 4);       // reflectors of one outer block
-  r.Y = off; off += align256((size_t)k * BR_QR_NBO * 4);       // V T or V T^T
-  r.W = off; off += align256((size_t)k * BR_QR_NBO * 4);       // V^T C
-  r.T = off; off += align256(blocks * BR_QR_NBO * BR_QR_NBO * 4);  // one factor per outer block
+  r.V = off; off += align256((size_t)k * BR_QR_NBT * 4);       // reflectors of one top block
+  r.Y = off; off += align256((size_t)k * BR_QR_NBT * 4);       // V T or V T^T
+  r.W = off; off += align256((size_t)k * BR_QR_NBT * 4);       // V^T C
+  r.T = off; off += align256(blocks * BR_QR_NBT * BR_QR_NBT * 4);  // one factor per top block
   r.Tp = off; off += align256((size_t)(BR_QR_NBM / BR_QR_NB) * BR_QR_NB * BR_QR_NB * 4);  // panel factors of a middle block
-  r.Tm = off; off += align256((size_t)(BR_QR_NBO / BR_QR_NBM) * BR_QR_NBM * BR_QR_NBM * 4);  // middle factors of an outer block
+  r.Tl = off; off += align256(qr_level_offset(kQrLevels) * 4);  // child factors of every doubling level
   r.G = off; off += align256((size_t)BR_QR_NBM * BR_QR_NBM * 4);  // Gram matrix of a middle block's reflectors
-  r.X = off; off += align256((size_t)BR_QR_NBM * BR_QR_NBM * 4);  // V_0^T V_1
-  r.Z = off; off += align256((size_t)BR_QR_NBM * BR_QR_NBM * 4);  // T_0 (V_0^T V_1)
+  r.X = off; off += align256((size_t)(BR_QR_NBT / 2) * (BR_QR_NBT / 2) * 4);  // V_0^T V_1
+  r.Z = off; off += align256((size_t)(BR_QR_NBT / 2) * (BR_QR_NBT / 2) * 4);  // T_0 (V_0^T V_1)
   r.diag = off; off += align256((size_t)k * 4);
   r.xch = off; off += align256(br_qr_panel_xch_floats((int)k) * 4);            // cluster exchange of one panel launch ...
   r.cnt = off; off += align256((size_t)((k + BR_QR_NB - 1) / BR_QR_NB) * 4);  // ... and one arrival counter per panel
@@ -835,23 +849,30 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 
 // Blocked Householder QR of the k x k matrices P (in place) for a batch of jobs, orthogonal
 // factor written to Q with the sign convention diag(R) >= 0, everything on stream s.
-// Three-level blocking.  Panels of BR_QR_NB columns are factorised by the panel kernel and
-// applied inside their middle block of BR_QR_NBM columns, whose reflectors are merged into one
-// compact-WY factor in LDS.  Two middle blocks form an outer block of BR_QR_NBO columns:
+// Recursive blocking.  Panels of BR_QR_NB columns are factorised by the panel kernel and applied
+// inside their middle block of BR_QR_NBM columns, whose reflectors are merged into one compact-WY
+// factor in LDS.  From there blocks are merged pairwise up to a top block of BR_QR_NBT columns:
+// the first child is factorised and applied to the second child's columns, the second child is
+// factorised, and
 //   T = [ T_0  -T_0 (V_0^T V_1) T_1 ]
 //       [ 0     T_1                 ]
-// which is applied to the trailing matrix, and later to Q, with K = BR_QR_NBO contractions.
+// The top block is applied to the trailing matrix, and later to Q, with K = BR_QR_NBT
+// contractions (the longer K is, the closer those run to the rate of a step contraction).
 static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs,
                      char* base, size_t stride, float* partial) {
-  const int NB = BR_QR_NB, NBM = BR_QR_NBM, NBO = BR_QR_NBO;
-  const int nblocks = (k + NBO - 1) / NBO;
+  const int NB = BR_QR_NB, NBM = BR_QR_NBM, NBT = BR_QR_NBT;
+  const int levels = kQrLevels;
+  const int ntop = (k + NBT - 1) / NBT;
   auto F = [&](int i, size_t off) { return reinterpret_cast<float*>(base + i * stride + off); };
-  auto V = [&](int i) { return F(i, rs.V); };
+  auto V = [&](int i) { return F(i, rs.V); };  // reflectors of the current top block, row stride NBT
   auto Y = [&](int i) { return F(i, rs.Y); };
   auto W = [&](int i) { return F(i, rs.W); };
-  auto T = [&](int i, int blk) { return F(i, rs.T) + (size_t)blk * NBO * NBO; };
+  auto Ttop = [&](int i, int tb) { return F(i, rs.T) + (size_t)tb * NBT * NBT; };
   auto Tp = [&](int i, int pnl) { return F(i, rs.Tp) + (size_t)pnl * NB * NB; };
-  auto Tm = [&](int i, int mid) { return F(i, rs.Tm) + (size_t)mid * NBM * NBM; };
+  auto Tl = [&](int i, int l, int slot) {
+    const size_t w = (size_t)(NBM << l);
+    return F(i, rs.Tl) + qr_level_offset(l) + (size_t)slot * w * w;
+  };
   auto D = [&](int i) { return F(i, rs.diag); };
   auto Cnt = [&](int i) { return reinterpret_cast<int*>(base + i * stride + rs.cnt); };
   auto mm = [&](const BrGemmArgs& a, const BrGemmBatch& gb) { return gemm(c, a, gb, false, partial, s); };
@@ -864,54 +885,41 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     for (int i = 0; i < B; ++i) cp[i] = Cnt(i);
     if (!hip_ok(c, br_launch_zero_ints(s, cp, B, (k + NB - 1) / NB), "counter clear launch")) return false;
   }
-  for (int blk = 0; blk < nblocks; ++blk) {
-    const int J0 = blk * NBO;
-    const int nbo = std::min(NBO, k - J0);  // columns of this outer block
-    const int rows = k - J0;                // rows of this outer block
-    const int nmid = (nbo + NBM - 1) / NBM;
-    if (nbo < NBO) {  // the reflector block of a narrow last outer block: unused columns must read as zero
-      int* vp[BR_MAXB];
-      for (int i = 0; i < B; ++i) vp[i] = reinterpret_cast<int*>(V(i));
-      if (!hip_ok(c, br_launch_zero_ints(s, vp, B, rows * NBO), "reflector clear launch")) return false;
-    }
-    for (int mid = 0; mid < nmid; ++mid) {
-      const int M0 = J0 + mid * NBM;
-      const int nbm = std::min(NBM, k - M0);  // columns of this middle block
-      const int mrows = k - M0;
-      const int npanels = (nbm + NB - 1) / NB;
-      if (mid > 0) {
-        // apply middle block 0 to this middle block's columns: Yt = V_0 T_0^T ; W = V_0^T C ; C <- C - Yt W
-        for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Tm(i, 0); gb.C[i] = Y(i); }
-        if (!mm(BrGemmArgs{rows, NBM, NBM, NBO, NBM, NBM, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
-        for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = P[i] + (size_t)J0 * k + M0; gb.C[i] = W(i); }
-        if (!mm(BrGemmArgs{NBM, nbm, rows, NBO, k, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
-        for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)J0 * k + M0; }
-        if (!mm(BrGemmArgs{rows, nbm, NBM, NBM, NBM, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
-      }
+  // Factorises columns [c0, c0 + ncols) of every P (ncols <= NBM << level) inside the top block that
+  // starts at S0; the block's factor goes to slot `slot` of the level's scratch, or to the top block's
+  // own place at the top level.
+  std::function<bool(int, int, int, int, int, int)> factor = [&](int level, int c0, int ncols, int S0, int slot, int tb) -> bool {
+    const int w = NBM << level;
+    const int vo = c0 - S0;  // first row and first column of this block inside the reflector block
+    const int r0 = k - c0;   // rows of this block
+    auto Tdst = [&](int i) { return level == levels ? Ttop(i, tb) : Tl(i, level, slot); };
+    auto V0 = [&](int i) { return V(i) + (size_t)vo * NBT + vo; };
+    if (level == 0) {
+      const int npanels = (ncols + NB - 1) / NB;
       for (int pnl = 0; pnl < npanels; ++pnl) {
-        const int j0 = M0 + pnl * NB;
-        const int nb = std::min(NB, k - j0);
+        const int j0 = c0 + pnl * NB;
+        const int nb = std::min(NB, c0 + ncols - j0);
         const int prow = k - j0;
-        const int voff = j0 - J0;  // this panel's first row and first column inside the reflector block
+        const int voff = j0 - S0;
         std::memset(&pb, 0, sizeof(pb));
         std::memset(&cb, 0, sizeof(cb));
         for (int i = 0; i < B; ++i) {
           pb.A[i] = P[i] + (size_t)j0 * k + j0;
-          pb.Vc[i] = V(i) + (size_t)voff * NBO + voff;
+          pb.Vc[i] = V(i) + (size_t)voff * NBT + voff;
           pb.T[i] = Tp(i, pnl);
           pb.diag[i] = D(i) + j0;
           cb.xch[i] = F(i, rs.xch);
           cb.cnt[i] = Cnt(i) + j0 / NB;
         }
-        if (!hip_ok(c, br_launch_qr_panel(s, pb, cb, B, prow, nb, k, NBO, voff), "qr panel launch")) return false;
-        const int nin = M0 + nbm - (j0 + nb);  // columns of the middle block still to the right
+        if (!hip_ok(c, br_launch_qr_panel(s, pb, cb, B, prow, nb, k, NBT, voff), "qr panel launch")) return false;
+        const int nin = c0 + ncols - (j0 + nb);  // columns of the middle block still to the right
         if (nin <= 0) continue;
         // Yt = Vp Tp^T  (prow x NB), Vp = this panel's slice of V
         for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = Tp(i, pnl); gb.C[i] = Y(i); }
-        if (!mm(BrGemmArgs{prow, NB, NB, NBO, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
+        if (!mm(BrGemmArgs{prow, NB, NB, NBT, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
         // W = Vp^T C, C = the middle block's remaining columns in the panel's rows
         for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
-        if (!mm(BrGemmArgs{NB, nin, prow, NBO, k, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+        if (!mm(BrGemmArgs{NB, nin, prow, NBT, k, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
         // C <- C - Yt W
         for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)j0 * k + j0 + nb; }
         if (!mm(BrGemmArgs{prow, nin, NB, NB, NBM, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
@@ -919,66 +927,87 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       // Merge the panels' factors: G = V_mid^T V_mid, then T_mid from the panel factors and G.
       const float* gp[BR_MAXB];
       const float* tpp[BR_MAXB];
-      float* tb[BR_MAXB];
+      float* tb_[BR_MAXB];
       if (npanels > 1) {
-        for (int i = 0; i < B; ++i) {
-          gb.A[i] = V(i) + (size_t)(mid * NBM) * NBO + mid * NBM;
-          gb.B[i] = gb.A[i];
-          gb.C[i] = F(i, rs.G);
-        }
-        if (!mm(BrGemmArgs{NBM, NBM, mrows, NBO, NBO, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+        for (int i = 0; i < B; ++i) { gb.A[i] = V0(i); gb.B[i] = V0(i); gb.C[i] = F(i, rs.G); }
+        if (!mm(BrGemmArgs{NBM, NBM, r0, NBT, NBT, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
       }
-      for (int i = 0; i < B; ++i) { gp[i] = F(i, rs.G); tpp[i] = Tp(i, 0); tb[i] = Tm(i, mid); }
-      if (!hip_ok(c, br_launch_qr_build_t(s, gp, tpp, tb, B, npanels), "qr factor merge launch")) return false;
+      for (int i = 0; i < B; ++i) { gp[i] = F(i, rs.G); tpp[i] = Tp(i, 0); tb_[i] = Tdst(i); }
+      return hip_ok(c, br_launch_qr_build_t(s, gp, tpp, tb_, B, npanels), "qr factor merge launch");
     }
-    {  // outer factor: diagonal blocks, then the coupling block -T_0 (V_0^T V_1) T_1
-      const float* tmp[BR_MAXB];
-      float* tb[BR_MAXB];
-      for (int i = 0; i < B; ++i) { tmp[i] = Tm(i, 0); tb[i] = T(i, blk); }
-      if (!hip_ok(c, br_launch_qr_assemble_t(s, tmp, tb, B, nmid), "qr outer factor launch")) return false;
-      if (nmid > 1) {
-        for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = V(i) + NBM; gb.C[i] = F(i, rs.X); }
-        if (!mm(BrGemmArgs{NBM, NBM, rows, NBO, NBO, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
-        for (int i = 0; i < B; ++i) { gb.A[i] = Tm(i, 0); gb.B[i] = F(i, rs.X); gb.C[i] = F(i, rs.Z); }
-        if (!mm(BrGemmArgs{NBM, NBM, NBM, NBM, NBM, NBM, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
-        for (int i = 0; i < B; ++i) { gb.A[i] = F(i, rs.Z); gb.B[i] = Tm(i, 1); gb.C[i] = T(i, blk) + NBM; }
-        if (!mm(BrGemmArgs{NBM, NBM, NBM, NBM, NBM, NBO, 0, 0, -1.f, 0.f, B, 0}, gb)) return false;
-      }
+    const int wc = w / 2;
+    const int n0 = std::min(wc, ncols), n1 = ncols - n0;
+    if (!factor(level - 1, c0, n0, S0, 0, tb)) return false;
+    if (n1 > 0) {
+      // apply the first child to the second child's columns: Yt = V_0 T_0^T ; W = V_0^T C ; C <- C - Yt W
+      for (int i = 0; i < B; ++i) { gb.A[i] = V0(i); gb.B[i] = Tl(i, level - 1, 0); gb.C[i] = Y(i); }
+      if (!mm(BrGemmArgs{r0, wc, wc, NBT, wc, wc, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
+      for (int i = 0; i < B; ++i) { gb.A[i] = V0(i); gb.B[i] = P[i] + (size_t)c0 * k + c0 + wc; gb.C[i] = W(i); }
+      if (!mm(BrGemmArgs{wc, n1, r0, NBT, k, wc, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+      for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)c0 * k + c0 + wc; }
+      if (!mm(BrGemmArgs{r0, n1, wc, wc, wc, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
+      if (!factor(level - 1, c0 + wc, n1, S0, 1, tb)) return false;
     }
-    const int nt = k - J0 - nbo;
+    {  // merged factor: diagonal blocks, then the coupling block -T_0 (V_0^T V_1) T_1
+      const float* tc[BR_MAXB];
+      float* td[BR_MAXB];
+      for (int i = 0; i < B; ++i) { tc[i] = Tl(i, level - 1, 0); td[i] = Tdst(i); }
+      if (!hip_ok(c, br_launch_qr_assemble_t(s, tc, td, B, n1 > 0 ? 2 : 1, wc), "qr factor assemble launch")) return false;
+    }
+    if (n1 > 0) {
+      for (int i = 0; i < B; ++i) { gb.A[i] = V0(i); gb.B[i] = V0(i) + wc; gb.C[i] = F(i, rs.X); }
+      if (!mm(BrGemmArgs{wc, wc, r0, NBT, NBT, wc, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+      for (int i = 0; i < B; ++i) { gb.A[i] = Tl(i, level - 1, 0); gb.B[i] = F(i, rs.X); gb.C[i] = F(i, rs.Z); }
+      if (!mm(BrGemmArgs{wc, wc, wc, wc, wc, wc, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
+      for (int i = 0; i < B; ++i) { gb.A[i] = F(i, rs.Z); gb.B[i] = Tl(i, level - 1, 1); gb.C[i] = Tdst(i) + wc; }
+      if (!mm(BrGemmArgs{wc, wc, wc, wc, wc, w, 0, 0, -1.f, 0.f, B, 0}, gb)) return false;
+    }
+    return true;
+  };
+  for (int tb = 0; tb < ntop; ++tb) {
+    const int S0 = tb * NBT;
+    const int ns = std::min(NBT, k - S0);  // columns of this top block
+    const int rows = k - S0;
+    if (ns < NBT) {  // the reflector block of a narrow last top block: unused columns must read as zero
+      int* vp[BR_MAXB];
+      for (int i = 0; i < B; ++i) vp[i] = reinterpret_cast<int*>(V(i));
+      if (!hip_ok(c, br_launch_zero_ints(s, vp, B, rows * NBT), "reflector clear launch")) return false;
+    }
+    if (!factor(levels, S0, ns, S0, 0, tb)) return false;
+    const int nt = k - S0 - ns;
     if (nt <= 0) continue;
     // Yt = V T^T ; W = V^T C ; C <- C - Yt W   on the trailing columns
-    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
-    if (!mm(BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
-    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = P[i] + (size_t)J0 * k + J0 + nbo; gb.C[i] = W(i); }
-    if (!mm(BrGemmArgs{NBO, nt, rows, NBO, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
-    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)J0 * k + J0 + nbo; }
-    if (!mm(BrGemmArgs{rows, nt, NBO, NBO, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Ttop(i, tb); gb.C[i] = Y(i); }
+    if (!mm(BrGemmArgs{rows, NBT, NBT, NBT, NBT, NBT, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = P[i] + (size_t)S0 * k + S0 + ns; gb.C[i] = W(i); }
+    if (!mm(BrGemmArgs{NBT, nt, rows, NBT, k, nt, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)S0 * k + S0 + ns; }
+    if (!mm(BrGemmArgs{rows, nt, NBT, NBT, nt, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
   }
-  // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before block blk is
-  // applied, Q differs from the identity only in Q[J1:, J1:] with J1 the next block's offset,
-  // so only the columns from J0 on change.
+  // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before top block tb is
+  // applied, Q differs from the identity only in Q[S1:, S1:] with S1 the next block's offset,
+  // so only the columns from S0 on change.
   // The identity carries the signs that make diag(R) >= 0 (a column of Q flips with its sign).
   const float* dg[BR_MAXB];
   for (int i = 0; i < B; ++i) dg[i] = D(i);
   if (!hip_ok(c, br_launch_qr_signed_identity(s, Q, dg, B, k), "signed identity launch")) return false;
-  for (int blk = nblocks - 1; blk >= 0; --blk) {
-    const int J0 = blk * NBO;
-    const int nbo = std::min(NBO, k - J0);
-    const int rows = k - J0;
+  for (int tb = ntop - 1; tb >= 0; --tb) {
+    const int S0 = tb * NBT;
+    const int ns = std::min(NBT, k - S0);
+    const int rows = k - S0;
     std::memset(&pb, 0, sizeof(pb));
     for (int i = 0; i < B; ++i) {
-      pb.A[i] = P[i] + (size_t)J0 * k + J0;
+      pb.A[i] = P[i] + (size_t)S0 * k + S0;
       pb.Vc[i] = V(i);
     }
-    if (!hip_ok(c, br_launch_qr_extract_v(s, pb, B, rows, nbo, k, NBO), "qr extract launch")) return false;
-    // Y = V T ; W = V^T Qsub ; Qsub <- Qsub - Y W,  Qsub = Q[J0:, J0:]
-    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = T(i, blk); gb.C[i] = Y(i); }
-    if (!mm(BrGemmArgs{rows, NBO, NBO, NBO, NBO, NBO, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
-    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Q[i] + (size_t)J0 * k + J0; gb.C[i] = W(i); }
-    if (!mm(BrGemmArgs{NBO, rows, rows, NBO, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
-    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Q[i] + (size_t)J0 * k + J0; }
-    if (!mm(BrGemmArgs{rows, rows, NBO, NBO, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
+    if (!hip_ok(c, br_launch_qr_extract_v(s, pb, B, rows, ns, k, NBT), "qr extract launch")) return false;
+    // Y = V T ; W = V^T Qsub ; Qsub <- Qsub - Y W,  Qsub = Q[S0:, S0:]
+    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Ttop(i, tb); gb.C[i] = Y(i); }
+    if (!mm(BrGemmArgs{rows, NBT, NBT, NBT, NBT, NBT, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Q[i] + (size_t)S0 * k + S0; gb.C[i] = W(i); }
+    if (!mm(BrGemmArgs{NBT, rows, rows, NBT, k, rows, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+    for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Q[i] + (size_t)S0 * k + S0; }
+    if (!mm(BrGemmArgs{rows, rows, NBT, NBT, rows, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
   }
   return true;
 }

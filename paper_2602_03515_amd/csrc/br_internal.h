@@ -149,7 +149,7 @@ hipError_t br_launch_bf16_to_f32(hipStream_t s, const uint16_t* src, float* dst,
 // ---- QR ---------------------------------------------------------------------------------
 #define BR_QR_NB 32    // inner panel width of the blocked Householder factorisation
 #define BR_QR_NBM 128  // middle block: four panels, merged into one block reflector inside LDS
-#define BR_QR_NBO 256  // outer block: two middle blocks share one trailing-matrix update (K = 256 contractions)
+#define BR_QR_NBT 256  // top block: middle blocks merged pairwise; one trailing-matrix update per top block (K = 256 contractions)
 
 struct BrQrPanelBatch {
   float* A[BR_MAXB];     // top-left corner of the panel inside the matrix being factorised
@@ -161,7 +161,7 @@ struct BrQrPanelBatch {
 // br_qr_panel_cluster(rows) workgroups per matrix, which exchange partial sums through xch
 // (br_qr_panel_xch_floats(rows) floats per matrix) and meet on the counter cnt (one int per
 // matrix and launch, ZERO before the launch; never reused without being cleared).
-#define BR_QR_MAX_RESIDENT 192  // workgroups of one panel launch: all of them must fit on the chip at once
+#define BR_QR_MAX_RESIDENT 192  // most workgroups of one panel launch (all of them must be on the chip at once)
 struct BrQrClusterBatch {
   float* xch[BR_MAXB];
   int* cnt[BR_MAXB];
@@ -182,9 +182,9 @@ hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int ba
 // matrix of the block's reflectors.
 hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const float* const* Tp, float* const* T, int batch,
                                 int npanels);
-// Diagonal blocks of an outer block's factor T (BR_QR_NBO x BR_QR_NBO) from its nmid middle
-// factors (consecutive BR_QR_NBM x BR_QR_NBM matrices); everything else zero.
-hipError_t br_launch_qr_assemble_t(hipStream_t s, const float* const* Tm, float* const* T, int batch, int nmid);
+// Diagonal blocks of a merged factor T (2w x 2w) from its nchild (1 or 2) child factors (consecutive
+// w x w matrices); everything else zero.
+hipError_t br_launch_qr_assemble_t(hipStream_t s, const float* const* Tc, float* const* T, int batch, int nchild, int w);
 // Q[:, j] *= sign(diag[j]) (zero counts as +).
 hipError_t br_launch_qr_signed_identity(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n);
 

@@ -1,8 +1,9 @@
 // Householder QR building blocks for the basis refresh (Section 3.2: "power iteration
 // followed by QR decomposition"; Algorithm 2 lines 3 and 6).
 //
-// The factorisation is blocked on three levels (panels of BR_QR_NB = 32 columns, middle blocks of
-// BR_QR_NBM = 128, outer blocks of BR_QR_NBO = 256) in compact-WY form:
+// The factorisation is blocked recursively (panels of BR_QR_NB = 32 columns, middle blocks of
+// BR_QR_NBM = 128 merged in LDS, then merged pairwise up to top blocks of BR_QR_NBT = 256) in
+// compact-WY form:
 //   H_1 H_2 ... H_nb = I - V T V^T,  V unit lower trapezoidal, T upper triangular.
 // This file holds the panel kernel; the trailing-matrix and Q-forming updates are GEMMs issued
 // by the host logic.  A panel is held ENTIRELY IN REGISTERS from its first load to its final
@@ -448,22 +449,23 @@ __global__ __launch_bounds__(BUILD_T_THREADS) void br_qr_build_t(BuildTArgs a, i
   for (int i = tid; i < BR_QR_NBM * BR_QR_NBM; i += BUILD_T_THREADS) Tout[i] = T[i / BR_QR_NBM][i % BR_QR_NBM];
 }
 
-// T of an outer block (BR_QR_NBO wide) from its middle blocks' factors: the diagonal blocks are
-// copied here, the rest is zeroed; the coupling block -T_0 (V_0^T V_1) T_1 is then written over
-// the upper right corner by two small contractions.
+// Merged factor T (2w x 2w) of two child blocks of width w: the children's factors are copied onto
+// the diagonal here, the rest is zeroed; the coupling block -T_0 (V_0^T V_1) T_1 is then written
+// over the upper right corner by small contractions.
 struct AssembleTArgs {
-  const float* Tm[BR_MAXB];  // nmid consecutive BR_QR_NBM x BR_QR_NBM factors
-  float* T[BR_MAXB];         // BR_QR_NBO x BR_QR_NBO output
+  const float* Tc[BR_MAXB];  // nchild consecutive w x w factors
+  float* T[BR_MAXB];         // 2w x 2w output
 };
 
-__global__ __launch_bounds__(256) void br_qr_assemble_t(AssembleTArgs a, int nmid) {
-  const float* __restrict__ Tm = a.Tm[blockIdx.y];
+__global__ __launch_bounds__(256) void br_qr_assemble_t(AssembleTArgs a, int nchild, int w) {
+  const float* __restrict__ Tc = a.Tc[blockIdx.y];
   float* __restrict__ T = a.T[blockIdx.y];
-  for (int i = blockIdx.x * 256 + threadIdx.x; i < BR_QR_NBO * BR_QR_NBO; i += gridDim.x * 256) {
-    const int r = i / BR_QR_NBO, c = i - r * BR_QR_NBO;
-    const int mb = r / BR_QR_NBM;
+  const int w2 = 2 * w;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < w2 * w2; i += gridDim.x * 256) {
+    const int r = i / w2, c = i - r * w2;
+    const int cb = r / w;
     float v = 0.f;
-    if (c / BR_QR_NBM == mb && mb < nmid) v = Tm[(size_t)mb * BR_QR_NBM * BR_QR_NBM + (r % BR_QR_NBM) * BR_QR_NBM + c % BR_QR_NBM];
+    if (c / w == cb && cb < nchild) v = Tc[(size_t)cb * w * w + (size_t)(r - cb * w) * w + (c - cb * w)];
     T[i] = v;
   }
 }
@@ -518,7 +520,20 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
   slab = (slab + br::QR_ROWS_PER_SWEEP - 1) / br::QR_ROWS_PER_SWEEP * br::QR_ROWS_PER_SWEEP;
   // A cluster waits for all of its workgroups: every workgroup of a launch must be resident at
   // the same time (one 1024-thread workgroup per compute unit), so large batches go in pieces.
-  const int per_launch = BR_QR_MAX_RESIDENT / nw;
+  // How many fit is asked of the device once (three quarters of its compute units, at most
+  // BR_QR_MAX_RESIDENT): on a partition with fewer units the pieces shrink, and a panel whose
+  // cluster alone does not fit is refused instead of being left to its bounded wait.
+  static int cap_of_device[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (cap_of_device[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
+    const int cap = cus * 3 / 4;
+    cap_of_device[dev] = cap < 1 ? 1 : (cap > BR_QR_MAX_RESIDENT ? BR_QR_MAX_RESIDENT : cap);
+  }
+  const int resident_cap = cap_of_device[dev];
+  const int per_launch = resident_cap / nw;
   if (per_launch < 1) return hipErrorInvalidValue;
   for (int off = 0; off < batch; off += per_launch) {
     const int b = (batch - off < per_launch) ? batch - off : per_launch;
@@ -574,15 +589,15 @@ hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const floa
   return hipGetLastError();
 }
 
-hipError_t br_launch_qr_assemble_t(hipStream_t s, const float* const* Tm, float* const* T, int batch, int nmid) {
+hipError_t br_launch_qr_assemble_t(hipStream_t s, const float* const* Tc, float* const* T, int batch, int nchild, int w) {
   if (batch <= 0) return hipSuccess;
-  if (batch > BR_MAXB || nmid < 1 || nmid * BR_QR_NBM > BR_QR_NBO) return hipErrorInvalidValue;
+  if (batch > BR_MAXB || nchild < 1 || nchild > 2 || w < BR_QR_NB || 2 * w > BR_QR_NBT) return hipErrorInvalidValue;
   br::AssembleTArgs a;
   for (int i = 0; i < BR_MAXB; ++i) {
-    a.Tm[i] = (i < batch) ? Tm[i] : nullptr;
+    a.Tc[i] = (i < batch) ? Tc[i] : nullptr;
     a.T[i] = (i < batch) ? T[i] : nullptr;
   }
-  hipLaunchKernelGGL(br::br_qr_assemble_t, dim3(16, batch), dim3(256), 0, s, a, nmid);
+  hipLaunchKernelGGL(br::br_qr_assemble_t, dim3(32, batch), dim3(256), 0, s, a, nchild, w);
   return hipGetLastError();
 }
 
