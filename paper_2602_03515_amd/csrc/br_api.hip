@@ -914,10 +914,22 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
         if (!hip_ok(c, br_launch_qr_panel(s, pb, cb, B, prow, nb, k, NBT, voff), "qr panel launch")) return false;
         const int nin = c0 + ncols - (j0 + nb);  // columns of the middle block still to the right
         if (nin <= 0) continue;
+        // C <- (I - Vp Tp^T Vp^T) C on the middle block's remaining columns, in the panel's rows
+        const size_t pfl = partial ? kSplitKBytes / sizeof(float) : 0;
+        if (nin <= 96 && pfl >= br_qr_panel_apply_floats(B, prow)) {
+          const float* vv[BR_MAXB];
+          const float* tt[BR_MAXB];
+          float* cc[BR_MAXB];
+          for (int i = 0; i < B; ++i) { vv[i] = pb.Vc[i]; tt[i] = Tp(i, pnl); cc[i] = P[i] + (size_t)j0 * k + j0 + nb; }
+          if (!hip_ok(c, br_launch_qr_panel_apply(s, vv, tt, cc, B, prow, nin, NBT, k, partial, pfl), "qr panel apply launch"))
+            return false;
+          continue;
+        }
+        // (orders too large for the scratch: the same as three general contractions)
         // Yt = Vp Tp^T  (prow x NB), Vp = this panel's slice of V
         for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = Tp(i, pnl); gb.C[i] = Y(i); }
         if (!mm(BrGemmArgs{prow, NB, NB, NBT, NB, NB, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
-        // W = Vp^T C, C = the middle block's remaining columns in the panel's rows
+        // W = Vp^T C
         for (int i = 0; i < B; ++i) { gb.A[i] = pb.Vc[i]; gb.B[i] = P[i] + (size_t)j0 * k + j0 + nb; gb.C[i] = W(i); }
         if (!mm(BrGemmArgs{NB, nin, prow, NBT, k, NBM, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
         // C <- C - Yt W

@@ -175,6 +175,12 @@ size_t br_qr_panel_xch_floats(int rows);
 hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQrClusterBatch& cb, int batch, int rows, int nb,
                               int lda, int ldv, int pre_rows);
 hipError_t br_launch_zero_ints(hipStream_t s, int* const* ptrs, int batch, int n);
+// C <- (I - V T^T V^T) C: a factorised panel's block reflector (V: rows x 32 clean reflectors, row
+// stride ldv; T: 32 x 32) applied to the rows x ncols block C (ncols <= 96, row stride ldc) to its
+// right.  partial: scratch of at least br_qr_panel_apply_floats(batch, rows) floats.
+size_t br_qr_panel_apply_floats(int batch, int rows);
+hipError_t br_launch_qr_panel_apply(hipStream_t s, const float* const* V, const float* const* T, float* const* C, int batch,
+                                    int rows, int ncols, int ldv, int ldc, float* partial, size_t partial_floats);
 // Copy the reflectors of an already factorised block of nb columns out into Vc (rows x width).
 hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda,
                                   int width);

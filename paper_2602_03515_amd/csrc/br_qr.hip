@@ -499,6 +499,140 @@ __global__ __launch_bounds__(256) void br_qr_signed_identity(SignArgs a, int n) 
   }
 }
 
+
+// ---- a panel's block reflector applied to the rest of its middle block -------------------
+// C <- (I - V T^T V^T) C for the rows x ncols block C right of a factorised panel (ncols <= 96,
+// V: rows x 32 clean reflectors, T: 32 x 32).  As three general contractions this is all latency
+// (M = 32, N <= 96, K = thousands: a split-K launch, its reduction, two more launches); here it is
+// two launches of small workgroups:
+//   br_qr_panel_vtc    partial[slab] = V_slab^T C_slab   (32 x ncols per PA_VSLAB rows; FP32 MFMA, a wave
+//                      per quarter of the rows and 32 columns, the quarters summed in LDS in a fixed order)
+//   br_qr_panel_apply  W = sum of the partials in slab order (deterministic), X = T^T W in LDS,
+//                      C_slab <- C_slab - V_slab X   (PA_SLAB rows per workgroup).
+typedef float qr_floatx16 __attribute__((ext_vector_type(16)));
+constexpr int PA_SLAB = 256;    // rows per workgroup of br_qr_panel_apply
+constexpr int PA_VSLAB = 1024;  // rows per workgroup of br_qr_panel_vtc (four quarters of 256, one wave each per 32 columns)
+constexpr int PA_MAXC = 96;
+
+struct PanelApplyArgs {
+  const float* V[BR_MAXB];
+  const float* T[BR_MAXB];
+  float* C[BR_MAXB];
+};
+
+__global__ __launch_bounds__(768) void br_qr_panel_vtc(PanelApplyArgs a, int rows, int ncols, int ldv, int ldc,
+                                                       float* __restrict__ partial) {
+  __shared__ float red[4][32][PA_MAXC + 1];
+  const int mat = blockIdx.y, slab = blockIdx.x, nslab = gridDim.x;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63, lk = lane >> 5, li = lane & 31;
+  const int cb = wave % 3, rq = wave / 3;  // 32-column block of C, quarter of the slab's rows
+  const float* __restrict__ V = a.V[mat];
+  const float* __restrict__ C = a.C[mat];
+  const int col = cb * 32 + li;
+  const bool col_ok = col < ncols;
+  if (cb * 32 < ncols) {  // wave-uniform
+    const int r_begin = slab * PA_VSLAB + rq * (PA_VSLAB / 4);
+    const int r_end = min(rows, r_begin + PA_VSLAB / 4);
+    qr_floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    // W[j][c] += V[r][j] C[r][c]: the matrix instruction takes A[i = j][k = r] and B[k = r][j = c], two rows per issue
+    for (int r = r_begin; r < r_end; r += 16) {
+      float av[8], bv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int rr = r + 2 * u + lk;
+        const bool ok = rr < r_end;
+        av[u] = ok ? V[(size_t)rr * ldv + li] : 0.f;
+        bv[u] = (ok && col_ok) ? C[(size_t)rr * ldc + col] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[rq][8 * (v >> 2) + 4 * lk + (v & 3)][col] = acc[v];
+  }
+  __syncthreads();
+  float* __restrict__ P = partial + ((size_t)mat * nslab + slab) * (32 * PA_MAXC);
+  for (int e = tid; e < 32 * PA_MAXC; e += 768) {
+    const int j = e / PA_MAXC, c = e - j * PA_MAXC;
+    if (c < ncols) P[e] = ((red[0][j][c] + red[1][j][c]) + red[2][j][c]) + red[3][j][c];  // fixed order
+  }
+}
+
+__global__ __launch_bounds__(512) void br_qr_panel_apply(PanelApplyArgs a, int rows, int ncols, int ldv, int ldc,
+                                                         const float* __restrict__ partial, int nvslab) {
+  __shared__ float Wl[32][PA_MAXC + 1];
+  __shared__ float Xl[32][PA_MAXC + 1];
+  __shared__ float Tl[32][33];
+  const int mat = blockIdx.y, slab = blockIdx.x;
+  const int tid = threadIdx.x;
+  const float* __restrict__ V = a.V[mat];
+  const float* __restrict__ T = a.T[mat];
+  float* __restrict__ C = a.C[mat];
+  for (int i = tid; i < 32 * 32; i += 512) Tl[i >> 5][i & 31] = T[i];
+  const float* __restrict__ P = partial + (size_t)mat * nvslab * (32 * PA_MAXC);
+  {
+    float sum[6];  // 32 * 96 / 512 entries per thread, summed over the partials in slab order (deterministic)
+#pragma unroll
+    for (int q = 0; q < 6; ++q) sum[q] = 0.f;
+    for (int sl = 0; sl < nvslab; ++sl) {
+#pragma unroll
+      for (int q = 0; q < 6; ++q) {
+        const int e = tid + 512 * q;
+        const int c = e % PA_MAXC;
+        if (c < ncols) sum[q] += P[(size_t)sl * (32 * PA_MAXC) + e];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 6; ++q) {
+      const int e = tid + 512 * q;
+      Wl[e / PA_MAXC][e % PA_MAXC] = sum[q];
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < 32 * PA_MAXC; e += 512) {  // X = T^T W, T upper triangular
+    const int j = e / PA_MAXC, c = e - j * PA_MAXC;
+    float s = 0.f;
+    for (int l = 0; l <= j; ++l) s += Tl[l][j] * Wl[l][c];
+    Xl[j][c] = s;
+  }
+  __syncthreads();
+  const int wave = tid >> 6, lane = tid & 63, lk = lane >> 5, li = lane & 31;
+  const int nblk = (ncols + 31) / 32;
+  const int r0 = slab * PA_SLAB + wave * 32;  // eight waves, 32 rows each
+  if (r0 >= rows) return;
+  // C[r][c] -= sum_k V[r][k] X[k][c]: A[i = row][k] = V, B[k][j = c] = X
+  float av[16];
+  {
+    const int rr = r0 + li;
+    const float* vrow = V + (size_t)rr * ldv + lk;
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) av[kk] = (rr < rows) ? vrow[2 * kk] : 0.f;
+  }
+  for (int cb = 0; cb < nblk; ++cb) {
+    qr_floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kk], Xl[2 * kk + lk][cb * 32 + li], acc, 0, 0, 0);
+    const int col = cb * 32 + li;
+    float old[16];  // all loads before the first store (a load behind a store to the same matrix waits for it)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int rr = r0 + 8 * (v >> 2) + 4 * lk + (v & 3);
+      old[v] = (rr < rows && col < ncols) ? C[(size_t)rr * ldc + col] : 0.f;
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int rr = r0 + 8 * (v >> 2) + 4 * lk + (v & 3);
+      if (rr < rows && col < ncols) C[(size_t)rr * ldc + col] = old[v] - acc[v];
+    }
+  }
+}
+
 }  // namespace br
 
 int br_qr_panel_cluster(int rows) { return (rows + br::QR_MAX_SLAB - 1) / br::QR_MAX_SLAB; }
@@ -562,6 +696,31 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
+}
+
+size_t br_qr_panel_apply_floats(int batch, int rows) {
+  return (size_t)batch * ((rows + br::PA_VSLAB - 1) / br::PA_VSLAB) * 32 * br::PA_MAXC;
+}
+
+hipError_t br_launch_qr_panel_apply(hipStream_t s, const float* const* V, const float* const* T, float* const* C, int batch,
+                                    int rows, int ncols, int ldv, int ldc, float* partial, size_t partial_floats) {
+  if (batch <= 0 || ncols <= 0) return hipSuccess;
+  if (batch > BR_MAXB || rows < 1 || ncols > br::PA_MAXC || ldv < BR_QR_NB || ldc < ncols || !partial ||
+      partial_floats < br_qr_panel_apply_floats(batch, rows))
+    return hipErrorInvalidValue;
+  br::PanelApplyArgs a;
+  for (int i = 0; i < BR_MAXB; ++i) {
+    a.V[i] = (i < batch) ? V[i] : nullptr;
+    a.T[i] = (i < batch) ? T[i] : nullptr;
+    a.C[i] = (i < batch) ? C[i] : nullptr;
+  }
+  const int nvslab = (rows + br::PA_VSLAB - 1) / br::PA_VSLAB;
+  const int nslab = (rows + br::PA_SLAB - 1) / br::PA_SLAB;
+  hipLaunchKernelGGL(br::br_qr_panel_vtc, dim3(nvslab, batch), dim3(768), 0, s, a, rows, ncols, ldv, ldc, partial);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(br::br_qr_panel_apply, dim3(nslab, batch), dim3(512), 0, s, a, rows, ncols, ldv, ldc, partial, nvslab);
+  return hipGetLastError();
 }
 
 hipError_t br_launch_qr_extract_v(hipStream_t s, const BrQrPanelBatch& p, int batch, int rows, int nb, int lda,
