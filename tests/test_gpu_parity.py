@@ -56,7 +56,9 @@ def _run(h, W0s, grads_per_step, freq, lr, tol=TOL, check_q=True, **kw):
     for i, st in enumerate(sb.states):
         for which, Q in ((sb.B.BR_STATE_QL, st.QL), (sb.B.BR_STATE_QR, st.QR)):
             if Q is not None:
-                assert orthogonality_defect(h.to_np(sb.opt.state(i, which))) < 1e-5
+                # BR_MATH_BF16 runs the QR's large updates on hi + lo split BF16 inputs (16-bit mantissas)
+                bar = 5e-5 if kw.get("math", 0) == 1 else 1e-5
+                assert orthogonality_defect(h.to_np(sb.opt.state(i, which))) < bar
     return sb, worst
 
 
