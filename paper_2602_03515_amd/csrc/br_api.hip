@@ -166,7 +166,7 @@ inline size_t plane_bytes(int64_t rows, int64_t k, const br_hparams& hp) {
 }
 
 struct RefreshScratch {
-  size_t P0, P1, gram, V, Y, W, T, Tp, Tl, G, X, Z, diag, xch, cnt, planesA, planesB, qrp, total;
+  size_t P0, P1, gram, V, Y, W, T, Tp, Tl, G, X, Z, diag, xch, planesA, planesB, qrp, total;
 };
 
 // Doubling levels of the QR's block-reflector merges above the LDS-merged middle block: level l
@@ -205,8 +205,7 @@ RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   r.X = off; off += align256((size_t)(BR_QR_NBT / 2) * (BR_QR_NBT / 2) * 4);  // V_0^T V_1
   r.Z = off; off += align256((size_t)(BR_QR_NBT / 2) * (BR_QR_NBT / 2) * 4);  // T_0 (V_0^T V_1)
   r.diag = off; off += align256((size_t)k * 4);
-  r.xch = off; off += align256(br_qr_panel_xch_floats((int)k) * 4);            // cluster exchange of one panel launch ...
-  r.cnt = off; off += align256((size_t)((k + BR_QR_NB - 1) / BR_QR_NB) * 4);  // ... and one arrival counter per panel
+  r.xch = off; off += align256(br_qr_panel_xch_floats((int)k) * 4);            // cluster exchange of one panel launch
   // BF16 math mode: hi + lo planes of the statistics and of the transposed basis for the power iteration
   const size_t pl = (hp.math == BR_MATH_BF16) ? align256(4 * br_plane_layout(k, k).elems) : 0;
   r.planesA = off; off += pl;
@@ -887,16 +886,15 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     return F(i, rs.Tl) + qr_level_offset(l) + (size_t)slot * w * w;
   };
   auto D = [&](int i) { return F(i, rs.diag); };
-  auto Cnt = [&](int i) { return reinterpret_cast<int*>(base + i * stride + rs.cnt); };
   auto mm = [&](const BrGemmArgs& a, const BrGemmBatch& gb) { return gemm(c, a, gb, false, partial, s); };
   BrQrPanelBatch pb;
   BrQrClusterBatch cb;
   BrGemmBatch gb;
   std::memset(&gb, 0, sizeof(gb));
-  {
-    int* cp[BR_MAXB];
-    for (int i = 0; i < B; ++i) cp[i] = Cnt(i);
-    if (!hip_ok(c, br_launch_zero_ints(s, cp, B, (k + NB - 1) / NB), "counter clear launch")) return false;
+  {  // the clusters' exchange words carry tags that are unique from here on: start from zero
+    int* xp[BR_MAXB];
+    for (int i = 0; i < B; ++i) xp[i] = reinterpret_cast<int*>(F(i, rs.xch));
+    if (!hip_ok(c, br_launch_zero_ints(s, xp, B, (int)br_qr_panel_xch_floats(k)), "exchange clear launch")) return false;
   }
   // Factorises columns [c0, c0 + ncols) of every P (ncols <= NBM << level) inside the top block that
   // starts at S0; the block's factor goes to slot `slot` of the level's scratch, or to the top block's
@@ -921,9 +919,9 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
           pb.Vc[i] = V(i) + (size_t)voff * NBT + voff;
           pb.T[i] = Tp(i, pnl);
           pb.diag[i] = D(i) + j0;
-          cb.xch[i] = F(i, rs.xch);
-          cb.cnt[i] = Cnt(i) + j0 / NB;
+          cb.xch[i] = reinterpret_cast<unsigned long long*>(F(i, rs.xch));
         }
+        cb.tag0 = (unsigned)(j0 / NB) * 64u;
         if (!hip_ok(c, br_launch_qr_panel(s, pb, cb, B, prow, nb, k, NBT, voff), "qr panel launch")) return false;
         const int nin = c0 + ncols - (j0 + nb);  // columns of the middle block still to the right
         if (nin <= 0) continue;

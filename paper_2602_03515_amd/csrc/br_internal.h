@@ -159,12 +159,13 @@ struct BrQrPanelBatch {
 };
 // Panels taller than one workgroup's register capacity are factorised by a cluster of
 // br_qr_panel_cluster(rows) workgroups per matrix, which exchange partial sums through xch
-// (br_qr_panel_xch_floats(rows) floats per matrix) and meet on the counter cnt (one int per
-// matrix and launch, ZERO before the launch; never reused without being cleared).
+// (br_qr_panel_xch_floats(rows) floats per matrix, 8-byte aligned).  Every exchanged word carries the
+// tag tag0 + step + 1 (step <= 32): xch must be ZERO before the first panel of a factorisation,
+// and tag0 must differ by at least 64 between the panels that share it afterwards.
 #define BR_QR_MAX_RESIDENT 192  // most workgroups of one panel launch (all of them must be on the chip at once)
 struct BrQrClusterBatch {
-  float* xch[BR_MAXB];
-  int* cnt[BR_MAXB];
+  unsigned long long* xch[BR_MAXB];
+  unsigned tag0;
 };
 int br_qr_panel_cluster(int rows);
 size_t br_qr_panel_xch_floats(int rows);

@@ -26,8 +26,8 @@ constexpr int QR_ROWS_PER_SWEEP = QR_THREADS / 8;  // 128
 constexpr int QR_WAVES = QR_THREADS / 64;          // 16
 constexpr int QR_RESIDENT_SWEEPS = 12;             // a workgroup keeps up to 12 x 128 = 1536 rows in registers
 constexpr int QR_MAX_SLAB = QR_RESIDENT_SWEEPS * QR_ROWS_PER_SWEEP;
-constexpr int QR_XCH_FLOATS = 64;                  // per (step, workgroup): 32 partial sums + the next pivot row
-constexpr unsigned QR_SPIN_LIMIT = 1u << 26;       // polls before a cluster gives up and poisons its result
+constexpr int QR_XCH_SLOTS = 64;                   // per (step, workgroup): 32 partial sums + the next pivot row
+constexpr unsigned QR_SPIN_LIMIT = 1u << 22;       // polls of one value before a cluster gives up and poisons its result
 
 // One lane's four columns of a panel row travel as a float4 VALUE (never through a pointer), so
 // that groups of rows stay in registers.
@@ -97,46 +97,53 @@ __device__ __forceinline__ float panel_reduce(float4 acc, float (*red)[32], floa
 }
 
 // Cluster part of the reduction (gridDim.y > 1): every workgroup publishes its 32 partial sums
-// (workgroup 0 also the pivot row of the next pass), announces it on the panel's counter and
-// waits until all have; then each sums the partials in workgroup order, so that all of them
-// hold bit-identical values.  Exchange slots are per step: nothing is ever overwritten.
-// The wait is bounded: a cluster that never becomes complete poisons its sums with NaN (which
-// reaches the basis and the weights) instead of hanging.
+// (workgroup 0 also the pivot row of the next pass) and reads the others'.  A published value is
+// one 8-byte word, the float and a tag that names the panel and the step, written and read with
+// single 8-byte atomic accesses: a reader polls the word itself until the tag is the one it
+// waits for, so the exchange is one store and one load deep, without a separate arrival counter.
+// The buffer is zeroed before a factorisation and tags are unique within it (never zero).
+// Each workgroup sums the partials in workgroup order, so that all of them hold bit-identical
+// values.  The wait is bounded: a value that never arrives becomes NaN (which reaches the basis
+// and the weights) instead of a hang.
 struct Cluster {
-  float* xch;   // [step][workgroup][QR_XCH_FLOATS] of this matrix
-  int* cnt;     // this panel's arrival counter (zero before the launch)
+  unsigned long long* xch;  // [step][workgroup][QR_XCH_SLOTS] of this matrix
+  unsigned tag0;            // this panel's tags are tag0 + step + 1
   int w, nw;
 };
 
-__device__ __forceinline__ void cluster_combine(const Cluster& cl, int step, float* comb, float* pivnext, int tid) {
-  if (cl.nw == 1) return;
-  float* mine = cl.xch + ((size_t)step * cl.nw + cl.w) * QR_XCH_FLOATS;
-  if (tid < 32) {
-    mine[tid] = comb[tid];
-    if (cl.w == 0) mine[32 + tid] = pivnext[tid];
+__device__ __forceinline__ unsigned long long xch_pack(float v, unsigned tag) {
+  return ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+}
+
+__device__ __forceinline__ float xch_wait(const unsigned long long* slot, unsigned tag) {
+  unsigned spins = 0;
+  for (;;) {
+    const unsigned long long v = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((unsigned)(v >> 32) == tag) return __uint_as_float((unsigned)v);
+    if (++spins > QR_SPIN_LIMIT) return __builtin_nanf("");
+    __builtin_amdgcn_s_sleep(1);
   }
-  __syncthreads();
-  __shared__ int gave_up;
-  if (tid == 0) {
-    gave_up = 0;
-    __hip_atomic_fetch_add(cl.cnt, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    const int target = cl.nw * (step + 1);
-    unsigned spins = 0;
-    while (__hip_atomic_load(cl.cnt, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      if (++spins > QR_SPIN_LIMIT) { gave_up = 1; break; }
-      __builtin_amdgcn_s_sleep(2);
-    }
-  }
-  __syncthreads();
+}
+
+// Threads 0..31 pass their column's partial sum and get the cluster's sum back; threads 64..95
+// carry the next pivot row (read from pivnext in workgroup 0, written to it in the others).  No
+// barrier inside: the caller's barrier after its own use of the sums also publishes pivnext.
+__device__ __forceinline__ float cluster_combine(const Cluster& cl, int step, float part, float* pivnext, int tid) {
+  const unsigned tag = cl.tag0 + (unsigned)step + 1u;
+  unsigned long long* base = cl.xch + (size_t)step * cl.nw * QR_XCH_SLOTS;
+  float s = 0.f;
   if (tid < 32) {
-    const float* base = cl.xch + (size_t)step * cl.nw * QR_XCH_FLOATS;
-    float s = 0.f;
+    __hip_atomic_store(base + (size_t)cl.w * QR_XCH_SLOTS + tid, xch_pack(part, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int ww = 0; ww < cl.nw; ++ww)
-      s += __hip_atomic_load(base + (size_t)ww * QR_XCH_FLOATS + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    comb[tid] = gave_up ? __builtin_nanf("") : s;
-    if (cl.w != 0) pivnext[tid] = __hip_atomic_load(base + 32 + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s += (ww == cl.w) ? part : xch_wait(base + (size_t)ww * QR_XCH_SLOTS + tid, tag);
+  } else if (tid >= 64 && tid < 96) {  // another wave than the sums': the two waits overlap
+    const int t = tid - 64;
+    if (cl.w == 0)
+      __hip_atomic_store(base + 32 + t, xch_pack(pivnext[t], tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+      pivnext[t] = xch_wait(base + 32 + t, tag);
   }
-  __syncthreads();
+  return s;
 }
 
 // State shared by all rows during pass j.
@@ -215,7 +222,7 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   const bool vec = vec_ok != 0;
   Cluster cl;
   cl.xch = cb.xch[blockIdx.x];
-  cl.cnt = cb.cnt[blockIdx.x];
+  cl.tag0 = cb.tag0;
   cl.w = blockIdx.y;
   cl.nw = gridDim.y;
   const bool first = (cl.w == 0);
@@ -261,12 +268,8 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
     }
   }
   {
-    const bool multi = cl.nw > 1;
-    float sum = panel_reduce(acc, red, comb, tid, multi);
-    if (multi) {
-      cluster_combine(cl, 0, comb, pivrow[0], tid);
-      if (tid < 32) sum = comb[tid];
-    }
+    float sum = panel_reduce(acc, red, comb, tid, false);
+    if (cl.nw > 1) sum = cluster_combine(cl, 0, sum, pivrow[0], tid);
     if (tid < 32) dvec[tid] = sum;
     __syncthreads();
   }
@@ -321,12 +324,8 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
     {
       // Column sums of this pass: for c > j the dot products of the next pass, for c < j the entries
       // v_c^T v_j of the Gram matrix of the reflectors.
-      const bool multi = cl.nw > 1;
-      float sum = panel_reduce(acc, red, comb, tid, multi);
-      if (multi) {
-        cluster_combine(cl, j + 1, comb, pivrow[cur ^ 1], tid);
-        if (tid < 32) sum = comb[tid];
-      }
+      float sum = panel_reduce(acc, red, comb, tid, false);
+      if (cl.nw > 1) sum = cluster_combine(cl, j + 1, sum, pivrow[cur ^ 1], tid);
       if (tid < 32) {
         if (tid > j) dvec[tid] = sum;
         else if (tid < j) Sl[tid][j] = sum;
@@ -638,7 +637,7 @@ __global__ __launch_bounds__(512) void br_qr_panel_apply(PanelApplyArgs a, int r
 int br_qr_panel_cluster(int rows) { return (rows + br::QR_MAX_SLAB - 1) / br::QR_MAX_SLAB; }
 
 size_t br_qr_panel_xch_floats(int rows) {
-  return (size_t)(BR_QR_NB + 1) * br_qr_panel_cluster(rows) * br::QR_XCH_FLOATS;
+  return (size_t)(BR_QR_NB + 1) * br_qr_panel_cluster(rows) * br::QR_XCH_SLOTS * 2;  // 8-byte slots
 }
 
 hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQrClusterBatch& cb, int batch, int rows, int nb,
@@ -673,6 +672,7 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
     const int b = (batch - off < per_launch) ? batch - off : per_launch;
     BrQrPanelBatch pp;
     BrQrClusterBatch cc;
+    cc.tag0 = cb.tag0;
     for (int i = 0; i < BR_MAXB; ++i) {
       const bool live = i < b;
       pp.A[i] = live ? p.A[off + i] : nullptr;
@@ -680,7 +680,6 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
       pp.T[i] = live ? p.T[off + i] : nullptr;
       pp.diag[i] = live ? p.diag[off + i] : nullptr;
       cc.xch[i] = live ? cb.xch[off + i] : nullptr;
-      cc.cnt[i] = live ? cb.cnt[off + i] : nullptr;
     }
     const int sweeps = slab / br::QR_ROWS_PER_SWEEP;
     if (sweeps <= 5)
