@@ -460,11 +460,30 @@ __global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int
   const int tr = blockIdx.x / tiles_c, tc = blockIdx.x - tr * tiles_c;
   const int r0 = tr * 64, c0 = tc * 64;  // source row (= k) and source column (= plane row) origin
   const int tid = threadIdx.x;
+  const bool vec = ((ld_src & 3) == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0);
+  if (vec && r0 + 64 <= R && c0 + 64 <= Ccols) {
+    // whole tile inside the source: four 16-byte loads per thread, all in flight together
+    float4 v[4];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int rr = i * 4 + (tid >> 6), cc = tid & 63;
-    const int r = r0 + rr, c = c0 + cc;
-    tile[rr][cc] = (r < R && c < Ccols) ? X[(size_t)r * ld_src + c] : 0.f;
+    for (int i = 0; i < 4; ++i) {
+      const int rr = i * 16 + (tid >> 4), c4 = (tid & 15) * 4;
+      v[i] = *reinterpret_cast<const float4*>(X + (size_t)(r0 + rr) * ld_src + c0 + c4);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rr = i * 16 + (tid >> 4), c4 = (tid & 15) * 4;
+      tile[rr][c4 + 0] = v[i].x;
+      tile[rr][c4 + 1] = v[i].y;
+      tile[rr][c4 + 2] = v[i].z;
+      tile[rr][c4 + 3] = v[i].w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int rr = i * 4 + (tid >> 6), cc = tid & 63;
+      const int r = r0 + rr, c = c0 + cc;
+      tile[rr][cc] = (r < R && c < Ccols) ? X[(size_t)r * ld_src + c] : 0.f;
+    }
   }
   __syncthreads();
 #pragma unroll
