@@ -74,10 +74,9 @@ typedef enum { BR_SRC_SECOND = 0, BR_SRC_FIRST = 1 } br_source;
  * F32 issues FP32 MFMA.  BF16 rounds both operands to BF16 (parity bar 2e-2).  BF16X3 splits
  * each FP32 operand into hi + lo BF16 parts and adds the products hi*hi + hi*lo + lo*hi in FP32:
  * 16-bit mantissa inputs, same 1e-4 bar as F32, about a third of the matrix-core time.  The
- * refresh (its L Q product and the QR) runs in FP32, except under BR_MATH_BF16: there L Q takes the
- * hi/lo split with all four partial products and the QR's large block-reflector updates take it
- * with three (panels and merges stay FP32); the bases of that mode are orthogonal to about 2e-5
- * (FP32: 1e-6). */
+ * refresh (its L Q product and the QR) runs in FP32, except under BR_MATH_BF16: there L Q and the
+ * QR's large block-reflector updates take the hi/lo split with three partial products (panels and
+ * merges stay FP32); the bases of that mode are orthogonal to about 2e-5 (FP32: 1e-6). */
 typedef enum { BR_MATH_F32 = 0, BR_MATH_BF16 = 1, BR_MATH_BF16X3 = 2 } br_math;
 
 /* Which buffer br_get_state returns. */

@@ -991,13 +991,28 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
   // Yb = V T^T or V T already in Y.  BR_MATH_BF16 runs its two contractions on the BF16 matrix cores
   // with hi + lo split operands and three partial products (16-bit mantissa inputs, FP32
   // accumulation, C itself stays FP32): the bases of that mode come from statistics that are
-  // only BF16 accurate, and these two products are three quarters of the refresh.  The product
+  // only BF16 accurate, and these two products are three quarters of the refresh.  The operand
+  // planes of C^T are not made again for every block: the whole matrix is split once per phase
+  // (planes of P^T, planes of Q^T), a block's C^T is a view into that set (blocks start at multiples
+  // of 256), and the update's epilogue rewrites the view from the values it stores.  The product
   // V^T C leaves its kernel transposed and already split, as the operand of the second one.
   const bool x3 = c->hp.math == BR_MATH_BF16;
   LowpCtx lx{c, nullptr, LowpLayout{}, B, 3, nullptr};
   lx.quiet = true;
   const size_t qchunk = qr_plane_chunk(k);
-  auto apply_top = [&](float* const* Cp, int rows, int ncols) -> bool {
+  const BrPlaneLayout Lk = br_plane_layout(k, k);
+  // hi plane of the view that starts at plane row row0 and at k0 inside the k x k plane set at `set`
+  auto view = [&](size_t set, int i, int row0, int k0) {
+    return reinterpret_cast<uint16_t*>(base + i * stride + set) + (((size_t)(k0 >> 4) * Lk.rows_p + row0) * 2) * 8;
+  };
+  auto split_whole = [&](float* const* Mx, size_t set) -> bool {  // planes of the transposed k x k matrices
+    const float* src[BR_MAXB];
+    uint16_t* dst[BR_MAXB];
+    for (int i = 0; i < B; ++i) { src[i] = Mx[i]; dst[i] = reinterpret_cast<uint16_t*>(base + i * stride + set); }
+    return lowp_split(lx, src, k, k, true, dst);
+  };
+  // Cp: the blocks (FP32); set/row0/k0: where their transposes live as planes
+  auto apply_top = [&](float* const* Cp, int rows, int ncols, size_t set, int row0, int k0) -> bool {
     if (!x3) {
       for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Cp[i]; gb.C[i] = W(i); }
       if (!mm(BrGemmArgs{NBT, ncols, rows, NBT, k, ncols, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
@@ -1005,23 +1020,39 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       return mm(BrGemmArgs{rows, ncols, NBT, NBT, ncols, k, 0, 0, -1.f, 1.f, B, 0}, gb);
     }
     const float* src[BR_MAXB];
-    uint16_t *pv[BR_MAXB], *py[BR_MAXB], *pw[BR_MAXB], *pc[BR_MAXB];
+    uint16_t *pv[BR_MAXB], *py[BR_MAXB], *pw[BR_MAXB];
     for (int i = 0; i < B; ++i) {
       char* q = base + i * stride + rs.qrp;
       pv[i] = reinterpret_cast<uint16_t*>(q);
       py[i] = reinterpret_cast<uint16_t*>(q + qchunk);
       pw[i] = reinterpret_cast<uint16_t*>(q + 2 * qchunk);
-      pc[i] = reinterpret_cast<uint16_t*>(base + i * stride + rs.planesA);
     }
     for (int i = 0; i < B; ++i) src[i] = V(i);
     if (!lowp_split(lx, src, rows, NBT, true, pv)) return false;            // planes of V^T   [NBT][rows]
     for (int i = 0; i < B; ++i) src[i] = Y(i);
     if (!lowp_split(lx, src, rows, NBT, false, py)) return false;           // planes of Yb    [rows][NBT]
-    for (int i = 0; i < B; ++i) src[i] = Cp[i];
-    if (!lowp_split(lx, src, rows, ncols, true, pc, k)) return false;       // planes of C^T   [ncols][rows]
-    if (!lowp_gemm(lx, pv, NBT, pc, ncols, rows, nullptr, 0, 1.f, 0.f, pw, false, 3, BR_EPI_PLANES)) return false;  // (V^T C)^T
-    return lowp_gemm(lx, py, rows, pw, ncols, NBT, Cp, k, -1.f, 1.f, nullptr, false, 3);
+    BrLowpBatch lb;
+    std::memset(&lb, 0, sizeof(lb));
+    for (int i = 0; i < B; ++i) { lb.A[i] = pv[i]; lb.B[i] = view(set, i, row0, k0); lb.shadow[i] = pw[i]; }
+    BrLowpArgs wa{NBT, ncols, rows, 0, 1.f, 0.f, B, 0, 3};                  // (V^T C)^T as planes [ncols][NBT]
+    wa.epilogue = BR_EPI_PLANES;
+    wa.out_lo = 1;
+    wa.b_stride_rows = (int)Lk.rows_p;
+    wa.b_plane_elems = Lk.elems;
+    if (!hip_ok(c, br_launch_gemm_lowp(s, wa, lb, nullptr), "qr bf16 product launch")) return false;
+    std::memset(&lb, 0, sizeof(lb));
+    for (int i = 0; i < B; ++i) {
+      lb.A[i] = py[i]; lb.B[i] = pw[i]; lb.C[i] = Cp[i];
+      lb.S[i] = reinterpret_cast<float*>(view(set, i, row0, k0));           // the updated C^T, for the next block
+    }
+    BrLowpArgs ua{rows, ncols, NBT, k, -1.f, 1.f, B, 0, 3};
+    ua.out_lo = 1;
+    ua.emit_transposed = 1;
+    ua.out_stride_rows = (int)Lk.rows_p;
+    ua.out_plane_elems = Lk.elems;
+    return hip_ok(c, br_launch_gemm_lowp(s, ua, lb, nullptr), "qr bf16 update launch");
   };
+  if (x3 && ntop > 1 && !split_whole(P, rs.planesA)) return false;
   float* cblk[BR_MAXB];
   for (int tb = 0; tb < ntop; ++tb) {
     const int S0 = tb * NBT;
@@ -1039,7 +1070,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Ttop(i, tb); gb.C[i] = Y(i); }
     if (!mm(BrGemmArgs{rows, NBT, NBT, NBT, NBT, NBT, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
     for (int i = 0; i < B; ++i) cblk[i] = P[i] + (size_t)S0 * k + S0 + ns;
-    if (!apply_top(cblk, rows, nt)) return false;
+    if (!apply_top(cblk, rows, nt, rs.planesA, S0 + ns, S0)) return false;
   }
   // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before top block tb is
   // applied, Q differs from the identity only in Q[S1:, S1:] with S1 the next block's offset,
@@ -1048,6 +1079,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
   const float* dg[BR_MAXB];
   for (int i = 0; i < B; ++i) dg[i] = D(i);
   if (!hip_ok(c, br_launch_qr_signed_identity(s, Q, dg, B, k), "signed identity launch")) return false;
+  if (x3 && !split_whole(Q, rs.planesB)) return false;
   for (int tb = ntop - 1; tb >= 0; --tb) {
     const int S0 = tb * NBT;
     const int ns = std::min(NBT, k - S0);
@@ -1062,7 +1094,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Ttop(i, tb); gb.C[i] = Y(i); }
     if (!mm(BrGemmArgs{rows, NBT, NBT, NBT, NBT, NBT, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
     for (int i = 0; i < B; ++i) cblk[i] = Q[i] + (size_t)S0 * k + S0;
-    if (!apply_top(cblk, rows, rows)) return false;
+    if (!apply_top(cblk, rows, rows, rs.planesB, S0, S0)) return false;
   }
   return true;
 }
@@ -1105,9 +1137,10 @@ br_status br_refresh_basis(br_ctx* ctx) {
       }
     }
     // P <- A^iters Q.  In the BF16 math mode the product runs on the BF16 matrix cores with both
-    // operands split into hi + lo planes and all four partial products (16-bit mantissa inputs);
-    // BF16X3 keeps FP32 here: the QR amplifies an input error by the condition number of A, and
-    // 2^-17 per entry is already too much for that mode's 1e-4 bar.
+    // operands split into hi + lo planes and three partial products (16-bit mantissa inputs), like
+    // the large updates of the QR that follows; BF16X3 keeps FP32 here: the QR amplifies an input
+    // error by the condition number of A, and 2^-17 per entry is already too much for that mode's
+    // 1e-4 bar.
     float** src = Q;
     float** dst = P0;
     const bool lowp = hp.math == BR_MATH_BF16;
@@ -1123,7 +1156,7 @@ br_status br_refresh_basis(br_ctx* ctx) {
         const float* s32[BR_MAXB];
         for (int i = 0; i < B; ++i) s32[i] = src[i];
         if (!lowp_split(lx, s32, k, k, true, plB)) return BR_ERR_HIP;  // planes of src^T: B[j][l] = src[l][j]
-        if (!lowp_gemm(lx, plA, k, plB, k, k, dst, k, 1.f, 0.f, nullptr, false, 4)) return BR_ERR_HIP;
+        if (!lowp_gemm(lx, plA, k, plB, k, k, dst, k, 1.f, 0.f, nullptr, false, 3)) return BR_ERR_HIP;
       } else {
         for (int i = 0; i < B; ++i) { gb.A[i] = A[i]; gb.B[i] = src[i]; gb.C[i] = dst[i]; }
         if (!gemm(c, BrGemmArgs{k, k, k, k, k, k, 0, 0, 1.f, 0.f, B, 0}, gb)) return BR_ERR_HIP;

@@ -91,6 +91,15 @@ struct BrLowpArgs {
   int out_lo = 0;
   BrAdamArgs adam = {};
   int adam_transposed = 0;  // BR_EPI_ADAM: the product is G~^T; moments (row stride ldc) are indexed [col][row]
+  // Views into a larger plane set (sub-blocks that start at multiples of 256 rows and 64 k): the B
+  // operand, and the emitted planes, then take that set's padded row count and hi-to-lo distance.
+  int b_stride_rows = 0;
+  size_t b_plane_elems = 0;
+  int out_stride_rows = 0;
+  size_t out_plane_elems = 0;
+  // BR_EPI_F32 only: the transpose of the stored result also leaves as operand planes (hi, and lo when
+  // out_lo) through the pointer carried in the batch's S slot.
+  int emit_transposed = 0;
 };
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name);
 // hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src) into planes of

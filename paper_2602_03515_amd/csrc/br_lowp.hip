@@ -60,6 +60,9 @@ struct LowpKernArgs {
   int out_lo;            // also emit the lo plane
   BrAdamArgs adam;       // EPI_ADAM
   int adam_t;            // EPI_ADAM: the tile is G~^T (row = column of G~): the moments are indexed [col][row]
+  int b_stride;          // padded row count that addresses the B planes (Np, or a larger set's when B is a view into it)
+  int out_stride;        // the same for the emitted planes
+  int emit_t;            // EPI_F32: the transpose of the stored result also leaves as planes (pointer in the batch's S slot)
 };
 
 enum { EPI_F32 = 0, EPI_PLANES = 1, EPI_ADAM = 2 };
@@ -82,6 +85,41 @@ __device__ __forceinline__ int swz(int row) { return (row >> 3) & 1; }
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 // ... and one that waits for lgkmcnt(0) only (LDS reads returned).
 constexpr int waitcnt_lgkm0() { return 15 | (3 << 14) | (7 << 4) | (0 << 8); }
+
+// Emission of a result's transpose as operand planes.  An accumulator lane holds, for one plane row
+// (col), four groups of four consecutive k: k = kbase + 8 g + 4 lk + (0..3), g = 0..3, lk = lane / 32;
+// w[g] are those four values as two packed BF16 pairs.  Lanes l and l ^ 32 hold the two halves of every
+// aligned 8-k chunk (16 bytes of a plane row): the pair swaps halves, so that each lane stores whole
+// 16-byte chunks (lk = 0 those of g = 0 and 2, lk = 1 those of g = 1 and 3) instead of 8-byte halves.
+__device__ __forceinline__ void emit_chunks(uint16_t* __restrict__ P, const uint32_t (&w)[4][2], int kbase, int col, int stride,
+                                            int lk) {
+#pragma unroll
+  for (int pr = 0; pr < 2; ++pr) {
+    // my half of the chunk my partner stores goes over; its half of the chunk I store comes back
+    const uint32_t s0 = lk ? w[2 * pr][0] : w[2 * pr + 1][0];
+    const uint32_t s1 = lk ? w[2 * pr][1] : w[2 * pr + 1][1];
+    const uint32_t r0 = (uint32_t)__shfl_xor((int)s0, 32, 64);
+    const uint32_t r1 = (uint32_t)__shfl_xor((int)s1, 32, 64);
+    const uint32_t m0 = lk ? w[2 * pr + 1][0] : w[2 * pr][0];
+    const uint32_t m1 = lk ? w[2 * pr + 1][1] : w[2 * pr][1];
+    const int kc = kbase + 8 * (2 * pr + lk);
+    const size_t o = (((size_t)(kc >> 4) * stride + col) * 2 + (((kc >> 3) & 1) ^ swz(col))) * 8;
+    *reinterpret_cast<uint4*>(P + o) = lk ? make_uint4(r0, r1, m0, m1) : make_uint4(m0, m1, r0, r1);
+  }
+}
+
+__device__ __forceinline__ void pack_hi_lo(const float (&val)[4], uint32_t (&hi)[2], uint32_t (&lo)[2], bool want_lo) {
+  uint16_t h[4], l[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    h[e] = f32_to_bf16_rne(val[e]);
+    l[e] = want_lo ? f32_to_bf16_rne(val[e] - bf16_to_f32(h[e])) : (uint16_t)0;
+  }
+  hi[0] = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+  hi[1] = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+  lo[0] = (uint32_t)l[0] | ((uint32_t)l[1] << 16);
+  lo[1] = (uint32_t)l[2] | ((uint32_t)l[3] << 16);
+}
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -155,7 +193,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
 
   // uint4 strides: one k-block (16 k) of a plane = rows * 2, one plane = elements / 8.  Wave w
   // moves the w-th KB of each sub-tile: source and destination are both linear, 64 lanes x 16 bytes.
-  const size_t a_kb = (size_t)g.Mp * 2, b_kb = (size_t)g.Np * 2;
+  const size_t a_kb = (size_t)g.Mp * 2, b_kb = (size_t)g.b_stride * 2;
   const size_t a_pl = g.a_plane >> 3, b_pl = g.b_plane >> 3;
   const uint4* __restrict__ a_src = Ap + (size_t)m0 * 2 + wave * 64 + lane;
   const uint4* __restrict__ b_src = Bp + (size_t)n0 * 2 + wave * 64 + lane;
@@ -287,6 +325,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
         const int a = mi * FN + ni;
         if (a + 1 < FM * FN) fetch_old(a + 1, oldv[(a + 1) & 1]);
         const float* old = oldv[a & 1];
+        uint32_t wh[4][2], wl[4][2];  // emit_t: the stored values as packed BF16 pairs (hi, lo), one entry per group of four rows
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
           const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;
@@ -302,6 +341,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
               if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
             }
           }
+          if (g.emit_t) pack_hi_lo(val, wh[vg], wl[vg], g.out_lo != 0);
           if (off_diag && col < g.N) {
             // transposed copy of a symmetric result: this lane's four rows are four consecutive columns there
             float* dst = C + (size_t)col * (size_t)g.ldc + row0;
@@ -312,6 +352,16 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
               for (int e = 0; e < 4; ++e)
                 if (row0 + e < g.M) dst[e] = val[e];
             }
+          }
+        }
+        {
+          // the stored values once more, transposed, as operand planes (hi + lo when out_lo): what the next
+          // contraction of a chain of updates reads; exactly zero in the padding (the operands are zero there)
+          const int kbase = m0 + (wm * FM + mi) * 32;
+          if (g.emit_t && kbase < g.out_kp) {  // out_kp is a multiple of 64: all four groups or none
+            uint16_t* __restrict__ Pt = reinterpret_cast<uint16_t*>(batch.S[mat]);
+            emit_chunks(Pt, wh, kbase, col, g.out_stride, lk);
+            if (g.out_lo) emit_chunks(Pt + g.out_plane, wl, kbase, col, g.out_stride, lk);
           }
         }
       }
@@ -347,6 +397,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
         if (EPI == EPI_ADAM && a + 1 < FM * FN) fetch_moments(a + 1, moldv[(a + 1) & 1], soldv[(a + 1) & 1]);
         const float* mold = moldv[a & 1];
         const float* sold = soldv[a & 1];
+        uint32_t wh[4][2], wl[4][2];
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
           const int row0 = m0 + (wm * FM + mi) * 32 + 8 * vg + 4 * lk;  // plane k of val[0]
@@ -373,20 +424,13 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
               val[e] = x;
             }
           }
-          if (row0 < g.out_kp) {  // out_kp is a multiple of 64 and row0 of 4: all four or none
-            const size_t o = (((size_t)(row0 >> 4) * g.Np + col) * 2 + (((row0 >> 3) & 1) ^ swz(col))) * 8 + (row0 & 7);
-            uint16_t h[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16_rne(val[e]);
-            *reinterpret_cast<uint2*>(Pout + o) =
-                make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
-            if (g.out_lo) {
-              uint16_t l[4];
-#pragma unroll
-              for (int e = 0; e < 4; ++e) l[e] = f32_to_bf16_rne(val[e] - bf16_to_f32(h[e]));
-              *reinterpret_cast<uint2*>(Pout + g.out_plane + o) =
-                  make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
-            }
+          pack_hi_lo(val, wh[vg], wl[vg], g.out_lo != 0);
+        }
+        {
+          const int kbase = m0 + (wm * FM + mi) * 32;
+          if (kbase < g.out_kp) {  // out_kp is a multiple of 64: all four groups or none
+            emit_chunks(Pout, wh, kbase, col, g.out_stride, lk);
+            if (g.out_lo) emit_chunks(Pout + g.out_plane, wl, kbase, col, g.out_stride, lk);
           }
         }
       }
@@ -572,6 +616,25 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
   k.out_lo = a.out_lo ? 1 : 0;
   k.adam = a.adam;
   k.adam_t = a.adam_transposed ? 1 : 0;
+  // operand B, or the emitted planes, as a view into a larger plane set: same tiles, the set's strides
+  k.b_stride = k.Np;
+  if (a.b_stride_rows) {
+    if (a.b_stride_rows < k.Np || (a.b_stride_rows % TILE) || a.b_plane_elems == 0) return hipErrorInvalidValue;
+    k.b_stride = a.b_stride_rows;
+    k.b_plane = a.b_plane_elems;
+  }
+  k.out_stride = k.Np;
+  if (a.out_stride_rows) {
+    if (a.out_stride_rows < k.Np || (a.out_stride_rows % TILE) || a.out_plane_elems == 0) return hipErrorInvalidValue;
+    k.out_stride = a.out_stride_rows;
+    k.out_plane = a.out_plane_elems;
+  }
+  k.emit_t = a.emit_transposed ? 1 : 0;
+  if (k.emit_t) {
+    if (a.epilogue != BR_EPI_F32 || a.mirror) return hipErrorInvalidValue;
+    for (int i = 0; i < a.batch; ++i)
+      if (!b.S[i] || (reinterpret_cast<uintptr_t>(b.S[i]) & 15u)) return hipErrorInvalidValue;
+  }
   long long grid = (long long)k.total_tiles * a.batch;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   if (a.epilogue == BR_EPI_ADAM) launch_lowp<EPI_ADAM>(s, a.nprod, (int)grid, k, b);
