@@ -170,11 +170,14 @@ struct RefreshScratch {
 };
 
 // Doubling levels of the QR's block-reflector merges above the LDS-merged middle block: level l
-// joins two factors of width BR_QR_NBM << l.  One level (top blocks of 256 columns) is what is
-// used: a second one (512) makes the K = 512 trailing updates 15 % faster and was measured to give
-// all of it back in the wider blocks' own merges and applies, for orders 2560 and 6912 alike.
-constexpr int kQrLevels = 1;
-static_assert((BR_QR_NBM << kQrLevels) == BR_QR_NBT, "top block = middle block doubled kQrLevels times");
+// joins two factors of width BR_QR_NBM << l.  One level (top blocks of 256 columns) is what the
+// FP32 refresh uses: a second one (512) makes its K = 512 trailing updates 15 % faster and was
+// measured to give all of it back in the wider blocks' own merges and applies.  BR_MATH_BF16 takes
+// two: its top-block updates are bound by the bytes of C they move, and 512-column blocks halve
+// the number of passes over C.
+constexpr int kQrMaxLevels = 2;
+static_assert((BR_QR_NBM << kQrMaxLevels) == BR_QR_NBT, "widest top block = middle block doubled kQrMaxLevels times");
+inline int qr_levels(const br_hparams& hp) { return hp.math == BR_MATH_BF16 ? 2 : 1; }
 // floats before level l's pair of child factors in the Tl scratch
 inline size_t qr_level_offset(int l) {
   size_t off = 0;
@@ -200,7 +203,7 @@ RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   r.W = off; off += align256((size_t)k * BR_QR_NBT * 4);       // V^T C
   r.T = off; off += align256(blocks * BR_QR_NBT * BR_QR_NBT * 4);  // one factor per top block
   r.Tp = off; off += align256((size_t)(BR_QR_NBM / BR_QR_NB) * BR_QR_NB * BR_QR_NB * 4);  // panel factors of a middle block
-  r.Tl = off; off += align256(qr_level_offset(kQrLevels) * 4);  // child factors of every doubling level
+  r.Tl = off; off += align256(qr_level_offset(kQrMaxLevels) * 4);  // child factors of every doubling level
   r.G = off; off += align256((size_t)BR_QR_NBM * BR_QR_NBM * 4);  // Gram matrix of a middle block's reflectors
   r.X = off; off += align256((size_t)(BR_QR_NBT / 2) * (BR_QR_NBT / 2) * 4);  // V_0^T V_1
   r.Z = off; off += align256((size_t)(BR_QR_NBT / 2) * (BR_QR_NBT / 2) * 4);  // T_0 (V_0^T V_1)
@@ -872,8 +875,9 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 // contractions (the longer K is, the closer those run to the rate of a step contraction).
 static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs,
                      char* base, size_t stride, float* partial) {
-  const int NB = BR_QR_NB, NBM = BR_QR_NBM, NBT = BR_QR_NBT;
-  const int levels = kQrLevels;
+  const int NB = BR_QR_NB, NBM = BR_QR_NBM;
+  const int levels = qr_levels(c->hp);
+  const int NBT = NBM << levels;  // width of a top block
   const int ntop = (k + NBT - 1) / NBT;
   auto F = [&](int i, size_t off) { return reinterpret_cast<float*>(base + i * stride + off); };
   auto V = [&](int i) { return F(i, rs.V); };  // reflectors of the current top block, row stride NBT
@@ -896,6 +900,76 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     for (int i = 0; i < B; ++i) xp[i] = reinterpret_cast<int*>(F(i, rs.xch));
     if (!hip_ok(c, br_launch_zero_ints(s, xp, B, (int)br_qr_panel_xch_floats(k)), "exchange clear launch")) return false;
   }
+  // The update both phases share: C <- C - Yb (V^T C) for the rows x ncols blocks C (row stride k), with
+  // Yb = V T^T or V T already in Y.  BR_MATH_BF16 runs its two contractions on the BF16 matrix cores
+  // with hi + lo split operands and three partial products (16-bit mantissa inputs, FP32
+  // accumulation, C itself stays FP32): the bases of that mode come from statistics that are
+  // only BF16 accurate, and these two products are three quarters of the refresh.  The operand
+  // planes of C^T are not made again for every block: the whole matrix is split once per phase
+  // (planes of P^T, planes of Q^T), a block's C^T is a view into that set (blocks start at multiples
+  // of 256), and the update's epilogue rewrites the view from the values it stores.  The product
+  // V^T C leaves its kernel transposed and already split, as the operand of the second one.
+  const bool x3 = c->hp.math == BR_MATH_BF16;
+  LowpCtx lx{c, nullptr, LowpLayout{}, B, 3, nullptr};
+  lx.quiet = true;
+  const size_t qchunk = qr_plane_chunk(k);
+  const BrPlaneLayout Lk = br_plane_layout(k, k);
+  // hi plane of the view that starts at plane row row0 and at k0 inside the k x k plane set at `set`
+  auto view = [&](size_t set, int i, int row0, int k0) {
+    return reinterpret_cast<uint16_t*>(base + i * stride + set) + (((size_t)(k0 >> 4) * Lk.rows_p + row0) * 2) * 8;
+  };
+  auto split_whole = [&](float* const* Mx, size_t set) -> bool {  // planes of the transposed k x k matrices
+    const float* src[BR_MAXB];
+    uint16_t* dst[BR_MAXB];
+    for (int i = 0; i < B; ++i) { src[i] = Mx[i]; dst[i] = reinterpret_cast<uint16_t*>(base + i * stride + set); }
+    return lowp_split(lx, src, k, k, true, dst);
+  };
+  // Vb: the block's reflectors (rows x width, row stride NBT); Yb in Y (rows x width, row stride width);
+  // Cp: the blocks C (FP32); set/row0/k0: where their transposes live as planes; emit: keep those planes current
+  auto apply_block = [&](float* const* Vb, int width, float* const* Cp, int rows, int ncols, size_t set, int row0, int k0,
+                         bool emit) -> bool {
+    if (!x3 || width < 256) {
+      for (int i = 0; i < B; ++i) { gb.A[i] = Vb[i]; gb.B[i] = Cp[i]; gb.C[i] = W(i); }
+      if (!mm(BrGemmArgs{width, ncols, rows, NBT, k, ncols, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
+      for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Cp[i]; }
+      return mm(BrGemmArgs{rows, ncols, width, width, ncols, k, 0, 0, -1.f, 1.f, B, 0}, gb);
+    }
+    const float* src[BR_MAXB];
+    uint16_t *pv[BR_MAXB], *py[BR_MAXB], *pw[BR_MAXB];
+    for (int i = 0; i < B; ++i) {
+      char* q = base + i * stride + rs.qrp;
+      pv[i] = reinterpret_cast<uint16_t*>(q);
+      py[i] = reinterpret_cast<uint16_t*>(q + qchunk);
+      pw[i] = reinterpret_cast<uint16_t*>(q + 2 * qchunk);
+    }
+    for (int i = 0; i < B; ++i) src[i] = Vb[i];
+    if (!lowp_split(lx, src, rows, width, true, pv, NBT)) return false;     // planes of V^T   [width][rows]
+    for (int i = 0; i < B; ++i) src[i] = Y(i);
+    if (!lowp_split(lx, src, rows, width, false, py)) return false;         // planes of Yb    [rows][width]
+    BrLowpBatch lb;
+    std::memset(&lb, 0, sizeof(lb));
+    for (int i = 0; i < B; ++i) { lb.A[i] = pv[i]; lb.B[i] = view(set, i, row0, k0); lb.shadow[i] = pw[i]; }
+    BrLowpArgs wa{width, ncols, rows, 0, 1.f, 0.f, B, 0, 3};                // (V^T C)^T as planes [ncols][width]
+    wa.epilogue = BR_EPI_PLANES;
+    wa.out_lo = 1;
+    wa.b_stride_rows = (int)Lk.rows_p;
+    wa.b_plane_elems = Lk.elems;
+    if (!hip_ok(c, br_launch_gemm_lowp(s, wa, lb, nullptr), "qr bf16 product launch")) return false;
+    std::memset(&lb, 0, sizeof(lb));
+    for (int i = 0; i < B; ++i) {
+      lb.A[i] = py[i]; lb.B[i] = pw[i]; lb.C[i] = Cp[i];
+      if (emit) lb.S[i] = reinterpret_cast<float*>(view(set, i, row0, k0));  // the updated C^T, for the next block
+    }
+    BrLowpArgs ua{rows, ncols, width, k, -1.f, 1.f, B, 0, 3};
+    if (emit) {
+      ua.out_lo = 1;
+      ua.emit_transposed = 1;
+      ua.out_stride_rows = (int)Lk.rows_p;
+      ua.out_plane_elems = Lk.elems;
+    }
+    return hip_ok(c, br_launch_gemm_lowp(s, ua, lb, nullptr), "qr bf16 update launch");
+  };
+  if (x3 && k > 256 && !split_whole(P, rs.planesA)) return false;
   // Factorises columns [c0, c0 + ncols) of every P (ncols <= NBM << level) inside the top block that
   // starts at S0; the block's factor goes to slot `slot` of the level's scratch, or to the top block's
   // own place at the top level.
@@ -962,13 +1036,13 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     const int n0 = std::min(wc, ncols), n1 = ncols - n0;
     if (!factor(level - 1, c0, n0, S0, 0, tb)) return false;
     if (n1 > 0) {
-      // apply the first child to the second child's columns: Yt = V_0 T_0^T ; W = V_0^T C ; C <- C - Yt W
+      // apply the first child to the second child's columns: Yt = V_0 T_0^T ; C <- C - Yt (V_0^T C)
       for (int i = 0; i < B; ++i) { gb.A[i] = V0(i); gb.B[i] = Tl(i, level - 1, 0); gb.C[i] = Y(i); }
       if (!mm(BrGemmArgs{r0, wc, wc, NBT, wc, wc, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
-      for (int i = 0; i < B; ++i) { gb.A[i] = V0(i); gb.B[i] = P[i] + (size_t)c0 * k + c0 + wc; gb.C[i] = W(i); }
-      if (!mm(BrGemmArgs{wc, n1, r0, NBT, k, wc, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
-      for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = P[i] + (size_t)c0 * k + c0 + wc; }
-      if (!mm(BrGemmArgs{r0, n1, wc, wc, wc, k, 0, 0, -1.f, 1.f, B, 0}, gb)) return false;
+      float *vb[BR_MAXB], *cp[BR_MAXB];
+      for (int i = 0; i < B; ++i) { vb[i] = V0(i); cp[i] = P[i] + (size_t)c0 * k + c0 + wc; }
+      // (these columns are factorised next and never read as planes again: nothing to keep current)
+      if (!apply_block(vb, wc, cp, r0, n1, rs.planesA, c0 + wc, c0, false)) return false;
       if (!factor(level - 1, c0 + wc, n1, S0, 1, tb)) return false;
     }
     {  // merged factor: diagonal blocks, then the coupling block -T_0 (V_0^T V_1) T_1
@@ -987,73 +1061,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     }
     return true;
   };
-  // The update both phases share: C <- C - Yb (V^T C) for the rows x ncols blocks C (row stride k), with
-  // Yb = V T^T or V T already in Y.  BR_MATH_BF16 runs its two contractions on the BF16 matrix cores
-  // with hi + lo split operands and three partial products (16-bit mantissa inputs, FP32
-  // accumulation, C itself stays FP32): the bases of that mode come from statistics that are
-  // only BF16 accurate, and these two products are three quarters of the refresh.  The operand
-  // planes of C^T are not made again for every block: the whole matrix is split once per phase
-  // (planes of P^T, planes of Q^T), a block's C^T is a view into that set (blocks start at multiples
-  // of 256), and the update's epilogue rewrites the view from the values it stores.  The product
-  // V^T C leaves its kernel transposed and already split, as the operand of the second one.
-  const bool x3 = c->hp.math == BR_MATH_BF16;
-  LowpCtx lx{c, nullptr, LowpLayout{}, B, 3, nullptr};
-  lx.quiet = true;
-  const size_t qchunk = qr_plane_chunk(k);
-  const BrPlaneLayout Lk = br_plane_layout(k, k);
-  // hi plane of the view that starts at plane row row0 and at k0 inside the k x k plane set at `set`
-  auto view = [&](size_t set, int i, int row0, int k0) {
-    return reinterpret_cast<uint16_t*>(base + i * stride + set) + (((size_t)(k0 >> 4) * Lk.rows_p + row0) * 2) * 8;
-  };
-  auto split_whole = [&](float* const* Mx, size_t set) -> bool {  // planes of the transposed k x k matrices
-    const float* src[BR_MAXB];
-    uint16_t* dst[BR_MAXB];
-    for (int i = 0; i < B; ++i) { src[i] = Mx[i]; dst[i] = reinterpret_cast<uint16_t*>(base + i * stride + set); }
-    return lowp_split(lx, src, k, k, true, dst);
-  };
-  // Cp: the blocks (FP32); set/row0/k0: where their transposes live as planes
-  auto apply_top = [&](float* const* Cp, int rows, int ncols, size_t set, int row0, int k0) -> bool {
-    if (!x3) {
-      for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Cp[i]; gb.C[i] = W(i); }
-      if (!mm(BrGemmArgs{NBT, ncols, rows, NBT, k, ncols, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
-      for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Cp[i]; }
-      return mm(BrGemmArgs{rows, ncols, NBT, NBT, ncols, k, 0, 0, -1.f, 1.f, B, 0}, gb);
-    }
-    const float* src[BR_MAXB];
-    uint16_t *pv[BR_MAXB], *py[BR_MAXB], *pw[BR_MAXB];
-    for (int i = 0; i < B; ++i) {
-      char* q = base + i * stride + rs.qrp;
-      pv[i] = reinterpret_cast<uint16_t*>(q);
-      py[i] = reinterpret_cast<uint16_t*>(q + qchunk);
-      pw[i] = reinterpret_cast<uint16_t*>(q + 2 * qchunk);
-    }
-    for (int i = 0; i < B; ++i) src[i] = V(i);
-    if (!lowp_split(lx, src, rows, NBT, true, pv)) return false;            // planes of V^T   [NBT][rows]
-    for (int i = 0; i < B; ++i) src[i] = Y(i);
-    if (!lowp_split(lx, src, rows, NBT, false, py)) return false;           // planes of Yb    [rows][NBT]
-    BrLowpBatch lb;
-    std::memset(&lb, 0, sizeof(lb));
-    for (int i = 0; i < B; ++i) { lb.A[i] = pv[i]; lb.B[i] = view(set, i, row0, k0); lb.shadow[i] = pw[i]; }
-    BrLowpArgs wa{NBT, ncols, rows, 0, 1.f, 0.f, B, 0, 3};                  // (V^T C)^T as planes [ncols][NBT]
-    wa.epilogue = BR_EPI_PLANES;
-    wa.out_lo = 1;
-    wa.b_stride_rows = (int)Lk.rows_p;
-    wa.b_plane_elems = Lk.elems;
-    if (!hip_ok(c, br_launch_gemm_lowp(s, wa, lb, nullptr), "qr bf16 product launch")) return false;
-    std::memset(&lb, 0, sizeof(lb));
-    for (int i = 0; i < B; ++i) {
-      lb.A[i] = py[i]; lb.B[i] = pw[i]; lb.C[i] = Cp[i];
-      lb.S[i] = reinterpret_cast<float*>(view(set, i, row0, k0));           // the updated C^T, for the next block
-    }
-    BrLowpArgs ua{rows, ncols, NBT, k, -1.f, 1.f, B, 0, 3};
-    ua.out_lo = 1;
-    ua.emit_transposed = 1;
-    ua.out_stride_rows = (int)Lk.rows_p;
-    ua.out_plane_elems = Lk.elems;
-    return hip_ok(c, br_launch_gemm_lowp(s, ua, lb, nullptr), "qr bf16 update launch");
-  };
-  if (x3 && ntop > 1 && !split_whole(P, rs.planesA)) return false;
-  float* cblk[BR_MAXB];
+  float *cblk[BR_MAXB], *vblk[BR_MAXB];
   for (int tb = 0; tb < ntop; ++tb) {
     const int S0 = tb * NBT;
     const int ns = std::min(NBT, k - S0);  // columns of this top block
@@ -1069,8 +1077,8 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     // Yt = V T^T ; C <- C - Yt (V^T C)   on the trailing columns
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Ttop(i, tb); gb.C[i] = Y(i); }
     if (!mm(BrGemmArgs{rows, NBT, NBT, NBT, NBT, NBT, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
-    for (int i = 0; i < B; ++i) cblk[i] = P[i] + (size_t)S0 * k + S0 + ns;
-    if (!apply_top(cblk, rows, nt, rs.planesA, S0 + ns, S0)) return false;
+    for (int i = 0; i < B; ++i) { cblk[i] = P[i] + (size_t)S0 * k + S0 + ns; vblk[i] = V(i); }
+    if (!apply_block(vblk, NBT, cblk, rows, nt, rs.planesA, S0 + ns, S0, true)) return false;
   }
   // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before top block tb is
   // applied, Q differs from the identity only in Q[S1:, S1:] with S1 the next block's offset,
@@ -1093,8 +1101,8 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     // Y = V T ; Qsub <- Qsub - Y (V^T Qsub),  Qsub = Q[S0:, S0:]
     for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Ttop(i, tb); gb.C[i] = Y(i); }
     if (!mm(BrGemmArgs{rows, NBT, NBT, NBT, NBT, NBT, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
-    for (int i = 0; i < B; ++i) cblk[i] = Q[i] + (size_t)S0 * k + S0;
-    if (!apply_top(cblk, rows, rows, rs.planesB, S0, S0)) return false;
+    for (int i = 0; i < B; ++i) { cblk[i] = Q[i] + (size_t)S0 * k + S0; vblk[i] = V(i); }
+    if (!apply_block(vblk, NBT, cblk, rows, rows, rs.planesB, S0, S0, true)) return false;
   }
   return true;
 }

@@ -158,7 +158,7 @@ hipError_t br_launch_bf16_to_f32(hipStream_t s, const uint16_t* src, float* dst,
 // ---- QR ---------------------------------------------------------------------------------
 #define BR_QR_NB 32    // inner panel width of the blocked Householder factorisation
 #define BR_QR_NBM 128  // middle block: four panels, merged into one block reflector inside LDS
-#define BR_QR_NBT 256  // top block: middle blocks merged pairwise; one trailing-matrix update per top block (K = 256 contractions)
+#define BR_QR_NBT 512  // widest top block: middle blocks merged pairwise (128 -> 256 -> 512); one trailing-matrix update per top block
 
 struct BrQrPanelBatch {
   float* A[BR_MAXB];     // top-left corner of the panel inside the matrix being factorised

@@ -2,7 +2,7 @@
 // followed by QR decomposition"; Algorithm 2 lines 3 and 6).
 //
 // The factorisation is blocked recursively (panels of BR_QR_NB = 32 columns, middle blocks of
-// BR_QR_NBM = 128 merged in LDS, then merged pairwise up to top blocks of BR_QR_NBT = 256) in
+// BR_QR_NBM = 128 merged in LDS, then merged pairwise up to top blocks of 256 or BR_QR_NBT = 512) in
 // compact-WY form:
 //   H_1 H_2 ... H_nb = I - V T V^T,  V unit lower trapezoidal, T upper triangular.
 // This file holds the panel kernel; the trailing-matrix and Q-forming updates are GEMMs issued
