@@ -385,6 +385,51 @@ def test_bf16_math_mode_meets_the_2e2_bar(harness, geometry):
     print("bf16 worst:", {k: f"{v:.2e}" for k, v in worst.items()})
 
 
+def _lapack_qr(P):
+    q, r = np.linalg.qr(P)
+    d = np.where(np.diag(r) < 0, -1.0, 1.0)
+    return q * d[None, :], r * d[:, None]
+
+
+@pytest.mark.parametrize("math", [0, 1, 2])
+def test_refresh_alone_on_injected_statistics_several_top_blocks(harness, math):
+    """The refresh by itself at orders with three and two ragged top blocks of the QR (1100 and 600
+    columns): well-conditioned statistics (Wishart, aspect 3, condition number 14) are written into
+    the state, br_refresh_basis runs from Q = I and once more from its own result, and both bases
+    are compared entry by entry with the oracle's (float64; LAPACK's QR with the same sign
+    convention, pinned against the oracle's own Householder loop in the CPU tests, which would take
+    a minute here).  Injecting the statistics keeps the comparison about the refresh: in the BF16
+    math mode the statistics themselves are only BF16 accurate, and a young second moment turns
+    that into O(1) differences of single update entries on a matrix this large.
+    Bars: FP32 refresh (F32, BF16X3) 1e-5, measured 1.2e-6; BR_MATH_BF16, whose L Q product and
+    large QR updates take 16-bit mantissa inputs, 1e-4, measured 1.5e-5."""
+    m, n = 1100, 600
+    rng = np.random.default_rng(77)
+
+    def wishart(k):
+        A = rng.standard_normal((k, 3 * k))
+        return (A @ A.T / (3 * k)).astype(np.float32)
+
+    L32, R32 = wishart(m), wishart(n)
+    W0 = rng.standard_normal((m, n)).astype(np.float32)
+    sb = harness.SideBySide([W0], freq=0, lr=1e-3, math=math)
+    B, st = sb.B, sb.states[0]
+    sb.opt.state(0, B.BR_STATE_L).copy_(torch.from_numpy(L32))
+    sb.opt.state(0, B.BR_STATE_R).copy_(torch.from_numpy(R32))
+    B.br_notify_state_written(sb.opt.ctx)
+    st.L, st.R = L32.astype(np.float64), R32.astype(np.float64)
+    bar, orth = (1e-4, 5e-5) if math == 1 else (1e-5, 1e-5)
+    for rep in range(2):
+        B.br_refresh_basis(sb.opt.ctx)
+        torch.cuda.synchronize()
+        oc.refresh(st, sb.hp, _lapack_qr)
+        for kind, Q in ((B.BR_STATE_QL, st.QL), (B.BR_STATE_QR, st.QR)):
+            q = harness.to_np(sb.opt.state(0, kind))
+            assert orthogonality_defect(q) < orth
+            e = rel_err(q, Q)
+            assert e <= bar, f"refresh {rep}, state {kind}: basis rel err {e:.3e} > {bar:.1e}"
+
+
 @pytest.mark.parametrize("math", [1, 2])
 def test_bf16_modes_injected_basis_midway(harness, math):
     """BF16 math modes keep operand planes of the bases between steps; overwriting the bases
