@@ -409,7 +409,7 @@ bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp,
 
 // Operand planes of this step's gradients in both orientations (kept until br_step), and a2 in the
 // BF16 modes for one chunk: L <- b L + (1-b) G G^T, R <- b R + (1-b) G^T G.
-bool lowp_stats(const LowpCtx& x, const float* const* G32, size_t off, bool with_stats) {
+bool lowp_stats(const LowpCtx& x, const float* const* G32, size_t off, bool with_stats, bool planes_ready = false) {
   const Group& g = *x.g;
   const br_hparams& hp = x.c->hp;
   const int m = (int)g.m, n = (int)g.n;
@@ -419,7 +419,7 @@ bool lowp_stats(const LowpCtx& x, const float* const* G32, size_t off, bool with
     gp[i] = x.c->mats[g.idx[off + i]].gp;
     gtp[i] = x.c->mats[g.idx[off + i]].gtp;
   }
-  if (!lowp_split(x, G32, m, n, false, gp) || !lowp_split(x, G32, m, n, true, gtp)) return false;
+  if (!planes_ready && (!lowp_split(x, G32, m, n, false, gp) || !lowp_split(x, G32, m, n, true, gtp))) return false;
   if (!with_stats) return true;
   if (g.rot_l) {
     for (int i = 0; i < x.B; ++i) out[i] = x.c->mats[g.idx[off + i]].L;
@@ -833,6 +833,23 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
         pb.out0[i] = m.M;
         pb.out1[i] = !need_g32 ? nullptr : (lowp ? lx.slot32(i, LS_G32) : scratch_buf(c, nbuf, mn, i, nbuf - 1));
         g32[i] = need_g32 ? reinterpret_cast<const float*>(pb.out1[i]) : reinterpret_cast<const float*>(grads[g.idx[off + i]]);
+      }
+      if (lowp && g.gdt == BR_F32) {
+        // BF16 math modes, FP32 gradients: the first moment and both plane sets of G from one read of G
+        float* Mp[BR_MAXB];
+        uint16_t *gp[BR_MAXB], *gtp[BR_MAXB];
+        for (int i = 0; i < B; ++i) {
+          const MatState& m = c->mats[g.idx[off + i]];
+          Mp[i] = m.M; gp[i] = m.gp; gtp[i] = m.gtp;
+        }
+        const int lo = hp.math == BR_MATH_BF16X3 ? 1 : 0;
+        {
+          Timed tm(c, "br_ingest_planes", 2.0 * count * B, (double)count * B * (12.0 + (lo ? 8.0 : 4.0)));
+          if (!hip_ok(c, br_launch_ingest_planes(c->stream, g32, Mp, gp, gtp, B, (int)g.m, (int)g.n, hp.beta1, lo),
+                      "ingest launch")) return BR_ERR_HIP;
+        }
+        if (!lowp_stats(lx, g32, off, hp.source == BR_SRC_SECOND, true)) return BR_ERR_HIP;
+        continue;
       }
       {
         double bytes = (double)count * B * (8.0 + (g.gdt == BR_BF16 ? 2.0 : 4.0) + (need_g32 ? 4.0 : 0.0));

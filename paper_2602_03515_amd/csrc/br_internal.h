@@ -107,6 +107,10 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
 // br_plane_layout(C, R).  The padding is written too (zeros).
 hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
                                   int ld_src, int transpose, int want_lo);
+// The first moment and both plane sets of the R x C gradients G[i] (contiguous) in one pass:
+// M <- beta1 M + (1 - beta1) G, planes of G into P (br_plane_layout(R, C)), planes of G^T into PT.
+hipError_t br_launch_ingest_planes(hipStream_t s, const float* const* G, float* const* M, uint16_t* const* P, uint16_t* const* PT,
+                                   int batch, int R, int Ccols, float beta1, int want_lo);
 
 // ---- elementwise ----------------------------------------------------------------------
 struct BrPtrBatch {

@@ -545,6 +545,103 @@ __global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int
   }
 }
 
+
+// First moment and both plane sets of a gradient in one pass (Algorithm 1 line 4, and the operands
+// of Algorithm 2 lines 2, 5 and Algorithm 1 line 8): M <- beta1 M + (1 - beta1) G, planes of G and
+// planes of G^T, the gradient read once.  One 64 x 64 tile per workgroup, transposed through LDS;
+// tiles past the matrix write the planes' zero padding.
+struct IngestArgs {
+  const float* G[BR_MAXB];
+  float* M[BR_MAXB];
+  uint16_t* P[BR_MAXB];   // planes of G    (rows x cols)
+  uint16_t* PT[BR_MAXB];  // planes of G^T  (cols x rows)
+};
+
+__global__ __launch_bounds__(256) void br_ingest_planes(IngestArgs a, int R, int Cc, float beta1, int RpP, int KpP, size_t planeP,
+                                                        int RpT, int KpT, size_t planeT, int tiles_c, int want_lo) {
+  __shared__ float tile[64][65];
+  const float* __restrict__ G = a.G[blockIdx.y];
+  float* __restrict__ M = a.M[blockIdx.y];
+  uint16_t* __restrict__ P = a.P[blockIdx.y];
+  uint16_t* __restrict__ PT = a.PT[blockIdx.y];
+  const int tr = blockIdx.x / tiles_c, tc = blockIdx.x - tr * tiles_c;
+  const int r0 = tr * 64, c0 = tc * 64;
+  const int tid = threadIdx.x;
+  const float w = 1.0f - beta1;
+  const bool vec = ((Cc & 3) == 0) && (((reinterpret_cast<uintptr_t>(G) | reinterpret_cast<uintptr_t>(M)) & 15u) == 0);
+  if (vec && r0 + 64 <= R && c0 + 64 <= Cc) {
+    float4 g[4], m[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rr = i * 16 + (tid >> 4), c4 = (tid & 15) * 4;
+      const size_t o = (size_t)(r0 + rr) * Cc + c0 + c4;
+      g[i] = *reinterpret_cast<const float4*>(G + o);
+      m[i] = *reinterpret_cast<const float4*>(M + o);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rr = i * 16 + (tid >> 4), c4 = (tid & 15) * 4;
+      const size_t o = (size_t)(r0 + rr) * Cc + c0 + c4;
+      m[i].x = beta1 * m[i].x + w * g[i].x;
+      m[i].y = beta1 * m[i].y + w * g[i].y;
+      m[i].z = beta1 * m[i].z + w * g[i].z;
+      m[i].w = beta1 * m[i].w + w * g[i].w;
+      *reinterpret_cast<float4*>(M + o) = m[i];
+      tile[rr][c4 + 0] = g[i].x;
+      tile[rr][c4 + 1] = g[i].y;
+      tile[rr][c4 + 2] = g[i].z;
+      tile[rr][c4 + 3] = g[i].w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int rr = i * 4 + (tid >> 6), cc = tid & 63;
+      const int r = r0 + rr, c = c0 + cc;
+      float gv = 0.f;
+      if (r < R && c < Cc) {
+        const size_t o = (size_t)r * Cc + c;
+        gv = G[o];
+        M[o] = beta1 * M[o] + w * gv;
+      }
+      tile[rr][cc] = gv;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    // planes of G: plane row = source row, 8 consecutive source columns per chunk
+    {
+      const int rr = (tid >> 3) + 32 * i, ch = tid & 7;
+      const int prow = r0 + rr, k0 = c0 + ch * 8;
+      if (k0 < KpP) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = tile[rr][ch * 8 + e];
+        uint4 hi4, lo4;
+        split8(x, &hi4, &lo4);
+        const size_t o = (((size_t)(k0 >> 4) * RpP + prow) * 2 + (((k0 >> 3) & 1) ^ swz(prow))) * 8;
+        *reinterpret_cast<uint4*>(P + o) = hi4;
+        if (want_lo) *reinterpret_cast<uint4*>(P + planeP + o) = lo4;
+      }
+    }
+    // planes of G^T: plane row = source column, 8 consecutive source rows per chunk
+    {
+      const int cc = (tid >> 3) + 32 * i, rch = tid & 7;
+      const int prow = c0 + cc, k0 = r0 + rch * 8;
+      if (k0 < KpT) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = tile[rch * 8 + e][cc];
+        uint4 hi4, lo4;
+        split8(x, &hi4, &lo4);
+        const size_t o = (((size_t)(k0 >> 4) * RpT + prow) * 2 + (((k0 >> 3) & 1) ^ swz(prow))) * 8;
+        *reinterpret_cast<uint4*>(PT + o) = hi4;
+        if (want_lo) *reinterpret_cast<uint4*>(PT + planeT + o) = lo4;
+      }
+    }
+  }
+}
+
 }  // namespace br
 
 hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
@@ -570,6 +667,26 @@ hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16
     hipLaunchKernelGGL(br::br_split_planes_t, dim3((int)tiles, batch), dim3(256), 0, s, a, R, Ccols, ld_src, (int)pl.rows_p,
                        (int)pl.k_p, pl.elems, want_lo);
   }
+  return hipGetLastError();
+}
+
+hipError_t br_launch_ingest_planes(hipStream_t s, const float* const* G, float* const* M, uint16_t* const* P, uint16_t* const* PT,
+                                   int batch, int R, int Ccols, float beta1, int want_lo) {
+  if (batch <= 0 || R <= 0 || Ccols <= 0) return hipSuccess;
+  if (batch > BR_MAXB) return hipErrorInvalidValue;
+  br::IngestArgs a;
+  for (int i = 0; i < BR_MAXB; ++i) {
+    a.G[i] = (i < batch) ? G[i] : nullptr;
+    a.M[i] = (i < batch) ? M[i] : nullptr;
+    a.P[i] = (i < batch) ? P[i] : nullptr;
+    a.PT[i] = (i < batch) ? PT[i] : nullptr;
+  }
+  const BrPlaneLayout lp = br_plane_layout(R, Ccols), lt = br_plane_layout(Ccols, R);
+  if (lp.rows_p > 0x7fffffffLL || lt.rows_p > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int64_t tiles_r = lp.rows_p >> 6, tiles_c = lt.rows_p >> 6;
+  if (tiles_r * tiles_c > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(br::br_ingest_planes, dim3((int)(tiles_r * tiles_c), batch), dim3(256), 0, s, a, R, Ccols, beta1,
+                     (int)lp.rows_p, (int)lp.k_p, lp.elems, (int)lt.rows_p, (int)lt.k_p, lt.elems, (int)tiles_c, want_lo);
   return hipGetLastError();
 }
 
