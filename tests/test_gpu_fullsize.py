@@ -51,8 +51,9 @@ def _young_moment_floor(hp, G):
 
 
 def _follow(h, opt, B, params, grads_per_step, sample, hp, freq, lr, w0_host, check_q=True, tol=TOL,
-            young_moment=False):
-    """Drive all matrices on the GPU; the oracle follows the matrices in `sample`."""
+            young_moment=False, ortho=1e-5, refs=None):
+    """Drive all matrices on the GPU; the oracle follows the matrices in `sample` (its final weights
+    are left in `refs` when a dict is passed)."""
     states = {i: oc.MatrixState(w0_host[i].shape[0], w0_host[i].shape[1], hp) for i in sample}
     W_ref = {i: w0_host[i].astype(np.float64) for i in sample}
     for t, grads in enumerate(grads_per_step, 1):
@@ -89,7 +90,9 @@ def _follow(h, opt, B, params, grads_per_step, sample, hp, freq, lr, w0_host, ch
             if Q is not None:
                 q = opt.state(i, kind).double()
                 defect = float((q.T @ q - torch.eye(q.shape[0], device=q.device, dtype=q.dtype)).abs().max())
-                assert defect < 1e-5, f"matrix {i}: ||Q^T Q - I||_max = {defect:.2e}"
+                assert defect < ortho, f"matrix {i}: ||Q^T Q - I||_max = {defect:.2e}"
+    if refs is not None:
+        refs.update(W_ref)
     return worst
 
 
@@ -153,6 +156,51 @@ def test_llama_layer_2048_bf16_config(h):
         for kind in (B.BR_STATE_QL, B.BR_STATE_QR):
             q = opt.state(i, kind).double()
             assert float((q.T @ q - torch.eye(q.shape[0], device=q.device, dtype=q.dtype)).abs().max()) < 1e-5
+
+
+def _stage_layer(h, math):
+    import bench
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+    dev = torch.device("cuda:0")
+    shapes = list(synth.STAGE_3B_LAYER)
+    params, ring = bench.make_inputs(shapes, bench.TAU + 1, seed=2, device=dev)
+    sample = [0, 4, 6]
+    w0 = {i: params[i].cpu().numpy().copy() for i in sample}
+    hp = oc.Hyper().rounded_to_f32()
+    lr = float(np.float32(1e-3))
+    opt = BasisRotationAdam(params, freq=4, lr=lr, math=math)
+    steps = [ring[t % (bench.TAU + 1)] for t in range(1, 6)]
+    return B, opt, params, steps, sample, hp, lr, w0
+
+
+def test_stage_layer_bf16x3_mode_sampled_matrices(h):
+    """BR_MATH_BF16X3 at the stage's real shapes (one layer: 2560 x 2560, 2560 x 6912, 6912 x 2560), refresh at
+    step 4 of 5: the hi + lo split keeps the FP32 path's 1e-4 bar at full size too (weights, moments,
+    statistics and the bases entry by entry)."""
+    B, opt, params, steps, sample, hp, lr, w0 = _stage_layer(h, 2)
+    worst = _follow(h, opt, B, params, steps, sample, hp, 4, lr, w0)
+    print("stage layer BF16X3 worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
+
+
+def test_stage_layer_bf16_mode_sampled_matrices(h):
+    """BR_MATH_BF16 at the same shapes.  Plain BF16 inputs put an error of about 2^-9 of the typical entry on
+    every product of the chain; on matrices of 6.5 to 17.7 million entries the LARGEST such error (what the
+    max-norm bar measures) sits four to five standard deviations out, and with the second moment only four
+    steps old it reaches 2.7e-2 to 3.1e-2 of the largest update entry at the first rotated step: above the 2e-2
+    that the same mode keeps on the matrices of up to 0.4 million entries of the small-size suite.  This test
+    therefore holds the maximum to 5e-2 and the root-mean-square error of the cumulative update to 5e-3
+    (measured 2.5e-3)."""
+    B, opt, params, steps, sample, hp, lr, w0 = _stage_layer(h, 1)
+    refs = {}
+    worst = _follow(h, opt, B, params, steps, sample, hp, 4, lr, w0, check_q=False, tol=5e-2, ortho=5e-5, refs=refs)
+    print("stage layer BF16 worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
+    for i in sample:
+        got = h.to_np(params[i]).astype(np.float64)
+        du_ref = refs[i] - w0[i]
+        rms = float(np.sqrt(np.mean((got - refs[i]) ** 2)) / np.sqrt(np.mean(du_ref ** 2)))
+        print(f"matrix {i}: rms error of the cumulative update {rms:.2e}")
+        assert rms <= 5e-3
 
 
 BF16_MODE_ORTHOGONALITY = 5e-5
