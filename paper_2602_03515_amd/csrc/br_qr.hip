@@ -63,7 +63,7 @@ __device__ __forceinline__ float pick4(float4 a, int q) {
   return r;
 }
 
-// Sum acc[] over all threads that own the same columns; result for column c in comb[c].
+// Sum of v over the eight row groups of a wave (the lanes that own the same columns).
 __device__ __forceinline__ float group_sum(float v) {
   v += __shfl_xor(v, 8, 64);
   v += __shfl_xor(v, 16, 64);
@@ -71,9 +71,9 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
-// The value for column tid is also returned to threads tid < 32; comb[] is only synchronised
-// when `publish` is set (the cluster exchange reads it from other threads).
-__device__ __forceinline__ float panel_reduce(float4 acc, float (*red)[32], float* comb, int tid, bool publish) {
+// Sum of acc over all threads of the workgroup that own the same columns; the sum for column tid
+// is returned to threads tid < 32 (other threads get zero).  One barrier.
+__device__ __forceinline__ float panel_reduce(float4 acc, float (*red)[32], int tid) {
   const int lane = tid & 63, wave = tid >> 6, sub = tid & 7;
   acc.x = group_sum(acc.x);
   acc.y = group_sum(acc.y);
@@ -90,9 +90,7 @@ __device__ __forceinline__ float panel_reduce(float4 acc, float (*red)[32], floa
   if (tid < 32) {
 #pragma unroll
     for (int w = 0; w < QR_WAVES; ++w) s += red[w][tid];
-    comb[tid] = s;
   }
-  if (publish) __syncthreads();
   return s;
 }
 
@@ -208,7 +206,6 @@ template <int U>
 __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int rows, int nb, int lda, int vec_ok,
                                                           int ldv, int pre_rows, int slab, BrQrClusterBatch cb) {
   __shared__ float red[QR_WAVES][32];
-  __shared__ float comb[32];
   __shared__ __attribute__((aligned(16))) float dvec[32];
   __shared__ __attribute__((aligned(16))) float pivrow[2][32];
   __shared__ float Sl[32][33];  // Sl[l][j] = v_l^T v_j for l < j: the strict upper triangle of V^T V
@@ -268,7 +265,7 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
     }
   }
   {
-    float sum = panel_reduce(acc, red, comb, tid, false);
+    float sum = panel_reduce(acc, red, tid);
     if (cl.nw > 1) sum = cluster_combine(cl, 0, sum, pivrow[0], tid);
     if (tid < 32) dvec[tid] = sum;
     __syncthreads();
@@ -324,7 +321,7 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
     {
       // Column sums of this pass: for c > j the dot products of the next pass, for c < j the entries
       // v_c^T v_j of the Gram matrix of the reflectors.
-      float sum = panel_reduce(acc, red, comb, tid, false);
+      float sum = panel_reduce(acc, red, tid);
       if (cl.nw > 1) sum = cluster_combine(cl, j + 1, sum, pivrow[cur ^ 1], tid);
       if (tid < 32) {
         if (tid > j) dvec[tid] = sum;
