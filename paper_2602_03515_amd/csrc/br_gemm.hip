@@ -246,6 +246,9 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
       const int cur = (kt - kt0) & 1;
       la.fetch_fast();
       lb.fetch_fast();
+      // keep the next tile's global loads HERE, a whole tile of matrix instructions ahead of the
+      // stores into LDS that wait for them (the scheduler otherwise sinks them next to those stores)
+      __builtin_amdgcn_sched_barrier(0);
       mfma_tile(cur);
       la.stash(As[cur ^ 1], tid);
       lb.stash(Bs[cur ^ 1], tid);
