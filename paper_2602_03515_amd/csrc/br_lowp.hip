@@ -129,11 +129,13 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 namespace br {
 
 // EPI selects what happens to the 256 x 256 tile of alpha A B^T:
-//   EPI_F32     C = tile + beta C in FP32 (optionally mirrored, optional BF16 image);
+//   EPI_F32     C = tile + beta C in FP32 (optionally mirrored, optional BF16 image; with emit_t the
+//               transpose of what was stored also leaves as operand planes, as under EPI_PLANES);
 //   EPI_PLANES  nothing is stored in FP32: the TRANSPOSE of the result is written as BF16 operand
 //               planes (hi, and lo when out_lo) ready to be the A or B operand of the next
 //               contraction.  An accumulator lane holds 4 consecutive M indices of one N index,
-//               i.e. 4 consecutive k of one plane row: an 8-byte store, two lanes per 16-byte chunk;
+//               i.e. 4 consecutive k of one plane row: half of a 16-byte chunk, whose other half sits in
+//               lane + 32; the two swap halves and each stores whole chunks (emit_chunks);
 //   EPI_ADAM    the tile is a rotated gradient G~: Adam's moments are advanced in place
 //               (S~ <- b2 S~ + (1-b2) G~ G~, and M~ <- b1 M~ + (1-b1) G~ when adam.update_mrot;
 //               Algorithm 1 lines 9-11) and X = M~ / sqrt(S~ + eps) leaves as planes like above.
