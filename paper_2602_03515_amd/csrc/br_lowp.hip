@@ -54,6 +54,7 @@ struct LowpKernArgs {
   size_t a_plane, b_plane;  // distance from the hi plane to the lo plane, in elements
   float alpha, beta;
   int tiles_m, tiles_n, total_tiles, mirror;
+  int all_tiles;         // total_tiles x matrices of the launch: the length of the tile sequence the grid walks
   // plane-emitting epilogues: the result's transpose as operand planes (rows = N index, k = M index)
   int out_kp;            // padded k extent of the emitted planes (M to a multiple of 64)
   size_t out_plane;      // elements from their hi plane to their lo plane
@@ -152,53 +153,50 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
   static_assert(U % 2 == 0, "operand double buffering assumes an even number of groups per stage");
   __shared__ uint4 lds[S * STAGE_U4];
 
-  int bid = blockIdx.x;
-  const int per = gridDim.x / NUM_XCD;
-  if (bid < per * NUM_XCD) bid = (bid % NUM_XCD) * per + bid / NUM_XCD;
-  const int mat = bid / g.total_tiles;
-  const int t = bid - mat * g.total_tiles;
-  int tm, tn;
-  if (g.mirror) {
-    int r = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
-    while ((r + 1) * (r + 2) / 2 <= t) ++r;
-    while (r * (r + 1) / 2 > t) --r;
-    tm = r;
-    tn = t - r * (r + 1) / 2;
-  } else {
-    const int group = GROUP_M * g.tiles_n;
-    const int grp = t / group;
-    const int first_m = grp * GROUP_M;
-    const int gm = min(GROUP_M, g.tiles_m - first_m);
-    const int r = t - grp * group;
-    tn = r / gm;
-    tm = first_m + (r - tn * gm);
-  }
-  const uint4* __restrict__ Ap = reinterpret_cast<const uint4*>(batch.A[mat]);
-  const uint4* __restrict__ Bp = reinterpret_cast<const uint4*>(batch.B[mat]);
-  float* __restrict__ C = batch.C[mat];
-  uint16_t* __restrict__ shadow = batch.shadow[mat];
-
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
-  const int m0 = tm * TILE, n0 = tn * TILE;
   const int lk = lane >> 5, li = lane & 31;
 
+  // Position v of the launch's tile sequence -> (matrix, tile row, tile column).  Positions that
+  // are congruent modulo the number of XCDs (the workgroups of one XCD, and all the positions a
+  // workgroup visits: the grid is a multiple of that number whenever it visits more than one) cover
+  // one contiguous run of tiles, so an XCD's L2 sees neighbouring tiles at the same time.
+  const int per = g.all_tiles / NUM_XCD;
+  auto decode = [&](int v, int& mat, int& tm, int& tn) {
+    if (v < per * NUM_XCD) v = (v % NUM_XCD) * per + v / NUM_XCD;
+    mat = v / g.total_tiles;
+    const int t = v - mat * g.total_tiles;
+    if (g.mirror) {
+      int r = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+      while ((r + 1) * (r + 2) / 2 <= t) ++r;
+      while (r * (r + 1) / 2 > t) --r;
+      tm = r;
+      tn = t - r * (r + 1) / 2;
+    } else {
+      const int group = GROUP_M * g.tiles_n;
+      const int grp = t / group;
+      const int first_m = grp * GROUP_M;
+      const int gm = min(GROUP_M, g.tiles_m - first_m);
+      const int r = t - grp * group;
+      tn = r / gm;
+      tm = first_m + (r - tn * gm);
+    }
+  };
+
   floatx16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // uint4 strides: one k-block (16 k) of a plane = rows * 2, one plane = elements / 8.  Wave w
   // moves the w-th KB of each sub-tile: source and destination are both linear, 64 lanes x 16 bytes.
   const size_t a_kb = (size_t)g.Mp * 2, b_kb = (size_t)g.b_stride * 2;
   const size_t a_pl = g.a_plane >> 3, b_pl = g.b_plane >> 3;
-  const uint4* __restrict__ a_src = Ap + (size_t)m0 * 2 + wave * 64 + lane;
-  const uint4* __restrict__ b_src = Bp + (size_t)n0 * 2 + wave * 64 + lane;
+  const uint4* a_src = nullptr;
+  const uint4* b_src = nullptr;
+  auto aim = [&](int mat, int tm, int tn) {  // the operand loads of the tile at (mat, tm, tn) start here
+    a_src = reinterpret_cast<const uint4*>(batch.A[mat]) + (size_t)tm * (TILE * 2) + wave * 64 + lane;
+    b_src = reinterpret_cast<const uint4*>(batch.B[mat]) + (size_t)tn * (TILE * 2) + wave * 64 + lane;
+  };
   auto load1k = [&](const uint4* src, int dst_u4) {
     __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)&lds[dst_u4], 16, 0, 0);
   };
@@ -263,9 +261,30 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
   // stage that has just been freed (nobody reads it), which keeps the loop free of branches and
   // the number of loads in flight constant.
   const int nkt = g.Kp / (16 * KS);
+  auto prologue = [&]() {
 #pragma unroll
-  for (int p = 0; p < S; ++p) issue(p, min(p, nkt - 1));
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm((S - 1) * LPT));  // this wave's share of stage 0 has landed
+    for (int p = 0; p < S; ++p) issue(p, min(p, nkt - 1));
+  };
+  // A workgroup walks the tile sequence with the grid as its stride.  The first S stages of a
+  // tile are requested before the epilogue of the tile before it, so their latency hides there.
+  int mat, tm, tn;
+  decode(blockIdx.x, mat, tm, tn);
+  aim(mat, tm, tn);
+  prologue();
+  for (int v = blockIdx.x; v < g.all_tiles; v += gridDim.x) {
+  float* __restrict__ C = batch.C[mat];
+  uint16_t* __restrict__ shadow = batch.shadow[mat];
+  const int m0 = tm * TILE, n0 = tn * TILE;
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  // This wave's share of stage 0 has landed.  After the first tile the count also holds the
+  // epilogue's stores, which may complete out of order with the loads: wait for everything.
+  if (v == (int)blockIdx.x) __builtin_amdgcn_s_waitcnt(waitcnt_vm((S - 1) * LPT));
+  else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
   // Bare barriers: __syncthreads() would add a fence that waits for ALL outstanding loads, the
   // ones of the later stages included, and serialise the pipeline.
   __builtin_amdgcn_s_barrier();
@@ -292,9 +311,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
         fetch_b(bf[KS & 1], nst, 0);
         fetch_a(af[0], nst, 0, 0);
       }
-      __builtin_amdgcn_sched_barrier(0);
       multiply(af[u & 1], bf[ks & 1], grp);
-      __builtin_amdgcn_sched_barrier(0);
     }
     if (KS & 1) bf[0] = bf[1];  // odd k-steps per stage: the next stage's B operands were fetched into bf[1]
     st = nst;
@@ -302,6 +319,14 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
   for (int kt = 0; kt + 1 < nkt; ++kt) stage(kt, false);
   stage(nkt - 1, true);
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // the surplus loads of the last iterations
+  int mat_n = mat, tm_n = tm, tn_n = tn;
+  if (v + (int)gridDim.x < g.all_tiles) {
+    __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+    __builtin_amdgcn_s_barrier();  // every wave has read its last operands and its surplus loads have landed: the ring is free
+    decode(v + (int)gridDim.x, mat_n, tm_n, tn_n);
+    aim(mat_n, tm_n, tn_n);
+    prologue();
+  }
 
   if (EPI == EPI_F32) {
     const bool use_beta = (g.beta != 0.0f);
@@ -438,6 +463,10 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
       }
     }
   }
+  mat = mat_n;
+  tm = tm_n;
+  tn = tn_n;
+  }  // tiles of this workgroup
 }
 
 // ---- operand preparation -----------------------------------------------------------------
@@ -693,6 +722,19 @@ hipError_t br_launch_ingest_planes(hipStream_t s, const float* const* G, float* 
 }
 
 namespace {
+// Compute units of the current device, rounded down to a multiple of the XCD count (cached per device).
+int lowp_resident_workgroups() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < NUM_XCD) return 0;
+    cached[dev] = cus / NUM_XCD * NUM_XCD;
+  }
+  return cached[dev];
+}
+
 template <int EPI>
 void launch_lowp(hipStream_t s, int nprod, int grid, const LowpKernArgs& k, const BrLowpBatch& b) {
   if (nprod == 4)
@@ -756,6 +798,11 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
   }
   long long grid = (long long)k.total_tiles * a.batch;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  k.all_tiles = (int)grid;
+  // one workgroup per compute unit (rounded down to whole XCDs) walks the tiles when there are more tiles than that
+  const int resident = lowp_resident_workgroups();
+  if (resident <= 0) return hipErrorInvalidDevice;
+  if (grid > resident) grid = resident;
   if (a.epilogue == BR_EPI_ADAM) launch_lowp<EPI_ADAM>(s, a.nprod, (int)grid, k, b);
   else if (a.epilogue == BR_EPI_PLANES) launch_lowp<EPI_PLANES>(s, a.nprod, (int)grid, k, b);
   else launch_lowp<EPI_F32>(s, a.nprod, (int)grid, k, b);
