@@ -294,7 +294,9 @@ static int lowp_gemm_bench(int M, int N, int K, int batch, int nprod, int mirror
   hipEvent_t e0, e1;
   CHECK_HIP(hipEventCreate(&e0));
   CHECK_HIP(hipEventCreate(&e1));
-  const int reps = 10;
+  const int reps = 20;
+  // the first launches after an idle period run slower (the clocks ramp up): time the steady state
+  for (int r = 0; r < reps; ++r) CHECK_HIP(br_launch_gemm_lowp(0, la, lb, nullptr));
   CHECK_HIP(hipEventRecord(e0, 0));
   for (int r = 0; r < reps; ++r) CHECK_HIP(br_launch_gemm_lowp(0, la, lb, nullptr));
   CHECK_HIP(hipEventRecord(e1, 0));
