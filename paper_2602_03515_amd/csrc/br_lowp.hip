@@ -25,12 +25,21 @@
 // v_mfma_f32_32x32x16_bf16 accumulators) per compute unit and 256 x 256 output tile.  Operands
 // stream through a ring of five 32 KB LDS stages (all 160 KB): a stage is 32 k of A and B
 // (NPROD = 1) or 16 k of A_hi, A_lo, B_hi, B_lo (NPROD >= 3).  Four stages are always in flight
-// from memory.  What bounds the kernel is the rate at which one compute unit can pull lines out
-// of L2 (about 20 bytes per clock measured), so the tile is as large as the register file allows:
-// 128 flop per operand byte for NPROD = 1, three and four times that for the split products.
+// from memory.  The grid is one workgroup per compute unit; each walks its share of the tiles and
+// requests the first stages of its next tile before the epilogue of the current one.
 // There is ONE workgroup barrier per stage and it sits between two groups of the stage's matrix
 // instructions: operands are fetched from LDS one group ahead of their use, so the matrix pipe
 // keeps running across the barrier.
+// What bounds it (NPROD = 1, measured with the pieces of the loop switched off one at a time): per
+// stage the matrix pipes need about 0.49 us, the LDS reads alone (96 KB at a little over 100 bytes
+// per clock) 0.42 us, the memory -> LDS loads alone 0.29 us when every line hits L2 and 0.5 to
+// 0.6 us with the real tile mix, and the three do not overlap freely: with all of them running
+// the clock falls from 2.2 to 1.8 GHz (power), and a stage takes 0.85 to 0.95 us.  The tile is as
+// large as the register file allows (128 flop per operand byte for NPROD = 1, three and four
+// times that for the split products).  A 4-wave variant with 128 x 128 wave tiles (a third less
+// LDS traffic, accumulators in AGPRs) was measured slower: one wave per SIMD leaves the matrix
+// pipe idle across each stage's barrier (1470 against 1860 TFLOP/s with nothing but matrix
+// instructions in the loop).
 #include "br_internal.h"
 
 namespace {
