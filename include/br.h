@@ -29,6 +29,14 @@
  *   streams    all work is enqueued on the HIP stream given to br_init (a
  *              hipStream_t passed as void*, NULL = the null stream).  No call
  *              synchronises with the host except br_profile_end.
+ *   graphs     br_accumulate_stats, br_refresh_basis, br_step, br_clip_gradients and
+ *              br_delay_compensate only launch kernels (no allocation, no memset, no
+ *              synchronisation), so they may be issued while the stream is being
+ *              captured into a HIP graph.  A captured call freezes what the host
+ *              folds into kernel arguments: the pointer arrays, lr, and with
+ *              bias_correction the factors of the step number it was captured at; the
+ *              host-side state (step counter, "statistics fresh", "basis changed")
+ *              advances at capture time, not at replay.  Profiling must be off.
  *   errors     every call returns a br_status; nothing throws or aborts.  Argument
  *              errors are detected on the host before anything is launched.  After
  *              BR_ERR_HIP the context is unusable (sticky).  br_last_error gives text.
