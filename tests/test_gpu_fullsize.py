@@ -319,3 +319,51 @@ def test_quadratic_with_delay_512x128(h, geometry, tau):
     qr_gpu = h.to_np(sb.opt.state(0, B.BR_STATE_QR))
     assert misalignment(qr_gpu, prob.H_R) < misalignment(np.eye(128), prob.H_R)
     assert abs(misalignment(qr_gpu, prob.H_R) - misalignment(st.QR, prob.H_R)) <= 1e-2 * misalignment(st.QR, prob.H_R)
+
+
+@pytest.mark.parametrize("math", [0, 1])
+def test_tall_factor_panels_span_nine_workgroups(h, math):
+    """A left factor of order 13000: its first QR panels are 13000 rows tall and are factorised by
+    clusters of nine workgroups (the stage's tallest, order 6912, needs five).  A well-conditioned
+    symmetric statistic (eigenvalues in about [1.4, 2.6]) is written into the state and the refresh
+    runs from Q = I, so the new basis is the orthogonal factor of that matrix itself.  The oracle's
+    QR of a matrix this large would take minutes, so what is unique is checked piecewise, in
+    float64 where it matters: the basis's first 48 columns are the orthogonal factor of the
+    statistic's first 48 columns (a 13000 x 48 LAPACK QR on the host, same sign convention);
+    Q^T Q = I; and R = Q^T L is upper triangular with a positive diagonal (float64 matrix products
+    on the device).  Bars: 1e-5 for the FP32 refresh; BR_MATH_BF16, whose large QR updates take
+    16-bit mantissa inputs, 1e-4 on the entries and 5e-5 on orthogonality, as at the smaller orders."""
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+
+    bar, orth = (1e-4, 5e-5) if math == 1 else (1e-5, 1e-5)
+    m, n = 13000, 40
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    N = torch.randn(m, m, device=dev, generator=gen, dtype=torch.float32)
+    L = (N + N.T) * (0.3 / (2.0 * np.sqrt(m)))
+    L.diagonal().add_(2.0)
+    del N
+    W = torch.zeros(m, n, device=dev)
+    opt = BasisRotationAdam([W], freq=0, lr=1e-3, math=math)
+    opt.state(0, B.BR_STATE_L).copy_(L)
+    opt.state(0, B.BR_STATE_R).copy_(torch.eye(n, device=dev) * 2.0)
+    B.br_notify_state_written(opt.ctx)
+    opt.refresh_basis()
+    torch.cuda.synchronize()
+    Q = opt.state(0, B.BR_STATE_QL)
+    assert bool(torch.isfinite(Q).all())
+    lead, _ = lapack_qr(L[:, :48].double().cpu().numpy())
+    e = rel_err(h.to_np(Q[:, :48]), lead)
+    assert e <= bar, f"leading columns: rel err {e:.3e}"
+    Qd = Q.double()
+    defect = float((Qd.T @ Qd - torch.eye(m, device=dev, dtype=torch.float64)).abs().max())
+    assert defect < orth, f"||Q^T Q - I||_max = {defect:.2e}"
+    R = Qd.T @ L.double()
+    below = float(torch.tril(R, diagonal=-1).abs().max())
+    assert below <= bar * float(R.abs().max()), f"Q^T L is not upper triangular: {below:.2e}"
+    assert float(R.diagonal().min()) > 0.0
+    # the right factor of order 40 went through the same call: identity statistics give back the identity
+    assert rel_err(h.to_np(opt.state(0, B.BR_STATE_QR)), np.eye(n)) <= (1e-4 if math == 1 else 1e-6)
+    opt.close()
