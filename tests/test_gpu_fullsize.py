@@ -321,15 +321,16 @@ def test_quadratic_with_delay_512x128(h, geometry, tau):
     assert abs(misalignment(qr_gpu, prob.H_R) - misalignment(st.QR, prob.H_R)) <= 1e-2 * misalignment(st.QR, prob.H_R)
 
 
-@pytest.mark.parametrize("math", [0, 1])
-def test_tall_factor_panels_span_nine_workgroups(h, math):
-    """A left factor of order 13000: its first QR panels are 13000 rows tall and are factorised by
-    clusters of nine workgroups (the stage's tallest, order 6912, needs five).  A well-conditioned
+@pytest.mark.parametrize("m,math", [(13000, 0), (13000, 1), (32000, 0)])
+def test_tall_factor_panels_span_many_workgroups(h, m, math):
+    """A left factor of order 13000 (32000: the vocabulary side of the embedding shard, were it
+    rotated): its first QR panels are that many rows tall and are factorised by clusters of nine
+    (twenty-one) workgroups (the stage's tallest, order 6912, needs five).  A well-conditioned
     symmetric statistic (eigenvalues in about [1.4, 2.6]) is written into the state and the refresh
     runs from Q = I, so the new basis is the orthogonal factor of that matrix itself.  The oracle's
     QR of a matrix this large would take minutes, so what is unique is checked piecewise, in
     float64 where it matters: the basis's first 48 columns are the orthogonal factor of the
-    statistic's first 48 columns (a 13000 x 48 LAPACK QR on the host, same sign convention);
+    statistic's first 48 columns (an m x 48 LAPACK QR on the host, same sign convention);
     Q^T Q = I; and R = Q^T L is upper triangular with a positive diagonal (float64 matrix products
     on the device).  Bars: 1e-5 for the FP32 refresh; BR_MATH_BF16, whose large QR updates take
     16-bit mantissa inputs, 1e-4 on the entries and 5e-5 on orthogonality, as at the smaller orders."""
@@ -337,7 +338,7 @@ def test_tall_factor_panels_span_nine_workgroups(h, math):
     from paper_2602_03515_amd.optimizer import BasisRotationAdam
 
     bar, orth = (1e-4, 5e-5) if math == 1 else (1e-5, 1e-5)
-    m, n = 13000, 40
+    n = 40
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
