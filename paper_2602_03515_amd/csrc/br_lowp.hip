@@ -17,7 +17,7 @@
 //   NPROD = 1: C = A_hi B_hi^T                                  (plain BF16 inputs)
 //   NPROD = 3: C = A_hi B_hi^T + A_hi B_lo^T + A_lo B_hi^T      (16-bit mantissa inputs, FP32
 //              accumulation: a product term is off by about 2^-16, the dropped lo*lo term)
-//   NPROD = 4: adds A_lo B_lo^T.  Used for the statistics G G^T, G^T G, whose diagonal would
+//   NPROD = 4: adds A_lo B_lo^T (in a mirrored product: on the diagonal tiles only).  Used for the statistics G G^T, G^T G, whose diagonal would
 //              otherwise carry the systematic bias sum_k lo_k^2, and whose error the refresh
 //              amplifies by the condition number of the statistics.
 //
@@ -249,13 +249,18 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
       if (SPLIT) f.lo[q] = __builtin_bit_cast(bf16x8, lds[base + SUB_U4 + q * 64]);
     }
   };
+  // NPROD = 4 exists for the symmetric statistics, whose DIAGONAL would otherwise carry the bias
+  // sum_k lo_k^2 (every term positive).  Off the diagonal the lo*lo terms have random signs and sum
+  // to about 2^-18 / sqrt(K) of the matrix's scale, below FP32 resolution: only the tiles on the
+  // diagonal of a mirrored product issue the fourth instruction.
+  bool lolo = true;
   auto multiply = [&](const AFrag& a, const BFrag& b, int grp) {
 #pragma unroll
     for (int q = 0; q < MPG; ++q) {
       const int mi = grp * MPG + q;
 #pragma unroll
       for (int ni = 0; ni < FN; ++ni) {
-        if (NPROD == 4)
+        if (NPROD == 4 && lolo)
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo[q], b.lo[ni], acc[mi][ni], 0, 0, 0);
         if (NPROD >= 3) {
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo[q], b.hi[ni], acc[mi][ni], 0, 0, 0);
@@ -284,6 +289,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
   float* __restrict__ C = batch.C[mat];
   uint16_t* __restrict__ shadow = batch.shadow[mat];
   const int m0 = tm * TILE, n0 = tn * TILE;
+  lolo = !g.mirror || tm == tn;
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
