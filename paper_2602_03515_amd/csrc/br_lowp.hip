@@ -812,7 +812,7 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
       if (!b.S[i] || (reinterpret_cast<uintptr_t>(b.S[i]) & 15u)) return hipErrorInvalidValue;
   }
   long long grid = (long long)k.total_tiles * a.batch;
-  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (grid > 0x7fffffffLL - 65536) return hipErrorInvalidValue;  // the kernel adds its grid size to a tile position
   k.all_tiles = (int)grid;
   // one workgroup per compute unit (rounded down to whole XCDs) walks the tiles when there are more tiles than that
   const int resident = lowp_resident_workgroups();
