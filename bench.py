@@ -6,7 +6,11 @@ delayed gradient from the ring, first moment + Kronecker statistics, basis refre
 t mod freq == 0, rotate, Adam in the rotated basis, rotate back and apply.  Inputs are
 synthetic and resident in HBM before the timed region starts.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: throughput in parameters per second for the whole stage ("value"), the
+milliseconds per step, "roofline" (the dominant contraction kernel against the matrix-core peak of
+its input type, timed with HIP events on the launch stream), "roofline_elementwise", a per-kernel
+table, the other math modes' short runs ("modes") and the CPU oracle timed on a bounded sample
+("cpu_baseline").
 """
 import argparse
 import json
