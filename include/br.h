@@ -71,11 +71,11 @@ typedef enum { BR_F32 = 0, BR_BF16 = 1 } br_dtype;
 
 /* Rotation geometry G of Algorithm 2.  Unilateral rotates only the side of size
  * min(m, n) (Section 3.2; memory-overhead appendix); a square matrix keeps the
- * left factor, as Algorithm 2 lines 7-9 do. */
+ * left factor, as Algorithm 2's unilateral branch does. */
 typedef enum { BR_BILATERAL = 0, BR_UNILATERAL = 1 } br_geometry;
 
-/* Approximation source S of Algorithm 2.  SECOND keeps L, R (lines 1-9); FIRST uses
- * M M^T and M^T M at refresh time and keeps no statistics buffers (lines 11-19). */
+/* Approximation source S of Algorithm 2.  SECOND keeps L, R (its first branch); FIRST uses
+ * M M^T and M^T M at refresh time and keeps no statistics buffers (its second branch). */
 typedef enum { BR_SRC_SECOND = 0, BR_SRC_FIRST = 1 } br_source;
 
 /* Input precision of the step's matrix-core contractions (statistics, rotations, rotate-back).
@@ -89,10 +89,10 @@ typedef enum { BR_MATH_F32 = 0, BR_MATH_BF16 = 1, BR_MATH_BF16X3 = 2 } br_math;
 
 /* Which buffer br_get_state returns. */
 typedef enum {
-  BR_STATE_M = 0,      /* first moment, original space, m x n  (Algorithm 1 line 4)      */
-  BR_STATE_S = 1,      /* second moment in the rotated basis, m x n  (line 10)           */
-  BR_STATE_L = 2,      /* EMA of G G^T, m x m  (Algorithm 2 line 2)                      */
-  BR_STATE_R = 3,      /* EMA of G^T G, n x n  (Algorithm 2 line 5)                      */
+  BR_STATE_M = 0,      /* first moment, original space, m x n  (Algorithm 1)             */
+  BR_STATE_S = 1,      /* second moment in the rotated basis, m x n  (Algorithm 1)       */
+  BR_STATE_L = 2,      /* EMA of G G^T, m x m  (Algorithm 2)                             */
+  BR_STATE_R = 3,      /* EMA of G^T G, n x n  (Algorithm 2)                             */
   BR_STATE_QL = 4,     /* left rotation U, m x m                                         */
   BR_STATE_QR = 5,     /* right rotation V, n x n                                        */
   BR_STATE_MASTER = 6, /* FP32 master weights of a BF16 parameter, m x n                 */
@@ -109,10 +109,10 @@ typedef struct {
 } br_matrix_desc;
 
 typedef struct {
-  float beta1, beta2;  /* Adam moment decay rates (Algorithm 1 lines 4, 10)              */
-  float eps;           /* inside the square root, as Algorithm 1 line 11 has it          */
+  float beta1, beta2;  /* Adam moment decay rates (Algorithm 1)                           */
+  float eps;           /* inside the square root, as Algorithm 1's update has it          */
   float weight_decay;  /* decoupled: W <- W - lr*wd*W on the pre-step W; 0 = Algorithm 1 */
-  float stat_beta;     /* decay of L, R; negative: use beta2 (Algorithm 2 lines 2, 5)    */
+  float stat_beta;     /* decay of L, R; negative: use beta2 (Algorithm 2)               */
   int32_t geometry;    /* br_geometry                                                    */
   int32_t source;      /* br_source                                                      */
   int32_t power_iters; /* multiplications by L (R) before the single QR; paper: 1        */
@@ -125,7 +125,7 @@ typedef struct {
                           (equal to rotating M, by linearity) instead of rotating M every
                           step; M~ is recomputed from M after every refresh.  Costs m*n
                           floats per rotated matrix, saves a quarter of the step's
-                          contractions.  0: rotate M every step (Algorithm 1 line 9 as is). */
+                          contractions.  0: rotate M every step (Algorithm 1 as printed). */
 } br_hparams;
 
 /* One line per kernel symbol of a profiled region (see br_profile_begin). */
@@ -158,9 +158,9 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
 
 /*
  * Consume this step's (delayed) gradients: M <- beta1 M + (1-beta1) G for every
- * matrix (Algorithm 1 line 4) and, for the second-order source,
+ * matrix (Algorithm 1, first-moment update) and, for the second-order source,
  * L <- b L + (1-b) G G^T, R <- b R + (1-b) G^T G on the rotated sides
- * (Algorithm 2 lines 2, 5), accumulated every step.
+ * (Algorithm 2, updates of L and R), accumulated every step.
  * `grads`: host array of n_mats device pointers, matrix i being m_i x n_i of
  * grad_dtype.  Must be called exactly once before each br_step.
  */
@@ -192,7 +192,7 @@ br_status br_delay_compensate(br_ctx* ctx, void* const* grads, const void* const
 br_status br_get_clip_result(br_ctx* ctx, void** dev_ptr);
 
 /*
- * Eigenbasis-Estimation for every rotated side (Algorithm 2 lines 3, 6 and
+ * Eigenbasis-Estimation for every rotated side (Algorithm 2's Power calls and
  * Section 3.2): P <- A^power_iters Q with A = L or R (first-order source: M M^T,
  * M^T M), then Q <- the orthogonal factor of the Householder QR of P with
  * diag(R) >= 0.  Needs no gradients; uses the statistics as they stand.
@@ -200,7 +200,7 @@ br_status br_get_clip_result(br_ctx* ctx, void** dev_ptr);
 br_status br_refresh_basis(br_ctx* ctx);
 
 /*
- * Algorithm 1 lines 8-11 for every matrix: G~ = Q_L^T G Q_R, M~ = Q_L^T M Q_R,
+ * Algorithm 1 from the rotation to the parameter update, for every matrix: G~ = Q_L^T G Q_R, M~ = Q_L^T M Q_R,
  * S~ <- beta2 S~ + (1-beta2) G~.G~, X = M~ / sqrt(S~ + eps),
  * W <- W - lr * Q_L X Q_R^T - lr * weight_decay * W.  Increments t.
  * `params`: host array of device pointers to the weights (param_dtype), updated in

@@ -2,18 +2,18 @@
 
 What is restated here, and where the paper defines it:
 
-  * first moment kept in the ORIGINAL space            -- Algorithm 1, line 4;
+  * first moment kept in the ORIGINAL space            -- Algorithm 1, first-moment update;
     Appendix "Connection to Recent Optimizers" (momentum accumulated in
     the original space, basis refreshed before the optimisation step)
   * Kronecker-factor statistics L, R as EMAs of G G^T, G^T G
-                                                       -- Algorithm 2, lines 2 and 5
+                                                       -- Algorithm 2, updates of L and R
   * Power(A, Q): one multiplication by A followed by a QR factorisation,
     Q <- qr(A Q).Q                                     -- Section 3.2, last paragraph
-  * unilateral geometry rotates only the smaller side  -- Algorithm 2, lines 7-9
+  * unilateral geometry rotates only the smaller side  -- Algorithm 2, unilateral branch
     together with Section 3.2 / the memory-overhead appendix (min(m, n)^2)
   * rotate, second moment in the rotated basis, rotate back
-                                                       -- Algorithm 1, lines 8-11
-  * epsilon INSIDE the square root, no bias correction -- Algorithm 1, line 11
+                                                       -- Algorithm 1, rotation to update
+  * epsilon INSIDE the square root, no bias correction -- Algorithm 1, update formula
     and the "standard Adam update" equation of Section 3.1
   * delayed-gradient indexing                          -- Appendix B, the
     delayed-gradient case equation
@@ -55,7 +55,7 @@ class Hyper:
     beta2: float = 0.95
     eps: float = 1e-8
     weight_decay: float = 0.0
-    stat_beta: Optional[float] = None      # None -> beta2 (Algorithm 2, line 2)
+    stat_beta: Optional[float] = None      # None -> beta2 (Algorithm 2, update of L)
     geometry: str = "bilateral"            # "bilateral" | "unilateral"
     source: str = "second"                 # "second" (L, R buffers) | "first" (M M^T, M^T M)
     power_iters: int = 1
@@ -163,7 +163,7 @@ def refresh(st: MatrixState, hp: Hyper, qr: Callable = householder_qr) -> None:
 
 
 def step(st: MatrixState, W: np.ndarray, G: np.ndarray, lr: float, hp: Hyper) -> np.ndarray:
-    """Lines 8-11 of Algorithm 1 for one matrix; returns the new weights.
+    """Algorithm 1 from the rotation of G and M to the parameter update, for one matrix; returns the new weights.
     `st.M` must already contain this step's gradient (see `ingest`)."""
     W = np.asarray(W, dtype=np.float64)
     G = np.asarray(G, dtype=np.float64)

@@ -108,7 +108,7 @@ void sides(const br_matrix_desc& d, const br_hparams& hp, bool* l, bool* r) {
   if (hp.geometry == BR_BILATERAL) {
     *l = *r = true;
   } else if (d.m <= d.n) {
-    *l = true;  // smaller side; a square matrix keeps the left factor (Algorithm 2 lines 7-9)
+    *l = true;  // smaller side; a square matrix keeps the left factor (Algorithm 2, unilateral branch)
   } else {
     *r = true;
   }
@@ -1150,7 +1150,7 @@ br_status br_refresh_basis(br_ctx* ctx) {
       P1[i] = reinterpret_cast<float*>(base + i * rs.total + rs.P1);
       if (hp.source == BR_SRC_SECOND) {
         A[i] = j.left ? m.L : m.R;
-      } else {  // first-order source: Gram matrix of the first moment (Algorithm 2 lines 12, 14)
+      } else {  // first-order source: Gram matrix of the first moment (Algorithm 2, first-order branch)
         float* gram = reinterpret_cast<float*>(base + i * rs.total + rs.gram);
         A[i] = gram;
         BrGemmBatch one;

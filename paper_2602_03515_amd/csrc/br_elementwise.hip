@@ -4,9 +4,9 @@
 // 2-read 1-write stream then runs at 5.6 TB/s against 4.6 TB/s for the same kernel with a
 // grid-stride loop (writes alone: 5.9 against 4.4 TB/s; reads alone 6.5 TB/s).
 //
-//   br_ema_first_moment   M <- beta1 M + (1-beta1) G                  (Algorithm 1 line 4)
+//   br_ema_first_moment   M <- beta1 M + (1-beta1) G                  (Algorithm 1, first-moment update)
 //   br_adam_rotated       S~ <- beta2 S~ + (1-beta2) G~.G~ ; X = M~/sqrt(S~+eps)
-//                                                                     (Algorithm 1 lines 10-11)
+//                                                                     (Algorithm 1, second moment and update)
 //   br_adam_plain         the same update for tensors that are not rotated, fused with
 //                         the weight update (embeddings, LM head: experimental details)
 //   br_norm_finalize      deterministic second stage of the per-matrix norm reductions

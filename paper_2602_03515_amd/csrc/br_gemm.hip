@@ -1,9 +1,9 @@
 // Batched FP32 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32).
 //
 // Serves every dense contraction of the path: the statistics G G^T and G^T G
-// (Algorithm 2 lines 2, 5), the power-iteration product L Q and the block-reflector
-// updates of the QR (Section 3.2), the rotations Q_L^T G Q_R (Algorithm 1 lines 8-9)
-// and the rotate-back-and-apply W <- W - lr Q_L X Q_R^T (line 11).
+// (Algorithm 2, the updates of L and R), the power-iteration product L Q and the block-reflector
+// updates of the QR (Section 3.2), the rotations Q_L^T G Q_R (Algorithm 1, the rotation step)
+// and the rotate-back-and-apply W <- W - lr Q_L X Q_R^T (Algorithm 1, the parameter update).
 //
 // Design: a 128 x 128 output tile per 256-thread workgroup (four wave64s in a 2 x 2
 // grid, each owning 64 x 64 = four 32 x 32 MFMA accumulators), K advanced 16 at a

@@ -1,6 +1,6 @@
 // BF16 matrix-core contractions for the optimizer step (math modes BR_MATH_BF16 and
-// BR_MATH_BF16X3): the statistics G G^T, G^T G (Algorithm 2 lines 2, 5), the rotations
-// Q_L^T G Q_R (Algorithm 1 lines 8-9) and the rotate-back Q_L X Q_R^T (line 11).
+// BR_MATH_BF16X3): the statistics G G^T, G^T G (Algorithm 2, the updates of L and R), the rotations
+// Q_L^T G Q_R (Algorithm 1, the rotation step) and the rotate-back Q_L X Q_R^T (its parameter update).
 //
 // Operands are first rewritten as BF16 "planes" by br_split_planes:
 //     hi = bf16(x),  lo = bf16(x - hi)            (round to nearest even)
@@ -148,7 +148,7 @@ namespace br {
 //               lane + 32; the two swap halves and each stores whole chunks (emit_chunks);
 //   EPI_ADAM    the tile is a rotated gradient G~: Adam's moments are advanced in place
 //               (S~ <- b2 S~ + (1-b2) G~ G~, and M~ <- b1 M~ + (1-b1) G~ when adam.update_mrot;
-//               Algorithm 1 lines 9-11) and X = M~ / sqrt(S~ + eps) leaves as planes like above.
+//               Algorithm 1, from the rotated moment to the update) and X = M~ / sqrt(S~ + eps) leaves as planes like above.
 //               With adam_t the tile is G~^T instead (right factor only: G~^T = Q_R^T G^T), the
 //               moments are indexed [col][row], and what leaves are the planes of X itself.
 template <int NPROD, int EPI>
@@ -592,8 +592,8 @@ __global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int
 }
 
 
-// First moment and both plane sets of a gradient in one pass (Algorithm 1 line 4, and the operands
-// of Algorithm 2 lines 2, 5 and Algorithm 1 line 8): M <- beta1 M + (1 - beta1) G, planes of G and
+// First moment and both plane sets of a gradient in one pass (Algorithm 1's first-moment update, and the operands
+// of Algorithm 2's statistics and of Algorithm 1's gradient rotation): M <- beta1 M + (1 - beta1) G, planes of G and
 // planes of G^T, the gradient read once.  One 64 x 64 tile per workgroup, transposed through LDS;
 // tiles past the matrix write the planes' zero padding.
 struct IngestArgs {

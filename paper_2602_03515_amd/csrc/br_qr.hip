@@ -1,5 +1,5 @@
-// Householder QR building blocks for the basis refresh (Section 3.2: "power iteration
-// followed by QR decomposition"; Algorithm 2 lines 3 and 6).
+// Householder QR building blocks for the basis refresh (Section 3.2: one power-iteration
+// product, then a QR factorisation; the Power calls of Algorithm 2).
 //
 // The factorisation is blocked recursively (panels of BR_QR_NB = 32 columns, middle blocks of
 // BR_QR_NBM = 128 merged in LDS, then merged pairwise up to top blocks of 256 or BR_QR_NBT = 512) in

@@ -184,7 +184,7 @@ def test_injected_basis_midway_rebuilds_cached_rotated_moment(harness):
 @pytest.mark.parametrize("geometry", [0, 1])
 def test_cached_and_recomputed_rotated_moment_agree(harness, geometry):
     """M~ advanced by its own EMA between refreshes (cache on) equals M~ rotated from M every
-    step (cache off, Algorithm 1 line 9 as printed) up to FP32 rounding; both match the oracle."""
+    step (cache off, Algorithm 1's rotation of M as printed) up to FP32 rounding; both match the oracle."""
     W0, grads = synth.spiked_gradients(seed=15, m=104, n=168, steps=9, noise_std=0.1)
     out = []
     for cache in (0, 1):
@@ -206,7 +206,7 @@ def test_textbook_flags_power_iters_and_stat_beta(harness):
 
 @pytest.mark.parametrize("shape", [(48, 200), (200, 48)])
 def test_first_moment_source_unilateral(harness, shape):
-    """First-order source (Algorithm 2 lines 11-19): Power(M M^T, U) with no L/R buffers.  A wide
+    """First-order source (Algorithm 2, first-order branch): Power(M M^T, U) with no L/R buffers.  A wide
     noisy M keeps M M^T well conditioned, so the bases are compared directly."""
     m, n = shape
     W0, grads = synth.lowrank_gradients(seed=12, m=m, n=n, steps=6, rank=8, sigma=0.05)

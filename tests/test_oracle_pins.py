@@ -85,7 +85,7 @@ def test_textbook_flags_match_torch_adam(wd):
 
 
 def test_moment_closed_forms_for_constant_gradient():
-    """EMA of a constant: M_t = (1 - b1^t) G, L_t = (1 - b2^t) G G^T (Alg. 1 l.4, Alg. 2 l.2, l.5)."""
+    """EMA of a constant: M_t = (1 - b1^t) G, L_t = (1 - b2^t) G G^T (first-moment update of Alg. 1, statistics of Alg. 2)."""
     rng = np.random.default_rng(12)
     G = rng.standard_normal((4, 6))
     hp = oc.Hyper(beta1=0.9, beta2=0.95)
