@@ -461,7 +461,10 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
                 const float st2 = ad.beta2 * sold[vg * 4 + e] + w2 * (gt * gt);
                 S[off] = st2;
                 const float num = mt * ad.c1, den = st2 * ad.c2;
-                x = ad.eps_outside ? num / (sqrtf(den) + ad.eps) : num / sqrtf(den + ad.eps);
+                // one-ulp hardware reciprocal square root / reciprocal (the arguments are normal numbers:
+                // den + eps >= eps); the quotient leaves as BF16 planes anyway
+                x = ad.eps_outside ? num * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(den) + ad.eps)
+                                   : num * __builtin_amdgcn_rsqf(den + ad.eps);
               }
               val[e] = x;
             }
