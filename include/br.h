@@ -192,6 +192,27 @@ br_status br_delay_compensate(br_ctx* ctx, void* const* grads, const void* const
 br_status br_get_clip_result(br_ctx* ctx, void** dev_ptr);
 
 /*
+ * br_clip_gradients for callers that cannot allocate device memory and hold no context or
+ * workspace: code that runs under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same kernels and arithmetic; the per-workgroup partial sums live in a device array
+ * inside the library (1 MiB per GPU, held until the process ends), the result goes to the caller.
+ * Calls no hipMalloc/hipFree or other allocating routine, and no memset; only launches kernels on
+ * `hip_stream` (a hipStream_t; NULL = the null stream), whose device must be the current one.
+ *   descs      host array of n_mats descriptors; m, n and grad_dtype are used
+ *   grads      host array of n_mats device pointers (16-byte aligned), scaled IN PLACE by
+ *              min(1, max_norm / (norm + 1e-6)), BF16 with round-to-nearest-even
+ *   dev_result device pointer to two floats (8-byte aligned) owned by the caller: receives the
+ *              global norm and the applied factor
+ * At most BR_STATIC_CLIP_MAX_MATS matrices per call: more returns BR_ERR_WORKSPACE and launches
+ * nothing.  Other argument errors as br_clip_gradients; the text is behind br_last_error(NULL).
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race; calls ordered on one stream, or separated by synchronisation, are safe.
+ */
+#define BR_STATIC_CLIP_MAX_MATS 4096
+br_status br_clip_gradients_static(const br_matrix_desc* descs, void* const* grads, int32_t n_mats,
+                                   float max_norm, void* dev_result, void* hip_stream);
+
+/*
  * Eigenbasis-Estimation for every rotated side (Algorithm 2's Power calls and
  * Section 3.2): P <- A^power_iters Q with A = L or R (first-order source: M M^T,
  * M^T M), then Q <- the orthogonal factor of the Householder QR of P with

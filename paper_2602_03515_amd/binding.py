@@ -69,6 +69,9 @@ _lib.br_delay_compensate.argtypes = [_ctx_p, C.POINTER(C.c_void_p), C.POINTER(C.
 _lib.br_delay_compensate.restype = C.c_int
 _lib.br_get_clip_result.argtypes = [_ctx_p, C.POINTER(C.c_void_p)]
 _lib.br_get_clip_result.restype = C.c_int
+_lib.br_clip_gradients_static.argtypes = [C.POINTER(br_matrix_desc), C.POINTER(C.c_void_p), C.c_int32, C.c_float, C.c_void_p,
+                                          C.c_void_p]
+_lib.br_clip_gradients_static.restype = C.c_int
 _lib.br_refresh_basis.argtypes = [_ctx_p]
 _lib.br_refresh_basis.restype = C.c_int
 _lib.br_step.argtypes = [_ctx_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_float]
@@ -93,7 +96,9 @@ _lib.br_version.restype = C.c_char_p
 _lib.br_destroy.argtypes = [_ctx_p]
 _lib.br_destroy.restype = None
 
-EXPORTED = ["br_workspace_bytes", "br_init", "br_delay_compensate", "br_clip_gradients", "br_get_clip_result", "br_accumulate_stats", "br_refresh_basis", "br_step", "br_get_state",
+BR_STATIC_CLIP_MAX_MATS = 4096
+
+EXPORTED = ["br_workspace_bytes", "br_init", "br_delay_compensate", "br_clip_gradients", "br_clip_gradients_static", "br_get_clip_result", "br_accumulate_stats", "br_refresh_basis", "br_step", "br_get_state",
             "br_notify_state_written", "br_get_step_count", "br_set_step_count", "br_profile_begin", "br_profile_end", "br_last_error",
             "br_version", "br_destroy"]
 
@@ -167,6 +172,12 @@ def br_accumulate_stats(ctx, grads: Sequence[int]):
 
 def br_clip_gradients(ctx, grads: Sequence[int], max_norm: float):
     _check(_lib.br_clip_gradients(ctx, _ptr_array(grads), len(grads), max_norm), "br_clip_gradients", ctx)
+
+
+def br_clip_gradients_static(descs, grads: Sequence[int], max_norm: float, dev_result: int, hip_stream: int = 0):
+    n = len(descs) if descs is not None else 0
+    _check(_lib.br_clip_gradients_static(descs, _ptr_array(grads), n, max_norm, C.c_void_p(dev_result or None),
+                                         C.c_void_p(hip_stream or None)), "br_clip_gradients_static")
 
 
 def br_delay_compensate(ctx, grads: Sequence[int], params_now: Sequence[int], params_stale: Sequence[int], lam: float):

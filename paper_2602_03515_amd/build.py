@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_NAME = "libbr_hip.so"
 LIB_PATH = os.path.join(HERE, LIB_NAME)
-SOURCES = ["br_api.hip", "br_gemm.hip", "br_lowp.hip", "br_elementwise.hip", "br_qr.hip"]
+SOURCES = ["br_api.hip", "br_gemm.hip", "br_lowp.hip", "br_elementwise.hip", "br_qr.hip", "br_static.hip"]
 ARCH = "gfx950"
 
 HIPCC_FLAGS = [

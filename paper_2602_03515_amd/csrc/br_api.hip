@@ -570,6 +570,8 @@ bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* con
 
 }  // namespace
 
+void br_set_static_error(const std::string& msg) { g_static_err = msg; }
+
 // =========================================================================================
 extern "C" {
 
