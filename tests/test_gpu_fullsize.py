@@ -1,5 +1,13 @@
 """Parity at the benchmark configurations' full sizes, in the launch configuration bench.py times.
 
+One layer of the 3B-class stage and the hidden-2048 layer run at their configurations' own schedule (refresh every 10
+steps, 12 steps, fresh noise in every gradient) in all three math modes against ONE oracle trajectory, at the bare bars:
+1e-4 for BR_MATH_F32 / BR_MATH_BF16X3, 2e-2 for BR_MATH_BF16.  (With a refresh at step 4 and only four distinct
+gradients, an earlier form of the BF16 test saw 3e-2 at the first rotated step: the quotient M~ / sqrt(S~ + eps) has
+entries whose S~ is nearly zero while the second moment holds few samples, and those amplify the small difference
+between bases computed from BF16-rounded and from exact statistics; injecting the exact basis brought that step to
+1.3e-2, and neither configuration has such a schedule.)
+
 The oracle cannot run a whole 634 M-parameter stage in seconds, so the GPU runs the full set of
 matrices (same batching and chunking as the benchmark) while the oracle follows a SAMPLE of them
 from the same inputs: every distinct shape, and matrices from different launch chunks.  At
@@ -126,81 +134,140 @@ def test_stage_3b_bilateral_sampled_matrices(h):
             assert float((q.T @ q - torch.eye(q.shape[0], device=dev, dtype=q.dtype)).abs().max()) < 1e-5
 
 
-def test_llama_layer_2048_bf16_config(h):
-    """One Llama-style layer at hidden 2048, BF16 parameters and gradients, FP32 master/state,
-    refresh every 10 steps, 12 steps.  All seven matrices run on the GPU; the oracle follows one
-    attention matrix for all 12 steps (the rectangular shapes are followed at full size in FP32 by
-    the stage test and in BF16 at hidden 256 by the small-size suite)."""
-    from paper_2602_03515_amd import binding as B
-    from paper_2602_03515_amd.optimizer import BasisRotationAdam
-    shapes = list(synth.LLAMA_LAYER_2048)
-    hp = oc.Hyper().rounded_to_f32()
-    lr = float(np.float32(1e-3))
-    W0s, seqs = [], []
-    for k, (m, n) in enumerate(shapes):
-        steps = 12 if k == 0 else 2          # only matrix 0 needs 12 distinct host gradients
-        W0, grads = synth.lowrank_gradients(seed=2000 + k, m=m, n=n, steps=steps, rank=64, sigma=0.01, bf16=True)
-        W0s.append(W0)
-        seqs.append(grads)
-    params = [h.to_dev(W, bf16=True) for W in W0s]
-    dev_grads = [[h.to_dev(g, bf16=True) for g in seq] for seq in seqs]
-    opt = BasisRotationAdam(params, freq=10, lr=lr, grad_dtype=torch.bfloat16)
-    per_step = [[dev_grads[k][t % len(dev_grads[k])] for k in range(len(shapes))] for t in range(12)]
-    w0 = {0: W0s[0]}
-    worst = _follow(h, opt, B, params, per_step, [0], hp, 10, lr, w0)
-    print("hidden-2048 BF16 worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
-    master = opt.state(0, B.BR_STATE_MASTER)
-    assert torch.equal(master.to(torch.bfloat16), params[0])
-    for i in range(1, len(shapes)):
-        assert torch.isfinite(params[i].float()).all()
-        for kind in (B.BR_STATE_QL, B.BR_STATE_QR):
-            q = opt.state(i, kind).double()
-            assert float((q.T @ q - torch.eye(q.shape[0], device=q.device, dtype=q.dtype)).abs().max()) < 1e-5
+MODE_NAMES = {0: "F32", 2: "BF16X3", 1: "BF16"}
+MODE_TOL = {0: TOL, 2: TOL, 1: 2e-2}          # the stated bars: 1e-4 (FP32-class inputs), 2e-2 (BF16 matrix-core inputs)
+MODE_ORTHO = {0: 1e-5, 2: 1e-5, 1: 5e-5}
 
 
-def _stage_layer(h, math):
+def _progress(request, msg):
+    """A line on the real stdout even while pytest captures output: the oracle's full-size steps take seconds each."""
+    cm = request.config.pluginmanager.getplugin("capturemanager")
+    if cm is None:
+        print(msg, flush=True)
+        return
+    with cm.global_and_fixture_disabled():
+        print(msg, flush=True)
+
+
+def _layer_all_modes(h, request, label, shapes, sample, bf16_io, seed, freq=10, steps=12):
+    """One transformer layer at the configuration's own schedule (refresh every `freq` steps, `steps` steps, a fresh
+    noise draw in every step's gradient, as the input recipe says), run in all three math modes side by side on the same
+    device-generated inputs while the float64 oracle follows the matrices in `sample` (one of each shape) ONCE.
+    Gradients do not depend on the weights here, so the delay ring would only rename buffers: step t consumes
+    gradient t.  Returns, per mode, the measured error of every comparison next to what the test allows, so that each
+    mode's test asserts (and prints) its own."""
     import bench
     from paper_2602_03515_amd import binding as B
     from paper_2602_03515_amd.optimizer import BasisRotationAdam
     dev = torch.device("cuda:0")
-    shapes = list(synth.STAGE_3B_LAYER)
-    params, ring = bench.make_inputs(shapes, bench.TAU + 1, seed=2, device=dev)
-    sample = [0, 4, 6]
-    w0 = {i: params[i].cpu().numpy().copy() for i in sample}
+    params, ring = bench.make_inputs(shapes, steps, seed=seed, device=dev)
+    if bf16_io:
+        params = [p.to(torch.bfloat16).contiguous() for p in params]
+        ring = [[g.to(torch.bfloat16).contiguous() for g in slot] for slot in ring]
+    gdt = torch.bfloat16 if bf16_io else torch.float32
     hp = oc.Hyper().rounded_to_f32()
     lr = float(np.float32(1e-3))
-    opt = BasisRotationAdam(params, freq=4, lr=lr, math=math)
-    steps = [ring[t % (bench.TAU + 1)] for t in range(1, 6)]
-    return B, opt, params, steps, sample, hp, lr, w0
+    w0 = {i: h.to_np(params[i]) for i in sample}
+    work = {k: [p.clone() for p in params] for k in MODE_NAMES}
+    opts = {k: BasisRotationAdam(work[k], freq=freq, lr=lr, math=k, grad_dtype=gdt) for k in MODE_NAMES}
+    states = {i: oc.MatrixState(w0[i].shape[0], w0[i].shape[1], hp) for i in sample}
+    W_ref = {i: w0[i].copy() for i in sample}
+    rec = {k: [] for k in MODE_NAMES}      # (what, measured, allowed)
+
+    def weights(k, i):
+        return h.to_np(opts[k].state(i, B.BR_STATE_MASTER)) if bf16_io else h.to_np(work[k][i])
+
+    prev_gpu = {k: {i: w0[i].copy() for i in sample} for k in MODE_NAMES}
+    for t in range(1, steps + 1):
+        grads = ring[t - 1]
+        for k in MODE_NAMES:
+            opts[k].step(grads, lr)
+        prev_ref = {i: W_ref[i] for i in sample}
+        for i in sample:
+            W_ref[i] = oc.optimizer_step(states[i], W_ref[i], h.to_np(grads[i]), lr, hp, freq, lapack_qr)
+        torch.cuda.synchronize()
+        _progress(request, f"[{label}] oracle and three GPU modes finished step {t}/{steps}")
+        for k in MODE_NAMES:
+            for i in sample:
+                got = weights(k, i)
+                cum, one = W_ref[i] - w0[i], W_ref[i] - prev_ref[i]
+                # FP32-class modes: the update is read back as a difference of FP32 weights (one ulp of W);
+                # the BF16 mode's bar is applied bare
+                fl_c = _floor(W_ref[i], cum) if k != 1 else 0.0
+                fl_1 = 2.0 * _floor(W_ref[i], one) if k != 1 else 0.0
+                rec[k].append((f"t={t} matrix {i} {w0[i].shape} cumulative update", rel_err(got - w0[i], cum), MODE_TOL[k] + fl_c))
+                rec[k].append((f"t={t} matrix {i} {w0[i].shape} step update", rel_err(got - prev_gpu[k][i], one), MODE_TOL[k] + fl_1))
+                prev_gpu[k][i] = got
+    for k in MODE_NAMES:
+        for i in sample:
+            st = states[i]
+            for name, kind, ref in (("M", B.BR_STATE_M, st.M), ("S", B.BR_STATE_S, st.S), ("L", B.BR_STATE_L, st.L),
+                                    ("R", B.BR_STATE_R, st.R), ("QL", B.BR_STATE_QL, st.QL), ("QR", B.BR_STATE_QR, st.QR)):
+                if k == 1 and name in ("QL", "QR"):
+                    continue   # that mode's bases come from BF16-accurate statistics: orthogonality is what it promises
+                rec[k].append((f"matrix {i} {w0[i].shape} {name}", rel_err(h.to_np(opts[k].state(i, kind)), ref), MODE_TOL[k]))
+            for name, kind in (("QL", B.BR_STATE_QL), ("QR", B.BR_STATE_QR)):
+                q = opts[k].state(i, kind).double()
+                defect = float((q.T @ q - torch.eye(q.shape[0], device=q.device, dtype=q.dtype)).abs().max())
+                rec[k].append((f"matrix {i} {name} orthogonality defect", defect, MODE_ORTHO[k]))
+            if bf16_io:   # the BF16 parameter is the round-to-nearest-even image of the master copy
+                same = torch.equal(opts[k].state(i, B.BR_STATE_MASTER).to(torch.bfloat16), work[k][i])
+                rec[k].append((f"matrix {i} parameter is the BF16 image of its master", 0.0 if same else 1.0, 0.5))
+            d = weights(k, i) - W_ref[i]
+            rms = float(np.sqrt(np.mean(d ** 2)) / np.sqrt(np.mean((W_ref[i] - w0[i]) ** 2)))
+            rec[k].append((f"matrix {i} {w0[i].shape} cumulative update, root-mean-square error", rms, 5e-3 if k == 1 else TOL))
+        for i in range(len(shapes)):
+            finite = bool(torch.isfinite(work[k][i].float()).all())
+            rec[k].append((f"matrix {i} finite", 0.0 if finite else 1.0, 0.5))
+        opts[k].close()
+    return rec
 
 
-def test_stage_layer_bf16x3_mode_sampled_matrices(h):
-    """BR_MATH_BF16X3 at the stage's real shapes (one layer: 2560 x 2560, 2560 x 6912, 6912 x 2560), refresh at
-    step 4 of 5: the hi + lo split keeps the FP32 path's 1e-4 bar at full size too (weights, moments,
-    statistics and the bases entry by entry)."""
-    B, opt, params, steps, sample, hp, lr, w0 = _stage_layer(h, 2)
-    worst = _follow(h, opt, B, params, steps, sample, hp, 4, lr, w0)
-    print("stage layer BF16X3 worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
+def _assert_mode(rec, k, label):
+    worst = {}
+    for what, got, lim in rec[k]:
+        key = what.split(" ")[-2] + " " + what.split(" ")[-1]
+        if got / lim > worst.get(key, (0.0, 0.0, 0.0))[0]:
+            worst[key] = (got / lim, got, lim)
+    print(f"{label} {MODE_NAMES[k]}: worst measured/allowed by kind: "
+          + "; ".join(f"{key} {v[1]:.2e}/{v[2]:.2e}" for key, v in sorted(worst.items())))
+    bad = [(w, g, l) for w, g, l in rec[k] if not g <= l]
+    assert not bad, f"{label} {MODE_NAMES[k]}: " + "; ".join(f"{w}: {g:.3e} > {l:.3e}" for w, g, l in bad[:6])
 
 
-def test_stage_layer_bf16_mode_sampled_matrices(h):
-    """BR_MATH_BF16 at the same shapes.  Plain BF16 inputs put an error of about 2^-9 of the typical entry on
-    every product of the chain; on matrices of 6.5 to 17.7 million entries the LARGEST such error (what the
-    max-norm bar measures) sits four to five standard deviations out, and with the second moment only four
-    steps old it reaches 2.7e-2 to 3.1e-2 of the largest update entry at the first rotated step: above the 2e-2
-    that the same mode keeps on the matrices of up to 0.4 million entries of the small-size suite.  This test
-    therefore holds the maximum to 5e-2 and the root-mean-square error of the cumulative update to 5e-3
-    (measured 2.5e-3)."""
-    B, opt, params, steps, sample, hp, lr, w0 = _stage_layer(h, 1)
-    refs = {}
-    worst = _follow(h, opt, B, params, steps, sample, hp, 4, lr, w0, check_q=False, tol=5e-2, ortho=5e-5, refs=refs)
-    print("stage layer BF16 worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
-    for i in sample:
-        got = h.to_np(params[i]).astype(np.float64)
-        du_ref = refs[i] - w0[i]
-        rms = float(np.sqrt(np.mean((got - refs[i]) ** 2)) / np.sqrt(np.mean(du_ref ** 2)))
-        print(f"matrix {i}: rms error of the cumulative update {rms:.2e}")
-        assert rms <= 5e-3
+@pytest.fixture(scope="module")
+def stage_layer_records(h, request):
+    """One layer of the 3B-class stage (2560 x 2560, 2560 x 6912, 6912 x 2560 followed), FP32 parameters and
+    gradients, the configuration's own schedule: refresh every 10 steps, 12 steps."""
+    return _layer_all_modes(h, request, "stage layer", list(synth.STAGE_3B_LAYER), [0, 4, 6], bf16_io=False, seed=2)
+
+
+@pytest.fixture(scope="module")
+def llama_layer_records(h, request):
+    """One Llama-style layer at hidden 2048 (2048 x 2048, 2048 x 5632, 5632 x 2048 followed), BF16 parameters and
+    gradients with FP32 master weights and state, refresh every 10 steps, 12 steps."""
+    return _layer_all_modes(h, request, "hidden-2048 layer", list(synth.LLAMA_LAYER_2048), [0, 4, 6], bf16_io=True, seed=3)
+
+
+def test_stage_layer_f32_mode_config_schedule(h, stage_layer_records):
+    _assert_mode(stage_layer_records, 0, "stage layer")
+
+
+def test_stage_layer_bf16x3_mode_sampled_matrices(h, stage_layer_records):
+    """BR_MATH_BF16X3 at the stage's real shapes: the hi + lo split keeps the FP32 path's 1e-4 bar at full size too
+    (weights and every step's update, moments, statistics and the bases entry by entry)."""
+    _assert_mode(stage_layer_records, 2, "stage layer")
+
+
+def test_stage_layer_bf16_mode_sampled_matrices(h, stage_layer_records):
+    """BR_MATH_BF16 at the same shapes: the bare 2e-2 on every step's update and on the cumulative update, moments and
+    statistics; root-mean-square error of the cumulative update below 5e-3."""
+    _assert_mode(stage_layer_records, 1, "stage layer")
+
+
+@pytest.mark.parametrize("math", [0, 2, 1])
+def test_llama_layer_2048_bf16_config(h, llama_layer_records, math):
+    _assert_mode(llama_layer_records, math, "hidden-2048 layer")
 
 
 BF16_MODE_ORTHOGONALITY = 5e-5
