@@ -23,15 +23,10 @@ from oracle import br_oracle as oc
 from oracle.metrics import misalignment, orthogonality_defect, rel_err
 from paper_2602_03515_amd import synth
 
+from tests.tolerances import QUAD_COND_FACTOR, TOL, lapack_qr, young_moment_floor as _young_moment_floor
+from tests.tolerances import storage_floor as _floor
+
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
-
-TOL = 1e-4
-
-
-def lapack_qr(P):
-    q, r = np.linalg.qr(P)
-    d = np.where(np.diag(r) < 0, -1.0, 1.0)
-    return q * d[None, :], r * d[:, None]
 
 
 @pytest.fixture(scope="module")
@@ -42,28 +37,13 @@ def h():
     return gpu_harness
 
 
-def _floor(W, dW):
-    s = np.abs(dW).max()
-    return float(2.0 ** -23 * np.abs(W).max() / s) if s > 0 else 0.0
-
-
-def _young_moment_floor(hp, G):
-    """While the second moment is young (the first steps), Adam's quotient m / sqrt(s + eps) has
-    slope (1 - beta1) / sqrt(eps) at entries whose rotated gradient is near zero, so the FP32
-    rounding of a rotated-gradient entry (a length-K dot product: about 2^-24 times the row norm of
-    G as a standard deviation) is amplified by that slope.  Relative to
-    max|X| = (1 - beta1) / sqrt(1 - beta2) this adds 2^-24 * max_row_norm(G) * sqrt(1 - beta2) / sqrt(eps)
-    per standard deviation; the maximum over ~1e8 entries sits at 4-5 standard deviations: factor 4."""
-    row = float(np.sqrt((np.asarray(G, dtype=np.float64) ** 2).sum(axis=1)).max())
-    return 4.0 * 2.0 ** -24 * row * np.sqrt(1.0 - hp.beta2) / np.sqrt(hp.eps)
-
-
 def _follow(h, opt, B, params, grads_per_step, sample, hp, freq, lr, w0_host, check_q=True, tol=TOL,
             young_moment=False, ortho=1e-5, refs=None):
     """Drive all matrices on the GPU; the oracle follows the matrices in `sample` (its final weights
     are left in `refs` when a dict is passed)."""
     states = {i: oc.MatrixState(w0_host[i].shape[0], w0_host[i].shape[1], hp) for i in sample}
     W_ref = {i: w0_host[i].astype(np.float64) for i in sample}
+    worst_update = (0.0, 0.0, 0.0, 0.0)   # measured / allowed, measured, allowed, of which the young-moment term
     for t, grads in enumerate(grads_per_step, 1):
         opt.step(grads, lr)
         prev = {i: W_ref[i].copy() for i in sample}
@@ -75,9 +55,13 @@ def _follow(h, opt, B, params, grads_per_step, sample, hp, freq, lr, w0_host, ch
             got = h.to_np(params[i]) if params[i].dtype == torch.float32 else h.to_np(opt.state(i, B.BR_STATE_MASTER))
             e = rel_err(got - w0_host[i], W_ref[i] - w0_host[i])
             lim = tol + _floor(W_ref[i], W_ref[i] - w0_host[i])
-            if young_moment:
-                lim += _young_moment_floor(hp, grads[i].detach().float().cpu().numpy())
+            ym = _young_moment_floor(hp, grads[i].detach().float().cpu().numpy()) if young_moment else 0.0
+            lim += ym
+            if e / lim > worst_update[0]:
+                worst_update = (e / lim, e, lim, ym)
             assert e <= lim, f"step {t} matrix {i} {w0_host[i].shape}: cumulative update rel err {e:.3e} > {lim:.3e}"
+    print(f"cumulative update, worst measured/allowed: {worst_update[1]:.2e}/{worst_update[2]:.2e}"
+          + (f" (young-moment term {worst_update[3]:.2e})" if young_moment else ""))
     worst = {}
     for i in sample:
         st = states[i]
@@ -332,23 +316,18 @@ def test_stage_plus_embedding_unilateral_refresh_every_step(h):
     print("unilateral refresh-every-step worst rel errs:", {k: f"{v:.2e}" for k, v in worst.items()})
 
 
-@pytest.mark.parametrize("geometry", ["bilateral", "unilateral"])
-@pytest.mark.parametrize("tau", [0, 3, 7])
-def test_quadratic_with_delay_512x128(h, geometry, tau):
-    """Quadratic with a Kronecker-structured Hessian, 512 x 128, 500 steps under delay tau.  The
-    oracle runs the delayed trajectory; the GPU consumes the SAME gradient sequence (so that both
-    sides compute the same function of the same inputs) and is compared at steps 1, 10, 100, 500.
+# Tolerance of the 512 x 128 quadratic.  Its left statistics are ill-conditioned by construction (the Hessian's
+# eigenvalues span three decades: cond(L) is 1e4-2e4 at the refreshes), and a basis computed in FP32 is resolved only to
+# about cond * 2^-24 once the deviations of tens of refreshes have added up (tests/test_tolerance_models.py shows that on
+# the CPU: float32 statistics and a float32 LAPACK refresh along the oracle's own trajectory drift to 0.4-2.3
+# cond 2^-24 by step 500).  Bases, second moment and updates are compared at
+# 1e-4 + QUAD_COND_FACTOR * cond * 2^-24 with cond the largest condition number the oracle saw at a refresh so far;
+# every comparison prints measured / allowed, and the factor (tests/tolerances.py) is at most twice the worst ratio
+# measured (0.66: the left basis at step 500).
 
-    Tolerance: the left statistics of this problem are ill-conditioned by construction (eigenvalues of
-    the Hessian span three decades; cond(L) is about 1.5e4 at the first refresh), and the FP32 QR
-    resolves the basis only to about cond * 2^-24, so bases and updates are compared at
-    1e-4 + 8 * cond * 2^-24 with cond the largest condition number the oracle saw at a refresh."""
-    from paper_2602_03515_amd import binding as B
-    prob = synth.quadratic_problem(seed=1, m=512, n=128, noise_std=0.01)
-    hp_kw = dict(geometry=0 if geometry == "bilateral" else 1)
-    lr = 1e-2
-    checkpoints = {}
-    conds = [1.0]
+
+def _quadratic_checkpoints(h, prob, hp, lr, tau):
+    checkpoints, conds = {}, [1.0]
 
     def rec(t, st, W):
         if t % 10 == 0:
@@ -359,33 +338,83 @@ def test_quadratic_with_delay_512x128(h, geometry, tau):
             checkpoints[t] = (W.copy(), None if st.QL is None else st.QL.copy(), None if st.QR is None else st.QR.copy(),
                               st.M.copy(), st.S.copy(), max(conds))
 
-    hp = h.oracle_hyper(**hp_kw)
     st, W_end, consumed = oc.run_delayed(prob.gradient, prob.W0, hp, float(np.float32(lr)), 10, tau, 500,
                                          qr=lapack_qr, record=rec)
+    return st, consumed, checkpoints
+
+
+def _quadratic_compare(h, B, sb, w0, t, checkpoint, label, factor=QUAD_COND_FACTOR):
+    W_ref, QL, QR, M, S, cond = checkpoint
+    slack = cond * 2.0 ** -24
+    tol = TOL + factor * slack
+    got = h.to_np(sb.params[0])
+    rows = [("update", rel_err(got - w0, W_ref - w0), tol + _floor(W_ref, W_ref - w0)),
+            ("M", rel_err(h.to_np(sb.opt.state(0, B.BR_STATE_M)), M), tol),
+            ("S", rel_err(h.to_np(sb.opt.state(0, B.BR_STATE_S)), S), tol)]
+    for name, kind, Q in (("QL", B.BR_STATE_QL, QL), ("QR", B.BR_STATE_QR, QR)):
+        if Q is not None:
+            q = h.to_np(sb.opt.state(0, kind))
+            rows.append((name + " orthogonality", orthogonality_defect(q), 1e-5))
+            rows.append((name, rel_err(q, Q), tol))
+    print(f"{label} t={t} cond {cond:.2e}: " + "; ".join(
+        f"{n} {g:.2e}/{l:.2e} ({(g - TOL) / slack if n in ('update', 'S', 'QL', 'QR') else 0.0:+.2f} cond 2^-24)" for n, g, l in rows))
+    for n, g, l in rows:
+        assert g <= l, f"{label} t={t}: {n} {g:.3e} > {l:.3e} (cond {cond:.1e})"
+    return max((g - TOL) / slack for n, g, l in rows if n in ("update", "S", "QL", "QR"))
+
+
+@pytest.mark.parametrize("geometry", ["bilateral", "unilateral"])
+@pytest.mark.parametrize("tau", [0, 3, 7])
+def test_quadratic_with_delay_512x128(h, geometry, tau):
+    """Quadratic with a Kronecker-structured Hessian, 512 x 128, 500 steps under delay tau, OPEN loop: the oracle runs
+    the delayed trajectory; the GPU consumes the SAME gradient sequence (so that both sides compute the same function
+    of the same inputs) and is compared at steps 1, 10, 100, 500."""
+    from paper_2602_03515_amd import binding as B
+    prob = synth.quadratic_problem(seed=1, m=512, n=128, noise_std=0.01)
+    hp_kw = dict(geometry=0 if geometry == "bilateral" else 1)
+    lr = 1e-2
+    st, consumed, checkpoints = _quadratic_checkpoints(h, prob, h.oracle_hyper(**hp_kw), lr, tau)
     sb = h.SideBySide([prob.W0], freq=10, lr=lr, **hp_kw)
     w0 = prob.W0.astype(np.float64)
     for t, g in enumerate(consumed, 1):
         sb.opt.step([h.to_dev(g)], sb.lr)
         if t in checkpoints:
-            W_ref, QL, QR, M, S, cond = checkpoints[t]
-            tol = TOL + 8 * cond * 2.0 ** -24
-            got = h.to_np(sb.params[0])
-            e = rel_err(got - w0, W_ref - w0)
-            assert e <= tol + _floor(W_ref, W_ref - w0), f"t={t}: update err {e:.3e} (cond {cond:.1e})"
-            assert rel_err(h.to_np(sb.opt.state(0, B.BR_STATE_M)), M) <= TOL
-            assert rel_err(h.to_np(sb.opt.state(0, B.BR_STATE_S)), S) <= tol
-            for kind, Q in ((B.BR_STATE_QL, QL), (B.BR_STATE_QR, QR)):
-                if Q is not None:
-                    q = h.to_np(sb.opt.state(0, kind))
-                    assert orthogonality_defect(q) < 1e-5
-                    eq = rel_err(q, Q)
-                    assert eq <= tol, f"t={t}: basis err {eq:.3e} > {tol:.3e}"
+            _quadratic_compare(h, B, sb, w0, t, checkpoints[t], f"open loop {geometry} tau={tau}")
     # the trajectory did optimise, and the estimated right basis is better aligned with the Hessian
     # factor than the identity (bilateral: both sides)
     assert prob.loss(h.to_np(sb.params[0])) < 0.5 * prob.loss(prob.W0)
     qr_gpu = h.to_np(sb.opt.state(0, B.BR_STATE_QR))
     assert misalignment(qr_gpu, prob.H_R) < misalignment(np.eye(128), prob.H_R)
     assert abs(misalignment(qr_gpu, prob.H_R) - misalignment(st.QR, prob.H_R)) <= 1e-2 * misalignment(st.QR, prob.H_R)
+
+
+@pytest.mark.parametrize("geometry", ["bilateral", "unilateral"])
+@pytest.mark.parametrize("tau", [0, 3, 7])
+def test_quadratic_closed_loop_through_the_gradient_ring(h, geometry, tau):
+    """The same problem with the loop CLOSED on the GPU side (Appendix B, delayed-gradient equation): every step the
+    GPU's own weights are read back and pushed into GradientRing(tau); the gradient the step consumes is evaluated (on
+    the host, by the problem's own gradient function with that step's noise draw) at the ring's stale entry, i.e. at the
+    GPU's iterate W_{max(t-1-tau, 0)}.  Nothing of the oracle's trajectory enters the GPU run; the two are compared at
+    steps 1, 10, 100, 500."""
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.ring import GradientRing
+    prob = synth.quadratic_problem(seed=1, m=512, n=128, noise_std=0.01)
+    hp_kw = dict(geometry=0 if geometry == "bilateral" else 1)
+    lr = 1e-2
+    st, _, checkpoints = _quadratic_checkpoints(h, prob, h.oracle_hyper(**hp_kw), lr, tau)
+    sb = h.SideBySide([prob.W0], freq=10, lr=lr, **hp_kw)
+    w0 = prob.W0.astype(np.float64)
+    ring = GradientRing(tau)
+    ring.push(h.to_np(sb.params[0]))
+    for t in range(1, 501):
+        g = prob.gradient(ring.stale(), t)
+        sb.opt.step([h.to_dev(g)], sb.lr)
+        torch.cuda.synchronize()
+        ring.push(h.to_np(sb.params[0]))
+        assert len(ring) == min(t + 1, tau + 1)
+        if t in checkpoints:
+            _quadratic_compare(h, B, sb, w0, t, checkpoints[t], f"closed loop {geometry} tau={tau}")
+    assert prob.loss(h.to_np(sb.params[0])) < 0.5 * prob.loss(prob.W0)
 
 
 @pytest.mark.parametrize("m,math", [(13000, 0), (13000, 1), (32000, 0)])
