@@ -120,6 +120,14 @@ typedef struct {
   int32_t eps_outside_sqrt; /* 1: m / (sqrt(s) + eps);            0 = Algorithm 1        */
   int32_t math;        /* br_math                                                        */
   int32_t compute_norms;    /* 1: keep ||G~||_F^2, ||X||_F^2 per matrix (BR_STATE_NORMS) */
+  int32_t stats_on_refresh_only; /* 0: L, R are accumulated at every step (br_accumulate_stats).
+                          1: Algorithm 2 as it is called from Algorithm 1: L and R are updated inside
+                          Eigenbasis-Estimation, i.e. only from the gradient of a step whose
+                          br_refresh_basis runs; br_accumulate_stats then only keeps the gradient
+                          pointers (they must stay valid until br_step, as they must anyway) and
+                          br_refresh_basis folds that gradient into L, R before its Power calls.  A
+                          br_refresh_basis that is not preceded by this step's br_accumulate_stats
+                          uses the statistics as they stand.                                    */
   int32_t cache_rotated_moment; /* 1: also keep M~ = Q_L^T M Q_R in the state and, while the
                           basis is unchanged, advance it by M~ <- beta1 M~ + (1-beta1) G~
                           (equal to rotating M, by linearity) instead of rotating M every
@@ -250,6 +258,31 @@ br_status br_get_state(br_ctx* ctx, int32_t mat, int32_t which, void** dev_ptr, 
  * Not needed after restoring a whole-state checkpoint taken between steps.
  */
 br_status br_notify_state_written(br_ctx* ctx);
+
+/*
+ * Health words: BR_HEALTH_WORDS (4) int32 counters in the state part of the workspace, zero from
+ * br_init on, that kernels bump when something went wrong:
+ *   [0]  a workgroup cluster of the QR panel kernel gave up its bounded wait for its partners (all
+ *        workgroups of a panel launch must be resident at once; the launches are sized for a GPU that
+ *        the library has to itself, and work on other streams can starve a cluster).  The bases of the
+ *        affected matrices are left as they were BEFORE that refresh: nothing non-finite reaches
+ *        the weights, the refresh is simply lost for them;
+ *   [1]  a weight that is not finite was stored by br_step (counted per wavefront that saw one).
+ * br_get_health returns the device pointer (no synchronisation; readable from a caller's own kernel
+ * or copy).  br_check_health copies the words to the host, which SYNCHRONISES the stream (not
+ * allowed while capturing), writes them to `counts` (4 values, may be NULL) and returns
+ * BR_ERR_STATE with a text for br_last_error when any is non-zero, BR_OK otherwise.  The counters
+ * are never reset by the library (they are part of a checkpoint); a caller may zero them.
+ */
+br_status br_get_health(br_ctx* ctx, void** dev_ptr);
+br_status br_check_health(br_ctx* ctx, int32_t* counts);
+
+/*
+ * Bound of the QR panel clusters' wait, in polls of one exchanged value (default 2^22, about a
+ * second; negative restores it).  0 makes every exchange give up at once without polling: the
+ * failure path, forced from the host so that every kernel still ends normally (used by the tests).
+ */
+br_status br_set_qr_wait_limit(br_ctx* ctx, int64_t polls);
 
 /* Number of completed steps t, and a way to set it when restoring a checkpoint. */
 br_status br_get_step_count(const br_ctx* ctx, int64_t* t);

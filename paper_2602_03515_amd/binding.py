@@ -44,7 +44,8 @@ class br_hparams(C.Structure):
     _fields_ = [("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float),
                 ("stat_beta", C.c_float), ("geometry", C.c_int32), ("source", C.c_int32),
                 ("power_iters", C.c_int32), ("bias_correction", C.c_int32), ("eps_outside_sqrt", C.c_int32),
-                ("math", C.c_int32), ("compute_norms", C.c_int32), ("cache_rotated_moment", C.c_int32)]
+                ("math", C.c_int32), ("compute_norms", C.c_int32), ("stats_on_refresh_only", C.c_int32),
+                ("cache_rotated_moment", C.c_int32)]
 
 
 class br_profile_entry(C.Structure):
@@ -79,6 +80,12 @@ _lib.br_step.restype = C.c_int
 _lib.br_get_state.argtypes = [_ctx_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_int64),
                               C.POINTER(C.c_int64)]
 _lib.br_get_state.restype = C.c_int
+_lib.br_get_health.argtypes = [_ctx_p, C.POINTER(C.c_void_p)]
+_lib.br_get_health.restype = C.c_int
+_lib.br_check_health.argtypes = [_ctx_p, C.POINTER(C.c_int32)]
+_lib.br_check_health.restype = C.c_int
+_lib.br_set_qr_wait_limit.argtypes = [_ctx_p, C.c_int64]
+_lib.br_set_qr_wait_limit.restype = C.c_int
 _lib.br_notify_state_written.argtypes = [_ctx_p]
 _lib.br_notify_state_written.restype = C.c_int
 _lib.br_get_step_count.argtypes = [_ctx_p, C.POINTER(C.c_int64)]
@@ -99,7 +106,7 @@ _lib.br_destroy.restype = None
 BR_STATIC_CLIP_MAX_MATS = 4096
 
 EXPORTED = ["br_workspace_bytes", "br_init", "br_delay_compensate", "br_clip_gradients", "br_clip_gradients_static", "br_get_clip_result", "br_accumulate_stats", "br_refresh_basis", "br_step", "br_get_state",
-            "br_notify_state_written", "br_get_step_count", "br_set_step_count", "br_profile_begin", "br_profile_end", "br_last_error",
+            "br_get_health", "br_check_health", "br_set_qr_wait_limit", "br_notify_state_written", "br_get_step_count", "br_set_step_count", "br_profile_begin", "br_profile_end", "br_last_error",
             "br_version", "br_destroy"]
 
 
@@ -127,10 +134,10 @@ def make_descs(shapes: Sequence, param_dtype=BR_F32, grad_dtype=BR_F32, rotate=1
 
 def make_hparams(beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, stat_beta=-1.0, geometry=BR_BILATERAL,
                  source=BR_SRC_SECOND, power_iters=1, bias_correction=0, eps_outside_sqrt=0, math=BR_MATH_F32,
-                 compute_norms=0, cache_rotated_moment=1) -> br_hparams:
+                 compute_norms=0, cache_rotated_moment=1, stats_on_refresh_only=0) -> br_hparams:
     return br_hparams(beta1, beta2, eps, weight_decay, stat_beta, geometry, source, power_iters,
                       int(bias_correction), int(eps_outside_sqrt), math, int(compute_norms),
-                      int(cache_rotated_moment))
+                      int(stats_on_refresh_only), int(cache_rotated_moment))
 
 
 def _ptr_array(ptrs: Sequence[int]):
@@ -206,6 +213,27 @@ def br_get_state(ctx, mat: int, which: int):
     p, r, c = C.c_void_p(), C.c_int64(), C.c_int64()
     _check(_lib.br_get_state(ctx, mat, which, C.byref(p), C.byref(r), C.byref(c)), "br_get_state", ctx)
     return p.value, r.value, c.value
+
+
+BR_HEALTH_QR_GAVE_UP, BR_HEALTH_NONFINITE_WEIGHT, BR_HEALTH_WORDS = 0, 1, 4
+
+
+def br_get_health(ctx) -> int:
+    """Device pointer to the BR_HEALTH_WORDS int32 health counters (no synchronisation)."""
+    p = C.c_void_p()
+    _check(_lib.br_get_health(ctx, C.byref(p)), "br_get_health", ctx)
+    return p.value
+
+
+def br_check_health(ctx):
+    """Synchronises; returns the four counters, raises BrError(BR_ERR_STATE) when any is non-zero."""
+    counts = (C.c_int32 * BR_HEALTH_WORDS)()
+    _check(_lib.br_check_health(ctx, counts), "br_check_health", ctx)
+    return list(counts)
+
+
+def br_set_qr_wait_limit(ctx, polls: int):
+    _check(_lib.br_set_qr_wait_limit(ctx, polls), "br_set_qr_wait_limit", ctx)
 
 
 def br_notify_state_written(ctx):

@@ -22,6 +22,8 @@ constexpr int kLowpChunk = 16;      // matrices per batched step launch in the B
 constexpr int64_t kMaxDim = 1 << 24;
 constexpr size_t kNormPartialBytes = (size_t)BR_MAXB * 2 * BR_NORM_BLOCKS * sizeof(float);
 constexpr size_t kSplitKBytes = (size_t)64 << 20;  // partial products of the QR's split-K contractions
+constexpr size_t kFailFlagBytes = 256;             // one int per factor of a refresh unit: "its factorisation was abandoned"
+static_assert(BR_MAXB * sizeof(int) <= kFailFlagBytes, "one flag per matrix of a batched launch");
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -82,8 +84,15 @@ struct br_ctx {
   char* phase = nullptr;  // scratch shared by the phases of a step (after the norm partials and the gradient planes)
   bool qplanes_valid = false;  // BF16 math modes: the bases' operand planes match the bases
   float* clip_result = nullptr;  // 2 floats at the end of the state region
+  int* health = nullptr;         // BR_HEALTH_WORDS counters behind them
+  unsigned qr_spin_limit = BR_QR_SPIN_LIMIT_DEFAULT;
   int64_t t = 0;
   bool stats_fresh = false;
+  int g32_group = -1;            // group whose FP32 images of BF16 gradients, written by br_accumulate_stats, are still in the
+                                 // scratch at br_step: only when it is the context's ONLY rotated group and a single chunk
+                                 // (groups and chunks take turns on the same scratch, in both calls); -1: none
+  bool stats_pending = false;    // stats_on_refresh_only: this step's gradients have not been folded into L, R
+  std::vector<const void*> pending_grads;
   bool mrot_valid = true;  // cached M~ equals Q_L^T M Q_R (true at t = 0: both are zero)
   bool dead = false;
   std::string err;
@@ -125,6 +134,7 @@ br_status validate(const br_matrix_desc* descs, int32_t n_mats, const br_hparams
   if (!(hp->stat_beta < 1.f)) { *why = "stat_beta must be below 1 (negative selects beta2)"; return BR_ERR_INVALID_ARG; }
   if (!(hp->eps >= 0.f) || !(hp->weight_decay >= 0.f)) { *why = "eps and weight_decay must be non-negative"; return BR_ERR_INVALID_ARG; }
   if (hp->cache_rotated_moment != 0 && hp->cache_rotated_moment != 1) { *why = "cache_rotated_moment must be 0 or 1"; return BR_ERR_INVALID_ARG; }
+  if (hp->stats_on_refresh_only != 0 && hp->stats_on_refresh_only != 1) { *why = "stats_on_refresh_only must be 0 or 1"; return BR_ERR_INVALID_ARG; }
   for (int i = 0; i < n_mats; ++i) {
     const br_matrix_desc& d = descs[i];
     if (d.m <= 0 || d.n <= 0 || d.m > kMaxDim || d.n > kMaxDim) { *why = "matrix " + std::to_string(i) + ": dimensions must be in 1..2^24"; return BR_ERR_SHAPE; }
@@ -284,12 +294,13 @@ void plan(const br_matrix_desc* descs, int32_t n_mats, const br_hparams& hp, Lay
       RefreshUnit u;
       u.k = kv.first;
       u.jobs.assign(kv.second.begin() + lo, kv.second.begin() + hi);
-      refresh_bytes = std::max(refresh_bytes, align256(u.jobs.size() * refresh_scratch(u.k, hp).total + kSplitKBytes));
+      refresh_bytes = std::max(refresh_bytes, align256(u.jobs.size() * refresh_scratch(u.k, hp).total + kFailFlagBytes + kSplitKBytes));
       lay->units.push_back(u);
     }
   }
   scratch = std::max(scratch, refresh_bytes);
   state += 256;  // global gradient norm and clipping factor
+  state += 256;  // health words
   lay->state_bytes = state;
   lay->scratch_bytes = scratch + kNormPartialBytes + lay->gplane_bytes;
 }
@@ -340,7 +351,9 @@ bool gemm(br_ctx* c, BrGemmArgs a, const BrGemmBatch& b, bool step = true, float
     const char* name = nullptr;
     double flops = 2.0 * a.M * a.N * (double)a.K * a.batch;
     if (a.mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (a.M + 127) / 128));
-    (void)br_launch_gemm(nullptr, BrGemmArgs{0, 0, 0, 0, 0, 0, a.transA, a.transB, 0, 0, 0, 0}, b, &name);
+    BrGemmArgs probe{0, 0, 0, 0, 0, 0, a.transA, a.transB, 0, 0, 0, 0};
+    probe.adam_epilogue = a.adam_epilogue;
+    (void)br_launch_gemm(nullptr, probe, b, &name);
     Timed tm(c, name, flops, 0.0);
     return hip_ok(c, br_launch_gemm(c->stream, a, b, nullptr), "gemm launch");
   }
@@ -381,7 +394,7 @@ bool lowp_split(const LowpCtx& x, const float* const* src, int R, int Ccols, boo
 bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp, int N, int K, float* const* C, int ldc,
                float alpha, float beta, uint16_t* const* out16, bool mirror, int nprod = 0, int epilogue = BR_EPI_F32,
                const BrAdamArgs* adam = nullptr, float* const* S = nullptr, float* const* Mrot = nullptr,
-               bool adam_transposed = false) {
+               bool adam_transposed = false, int* health = nullptr) {
   if (nprod == 0) nprod = x.nprod;
   BrLowpBatch b;
   std::memset(&b, 0, sizeof(b));
@@ -398,6 +411,7 @@ bool lowp_gemm(const LowpCtx& x, uint16_t* const* A, int M, uint16_t* const* Bp,
   a.out_lo = (x.nprod == 3) ? 1 : 0;
   if (adam) a.adam = *adam;
   a.adam_transposed = adam_transposed ? 1 : 0;
+  a.health = health;
   double flops = 2.0 * M * N * (double)K * x.B;
   if (mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (M + 255) / 256));
   if (x.quiet) return hip_ok(x.c, br_launch_gemm_lowp(x.c->stream, a, b, nullptr), "bf16 gemm launch");
@@ -492,10 +506,10 @@ bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* con
       if (!lowp_gemm(x, GTP, n, QLt, m, m, nullptr, 0, 1.f, 0.f, T1P, false, 0, BR_EPI_PLANES)) return false;            // T
       if (!lowp_gemm(x, T1P, m, QRt, n, n, nullptr, n, 1.f, 0.f, XTP, false, 0, BR_EPI_ADAM, &aa, Sp, Mt)) return false;  // X^T
       if (!lowp_gemm(x, XTP, n, QLp, m, m, nullptr, 0, 1.f, 0.f, YP, false, 0, BR_EPI_PLANES)) return false;             // Y
-      return lowp_gemm(x, YP, m, QRp, n, n, Wp, n, -lr, decay, shadow, false);                                          // W
+      return lowp_gemm(x, YP, m, QRp, n, n, Wp, n, -lr, decay, shadow, false, 0, BR_EPI_F32, nullptr, nullptr, nullptr, false, c->health);                                          // W
     }
     if (!lowp_gemm(x, QLt, m, GTP, n, m, nullptr, n, 1.f, 0.f, XTP, false, 0, BR_EPI_ADAM, &aa, Sp, Mt)) return false;    // X^T
-    return lowp_gemm(x, QLp, m, XTP, n, m, Wp, n, -lr, decay, shadow, false);                                            // W -= lr Q_L X
+    return lowp_gemm(x, QLp, m, XTP, n, m, Wp, n, -lr, decay, shadow, false, 0, BR_EPI_F32, nullptr, nullptr, nullptr, false, c->health);                                            // W -= lr Q_L X
   }
   if (!aa.compute_norms && g.rot_r) {  // right factor only, fused: G~^T = Q_R^T G^T carries Adam, X leaves as planes
     uint16_t* XP[BR_MAXB];
@@ -506,7 +520,7 @@ bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* con
       if (!lowp_gemm(x, P0, m, QRt, n, n, Mt, n, 1.f, 0.f, nullptr, false)) return false;
     }
     if (!lowp_gemm(x, QRt, n, GP, m, n, nullptr, n, 1.f, 0.f, XP, false, 0, BR_EPI_ADAM, &aa, Sp, Mt, true)) return false;  // X
-    return lowp_gemm(x, XP, m, QRp, n, n, Wp, n, -lr, decay, shadow, false);                                              // W -= lr X Q_R^T
+    return lowp_gemm(x, XP, m, QRp, n, n, Wp, n, -lr, decay, shadow, false, 0, BR_EPI_F32, nullptr, nullptr, nullptr, false, c->health);                                              // W -= lr X Q_R^T
   }
   // rotate one m x n matrix into `out`; its planes are given (gradient) or made here from `in` (first moment)
   auto rotate_in = [&](const float* const* in, uint16_t* const* in_p, uint16_t* const* in_tp, float* const* out, int s_t,
@@ -558,14 +572,14 @@ bool lowp_step(const LowpCtx& x, size_t off, const float* const* G32, float* con
     if (!lowp_gemm(x, QLp, m, P0, n, m, dst, n, 1.f, 0.f, nullptr, false)) return false;       // Y = Q_L X
     for (int i = 0; i < B; ++i) { src[i] = x.slot32(i, LS_T1); P1[i] = x.slot16(i, LS_T1P); }
     if (!lowp_split(x, src, m, n, false, P1)) return false;
-    return lowp_gemm(x, P1, m, QRp, n, n, Wp, n, -lr, decay, shadow, false);                  // W -= lr Y Q_R^T
+    return lowp_gemm(x, P1, m, QRp, n, n, Wp, n, -lr, decay, shadow, false, 0, BR_EPI_F32, nullptr, nullptr, nullptr, false, c->health);                  // W -= lr Y Q_R^T
   }
   if (g.rot_l) {
     if (!lowp_split(x, src, m, n, true, P0)) return false;
-    return lowp_gemm(x, QLp, m, P0, n, m, Wp, n, -lr, decay, shadow, false);                  // W -= lr Q_L X
+    return lowp_gemm(x, QLp, m, P0, n, m, Wp, n, -lr, decay, shadow, false, 0, BR_EPI_F32, nullptr, nullptr, nullptr, false, c->health);                  // W -= lr Q_L X
   }
   if (!lowp_split(x, src, m, n, false, P0)) return false;
-  return lowp_gemm(x, P0, m, QRp, n, n, Wp, n, -lr, decay, shadow, false);                    // W -= lr X Q_R^T
+  return lowp_gemm(x, P0, m, QRp, n, n, Wp, n, -lr, decay, shadow, false, 0, BR_EPI_F32, nullptr, nullptr, nullptr, false, c->health);                    // W -= lr X Q_R^T
 }
 
 }  // namespace
@@ -647,6 +661,7 @@ br_status br_init(br_ctx** out, const br_matrix_desc* descs, int32_t n_mats, con
     }
   }
   c->clip_result = reinterpret_cast<float*>(p);
+  c->health = reinterpret_cast<int*>(p + 256);
   c->scratch = reinterpret_cast<char*>(dev_workspace) + c->lay.state_bytes;
   c->phase = c->scratch + kNormPartialBytes + c->lay.gplane_bytes;
   // zero state, identity bases
@@ -737,6 +752,41 @@ static br_status check_call(br_ctx* ctx, const void* const* a, const void* const
   return BR_OK;
 }
 
+br_status br_get_health(br_ctx* ctx, void** dev_ptr) {
+  if (!ctx || !dev_ptr) return BR_ERR_INVALID_ARG;
+  *dev_ptr = ctx->health;
+  return BR_OK;
+}
+
+br_status br_check_health(br_ctx* ctx, int32_t* counts) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  if (ctx->dead) return BR_ERR_HIP;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(ctx->stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+    return fail(ctx, BR_ERR_STATE, "br_check_health synchronises and cannot run while the stream is being captured");
+  int32_t h[BR_HEALTH_WORDS] = {0, 0, 0, 0};
+  if (!hip_ok(ctx, hipMemcpyAsync(h, ctx->health, sizeof(h), hipMemcpyDeviceToHost, ctx->stream), "health copy")) return BR_ERR_HIP;
+  if (!hip_ok(ctx, hipStreamSynchronize(ctx->stream), "health sync")) return BR_ERR_HIP;
+  if (counts) std::memcpy(counts, h, sizeof(h));
+  if (h[BR_HEALTH_QR_GAVE_UP] == 0 && h[BR_HEALTH_NONFINITE_WEIGHT] == 0) return BR_OK;
+  std::string msg;
+  if (h[BR_HEALTH_QR_GAVE_UP])
+    msg += "a QR panel cluster gave up waiting for its partner workgroups " + std::to_string(h[BR_HEALTH_QR_GAVE_UP]) +
+           " time(s): the affected bases were left as they were before that refresh (was the GPU shared with other work?)";
+  if (h[BR_HEALTH_NONFINITE_WEIGHT]) {
+    if (!msg.empty()) msg += "; ";
+    msg += "non-finite weights were stored (" + std::to_string(h[BR_HEALTH_NONFINITE_WEIGHT]) + " wavefront(s) saw one)";
+  }
+  return fail(ctx, BR_ERR_STATE, msg);
+}
+
+br_status br_set_qr_wait_limit(br_ctx* ctx, int64_t polls) {
+  if (!ctx) return BR_ERR_INVALID_ARG;
+  if (polls > 0xffffffffLL) return fail(ctx, BR_ERR_INVALID_ARG, "wait limit must fit 32 bits");
+  ctx->qr_spin_limit = polls < 0 ? BR_QR_SPIN_LIMIT_DEFAULT : (unsigned)polls;
+  return BR_OK;
+}
+
 br_status br_get_clip_result(br_ctx* ctx, void** dev_ptr) {
   if (!ctx || !dev_ptr) return BR_ERR_INVALID_ARG;
   *dev_ptr = ctx->clip_result;
@@ -809,12 +859,69 @@ br_status br_clip_gradients(br_ctx* ctx, void* const* grads, int32_t n_mats, flo
   return BR_OK;
 }
 
+// a2 in BR_MATH_F32 for one chunk of a group: L <- b L + (1-b) G G^T, R <- b R + (1-b) G^T G (Algorithm 2,
+// updates of L and R) from the FP32 gradients g32.
+static bool stats_chunk_f32(br_ctx* c, const Group& g, size_t off, int B, const float* const* g32) {
+  const br_hparams& hp = c->hp;
+  BrGemmBatch gb;
+  std::memset(&gb, 0, sizeof(gb));
+  if (g.rot_l) {  // L <- b L + (1-b) G G^T
+    for (int i = 0; i < B; ++i) { gb.A[i] = g32[i]; gb.B[i] = g32[i]; gb.C[i] = c->mats[g.idx[off + i]].L; }
+    BrGemmArgs a{(int)g.m, (int)g.m, (int)g.n, (int)g.n, (int)g.n, (int)g.m, 0, 1, 1.0f - hp.stat_beta, hp.stat_beta, B, 1};
+    if (!gemm(c, a, gb)) return false;
+  }
+  if (g.rot_r) {  // R <- b R + (1-b) G^T G
+    for (int i = 0; i < B; ++i) { gb.A[i] = g32[i]; gb.B[i] = g32[i]; gb.C[i] = c->mats[g.idx[off + i]].R; }
+    BrGemmArgs a{(int)g.n, (int)g.n, (int)g.m, (int)g.n, (int)g.n, (int)g.n, 1, 0, 1.0f - hp.stat_beta, hp.stat_beta, B, 1};
+    if (!gemm(c, a, gb)) return false;
+  }
+  return true;
+}
+
+// stats_on_refresh_only: the statistics update that br_accumulate_stats left out, from the gradient
+// pointers it kept (Algorithm 2 updates L and R inside Eigenbasis-Estimation, which Algorithm 1 calls
+// on refresh steps only).  Runs at the start of br_refresh_basis, before the refresh takes the scratch.
+static bool fold_pending_statistics(br_ctx* c) {
+  const br_hparams& hp = c->hp;
+  for (const Group& g : c->lay.groups) {
+    if (!(g.rot_l || g.rot_r) || hp.source != BR_SRC_SECOND) continue;
+    const int64_t count = g.m * g.n;
+    const size_t mn = align256((size_t)count * 4);
+    const int nbuf = step_buffers(g, hp);
+    const bool lowp = hp.math != BR_MATH_F32;
+    const size_t chunk = lowp ? g.lowp_chunk : kStepChunk;
+    for (size_t off = 0; off < g.idx.size(); off += chunk) {
+      const int B = (int)std::min<size_t>(chunk, g.idx.size() - off);
+      if (lowp) {  // the gradients' operand planes were made by br_accumulate_stats and live until br_step
+        LowpCtx lx{c, &g, lowp_layout(g), B, hp.math == BR_MATH_BF16X3 ? 3 : 1, c->phase};
+        if (!lowp_stats(lx, nullptr, off, true, true)) return false;
+        continue;
+      }
+      const float* g32[kStepChunk];
+      for (int i = 0; i < B; ++i) {
+        const void* gp = c->pending_grads[g.idx[off + i]];
+        if (g.gdt == BR_BF16) {
+          float* dst = scratch_buf(c, nbuf, mn, i, nbuf - 1);
+          if (!hip_ok(c, br_launch_bf16_to_f32(c->stream, reinterpret_cast<const uint16_t*>(gp), dst, count), "gradient widen")) return false;
+          g32[i] = dst;
+        } else {
+          g32[i] = reinterpret_cast<const float*>(gp);
+        }
+      }
+      if (!stats_chunk_f32(c, g, off, B, g32)) return false;
+    }
+  }
+  return true;
+}
+
 br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_mats) {
   br_status st = check_call(ctx, grads, nullptr, false, n_mats);
   if (st != BR_OK) return st;
   br_ctx* c = ctx;
   if (c->stats_fresh) return fail(c, BR_ERR_STATE, "br_accumulate_stats called twice without br_step");
   const br_hparams& hp = c->hp;
+  // Statistics now (every step), or left to this step's br_refresh_basis, if there is one (Algorithm 2 as printed)
+  const bool stats_now = hp.source == BR_SRC_SECOND && !hp.stats_on_refresh_only;
   for (const Group& g : c->lay.groups) {
     const int64_t count = g.m * g.n;
     const size_t mn = align256((size_t)count * 4);
@@ -850,7 +957,7 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
           if (!hip_ok(c, br_launch_ingest_planes(c->stream, g32, Mp, gp, gtp, B, (int)g.m, (int)g.n, hp.beta1, lo),
                       "ingest launch")) return BR_ERR_HIP;
         }
-        if (!lowp_stats(lx, g32, off, hp.source == BR_SRC_SECOND, true)) return BR_ERR_HIP;
+        if (!lowp_stats(lx, g32, off, stats_now, true)) return BR_ERR_HIP;
         continue;
       }
       {
@@ -859,25 +966,29 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
         if (!hip_ok(c, br_launch_ema(c->stream, pb, B, count, g.gdt == BR_BF16, hp.beta1), "first-moment launch")) return BR_ERR_HIP;
       }
       if (lowp) {
-        if (!lowp_stats(lx, g32, off, hp.source == BR_SRC_SECOND)) return BR_ERR_HIP;
+        if (!lowp_stats(lx, g32, off, stats_now)) return BR_ERR_HIP;
         continue;
       }
-      if (hp.source != BR_SRC_SECOND || !rotated) continue;
-      BrGemmBatch gb;
-      std::memset(&gb, 0, sizeof(gb));
-      if (g.rot_l) {  // L <- b L + (1-b) G G^T
-        for (int i = 0; i < B; ++i) { gb.A[i] = g32[i]; gb.B[i] = g32[i]; gb.C[i] = c->mats[g.idx[off + i]].L; }
-        BrGemmArgs a{(int)g.m, (int)g.m, (int)g.n, (int)g.n, (int)g.n, (int)g.m, 0, 1, 1.0f - hp.stat_beta, hp.stat_beta, B, 1};
-        if (!gemm(c, a, gb)) return BR_ERR_HIP;
-      }
-      if (g.rot_r) {  // R <- b R + (1-b) G^T G
-        for (int i = 0; i < B; ++i) { gb.A[i] = g32[i]; gb.B[i] = g32[i]; gb.C[i] = c->mats[g.idx[off + i]].R; }
-        BrGemmArgs a{(int)g.n, (int)g.n, (int)g.m, (int)g.n, (int)g.n, (int)g.n, 1, 0, 1.0f - hp.stat_beta, hp.stat_beta, B, 1};
-        if (!gemm(c, a, gb)) return BR_ERR_HIP;
-      }
+      if (!stats_now || !rotated) continue;
+      if (!stats_chunk_f32(c, g, off, B, g32)) return BR_ERR_HIP;
     }
   }
   c->stats_fresh = true;
+  c->g32_group = -1;
+  {
+    int rotated_groups = 0, only = -1;
+    for (size_t gi = 0; gi < c->lay.groups.size(); ++gi)
+      if (c->lay.groups[gi].rot_l || c->lay.groups[gi].rot_r) { ++rotated_groups; only = (int)gi; }
+    if (rotated_groups == 1) {
+      const Group& g = c->lay.groups[only];
+      const size_t chunk = hp.math != BR_MATH_F32 ? g.lowp_chunk : (size_t)kStepChunk;
+      if (g.gdt == BR_BF16 && g.idx.size() <= chunk) c->g32_group = only;
+    }
+  }
+  if (hp.stats_on_refresh_only && hp.source == BR_SRC_SECOND) {
+    c->pending_grads.assign(grads, grads + n_mats);
+    c->stats_pending = true;
+  }
   return BR_OK;
 }
 
@@ -892,8 +1003,10 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 //       [ 0     T_1                 ]
 // The top block is applied to the trailing matrix, and later to Q, with K = BR_QR_NBT
 // contractions (the longer K is, the closer those run to the rate of a step contraction).
+// failed: B ints of scratch; a matrix whose panel clusters gave up their bounded wait gets its flag set
+// by the panel kernel, and every launch that writes Q then leaves that matrix's previous basis alone.
 static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs,
-                     char* base, size_t stride, float* partial) {
+                     char* base, size_t stride, float* partial, int* failed) {
   const int NB = BR_QR_NB, NBM = BR_QR_NBM;
   const int levels = qr_levels(c->hp);
   const int NBT = NBM << levels;  // width of a top block
@@ -918,7 +1031,10 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     int* xp[BR_MAXB];
     for (int i = 0; i < B; ++i) xp[i] = reinterpret_cast<int*>(F(i, rs.xch));
     if (!hip_ok(c, br_launch_zero_ints(s, xp, B, (int)br_qr_panel_xch_floats(k)), "exchange clear launch")) return false;
+    int* fp[1] = {failed};
+    if (!hip_ok(c, br_launch_zero_ints(s, fp, 1, BR_MAXB), "failure flag clear launch")) return false;
   }
+  const int* skip_q = nullptr;  // set for the phase that writes Q
   // The update both phases share: C <- C - Yb (V^T C) for the rows x ncols blocks C (row stride k), with
   // Yb = V T^T or V T already in Y.  BR_MATH_BF16 runs its two contractions on the BF16 matrix cores
   // with hi + lo split operands and three partial products (16-bit mantissa inputs, FP32
@@ -951,7 +1067,9 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       for (int i = 0; i < B; ++i) { gb.A[i] = Vb[i]; gb.B[i] = Cp[i]; gb.C[i] = W(i); }
       if (!mm(BrGemmArgs{width, ncols, rows, NBT, k, ncols, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
       for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Cp[i]; }
-      return mm(BrGemmArgs{rows, ncols, width, width, ncols, k, 0, 0, -1.f, 1.f, B, 0}, gb);
+      BrGemmArgs ua{rows, ncols, width, width, ncols, k, 0, 0, -1.f, 1.f, B, 0};
+      ua.skip = skip_q;
+      return mm(ua, gb);
     }
     const float* src[BR_MAXB];
     uint16_t *pv[BR_MAXB], *py[BR_MAXB], *pw[BR_MAXB];
@@ -980,6 +1098,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       if (emit) lb.S[i] = reinterpret_cast<float*>(view(set, i, row0, k0));  // the updated C^T, for the next block
     }
     BrLowpArgs ua{rows, ncols, width, k, -1.f, 1.f, B, 0, 3};
+    ua.skip = skip_q;
     if (emit) {
       ua.out_lo = 1;
       ua.emit_transposed = 1;
@@ -1013,7 +1132,10 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
           pb.T[i] = Tp(i, pnl);
           pb.diag[i] = D(i) + j0;
           cb.xch[i] = reinterpret_cast<unsigned long long*>(F(i, rs.xch));
+          cb.failed[i] = failed + i;
         }
+        cb.health = c->health;
+        cb.spin_limit = c->qr_spin_limit;
         cb.tag0 = (unsigned)(j0 / NB) * 64u;
         if (!hip_ok(c, br_launch_qr_panel(s, pb, cb, B, prow, nb, k, NBT, voff), "qr panel launch")) return false;
         const int nin = c0 + ncols - (j0 + nb);  // columns of the middle block still to the right
@@ -1105,7 +1227,8 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
   // The identity carries the signs that make diag(R) >= 0 (a column of Q flips with its sign).
   const float* dg[BR_MAXB];
   for (int i = 0; i < B; ++i) dg[i] = D(i);
-  if (!hip_ok(c, br_launch_qr_signed_identity(s, Q, dg, B, k), "signed identity launch")) return false;
+  skip_q = failed;  // from here on Q is written: an abandoned factorisation keeps its previous basis
+  if (!hip_ok(c, br_launch_qr_signed_identity(s, Q, dg, B, k, skip_q), "signed identity launch")) return false;
   if (x3 && !split_whole(Q, rs.planesB)) return false;
   for (int tb = ntop - 1; tb >= 0; --tb) {
     const int S0 = tb * NBT;
@@ -1132,6 +1255,11 @@ br_status br_refresh_basis(br_ctx* ctx) {
   br_ctx* c = ctx;
   const br_hparams& hp = c->hp;
   char* base = c->phase;
+  if (c->stats_pending) {
+    if (!fold_pending_statistics(c)) return BR_ERR_HIP;
+    c->stats_pending = false;
+  }
+  c->g32_group = -1;      // the refresh takes the scratch that held the FP32 images of BF16 gradients
   c->mrot_valid = false;  // the bases change: M~ must be rebuilt from M at the next step
   c->qplanes_valid = false;
   for (const RefreshUnit& u : c->lay.units) {
@@ -1193,8 +1321,9 @@ br_status br_refresh_basis(br_ctx* ctx) {
     }
     {
       Timed tm(c, "qr_householder(region)", (8.0 / 3.0) * (double)k * k * k * B, 0.0);
-      float* part = reinterpret_cast<float*>(base + (size_t)B * rs.total);
-      if (!qr_batch(c, c->stream, B, k, src, Q, rs, base, rs.total, part)) return BR_ERR_HIP;
+      int* failed = reinterpret_cast<int*>(base + (size_t)B * rs.total);
+      float* part = reinterpret_cast<float*>(base + (size_t)B * rs.total + kFailFlagBytes);
+      if (!qr_batch(c, c->stream, B, k, src, Q, rs, base, rs.total, part, failed)) return BR_ERR_HIP;
     }
   }
   return BR_OK;
@@ -1266,18 +1395,23 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
           pb.out0[i] = ms.S;
           pb.out1[i] = Wp[i];
         }
-        BrPlainArgs pa{hp.beta2, hp.eps, aa.c1, aa.c2, lr, decay, hp.eps_outside_sqrt, g.gdt == BR_BF16};
+        BrPlainArgs pa{hp.beta2, hp.eps, aa.c1, aa.c2, lr, decay, hp.eps_outside_sqrt, g.gdt == BR_BF16, c->health};
         double bytes = (double)count * B * (4.0 + 8.0 + 8.0 + (g.gdt == BR_BF16 ? 2.0 : 4.0) + (g.pdt == BR_BF16 ? 2.0 : 0.0));
         Timed tm(c, "br_adam_plain", 10.0 * count * B, bytes);
         if (!hip_ok(c, br_launch_adam_plain(c->stream, pb, shadow, B, count, pa), "plain adam launch")) return BR_ERR_HIP;
         continue;
       }
-      // FP32 image of BF16 gradients
+      // FP32 image of BF16 gradients.  The fused chain of the BF16 modes reads the gradients' operand planes
+      // only and needs none.  Otherwise br_accumulate_stats wrote the same images into the same slots; they are
+      // still there when nothing else has used the scratch since (a single rotated group, no refresh).
+      const bool image_unused = lowp && !aa.compute_norms;
+      const bool image_kept = image_unused || (c->g32_group >= 0 && &g == &c->lay.groups[c->g32_group]);
       for (int i = 0; i < B; ++i) {
         const void* gp = grads[g.idx[off + i]];
         if (g.gdt == BR_BF16) {
           float* dst = lowp ? lx.slot32(i, LS_G32) : scratch_buf(c, nbuf, mn, i, nbuf - 1);
-          if (!hip_ok(c, br_launch_bf16_to_f32(c->stream, reinterpret_cast<const uint16_t*>(gp), dst, count), "gradient widen")) return BR_ERR_HIP;
+          if (!image_kept &&
+              !hip_ok(c, br_launch_bf16_to_f32(c->stream, reinterpret_cast<const uint16_t*>(gp), dst, count), "gradient widen")) return BR_ERR_HIP;
           G32[i] = dst;
         } else {
           G32[i] = reinterpret_cast<const float*>(gp);
@@ -1298,37 +1432,89 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
         Gt[i] = scratch_buf(c, nbuf, mn, i, sGt);
         Mt[i] = cached ? ms.Mrot : scratch_buf(c, nbuf, mn, i, sMt);
       }
-      const int nrot = advance ? B : 2 * B;  // rotate G only, or G and M
+      // Adam's moments are advanced in the epilogue of the contraction that produces G~, so that G~ never reaches
+      // memory (the appendix on related optimizers notes that the rotated update can be fused this way).  That
+      // epilogue needs M~ as an input when it is not advanced from G~ itself: on such steps M is rotated first, by
+      // launches of its own.  With norms requested the products are stored and br_adam_rotated does the rest.
+      const bool fused = !aa.compute_norms;
+      const int nrot = advance ? B : 2 * B;  // unfused: rotate G only, or G and M, in one launch
+      auto adam_args = [&](BrGemmArgs a) {
+        a.adam_epilogue = 1;
+        a.adam = aa;
+        return a;
+      };
+      auto with_moments = [&]() {
+        for (int i = 0; i < B; ++i) { gb.S[i] = c->mats[g.idx[off + i]].S; gb.Mrot[i] = Mt[i]; }
+      };
       if (bilateral) {
         // T = Q_L^T [G | M], then [G~ | M~] = T Q_R
+        if (fused && !advance) {  // M~ = Q_L^T M Q_R ahead of the fused launch
+          for (int i = 0; i < B; ++i) {
+            const MatState& ms = c->mats[g.idx[off + i]];
+            gb.A[i] = ms.QL; gb.B[i] = ms.M; gb.C[i] = scratch_buf(c, nbuf, mn, i, sT2);
+          }
+          if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, B, 0}, gb)) return BR_ERR_HIP;
+          for (int i = 0; i < B; ++i) {
+            const MatState& ms = c->mats[g.idx[off + i]];
+            gb.A[i] = scratch_buf(c, nbuf, mn, i, sT2); gb.B[i] = ms.QR; gb.C[i] = Mt[i];
+          }
+          if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, B, 0}, gb)) return BR_ERR_HIP;
+        }
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
           gb.A[i] = ms.QL; gb.B[i] = G32[i]; gb.C[i] = scratch_buf(c, nbuf, mn, i, sT1);
           gb.A[B + i] = ms.QL; gb.B[B + i] = ms.M; gb.C[B + i] = scratch_buf(c, nbuf, mn, i, sT2);
         }
-        if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, nrot, 0}, gb)) return BR_ERR_HIP;
+        if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, fused ? B : nrot, 0}, gb)) return BR_ERR_HIP;
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
           gb.A[i] = scratch_buf(c, nbuf, mn, i, sT1); gb.B[i] = ms.QR; gb.C[i] = Gt[i];
           gb.A[B + i] = scratch_buf(c, nbuf, mn, i, sT2); gb.B[B + i] = ms.QR; gb.C[B + i] = Mt[i];
         }
-        if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, nrot, 0}, gb)) return BR_ERR_HIP;
-      } else {
-        for (int i = 0; i < B; ++i) {
-          const MatState& ms = c->mats[g.idx[off + i]];
-          if (g.rot_l) {
-            gb.A[i] = ms.QL; gb.B[i] = G32[i]; gb.C[i] = Gt[i];
-            gb.A[B + i] = ms.QL; gb.B[B + i] = ms.M; gb.C[B + i] = Mt[i];
-          } else {
-            gb.A[i] = G32[i]; gb.B[i] = ms.QR; gb.C[i] = Gt[i];
-            gb.A[B + i] = ms.M; gb.B[B + i] = ms.QR; gb.C[B + i] = Mt[i];
-          }
+        if (fused) {
+          with_moments();
+          if (!gemm(c, adam_args(BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, B, 0}), gb)) return BR_ERR_HIP;
+        } else if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, nrot, 0}, gb)) {
+          return BR_ERR_HIP;
         }
-        BrGemmArgs a = g.rot_l ? BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, nrot, 0}
-                               : BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, nrot, 0};
-        if (!gemm(c, a, gb)) return BR_ERR_HIP;
+      } else {
+        const BrGemmArgs a = g.rot_l ? BrGemmArgs{m, n, m, m, n, n, 1, 0, 1.f, 0.f, nrot, 0}
+                                     : BrGemmArgs{m, n, n, n, n, n, 0, 0, 1.f, 0.f, nrot, 0};
+        auto one_side = [&](bool moment_too) {
+          for (int i = 0; i < B; ++i) {
+            const MatState& ms = c->mats[g.idx[off + i]];
+            const int j = moment_too ? B + i : i;
+            if (g.rot_l) {
+              gb.A[i] = ms.QL; gb.B[i] = G32[i]; gb.C[i] = Gt[i];
+              gb.A[j] = ms.QL; gb.B[j] = moment_too ? ms.M : G32[i]; gb.C[j] = moment_too ? Mt[i] : Gt[i];
+            } else {
+              gb.A[i] = G32[i]; gb.B[i] = ms.QR; gb.C[i] = Gt[i];
+              gb.A[j] = moment_too ? ms.M : G32[i]; gb.B[j] = ms.QR; gb.C[j] = moment_too ? Mt[i] : Gt[i];
+            }
+          }
+        };
+        if (fused) {
+          if (!advance) {  // M~ = Q_L^T M (or M Q_R) ahead of the fused launch
+            for (int i = 0; i < B; ++i) {
+              const MatState& ms = c->mats[g.idx[off + i]];
+              if (g.rot_l) { gb.A[i] = ms.QL; gb.B[i] = ms.M; } else { gb.A[i] = ms.M; gb.B[i] = ms.QR; }
+              gb.C[i] = Mt[i];
+            }
+            BrGemmArgs am = a;
+            am.batch = B;
+            if (!gemm(c, am, gb)) return BR_ERR_HIP;
+          }
+          one_side(false);
+          with_moments();
+          BrGemmArgs ag = adam_args(a);
+          ag.batch = B;
+          if (!gemm(c, ag, gb)) return BR_ERR_HIP;
+        } else {
+          one_side(true);
+          if (!gemm(c, a, gb)) return BR_ERR_HIP;
+        }
       }
-      {  // Adam in the rotated basis; X overwrites G~
+      if (!fused) {  // Adam in the rotated basis; X overwrites G~
         BrAdamBatch ab;
         std::memset(&ab, 0, sizeof(ab));
         for (int i = 0; i < B; ++i) {
@@ -1343,6 +1529,10 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
       }
       // rotate back and apply: W <- decay W - lr Q_L X Q_R^T   (X sits in the G~ buffer)
       std::memset(&gb, 0, sizeof(gb));
+      auto weight_update = [&](BrGemmArgs a) {  // the launch that stores the weights also watches them for non-finite values
+        a.health = c->health;
+        return a;
+      };
       if (bilateral) {
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
@@ -1353,19 +1543,19 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
           const MatState& ms = c->mats[g.idx[off + i]];
           gb.A[i] = scratch_buf(c, nbuf, mn, i, sT1); gb.B[i] = ms.QR; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
         }
-        if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 1, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
+        if (!gemm(c, weight_update(BrGemmArgs{m, n, n, n, n, n, 0, 1, -lr, decay, B, 0}), gb)) return BR_ERR_HIP;
       } else if (g.rot_l) {
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
           gb.A[i] = ms.QL; gb.B[i] = Gt[i]; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
         }
-        if (!gemm(c, BrGemmArgs{m, n, m, m, n, n, 0, 0, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
+        if (!gemm(c, weight_update(BrGemmArgs{m, n, m, m, n, n, 0, 0, -lr, decay, B, 0}), gb)) return BR_ERR_HIP;
       } else {
         for (int i = 0; i < B; ++i) {
           const MatState& ms = c->mats[g.idx[off + i]];
           gb.A[i] = Gt[i]; gb.B[i] = ms.QR; gb.C[i] = Wp[i]; gb.shadow[i] = shadow[i];
         }
-        if (!gemm(c, BrGemmArgs{m, n, n, n, n, n, 0, 1, -lr, decay, B, 0}, gb)) return BR_ERR_HIP;
+        if (!gemm(c, weight_update(BrGemmArgs{m, n, n, n, n, n, 0, 1, -lr, decay, B, 0}), gb)) return BR_ERR_HIP;
       }
     }
   }
@@ -1373,6 +1563,8 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
   c->qplanes_valid = true;
   c->t = t;
   c->stats_fresh = false;
+  c->g32_group = -1;
+  c->stats_pending = false;  // a step without a refresh: Algorithm 2's statistics do not see this gradient
   return BR_OK;
 }
 

@@ -235,16 +235,42 @@ __global__ __launch_bounds__(256) void br_adam_plain(BrPtrBatch p, ShadowPtrs sh
   float* __restrict__ W = reinterpret_cast<float*>(p.out1[b]);
   uint16_t* __restrict__ shadow = sh.p[b];
   const float w = 1.0f - a.beta2;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-    float g = load_grad1(G, i, a.grad_bf16);
-    float s = a.beta2 * S[i] + w * (g * g);
-    float x = adam_x(M[i], s, a);
-    float wv = a.decay * W[i] - a.lr * x;
-    S[i] = s;
-    W[i] = wv;
-    if (shadow) shadow[i] = f32_to_bf16_rne(wv);
+  bool bad = false;
+  auto one = [&](float g, float m, float s, float wo, float& so, float& wn) {
+    so = a.beta2 * s + w * (g * g);
+    wn = a.decay * wo - a.lr * adam_x(m, so, a);
+    bad |= (__float_as_uint(wn) & 0x7f800000u) == 0x7f800000u;
+  };
+  // every workgroup walks one contiguous range, 16 bytes per lane and array, non-temporal
+  const int64_t n4 = count >> 2;
+  int64_t lo, hi;
+  block_range(n4, &lo, &hi);
+  for (int64_t i = lo + threadIdx.x; i < hi; i += 256) {
+    const float4 g = nt_load_grad4(G, i, a.grad_bf16);
+    const float4 m = nt_load4(M, i), s = nt_load4(S, i), wo = nt_load4(W, i);
+    float4 so, wn;
+    one(g.x, m.x, s.x, wo.x, so.x, wn.x);
+    one(g.y, m.y, s.y, wo.y, so.y, wn.y);
+    one(g.z, m.z, s.z, wo.z, so.z, wn.z);
+    one(g.w, m.w, s.w, wo.w, so.w, wn.w);
+    nt_store4(S, i, so);
+    nt_store4(W, i, wn);
+    if (shadow) {
+      const u2v o = {(uint32_t)f32_to_bf16_rne(wn.x) | ((uint32_t)f32_to_bf16_rne(wn.y) << 16),
+                     (uint32_t)f32_to_bf16_rne(wn.z) | ((uint32_t)f32_to_bf16_rne(wn.w) << 16)};
+      __builtin_nontemporal_store(o, reinterpret_cast<u2v*>(shadow) + i);
+    }
   }
+  if (blockIdx.x == 0) {
+    for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
+      float so, wn;
+      one(load_grad1(G, i, a.grad_bf16), M[i], S[i], W[i], so, wn);
+      S[i] = so;
+      W[i] = wn;
+      if (shadow) shadow[i] = f32_to_bf16_rne(wn);
+    }
+  }
+  if (a.health && __any(bad) && (threadIdx.x & 63) == 0) atomicAdd(a.health + BR_HEALTH_NONFINITE_WEIGHT, 1);
 }
 
 // in0 = gradient (f32 or bf16); one partial per workgroup at partials[slot0 + blockIdx.y * gridDim.x + blockIdx.x]
@@ -402,7 +428,7 @@ hipError_t br_launch_adam_plain(hipStream_t s, const BrPtrBatch& p, uint16_t* co
   if (batch <= 0 || count <= 0) return hipSuccess;
   br::ShadowPtrs sh;
   for (int i = 0; i < BR_MAXB; ++i) sh.p[i] = (i < batch) ? shadow[i] : nullptr;
-  dim3 grid(br::grid_for(count, batch), batch);
+  dim3 grid(br::grid_for(count / 4 + 1, batch), batch);
   hipLaunchKernelGGL(br::br_adam_plain, grid, dim3(256), 0, s, p, sh, count, a);
   return hipGetLastError();
 }

@@ -37,7 +37,17 @@ struct GemmKernArgs {
   int splitk;        // SPLIT kernels only: number of K ranges per output tile
   int kt_per_split;  // K tiles (of BK) per range
   float* partial;    // SPLIT kernels with splitk > 1: [batch][splitk][M][N] partial products
+  const int* skip;   // optional, one int per matrix: non-zero = this matrix's C is left untouched
+  int* health;       // optional health words: a stored value that is not finite bumps BR_HEALTH_NONFINITE_WEIGHT
+  BrAdamArgs adam;   // ADAM kernels only
 };
+
+__device__ __forceinline__ bool not_finite(float v) { return (__float_as_uint(v) & 0x7f800000u) == 0x7f800000u; }
+
+__device__ __forceinline__ float adam_quotient(float m, float s, const BrAdamArgs& a) {
+  const float num = m * a.c1, den = s * a.c2;
+  return a.eps_outside ? num / (sqrtf(den) + a.eps) : num / sqrtf(den + a.eps);
+}
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
@@ -149,7 +159,11 @@ namespace br {
 // would otherwise run on a handful of workgroups: blockIdx additionally selects one of
 // `splitk` K ranges and the partial product goes to `partial`, summed in a fixed order by
 // br_splitk_reduce (deterministic, no atomics).
-template <bool TA, bool TB, bool VEC, bool SPLIT>
+// ADAM = true (step kernels with op(B) stored K x N only): the product is a rotated gradient G~ and the
+// epilogue is Algorithm 1 from the second moment to the quotient: S~ <- b2 S~ + (1-b2) G~.G~ in place,
+// M~ <- b1 M~ + (1-b1) G~ in place when adam.update_mrot, and X = M~ / sqrt(S~ + eps) stored to C; G~ itself
+// never reaches memory.
+template <bool TA, bool TB, bool VEC, bool SPLIT, bool ADAM>
 __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGemmBatch batch) {
   __shared__ __attribute__((aligned(16))) float As[2][BK][LDS_LD];
   __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDS_LD];
@@ -190,6 +204,7 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
       tm = first_m + (r - tn * gm);
     }
   }
+  if (g.skip && g.skip[mat]) return;  // uniform over the workgroup, ahead of every barrier
   const float* __restrict__ A = batch.A[mat];
   const float* __restrict__ B = batch.B[mat];
   float* __restrict__ C = batch.C[mat];
@@ -291,8 +306,49 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
       }
     return;
   }
+  if (ADAM) {
+    float* __restrict__ S = batch.S[mat];
+    float* __restrict__ Mr = batch.Mrot[mat];
+    const BrAdamArgs ad = g.adam;
+    const float w1 = 1.0f - ad.beta1, w2 = 1.0f - ad.beta2;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int col = n0 + wn * 64 + ni * 32 + li;
+        // both moments of this accumulator's sixteen entries are fetched before the first store
+        float sold[16], mold[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+          const bool in = row < g.M && col < g.N;
+          const size_t off = (size_t)row * (size_t)g.ldc + col;
+          sold[v] = in ? S[off] : 0.f;
+          mold[v] = in ? Mr[off] : 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+          if (row < g.M && col < g.N) {
+            const size_t off = (size_t)row * (size_t)g.ldc + col;
+            const float gt = g.alpha * acc[mi][ni][v];
+            float mt = mold[v];
+            if (ad.update_mrot) {
+              mt = ad.beta1 * mt + w1 * gt;
+              Mr[off] = mt;
+            }
+            const float st = ad.beta2 * sold[v] + w2 * (gt * gt);
+            S[off] = st;
+            C[off] = adam_quotient(mt, st, ad);
+          }
+        }
+      }
+    }
+    return;
+  }
   const bool use_beta = (g.beta != 0.0f);
   const bool off_diag = g.mirror && (tm != tn);
+  bool bad = false;
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
@@ -319,6 +375,7 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
             size_t off = (size_t)row * (size_t)g.ldc + col;
             C[off] = val[e];
             if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
+            bad |= not_finite(val[e]);
           }
         }
         if (off_diag && col < g.N) {
@@ -335,6 +392,8 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
       }
     }
   }
+  // one count per wave that stored something not finite (integer atomic: the results stay deterministic)
+  if (g.health && __any(bad) && lane == 0) atomicAdd(g.health + BR_HEALTH_NONFINITE_WEIGHT, 1);
 }
 
 struct ReduceArgs {
@@ -343,7 +402,8 @@ struct ReduceArgs {
 
 // C_b = beta C_b + sum_s partial[b][s]   (fixed summation order)
 __global__ __launch_bounds__(256) void br_splitk_reduce(ReduceArgs r, const float* __restrict__ partial, int M, int N,
-                                                        int ldc, int splitk, float beta) {
+                                                        int ldc, int splitk, float beta, const int* __restrict__ skip) {
+  if (skip && skip[blockIdx.y]) return;
   float* __restrict__ C = r.C[blockIdx.y];
   const size_t mn = (size_t)M * N;
   const float* __restrict__ P = partial + (size_t)blockIdx.y * splitk * mn;
@@ -361,21 +421,21 @@ __global__ __launch_bounds__(256) void br_splitk_reduce(ReduceArgs r, const floa
 
 namespace {
 
-template <bool TA, bool TB, bool SPLIT>
+template <bool TA, bool TB, bool SPLIT, bool ADAM>
 hipError_t launch_variant(hipStream_t s, const GemmKernArgs& k, const BrGemmBatch& b, int grid, bool vec) {
   if (vec)
-    hipLaunchKernelGGL((br::br_gemm_f32_mfma<TA, TB, true, SPLIT>), dim3(grid), dim3(256), 0, s, k, b);
+    hipLaunchKernelGGL((br::br_gemm_f32_mfma<TA, TB, true, SPLIT, ADAM>), dim3(grid), dim3(256), 0, s, k, b);
   else
-    hipLaunchKernelGGL((br::br_gemm_f32_mfma<TA, TB, false, SPLIT>), dim3(grid), dim3(256), 0, s, k, b);
+    hipLaunchKernelGGL((br::br_gemm_f32_mfma<TA, TB, false, SPLIT, ADAM>), dim3(grid), dim3(256), 0, s, k, b);
   return hipGetLastError();
 }
 
 template <bool SPLIT>
 hipError_t launch_any(hipStream_t s, const BrGemmArgs& a, const GemmKernArgs& k, const BrGemmBatch& b, int grid, bool vec) {
-  if (!a.transA && !a.transB) return launch_variant<false, false, SPLIT>(s, k, b, grid, vec);
-  if (!a.transA && a.transB) return launch_variant<false, true, SPLIT>(s, k, b, grid, vec);
-  if (a.transA && !a.transB) return launch_variant<true, false, SPLIT>(s, k, b, grid, vec);
-  return launch_variant<true, true, SPLIT>(s, k, b, grid, vec);
+  if (!a.transA && !a.transB) return launch_variant<false, false, SPLIT, false>(s, k, b, grid, vec);
+  if (!a.transA && a.transB) return launch_variant<false, true, SPLIT, false>(s, k, b, grid, vec);
+  if (a.transA && !a.transB) return launch_variant<true, false, SPLIT, false>(s, k, b, grid, vec);
+  return launch_variant<true, true, SPLIT, false>(s, k, b, grid, vec);
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -386,10 +446,17 @@ hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch&
   static const char* names[8] = {"br_gemm_f32_mfma<nn>", "br_gemm_f32_mfma<nt>", "br_gemm_f32_mfma<tn>",
                                  "br_gemm_f32_mfma<tt>", "br_gemm_f32_mfma<nn,split>", "br_gemm_f32_mfma<nt,split>",
                                  "br_gemm_f32_mfma<tn,split>", "br_gemm_f32_mfma<tt,split>"};
-  if (kernel_name) *kernel_name = names[(a.qr_role ? 4 : 0) + (a.transA ? 2 : 0) + (a.transB ? 1 : 0)];
+  if (kernel_name) {
+    *kernel_name = names[(a.qr_role ? 4 : 0) + (a.transA ? 2 : 0) + (a.transB ? 1 : 0)];
+    if (a.adam_epilogue) *kernel_name = a.transA ? "br_gemm_f32_mfma<tn,adam>" : "br_gemm_f32_mfma<nn,adam>";
+  }
   if (a.batch <= 0 || a.M <= 0 || a.N <= 0) return hipSuccess;
   if (a.batch > BR_MAXB || a.K < 0) return hipErrorInvalidValue;
   if (a.mirror && (a.M != a.N)) return hipErrorInvalidValue;
+  if (a.adam_epilogue && (a.transB || a.mirror || a.qr_role)) return hipErrorInvalidValue;
+  if (a.adam_epilogue)
+    for (int i = 0; i < a.batch; ++i)
+      if (!b.S[i] || !b.Mrot[i]) return hipErrorInvalidValue;
   GemmKernArgs k;
   k.M = a.M; k.N = a.N; k.K = a.K;
   k.lda = a.lda; k.ldb = a.ldb; k.ldc = a.ldc;
@@ -401,10 +468,16 @@ hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch&
   k.splitk = 1;
   k.kt_per_split = (a.K + BK - 1) / BK;
   k.partial = nullptr;
+  k.skip = a.skip;
+  k.health = a.health;
+  k.adam = a.adam;
   long long grid = (long long)k.total_tiles * a.batch;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   bool vec = (a.lda % 4 == 0) && (a.ldb % 4 == 0);
   for (int i = 0; i < a.batch && vec; ++i) vec = aligned16(b.A[i]) && aligned16(b.B[i]) && (!a.mirror || aligned16(b.C[i]));
+  if (a.adam_epilogue)
+    return a.transA ? launch_variant<true, false, false, true>(s, k, b, (int)grid, vec)
+                    : launch_variant<false, false, false, true>(s, k, b, (int)grid, vec);
   if (!a.qr_role) return launch_any<false>(s, a, k, b, (int)grid, vec);
   // Split K when the launch would leave most of the 256 compute units idle.  (Splitting launches
   // of a few tiles per compute unit as well, to shorten their tails, was measured and gained nothing.)
@@ -427,6 +500,6 @@ hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch&
   long long blocks = ((long long)a.M * a.N + 255) / 256;
   if (blocks > 64) blocks = 64;
   hipLaunchKernelGGL(br::br_splitk_reduce, dim3((int)blocks, a.batch), dim3(256), 0, s, r, k.partial, a.M, a.N, a.ldc,
-                     k.splitk, a.beta);
+                     k.splitk, a.beta, a.skip);
   return hipGetLastError();
 }

@@ -20,7 +20,20 @@ struct BrGemmBatch {
   const float* B[BR_MAXB];
   float* C[BR_MAXB];
   uint16_t* shadow[BR_MAXB];
+  float* S[BR_MAXB];     // adam_epilogue: second moment in the rotated basis (row stride ldc), updated in place
+  float* Mrot[BR_MAXB];  // adam_epilogue: rotated first moment (row stride ldc); rewritten when adam.update_mrot
 };
+
+struct BrAdamArgs {
+  float beta1, beta2, eps;
+  float c1, c2;     // bias-correction multipliers for the first/second moment (1 when disabled)
+  int eps_outside;
+  int compute_norms;
+  int update_mrot;  // 1: M~ <- beta1 M~ + (1-beta1) G~ before it is used (cached rotated moment)
+};
+
+// Health words of a context (device memory, int32): counters that kernels bump when something went wrong.
+enum { BR_HEALTH_QR_GAVE_UP = 0, BR_HEALTH_NONFINITE_WEIGHT = 1, BR_HEALTH_WORDS = 4 };
 
 struct BrGemmArgs {
   int M, N, K;
@@ -32,17 +45,16 @@ struct BrGemmArgs {
   int qr_role = 0;             // 1: launch the split-K capable variant used inside the QR
   float* partial = nullptr;    // qr_role: scratch for split-K partial products (optional)
   size_t partial_floats = 0;   // its capacity in floats
+  // adam_epilogue: the product alpha op(A) op(B) is a rotated gradient G~.  Instead of storing it, the
+  // kernel advances Adam's moments in place (batch.S, batch.Mrot) and stores X = M~ / sqrt(S~ + eps) to C.
+  // Needs transB == 0, no mirror, not qr_role; beta is ignored.
+  int adam_epilogue = 0;
+  BrAdamArgs adam = {};
+  const int* skip = nullptr;   // device array, one int per matrix of the batch: non-zero = leave that matrix's C untouched
+  int* health = nullptr;       // device health words: BR_HEALTH_NONFINITE_WEIGHT is bumped when a stored value is not finite
 };
 
 hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch& b, const char** kernel_name);
-
-struct BrAdamArgs {
-  float beta1, beta2, eps;
-  float c1, c2;     // bias-correction multipliers for the first/second moment (1 when disabled)
-  int eps_outside;
-  int compute_norms;
-  int update_mrot;  // 1: M~ <- beta1 M~ + (1-beta1) G~ before it is used (cached rotated moment)
-};
 
 // ---- BF16 matrix-core contractions on pre-split operand planes ----------------------------
 // A plane holds an R x K operand as BF16 in the order the contraction kernel wants its LDS tiles:
@@ -100,6 +112,8 @@ struct BrLowpArgs {
   // BR_EPI_F32 only: the transpose of the stored result also leaves as operand planes (hi, and lo when
   // out_lo) through the pointer carried in the batch's S slot.
   int emit_transposed = 0;
+  const int* skip = nullptr;   // BR_EPI_F32: device array, one int per matrix: non-zero = store nothing for that matrix
+  int* health = nullptr;       // BR_EPI_F32: BR_HEALTH_NONFINITE_WEIGHT is bumped when a stored value is not finite
 };
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name);
 // hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src) into planes of
@@ -140,6 +154,7 @@ hipError_t br_launch_adam_rotated(hipStream_t s, const BrAdamBatch& p, int batch
 struct BrPlainArgs {
   float beta2, eps, c1, c2, lr, decay;  // decay = 1 - lr*wd
   int eps_outside, grad_bf16;
+  int* health = nullptr;  // BR_HEALTH_NONFINITE_WEIGHT is bumped when a stored weight is not finite
 };
 hipError_t br_launch_adam_plain(hipStream_t s, const BrPtrBatch& p, uint16_t* const* shadow, int batch,
                                 int64_t count, const BrPlainArgs& a);
@@ -176,9 +191,17 @@ struct BrQrPanelBatch {
 // tag tag0 + step + 1 (step <= 32): xch must be ZERO before the first panel of a factorisation,
 // and tag0 must differ by at least 64 between the panels that share it afterwards.
 #define BR_QR_MAX_RESIDENT 192  // most workgroups of one panel launch (all of them must be on the chip at once)
+// spin_limit: polls of one exchanged value before a workgroup gives up waiting for its cluster; 0 = give up
+// without polling (every exchange fails: the host-forced test of the failure path).  A workgroup that gives
+// up sets failed[matrix] (one int per matrix of the batch, device memory) and bumps
+// health[BR_HEALTH_QR_GAVE_UP]; its results are garbage from then on and must not be used.
+#define BR_QR_SPIN_LIMIT_DEFAULT (1u << 22)
 struct BrQrClusterBatch {
   unsigned long long* xch[BR_MAXB];
+  int* failed[BR_MAXB];
+  int* health;
   unsigned tag0;
+  unsigned spin_limit;
 };
 int br_qr_panel_cluster(int rows);
 size_t br_qr_panel_xch_floats(int rows);
@@ -205,7 +228,8 @@ hipError_t br_launch_qr_build_t(hipStream_t s, const float* const* G, const floa
 // Diagonal blocks of a merged factor T (2w x 2w) from its nchild (1 or 2) child factors (consecutive
 // w x w matrices); everything else zero.
 hipError_t br_launch_qr_assemble_t(hipStream_t s, const float* const* Tc, float* const* T, int batch, int nchild, int w);
-// Q[:, j] *= sign(diag[j]) (zero counts as +).
-hipError_t br_launch_qr_signed_identity(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n);
+// Q = diag(sign(diag[j])) (zero counts as +).  skip (optional): device array, non-zero = leave that Q untouched.
+hipError_t br_launch_qr_signed_identity(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n,
+                                        const int* skip);
 
 #endif  // BR_INTERNAL_H_

@@ -73,7 +73,11 @@ struct LowpKernArgs {
   int b_stride;          // padded row count that addresses the B planes (Np, or a larger set's when B is a view into it)
   int out_stride;        // the same for the emitted planes
   int emit_t;            // EPI_F32: the transpose of the stored result also leaves as planes (pointer in the batch's S slot)
+  const int* skip;       // EPI_F32, optional: one int per matrix, non-zero = nothing is stored for that matrix
+  int* health;           // EPI_F32, optional: a stored value that is not finite bumps BR_HEALTH_NONFINITE_WEIGHT
 };
+
+__device__ __forceinline__ bool not_finite(float v) { return (__float_as_uint(v) & 0x7f800000u) == 0x7f800000u; }
 
 enum { EPI_F32 = 0, EPI_PLANES = 1, EPI_ADAM = 2 };
 
@@ -346,6 +350,8 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
   if (EPI == EPI_F32) {
     const bool use_beta = (g.beta != 0.0f);
     const bool off_diag = g.mirror && (tm != tn);
+    const int Mlim = (g.skip && g.skip[mat]) ? 0 : g.M;  // a skipped matrix stores nothing
+    bool bad = false;
     // Old values of an accumulator's sixteen outputs are fetched together, one accumulator ahead
     // of the stores: a load issued after a store to the same matrix would wait for it.
     float oldv[2][16];
@@ -355,7 +361,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + (wm * FM + mi) * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-        dst[v] = (use_beta && row < g.M && col < g.N) ? C[(size_t)row * (size_t)g.ldc + col] : 0.f;
+        dst[v] = (use_beta && row < Mlim && col < g.N) ? C[(size_t)row * (size_t)g.ldc + col] : 0.f;
       }
     };
     fetch_old(0, oldv[0]);
@@ -377,14 +383,15 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
             const int row = row0 + e;
             val[e] = g.alpha * acc[mi][ni][vg * 4 + e];
             if (use_beta) val[e] += g.beta * old[vg * 4 + e];
-            if (row < g.M && col < g.N) {
+            if (row < Mlim && col < g.N) {
               const size_t off = (size_t)row * (size_t)g.ldc + col;
               C[off] = val[e];
               if (shadow) shadow[off] = f32_to_bf16_rne(val[e]);
+              bad |= not_finite(val[e]);
             }
           }
           if (g.emit_t) pack_hi_lo(val, wh[vg], wl[vg], g.out_lo != 0);
-          if (off_diag && col < g.N) {
+          if (off_diag && col < g.N && Mlim > 0) {
             // transposed copy of a symmetric result: this lane's four rows are four consecutive columns there
             float* dst = C + (size_t)col * (size_t)g.ldc + row0;
             if (row0 + 3 < g.M && ((g.ldc & 3) == 0)) {
@@ -400,7 +407,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
           // the stored values once more, transposed, as operand planes (hi + lo when out_lo): what the next
           // contraction of a chain of updates reads; exactly zero in the padding (the operands are zero there)
           const int kbase = m0 + (wm * FM + mi) * 32;
-          if (g.emit_t && kbase < g.out_kp) {  // out_kp is a multiple of 64: all four groups or none
+          if (g.emit_t && kbase < g.out_kp && Mlim > 0) {  // out_kp is a multiple of 64: all four groups or none
             uint16_t* __restrict__ Pt = reinterpret_cast<uint16_t*>(batch.S[mat]);
             emit_chunks(Pt, wh, kbase, col, g.out_stride, lk);
             if (g.out_lo) emit_chunks(Pt + g.out_plane, wl, kbase, col, g.out_stride, lk);
@@ -408,6 +415,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
         }
       }
     }
+    if (g.health && __any(bad) && lane == 0) atomicAdd(g.health + BR_HEALTH_NONFINITE_WEIGHT, 1);
   } else {
     uint16_t* __restrict__ Pout = shadow;  // the emitted planes travel in the batch's 16-bit output slot
     float* __restrict__ S = batch.S[mat];
@@ -808,6 +816,8 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
     k.out_stride = a.out_stride_rows;
     k.out_plane = a.out_plane_elems;
   }
+  k.skip = a.skip;
+  k.health = a.health;
   k.emit_t = a.emit_transposed ? 1 : 0;
   if (k.emit_t) {
     if (a.epilogue != BR_EPI_F32 || a.mirror) return hipErrorInvalidValue;

@@ -27,7 +27,6 @@ constexpr int QR_WAVES = QR_THREADS / 64;          // 16
 constexpr int QR_RESIDENT_SWEEPS = 12;             // a workgroup keeps up to 12 x 128 = 1536 rows in registers
 constexpr int QR_MAX_SLAB = QR_RESIDENT_SWEEPS * QR_ROWS_PER_SWEEP;
 constexpr int QR_XCH_SLOTS = 64;                   // per (step, workgroup): 32 partial sums + the next pivot row
-constexpr unsigned QR_SPIN_LIMIT = 1u << 22;       // polls of one value before a cluster gives up and poisons its result
 
 // One lane's four columns of a panel row travel as a float4 VALUE (never through a pointer), so
 // that groups of rows stay in registers.
@@ -101,11 +100,16 @@ __device__ __forceinline__ float panel_reduce(float4 acc, float (*red)[32], int 
 // waits for, so the exchange is one store and one load deep, without a separate arrival counter.
 // The buffer is zeroed before a factorisation and tags are unique within it (never zero).
 // Each workgroup sums the partials in workgroup order, so that all of them hold bit-identical
-// values.  The wait is bounded: a value that never arrives becomes NaN (which reaches the basis
-// and the weights) instead of a hang.
+// values.  The wait is bounded (the workgroups of a launch must all be resident; a launch that
+// shares the GPU with other work could starve one): a workgroup whose wait runs out sets its
+// matrix's `failed` flag, bumps the context's health word and carries on with a NaN, so that every
+// kernel still ends.  The host logic leaves the previous basis of a flagged matrix in place.
 struct Cluster {
   unsigned long long* xch;  // [step][workgroup][QR_XCH_SLOTS] of this matrix
+  int* failed;              // this matrix's flag
+  int* health;              // the context's health words (may be null)
   unsigned tag0;            // this panel's tags are tag0 + step + 1
+  unsigned spin_limit;
   int w, nw;
 };
 
@@ -113,14 +117,14 @@ __device__ __forceinline__ unsigned long long xch_pack(float v, unsigned tag) {
   return ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
 }
 
-__device__ __forceinline__ float xch_wait(const unsigned long long* slot, unsigned tag) {
-  unsigned spins = 0;
-  for (;;) {
+__device__ __forceinline__ float xch_wait(const unsigned long long* slot, unsigned tag, unsigned limit, bool& gave_up) {
+  for (unsigned spins = 0; spins < limit; ++spins) {
     const unsigned long long v = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((unsigned)(v >> 32) == tag) return __uint_as_float((unsigned)v);
-    if (++spins > QR_SPIN_LIMIT) return __builtin_nanf("");
     __builtin_amdgcn_s_sleep(1);
   }
+  gave_up = true;
+  return __builtin_nanf("");
 }
 
 // Threads 0..31 pass their column's partial sum and get the cluster's sum back; threads 64..95
@@ -130,16 +134,21 @@ __device__ __forceinline__ float cluster_combine(const Cluster& cl, int step, fl
   const unsigned tag = cl.tag0 + (unsigned)step + 1u;
   unsigned long long* base = cl.xch + (size_t)step * cl.nw * QR_XCH_SLOTS;
   float s = 0.f;
+  bool gave_up = false;
   if (tid < 32) {
     __hip_atomic_store(base + (size_t)cl.w * QR_XCH_SLOTS + tid, xch_pack(part, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int ww = 0; ww < cl.nw; ++ww)
-      s += (ww == cl.w) ? part : xch_wait(base + (size_t)ww * QR_XCH_SLOTS + tid, tag);
+      s += (ww == cl.w) ? part : xch_wait(base + (size_t)ww * QR_XCH_SLOTS + tid, tag, cl.spin_limit, gave_up);
   } else if (tid >= 64 && tid < 96) {  // another wave than the sums': the two waits overlap
     const int t = tid - 64;
     if (cl.w == 0)
       __hip_atomic_store(base + 32 + t, xch_pack(pivnext[t], tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     else
-      pivnext[t] = xch_wait(base + 32 + t, tag);
+      pivnext[t] = xch_wait(base + 32 + t, tag, cl.spin_limit, gave_up);
+  }
+  if (gave_up) {  // rare: flag the matrix (plain store; every writer stores the same 1) and count it
+    *cl.failed = 1;
+    if (cl.health) atomicAdd(cl.health + BR_HEALTH_QR_GAVE_UP, 1);
   }
   return s;
 }
@@ -219,6 +228,9 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   const bool vec = vec_ok != 0;
   Cluster cl;
   cl.xch = cb.xch[blockIdx.x];
+  cl.failed = cb.failed[blockIdx.x];
+  cl.health = cb.health;
+  cl.spin_limit = cb.spin_limit;
   cl.tag0 = cb.tag0;
   cl.w = blockIdx.y;
   cl.nw = gridDim.y;
@@ -484,7 +496,8 @@ struct SignArgs {
 // formed.  (H_1 ... H_k) diag(s) equals (H_1 ... H_k I) with its columns' signs flipped, entry by
 // entry and bit for bit, so starting from the signed identity makes diag(R) >= 0 without a pass
 // over Q afterwards.
-__global__ __launch_bounds__(256) void br_qr_signed_identity(SignArgs a, int n) {
+__global__ __launch_bounds__(256) void br_qr_signed_identity(SignArgs a, int n, const int* __restrict__ skip) {
+  if (skip && skip[blockIdx.y]) return;  // this matrix's factorisation was abandoned: its previous basis stays
   float* __restrict__ Q = a.Q[blockIdx.y];
   const float* __restrict__ d = a.diag[blockIdx.y];
   const int64_t total = (int64_t)n * n;
@@ -645,6 +658,9 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
   int vec = (lda % 4 == 0);
   for (int i = 0; i < batch && vec; ++i) vec = ((reinterpret_cast<uintptr_t>(p.A[i]) & 15u) == 0);
   const int nw = br_qr_panel_cluster(rows);
+  if (nw > 1)
+    for (int i = 0; i < batch; ++i)
+      if (!cb.xch[i] || !cb.failed[i]) return hipErrorInvalidValue;
   // balanced slabs, whole sweeps
   int slab = (rows + nw - 1) / nw;
   slab = (slab + br::QR_ROWS_PER_SWEEP - 1) / br::QR_ROWS_PER_SWEEP * br::QR_ROWS_PER_SWEEP;
@@ -670,8 +686,11 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
     BrQrPanelBatch pp;
     BrQrClusterBatch cc;
     cc.tag0 = cb.tag0;
+    cc.spin_limit = cb.spin_limit;
+    cc.health = cb.health;
     for (int i = 0; i < BR_MAXB; ++i) {
       const bool live = i < b;
+      cc.failed[i] = live ? cb.failed[off + i] : nullptr;
       pp.A[i] = live ? p.A[off + i] : nullptr;
       pp.Vc[i] = live ? p.Vc[off + i] : nullptr;
       pp.T[i] = live ? p.T[off + i] : nullptr;
@@ -765,7 +784,8 @@ hipError_t br_launch_zero_ints(hipStream_t s, int* const* ptrs, int batch, int n
   return hipGetLastError();
 }
 
-hipError_t br_launch_qr_signed_identity(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n) {
+hipError_t br_launch_qr_signed_identity(hipStream_t s, float* const* Q, const float* const* diag, int batch, int n,
+                                        const int* skip) {
   if (batch <= 0) return hipSuccess;
   if (batch > BR_MAXB) return hipErrorInvalidValue;
   br::SignArgs a;
@@ -776,6 +796,6 @@ hipError_t br_launch_qr_signed_identity(hipStream_t s, float* const* Q, const fl
   int64_t blocks = ((int64_t)n * n + 255) / 256;
   int64_t cap = (2048 + batch - 1) / batch;
   if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL(br::br_qr_signed_identity, dim3((int)blocks, batch), dim3(256), 0, s, a, n);
+  hipLaunchKernelGGL(br::br_qr_signed_identity, dim3((int)blocks, batch), dim3(256), 0, s, a, n, skip);
   return hipGetLastError();
 }

@@ -6,7 +6,7 @@ import numpy as np
 import torch
 
 from oracle import br_oracle as oc
-from oracle.metrics import rel_err
+from oracle.metrics import orthogonality_defect, rel_err  # noqa: F401  (re-exported for the tests)
 
 
 def f32(x):
@@ -21,7 +21,8 @@ def oracle_hyper(**kw):
                   weight_decay=kw.pop("weight_decay", 0.0), stat_beta=None if sb < 0 else sb,
                   geometry=geometry, source=source, power_iters=kw.pop("power_iters", 1),
                   bias_correction=bool(kw.pop("bias_correction", 0)),
-                  eps_outside_sqrt=bool(kw.pop("eps_outside_sqrt", 0)))
+                  eps_outside_sqrt=bool(kw.pop("eps_outside_sqrt", 0)),
+                  stats_on_refresh_only=bool(kw.pop("stats_on_refresh_only", 0)))
     kw.pop("compute_norms", None)
     kw.pop("math", None)
     kw.pop("cache_rotated_moment", None)

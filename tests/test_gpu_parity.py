@@ -478,10 +478,14 @@ def test_bf16_modes_right_factor_only_chain(harness, math):
     _run(harness, [W0], [[g] for g in grads], freq=3, lr=1e-3, geometry=1, math=math, tol=tol, check_q=(math == 2))
 
 
+@pytest.mark.parametrize("math", [2, 0])
 @pytest.mark.parametrize("geometry", [0, 1])
-def test_bf16x3_fused_and_unfused_chains_agree(harness, geometry):
-    """With per-matrix norms requested the BF16 modes store every product in FP32 and split it
-    again; without, products travel as operand planes and Adam runs in an epilogue.  Same result."""
+def test_bf16x3_fused_and_unfused_chains_agree(harness, geometry, math):
+    """With per-matrix norms requested every product is stored in FP32 and Adam's update is a kernel
+    of its own (the BF16 modes also split the stored products again); without, Adam runs in the
+    epilogue of the contraction that produces the rotated gradient (math = 0: the FP32 kernel stores X
+    instead of G~; BF16 modes: products travel as operand planes).  Same result, both against the
+    oracle at 1e-4 and against each other."""
     shapes = [(264, 136), (136, 264), (200, 200)]
     W0s, seqs = [], []
     for k, (m, n) in enumerate(shapes):
@@ -491,7 +495,7 @@ def test_bf16x3_fused_and_unfused_chains_agree(harness, geometry):
     steps = [[seqs[k][t] for k in range(len(shapes))] for t in range(7)]
     out = []
     for norms in (0, 1):
-        sb, _ = _run(harness, W0s, steps, freq=3, lr=1e-3, geometry=geometry, math=2, compute_norms=norms)
+        sb, _ = _run(harness, W0s, steps, freq=3, lr=1e-3, geometry=geometry, math=math, compute_norms=norms)
         out.append([sb.gpu_weights(i) for i in range(len(shapes))])
     for i, W0 in enumerate(W0s):
         w0 = np.asarray(W0, dtype=np.float64)
@@ -529,3 +533,126 @@ def test_delay_compensation(harness, bf16):
             assert rel_err(got, ref) <= 1e-6
     with pytest.raises(Exception):
         sb.opt.delay_compensate(dev_g, dev_s, 1.5)
+
+
+@pytest.mark.parametrize("math,geometry,cache", [(0, 0, 1), (0, 1, 1), (0, 1, 0), (2, 1, 1), (2, 1, 0)])
+def test_statistics_only_on_refresh_steps(harness, math, geometry, cache):
+    """Algorithm 2 exactly as Algorithm 1 calls it: L and R are updated inside Eigenbasis-Estimation, i.e. only
+    from the gradients of refresh steps (stats_on_refresh_only), against the oracle's flag of the same name.
+    Several matrices in two shapes plus an unrotated tensor, refresh every 3 of 8 steps.  At the first refresh the
+    statistics hold ONE gradient, so a factor is full rank only on a side no longer than the other: the bilateral
+    case takes square matrices, the unilateral one (smaller side) rectangular ones.  The Gram matrix of ONE square
+    noisy gradient is ill-conditioned (condition number 1e4 and more), so in the bilateral case the bases are held
+    to orthogonality and to what they produce (every update, moments, statistics at the bar), not entry by entry, and
+    only the FP32 mode runs it (the split-BF16 modes' bars assume condition numbers of about 100 at most).  Plain
+    BF16 inputs are left out: with a first rotation on a two-step-old second moment that mode's 2e-2 does not hold
+    (3.6e-2 here at step 3), as its documentation says; the deferred statistics of that mode share every launch
+    with BR_MATH_BF16X3."""
+    shapes = [(96, 96), (160, 160), (96, 96), (300, 48)] if geometry == 0 else [(136, 200), (200, 136), (136, 200), (300, 48)]
+    rotate = [True, True, True, False]
+    W0s, seqs = [], []
+    for k, (m, n) in enumerate(shapes):
+        W0, grads = synth.spiked_gradients(seed=70 + k, m=m, n=n, steps=8, noise_std=0.1)
+        W0s.append(W0)
+        seqs.append(grads)
+    steps = [[seqs[k][t] for k in range(len(shapes))] for t in range(8)]
+    tol = 2e-2 if math == 1 else TOL
+    sb, _ = _run(harness, W0s, steps, freq=3, lr=1e-3, tol=tol, check_q=(math != 1 and geometry == 1), rotate=rotate,
+                 math=math, geometry=geometry, cache_rotated_moment=cache, stats_on_refresh_only=1)
+    # the flag did something: the statistics hold exactly two gradients' worth (steps 3 and 6)
+    st = sb.states[0]
+    b = sb.hp.beta2
+    G3, G6 = np.asarray(seqs[0][2], dtype=np.float64), np.asarray(seqs[0][5], dtype=np.float64)
+    assert rel_err(st.L, (1 - b) * (G6 @ G6.T) + b * (1 - b) * (G3 @ G3.T)) < 1e-12
+
+
+def test_statistics_only_on_refresh_steps_bf16_gradients(harness):
+    """BF16 gradients: the deferred statistics widen them again at the refresh (unilateral: well conditioned)."""
+    shapes = [(136, 200), (200, 136)]
+    W0s, seqs = [], []
+    for k, (m, n) in enumerate(shapes):
+        W0, grads = synth.lowrank_gradients(seed=80 + k, m=m, n=n, steps=7, rank=16, sigma=0.05, bf16=True)
+        W0s.append(W0)
+        seqs.append(grads)
+    steps = [[seqs[k][t] for k in range(len(shapes))] for t in range(7)]
+    _run(harness, W0s, steps, freq=3, lr=1e-3, bf16_params=True, bf16_grads=True, geometry=1, stats_on_refresh_only=1)
+
+
+def test_health_words_qr_wait_given_up_keeps_previous_basis(harness):
+    """The failure path of the QR panel clusters, forced from the host: with a wait limit of 0 every exchange
+    between the workgroups of a cluster gives up at once (all kernels still end normally).  The left factor of
+    a 2000 x 40 matrix (order 2000: panels of two workgroups) must then keep the basis it had before that
+    refresh, bit for bit; the right factor (order 40, one workgroup, no exchange) is refreshed as usual; the
+    weights stay finite; the health word counts the event and br_check_health reports it.  Statistics are
+    injected (well conditioned, full rank) so that every basis is unique and can be checked against the oracle's
+    Power step."""
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+    from tests.tolerances import lapack_qr
+    m, n = 2000, 40
+    rng = np.random.default_rng(91)
+
+    def spd(k, seed_shift):
+        N = np.random.default_rng(910 + seed_shift).standard_normal((k, k))
+        return (N + N.T) * (0.3 / (2.0 * np.sqrt(k))) + 2.0 * np.eye(k)
+
+    L1, L2, R1, R2 = spd(m, 1), spd(m, 2), spd(n, 3), spd(n, 4)
+    W = harness.to_dev(0.02 * rng.standard_normal((m, n)))
+    opt = BasisRotationAdam([W], freq=0, lr=1e-3)
+
+    def inject(L, R):
+        opt.state(0, B.BR_STATE_L).copy_(harness.to_dev(L))
+        opt.state(0, B.BR_STATE_R).copy_(harness.to_dev(R))
+        B.br_notify_state_written(opt.ctx)
+
+    inject(L1, R1)
+    opt.refresh_basis()                                     # a normal refresh
+    torch.cuda.synchronize()
+    assert B.br_check_health(opt.ctx) == [0, 0, 0, 0]
+    ql1, qr1 = opt.state(0, B.BR_STATE_QL).clone(), opt.state(0, B.BR_STATE_QR).clone()
+    assert rel_err(harness.to_np(ql1), oc.power_qr(L1, np.eye(m), 1, lapack_qr)) <= 1e-5
+    inject(L2, R2)
+    B.br_set_qr_wait_limit(opt.ctx, 0)
+    opt.refresh_basis()                                     # every cluster exchange gives up
+    g = harness.to_dev(0.01 * rng.standard_normal((m, n)))
+    opt.step([g], 1e-3)                                     # freq = 0: no further refresh
+    torch.cuda.synchronize()
+    assert torch.equal(opt.state(0, B.BR_STATE_QL), ql1)                   # previous basis kept, bit for bit
+    assert rel_err(harness.to_np(opt.state(0, B.BR_STATE_QR)),             # the small factor was refreshed as usual
+                   oc.power_qr(R2, harness.to_np(qr1), 1, lapack_qr)) <= 1e-5
+    assert bool(torch.isfinite(W).all())
+    off = B.br_get_health(opt.ctx) - opt.workspace.data_ptr()
+    health = opt.workspace[off:off + 16].view(torch.int32)
+    assert int(health[0]) > 0 and int(health[1]) == 0
+    with pytest.raises(B.BrError) as e:
+        B.br_check_health(opt.ctx)
+    assert e.value.status == B.BR_ERR_STATE and "gave up" in str(e.value)
+    # back to the default wait: the next refresh works again, from the basis that was kept
+    B.br_set_qr_wait_limit(opt.ctx, -1)
+    count_before = int(health[0])
+    opt.refresh_basis()
+    torch.cuda.synchronize()
+    L_now = harness.to_np(opt.state(0, B.BR_STATE_L))      # L2 plus the step's gradient (the statistics went on)
+    assert rel_err(harness.to_np(opt.state(0, B.BR_STATE_QL)), oc.power_qr(L_now, harness.to_np(ql1), 1, lapack_qr)) <= 1e-5
+    assert int(health[0]) == count_before
+    opt.close()
+
+
+@pytest.mark.parametrize("math", [0, 1])
+def test_health_word_counts_non_finite_weights(harness, math):
+    """An infinite learning rate (not rejected: only NaN is) makes the stored weights non-finite; the kernels
+    that store weights count it, for rotated matrices and for plain-Adam tensors."""
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+    for rotate in (True, False):
+        W = torch.ones(72, 40, device="cuda")
+        g = torch.ones(72, 40, device="cuda")
+        opt = BasisRotationAdam([W], freq=0, lr=1e-3, rotate=[rotate], math=math)
+        opt.step([g], 1e-3)
+        assert B.br_check_health(opt.ctx) == [0, 0, 0, 0]
+        opt.step([g], float("inf"))
+        with pytest.raises(B.BrError) as e:
+            B.br_check_health(opt.ctx)
+        assert e.value.status == B.BR_ERR_STATE and "non-finite" in str(e.value)
+        assert not bool(torch.isfinite(W).all())
+        opt.close()
