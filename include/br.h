@@ -37,6 +37,13 @@
  *              bias_correction the factors of the step number it was captured at; the
  *              host-side state (step counter, "statistics fresh", "basis changed")
  *              advances at capture time, not at replay.  Profiling must be off.
+ *              Two consequences.  (1) With cache_rotated_moment, a step captured while the
+ *              cached M~ is current contains "advance M~", one captured right after a refresh or
+ *              br_notify_state_written contains "rebuild M~ from M": capture a plain-step
+ *              graph after an eager (or captured) post-refresh step, and replay it only between
+ *              refreshes.  (2) The first br_step of BF16 parameters initialises their FP32 master
+ *              copies; br_step returns BR_ERR_STATE when asked to capture that step: run one
+ *              step eagerly first.
  *   errors     every call returns a br_status; nothing throws or aborts.  Argument
  *              errors are detected on the host before anything is launched.  After
  *              BR_ERR_HIP the context is unusable (sticky).  br_last_error gives text.

@@ -1336,6 +1336,16 @@ br_status br_step(br_ctx* ctx, void* const* params, const void* const* grads, in
   if (!c->stats_fresh) return fail(c, BR_ERR_STATE, "br_step needs br_accumulate_stats for this step first");
   if (!(lr == lr)) return fail(c, BR_ERR_INVALID_ARG, "learning rate is NaN");
   const br_hparams& hp = c->hp;
+  {
+    // The first step of a BF16 parameter copies it into its FP32 master.  Captured into a graph, that copy would
+    // run again at every replay and throw away what the master has accumulated below one BF16 ulp.
+    bool master_missing = false;
+    for (const MatState& ms : c->mats) master_missing |= (ms.master != nullptr && !ms.master_ready);
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (master_missing && hipStreamIsCapturing(c->stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+      return fail(c, BR_ERR_STATE, "the first br_step of BF16 parameters initialises their FP32 master copies and must not be "
+                                   "captured into a graph: run one step eagerly first");
+  }
   const int64_t t = c->t + 1;
   BrAdamArgs aa;
   aa.beta1 = hp.beta1;

@@ -88,3 +88,68 @@ def test_captured_steps_replay_like_eager_ones(math):
         assert torch.equal(a, b)
     oe.close()
     og.close()
+
+
+def test_bf16_parameters_first_step_cannot_be_captured_then_replays_match_eager():
+    """BF16 parameters keep an FP32 master copy that the first br_step initialises from the parameter.  Baked into
+    a graph, that copy would reset the master at every replay, so br_step refuses to capture it (BR_ERR_STATE);
+    after one eager step the captured step replays bit for bit like eager steps, the master keeping what it has
+    accumulated below one BF16 ulp."""
+    from paper_2602_03515_amd import binding as B
+    from paper_2602_03515_amd.optimizer import BasisRotationAdam
+
+    shape, steps = (200, 136), 4
+    rng = np.random.default_rng(6)
+    W0 = torch.from_numpy(rng.standard_normal(shape).astype(np.float32)).to(torch.bfloat16)
+    G = [torch.from_numpy((rng.standard_normal(shape) * 0.1).astype(np.float32)).to(torch.bfloat16) for _ in range(steps)]
+    dev = torch.device("cuda:0")
+    side = torch.cuda.Stream(device=dev)
+
+    def make():
+        p = [W0.to(dev).clone()]
+        g = [torch.zeros(shape, dtype=torch.bfloat16, device=dev)]
+        with torch.cuda.stream(side):
+            opt = BasisRotationAdam(p, freq=0, lr=1e-4, grad_dtype=torch.bfloat16)
+        return p, g, opt
+
+    pe, ge, oe = make()
+    for t in range(steps):
+        with torch.cuda.stream(side):
+            ge[0].copy_(G[t].to(dev))
+            oe.accumulate_stats(ge)
+            oe.apply(ge)
+    side.synchronize()
+
+    pg, gg, og = make()
+    with torch.cuda.stream(side):
+        gg[0].copy_(G[0].to(dev))
+    side.synchronize()
+    refused = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(refused, stream=side):
+        og.accumulate_stats(gg)
+        with pytest.raises(B.BrError) as e:
+            og.apply(gg)
+    assert e.value.status == B.BR_ERR_STATE and "eagerly" in str(e.value)
+    del refused                      # never replayed: it holds step 1's statistics update only
+    pg, gg, og = make()              # a fresh context: the refused capture advanced the host-side state of the old one
+    with torch.cuda.stream(side):
+        gg[0].copy_(G[0].to(dev))
+        og.accumulate_stats(gg)
+        og.apply(gg)
+    side.synchronize()
+    plain = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(plain, stream=side):
+        og.accumulate_stats(gg)
+        og.apply(gg)
+    for t in range(1, steps):
+        with torch.cuda.stream(side):
+            gg[0].copy_(G[t].to(dev))
+        side.synchronize()
+        plain.replay()
+        torch.cuda.synchronize()
+    assert torch.equal(pe[0], pg[0])
+    assert torch.equal(oe.state(0, B.BR_STATE_MASTER), og.state(0, B.BR_STATE_MASTER))
+    # lr = 1e-4: single updates are below half a BF16 ulp of O(1) weights; only the master copy keeps them
+    assert not torch.equal(oe.state(0, B.BR_STATE_MASTER).to(torch.bfloat16).float(), oe.state(0, B.BR_STATE_MASTER))
+    oe.close()
+    og.close()
