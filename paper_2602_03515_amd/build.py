@@ -60,17 +60,45 @@ def build_library(verbose: bool = False) -> str:
         print(res.stdout, file=sys.stderr)
         raise RuntimeError("link failed")
     os.replace(tmp, LIB_PATH)
-    # stand-alone C driver of the ABI (used for hardware-counter runs)
-    exe = os.path.join(HERE, "br_native_bench")
-    cmd = [hipcc, *HIPCC_FLAGS, os.path.join(CSRC, "br_native_bench.hip"), "-o", exe + ".tmp",
-           f"-L{HERE}", "-lbr_hip", "-Wl,-rpath,$ORIGIN"]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        print(res.stdout, file=sys.stderr)
-        raise RuntimeError("native driver build failed")
-    os.replace(exe + ".tmp", exe)
+    # stand-alone executables: the C driver of the ABI (hardware-counter runs; includes br.h only) and the
+    # measurement probes (machine peaks, single-kernel timings through the internal launchers)
+    for name in ("br_native_bench", "br_probes"):
+        exe = os.path.join(HERE, name)
+        cmd = [hipcc, *HIPCC_FLAGS, os.path.join(CSRC, name + ".hip"), "-o", exe + ".tmp",
+               f"-L{HERE}", "-lbr_hip", "-Wl,-rpath,$ORIGIN"]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if res.returncode != 0:
+            print(res.stdout, file=sys.stderr)
+            raise RuntimeError(f"{name} build failed")
+        os.replace(exe + ".tmp", exe)
     return LIB_PATH
 
 
+def build_sanitized(verbose: bool = False) -> str:
+    """The C driver and every library source in ONE executable whose HOST code is instrumented with
+    AddressSanitizer and UndefinedBehaviorSanitizer (device code is compiled as usual: GPU sanitizers are
+    not used).  `br_native_bench_san --host-only` needs no GPU; with one, `--small --steps 6 --freq 2` runs every
+    call of the ABI under the sanitizers."""
+    hipcc = hipcc_path()
+    exe = os.path.join(HERE, "br_native_bench_san")
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"] + ["-O1", "-g", "-fno-omit-frame-pointer"]
+    for san in ("address", "undefined"):
+        flags += ["-Xarch_host", f"-fsanitize={san}"]
+    flags += ["-Xarch_host", "-fno-sanitize-recover=undefined"]
+    srcs = [os.path.join(CSRC, s) for s in SOURCES + ["br_native_bench.hip"]]
+    cmd = [hipcc, *flags, *srcs, "-o", exe + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        print(res.stdout, file=sys.stderr)
+        raise RuntimeError("sanitizer build failed")
+    os.replace(exe + ".tmp", exe)
+    return exe
+
+
 if __name__ == "__main__":
-    print(build_library(verbose="-v" in sys.argv))
+    if "--sanitize" in sys.argv:
+        print(build_sanitized(verbose="-v" in sys.argv))
+    else:
+        print(build_library(verbose="-v" in sys.argv))

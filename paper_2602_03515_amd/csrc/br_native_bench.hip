@@ -1,33 +1,15 @@
 // Stand-alone driver of the C ABI (no Python, no torch): allocates one pipeline stage's
-// matrices with hipMalloc, fills them with hash-generated low-rank-free noise, and runs
-// optimizer steps.  It exists for hardware-counter runs (a profiler attaches to a plain
-// executable) and as a C usage example of include/br.h.
+// matrices with hipMalloc, fills them with hash-generated noise, and runs optimizer steps through
+// the calls of include/br.h and nothing else.  It exists for hardware-counter runs (a profiler
+// attaches to a plain executable) and as a C usage example of the library.
 //
-//   br_native_bench [--layers N] [--steps K] [--freq F] [--math 0|1|2] [--copy-calibration] [--mfma-peak]
-//   br_native_bench --lowp-gemm M N K BATCH NPROD MIRROR
-//   br_native_bench --f32-gemm M N K BATCH TA TB QR LDC BETA
-//   br_native_bench --stream-peak
+//   br_native_bench [--layers N] [--steps K] [--freq F] [--math 0|1|2] [--small] [--copy-calibration]
+//   br_native_bench --host-only
 //
-// --f32-gemm times the FP32 matrix-core contraction alone at one shape (10 launches), e.g. the
-// trailing updates of the QR: QR = 1 selects the variant the factorisation uses, LDC > N updates
-// a block inside a wider matrix, BETA != 0 makes the kernel read C as well.
-//
-// --lowp-gemm checks and times the BF16 matrix-core contraction alone: BATCH products
-// C = A B^T (A: M x K, B: N x K, FP32 noise split into BF16 planes by the library's own split
-// kernel; MIRROR = 1 computes A A^T on the lower tiles only), compared on a strided sample of
-// the output with a plain one-thread-per-element kernel that forms the same BF16 products in
-// FP64, then timed over 10 launches.
-//
-// --mfma-peak runs br_mfma_peak instead of the optimizer: a register-only loop of
-// v_mfma_f32_32x32x2_f32 on every SIMD, once as a ~25 ms burst and once sustained for ~0.5 s,
-// which gives the FP32 matrix-core rate this machine actually holds (clocks drop under
-// sustained load), the practical ceiling for the contraction kernel; then the same for
-// v_mfma_f32_32x32x16_bf16 (br_mfma_peak_bf16).
-//
-// --stream-peak measures what the memory system sustains for the access mixes of the elementwise
-// kernels on 1 GiB arrays of noise: reads only, writes only, a copy, and the 2-read 1-write mix of
-// the first-moment update, each workgroup walking one contiguous range (as the library's kernels
-// do) and, for comparison, the last one with a grid-stride loop.
+// --small uses one layer of small ragged matrices instead of the 3B-class shapes (a quick run of every
+// call, e.g. under host-side sanitizers).  --host-only needs no GPU: it walks the library's host logic
+// alone (workspace planning for many configurations, every argument check of br_workspace_bytes,
+// br_init and br_clip_gradients_static) and is what a sanitizer build runs on a machine without one.
 //
 // --copy-calibration additionally launches br_plain_copy on 1 GiB (reads 1 GiB, writes 1 GiB),
 // the known-traffic kernel against which HBM byte counters are scaled.
@@ -40,7 +22,6 @@
 #include <vector>
 
 #include "../../include/br.h"
-#include "br_internal.h"
 
 #define CHECK_HIP(x)                                                                  \
   do {                                                                                \
@@ -65,318 +46,86 @@ __global__ void br_plain_copy(const float4* __restrict__ src, float4* __restrict
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
 }
 
-typedef float br_f4 __attribute__((ext_vector_type(4)));
-
-// mode 0: read, 1: write, 2: copy a -> b, 3: b = 0.9 b + 0.1 a; contiguous range per workgroup, or grid-stride
-__global__ __launch_bounds__(256) void br_stream(const br_f4* __restrict__ a, br_f4* __restrict__ b, size_t n4, int mode, int strided) {
-  size_t lo, hi, step;
-  if (strided) {
-    lo = (size_t)blockIdx.x * 256; hi = n4; step = (size_t)gridDim.x * 256;
-  } else {
-    const size_t per = (n4 + gridDim.x - 1) / gridDim.x;
-    lo = (size_t)blockIdx.x * per; hi = (lo + per < n4) ? lo + per : n4; step = 256;
-  }
-  br_f4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (size_t i = lo + threadIdx.x; i < hi; i += step) {
-    if (mode == 0) acc += __builtin_nontemporal_load(a + i);
-    else if (mode == 1) __builtin_nontemporal_store(br_f4{1.f, 2.f, 3.f, 4.f}, b + i);
-    else if (mode == 2) __builtin_nontemporal_store(__builtin_nontemporal_load(a + i), b + i);
-    else __builtin_nontemporal_store(0.9f * __builtin_nontemporal_load(b + i) + 0.1f * __builtin_nontemporal_load(a + i), b + i);
-  }
-  if (mode == 0 && acc.x == 1.2345f) b[0] = acc;
-}
-
-static int stream_peak() {
-  const size_t n4 = (size_t)1 << 26;  // 1 GiB per array
-  br_f4 *a, *b;
-  CHECK_HIP(hipMalloc(&a, n4 * 16));
-  CHECK_HIP(hipMalloc(&b, n4 * 16));
-  hipLaunchKernelGGL(br_fill_noise, dim3(4096), dim3(256), 0, 0, (float*)a, n4 * 4, 1u, 1.0f);
-  hipLaunchKernelGGL(br_fill_noise, dim3(4096), dim3(256), 0, 0, (float*)b, n4 * 4, 2u, 1.0f);
-  hipEvent_t e0, e1;
-  CHECK_HIP(hipEventCreate(&e0));
-  CHECK_HIP(hipEventCreate(&e1));
-  const char* names[5] = {"read", "write", "copy (1 read, 1 write)", "2 reads, 1 write", "2 reads, 1 write, grid-stride loop"};
-  const double arrays[5] = {1, 1, 2, 3, 3};
-  for (int k = 0; k < 5; ++k) {
-    const int mode = k < 4 ? k : 3, strided = k == 4;
-    hipLaunchKernelGGL(br_stream, dim3(2048), dim3(256), 0, 0, a, b, n4, mode, strided);
-    CHECK_HIP(hipDeviceSynchronize());
-    CHECK_HIP(hipEventRecord(e0, 0));
-    for (int r = 0; r < 5; ++r) hipLaunchKernelGGL(br_stream, dim3(2048), dim3(256), 0, 0, a, b, n4, mode, strided);
-    CHECK_HIP(hipEventRecord(e1, 0));
-    CHECK_HIP(hipEventSynchronize(e1));
-    float ms = 0.f;
-    CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
-    std::printf("br_stream %-36s %7.3f ms  %6.0f GB/s\n", names[k], ms / 5, arrays[k] * n4 * 16 / (ms / 5 * 1e-3) / 1e9);
-  }
-  return 0;
-}
-
-typedef float br_floatx16 __attribute__((ext_vector_type(16)));
-
-__global__ __launch_bounds__(256) void br_mfma_peak(float* out, int iters) {
-  br_floatx16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
-  unsigned x = (threadIdx.x + 1 + blockIdx.x * 977) * 2654435761u;
-  x ^= x >> 15; x *= 0x2c1b3c6du; x ^= x >> 12;
-  float a0 = (float)(x & 0xffff) / 65536.f - 0.5f, a1 = (float)(x >> 16) / 65536.f - 0.5f;
-  x *= 0x297a2d39u; x ^= x >> 15;
-  float b0 = (float)(x & 0xffff) / 65536.f - 0.5f, b1 = (float)(x >> 16) / 65536.f - 0.5f;
-  for (int i = 0; i < iters; i += 4) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, c0, 0, 0, 0);
-      c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, c1, 0, 0, 0);
-      c2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, c2, 0, 0, 0);
-      c3 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, c3, 0, 0, 0);
-    }
-  }
-  float s = 0.f;
-  for (int v = 0; v < 16; ++v) s += c0[v] + c1[v] + c2[v] + c3[v];
-  if (s == 12345.f) out[threadIdx.x] = s;  // keeps the loop alive
-}
-
-typedef __bf16 br_bf16x8 __attribute__((ext_vector_type(8)));
-typedef unsigned br_uintx4 __attribute__((ext_vector_type(4)));
-
-// Same register-only loop on v_mfma_f32_32x32x16_bf16 with pseudo-random BF16 operands.
-__global__ __launch_bounds__(256) void br_mfma_peak_bf16(float* out, int iters) {
-  br_floatx16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
-  unsigned x = (threadIdx.x + 1 + blockIdx.x * 977) * 2654435761u;
-  br_uintx4 ua, ub, uc, ud;
-  for (int e = 0; e < 4; ++e) {
-    x ^= x >> 15; x *= 0x2c1b3c6du; x ^= x >> 12;
-    ua[e] = (x & 0x807f807fu) | 0x3f003f00u;  // two BF16 values of magnitude 0.5 .. 1, random signs
-    x *= 0x297a2d39u; x ^= x >> 15;
-    ub[e] = (x & 0x807f807fu) | 0x3f003f00u;
-    uc[e] = ua[e] ^ 0x80000000u;
-    ud[e] = ub[e] ^ 0x00008000u;
-  }
-  const br_bf16x8 a0 = __builtin_bit_cast(br_bf16x8, ua), a1 = __builtin_bit_cast(br_bf16x8, uc);
-  const br_bf16x8 b0 = __builtin_bit_cast(br_bf16x8, ub), b1 = __builtin_bit_cast(br_bf16x8, ud);
-  for (int i = 0; i < iters; i += 4) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, c0, 0, 0, 0);
-      c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, c1, 0, 0, 0);
-      c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, c2, 0, 0, 0);
-      c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, c3, 0, 0, 0);
-    }
-  }
-  float s = 0.f;
-  for (int v = 0; v < 16; ++v) s += c0[v] + c1[v] + c2[v] + c3[v];
-  if (s == 12345.f) out[threadIdx.x] = s;  // keeps the loop alive
-}
-
-static int mfma_peak() {
-  float* d = nullptr;
-  CHECK_HIP(hipMalloc(&d, 4096));
-  hipEvent_t e0, e1;
-  CHECK_HIP(hipEventCreate(&e0));
-  CHECK_HIP(hipEventCreate(&e1));
-  const int grid = 256 * 4;  // four workgroups of four waves per compute unit
-  const int iters_list[2] = {50000, 1000000};
-  for (int k = 0; k < 2; ++k) {
-    hipLaunchKernelGGL(br_mfma_peak, dim3(grid), dim3(256), 0, 0, d, 1000);
-    CHECK_HIP(hipDeviceSynchronize());
-    CHECK_HIP(hipEventRecord(e0, 0));
-    hipLaunchKernelGGL(br_mfma_peak, dim3(grid), dim3(256), 0, 0, d, iters_list[k]);
-    CHECK_HIP(hipEventRecord(e1, 0));
-    CHECK_HIP(hipEventSynchronize(e1));
-    float ms = 0.f;
-    CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
-    double flops = (double)grid * 4 * iters_list[k] * 4.0 * 4096.0;
-    std::printf("br_mfma_peak %s: %.1f ms, %.1f TFLOP/s FP32 MFMA\n", k ? "sustained" : "burst", ms, flops / (ms * 1e-3) / 1e12);
-  }
-  for (int waves = 1; waves <= 2; ++waves) {  // waves per SIMD
-    for (int k = 0; k < 2; ++k) {
-      const int g2 = 256 * waves;
-      hipLaunchKernelGGL(br_mfma_peak_bf16, dim3(g2), dim3(256), 0, 0, d, 1000);
-      CHECK_HIP(hipDeviceSynchronize());
-      CHECK_HIP(hipEventRecord(e0, 0));
-      hipLaunchKernelGGL(br_mfma_peak_bf16, dim3(g2), dim3(256), 0, 0, d, iters_list[k] / waves);
-      CHECK_HIP(hipEventRecord(e1, 0));
-      CHECK_HIP(hipEventSynchronize(e1));
-      float ms = 0.f;
-      CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
-      double flops = (double)g2 * 4 * (iters_list[k] / waves) * 4.0 * 32768.0;
-      std::printf("br_mfma_peak_bf16 %s, %d wave(s) per SIMD: %.1f ms, %.1f TFLOP/s BF16 MFMA\n", k ? "sustained" : "burst", waves, ms,
-                  flops / (ms * 1e-3) / 1e12);
-    }
-  }
-  CHECK_HIP(hipFree(d));
-  return 0;
-}
-
-// ---- --lowp-gemm ---------------------------------------------------------------------------
-__device__ inline float nb_bf16_round(float f) {
-  unsigned u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return __uint_as_float(u & 0xffff0000u);
-}
-
-// ref[s] for sample s = (i, j) on a strided grid; err[0] = max |C - ref|, err[1] = max |ref| (as uint bits of floats)
-__global__ void br_lowp_reference(const float* A, const float* B, const float* C, int M, int N, int K, int nprod, int si, int sj,
-                                  int mirror, float alpha, unsigned* err) {
-  const int ni = (M + si - 1) / si, nj = (N + sj - 1) / sj;
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= ni * nj) return;
-  const int i = (s / nj) * si, j = (s % nj) * sj;
-  double acc = 0.0;
-  for (int k = 0; k < K; ++k) {
-    const float a = A[(size_t)i * K + k], b = B[(size_t)j * K + k];
-    const float ah = nb_bf16_round(a), bh = nb_bf16_round(b);
-    const float al = nb_bf16_round(a - ah), bl = nb_bf16_round(b - bh);
-    double p = (double)ah * bh;
-    if (nprod >= 3) p += (double)ah * bl + (double)al * bh;
-    if (nprod == 4 && (!mirror || i / 256 == j / 256)) p += (double)al * bl;  // mirrored: diagonal tiles only
-    acc += p;
-  }
-  const float ref = (float)(alpha * acc);
-  const float d = fabsf(C[(size_t)i * N + j] - ref);
-  atomicMax(&err[0], __float_as_uint(d));
-  atomicMax(&err[1], __float_as_uint(fabsf(ref)));
-}
-
-static int lowp_gemm_bench(int M, int N, int K, int batch, int nprod, int mirror) {
-  if (M <= 0 || N <= 0 || K <= 0 || batch < 1 || batch > BR_MAXB || (nprod != 1 && nprod != 3 && nprod != 4) || (mirror && M != N)) {
-    std::fprintf(stderr, "bad --lowp-gemm arguments\n");
-    return 2;
-  }
-  const BrPlaneLayout pa = br_plane_layout(M, K), pb = br_plane_layout(N, K);
-  std::vector<float*> A(batch), B(batch), C(batch);
-  std::vector<uint16_t*> Ap(batch), Bp(batch);
-  for (int i = 0; i < batch; ++i) {
-    CHECK_HIP(hipMalloc(&A[i], (size_t)M * K * 4));
-    CHECK_HIP(hipMalloc(&C[i], (size_t)M * N * 4));
-    CHECK_HIP(hipMalloc(&Ap[i], pa.elems * 4));
-    hipLaunchKernelGGL(br_fill_noise, dim3(2048), dim3(256), 0, 0, A[i], (size_t)M * K, 101u + i, 1.0f);
-    if (mirror) {
-      B[i] = A[i];
-      Bp[i] = Ap[i];
-    } else {
-      CHECK_HIP(hipMalloc(&B[i], (size_t)N * K * 4));
-      CHECK_HIP(hipMalloc(&Bp[i], pb.elems * 4));
-      hipLaunchKernelGGL(br_fill_noise, dim3(2048), dim3(256), 0, 0, B[i], (size_t)N * K, 7001u + i, 1.0f);
-    }
-    CHECK_HIP(hipMemset(C[i], 0xff, (size_t)M * N * 4));  // NaN pattern: unwritten outputs are caught
-  }
-  const int want_lo = nprod > 1;
-  CHECK_HIP(br_launch_split_planes(0, A.data(), Ap.data(), batch, M, K, K, 0, want_lo));
-  if (!mirror) CHECK_HIP(br_launch_split_planes(0, B.data(), Bp.data(), batch, N, K, K, 0, want_lo));
-  BrLowpBatch lb;
-  std::memset(&lb, 0, sizeof(lb));
-  for (int i = 0; i < batch; ++i) { lb.A[i] = Ap[i]; lb.B[i] = Bp[i]; lb.C[i] = C[i]; }
-  const float alpha = 0.5f;
-  BrLowpArgs la{M, N, K, N, alpha, 0.f, batch, mirror, nprod};
-  const char* name = nullptr;
-  CHECK_HIP(br_launch_gemm_lowp(0, la, lb, &name));
-  CHECK_HIP(hipDeviceSynchronize());
-  unsigned* err;
-  CHECK_HIP(hipMalloc(&err, 8));
-  const int si = M <= 512 ? 1 : 7, sj = N <= 512 ? 1 : 5;
-  const int samples = ((M + si - 1) / si) * ((N + sj - 1) / sj);
-  double worst = 0.0;
-  for (int i = 0; i < batch; i += (batch > 2 ? batch - 1 : 1)) {
-    CHECK_HIP(hipMemset(err, 0, 8));
-    hipLaunchKernelGGL(br_lowp_reference, dim3((samples + 255) / 256), dim3(256), 0, 0, A[i], B[i], C[i], M, N, K, nprod, si, sj,
-                       mirror, alpha, err);
-    unsigned h[2];
-    CHECK_HIP(hipMemcpy(h, err, 8, hipMemcpyDeviceToHost));
-    float d, r;
-    std::memcpy(&d, &h[0], 4);
-    std::memcpy(&r, &h[1], 4);
-    std::printf("matrix %d: max |C - ref| = %.3e, max |ref| = %.3e, ratio %.3e\n", i, d, r, d / r);
-    if (!(d / r < 1e-4)) worst = 1.0;
-    if (d / r > worst) worst = d / r;
-  }
-  hipEvent_t e0, e1;
-  CHECK_HIP(hipEventCreate(&e0));
-  CHECK_HIP(hipEventCreate(&e1));
-  const int reps = 20;
-  // the first launches after an idle period run slower (the clocks ramp up): time the steady state
-  for (int r = 0; r < reps; ++r) CHECK_HIP(br_launch_gemm_lowp(0, la, lb, nullptr));
-  CHECK_HIP(hipEventRecord(e0, 0));
-  for (int r = 0; r < reps; ++r) CHECK_HIP(br_launch_gemm_lowp(0, la, lb, nullptr));
-  CHECK_HIP(hipEventRecord(e1, 0));
-  CHECK_HIP(hipEventSynchronize(e1));
-  float ms = 0.f;
-  CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
-  double flops = 2.0 * M * N * (double)K * batch * (mirror ? 0.5 : 1.0);
-  std::printf("%s M=%d N=%d K=%d batch=%d mirror=%d: %.3f ms/launch, %.1f TFLOP/s (algorithmic), check %s\n", name, M, N, K, batch,
-              mirror, ms / reps, flops / (ms / reps * 1e-3) / 1e12, worst < 1e-4 ? "OK" : "FAILED");
-  return worst < 1e-4 ? 0 : 1;
-}
-
-// ---- --f32-gemm ----------------------------------------------------------------------------
-// Times one batched FP32 contraction at a given shape: C (M x N, row stride LDC) <- beta C +
-// alpha op(A) op(B), the operands stored with their natural row strides.  QR = 1 runs the
-// variant used inside the QR factorisation.  Timing only (the parity tests cover the values).
-static int f32_gemm_bench(int M, int N, int K, int batch, int ta, int tb, int qr, int ldc, float beta) {
-  if (M <= 0 || N <= 0 || K <= 0 || batch < 1 || batch > BR_MAXB || ldc < N) {
-    std::fprintf(stderr, "bad --f32-gemm arguments\n");
-    return 2;
-  }
-  const size_t ea = (size_t)M * K, eb = (size_t)N * K, ec = (size_t)M * ldc;
-  BrGemmBatch gb;
-  std::memset(&gb, 0, sizeof(gb));
-  for (int i = 0; i < batch; ++i) {
-    float *a, *b, *c;
-    CHECK_HIP(hipMalloc(&a, ea * 4));
-    CHECK_HIP(hipMalloc(&b, eb * 4));
-    CHECK_HIP(hipMalloc(&c, ec * 4));
-    hipLaunchKernelGGL(br_fill_noise, dim3(2048), dim3(256), 0, 0, a, ea, 11u + i, 1.0f);
-    hipLaunchKernelGGL(br_fill_noise, dim3(2048), dim3(256), 0, 0, b, eb, 911u + i, 1.0f);
-    CHECK_HIP(hipMemset(c, 0, ec * 4));
-    gb.A[i] = a; gb.B[i] = b; gb.C[i] = c;
-  }
-  BrGemmArgs a{M, N, K, ta ? M : K, tb ? K : N, ldc, ta, tb, 1e-3f, beta, batch, 0};
-  a.qr_role = qr;
-  float* partial = nullptr;
-  if (qr) {
-    a.partial_floats = (size_t)16 << 20;
-    CHECK_HIP(hipMalloc(&partial, a.partial_floats * 4));
-    a.partial = partial;
-  }
-  const char* name = nullptr;
-  CHECK_HIP(br_launch_gemm(0, a, gb, &name));
-  CHECK_HIP(hipDeviceSynchronize());
-  hipEvent_t e0, e1;
-  CHECK_HIP(hipEventCreate(&e0));
-  CHECK_HIP(hipEventCreate(&e1));
-  const int reps = 10;
-  CHECK_HIP(hipEventRecord(e0, 0));
-  for (int r = 0; r < reps; ++r) CHECK_HIP(br_launch_gemm(0, a, gb, nullptr));
-  CHECK_HIP(hipEventRecord(e1, 0));
-  CHECK_HIP(hipEventSynchronize(e1));
-  float ms = 0.f;
-  CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
-  const double flops = 2.0 * M * N * (double)K * batch;
-  std::printf("%s M=%d N=%d K=%d batch=%d ldc=%d beta=%g: %.3f ms/launch, %.1f TFLOP/s\n", name, M, N, K, batch, ldc, beta, ms / reps,
-              flops / (ms / reps * 1e-3) / 1e12);
-  return 0;
+// Host logic only: no kernel is launched, no device memory exists.  Returns the number of surprises.
+static int host_only() {
+  int bad = 0;
+  auto expect = [&](br_status got, br_status want, const char* what) {
+    if (got != want) { std::fprintf(stderr, "host-only: %s returned %d, expected %d (%s)\n", what, (int)got, (int)want, br_last_error(nullptr)); ++bad; }
+  };
+  const int64_t shapes[][2] = {{1, 1}, {37, 53}, {256, 256}, {2560, 6912}, {6912, 2560}, {32000, 2560}, {13000, 40}, {1 << 20, 3}};
+  size_t planned = 0;
+  for (int math = 0; math < 3; ++math)
+    for (int geometry = 0; geometry < 2; ++geometry)
+      for (int source = 0; source < 2; ++source)
+        for (int iters = 1; iters <= 2; ++iters)
+          for (int cache = 0; cache < 2; ++cache)
+            for (int dt = 0; dt < 2; ++dt) {
+              std::vector<br_matrix_desc> d;
+              for (auto& sh : shapes) d.push_back(br_matrix_desc{sh[0], sh[1], dt, dt, 1, 0});
+              for (int r = 0; r < 70; ++r) d.push_back(br_matrix_desc{96, 130, dt, BR_F32, r % 7 != 0, 0});  // more than one launch batch
+              br_hparams hp;
+              std::memset(&hp, 0, sizeof(hp));
+              hp.beta1 = 0.9f; hp.beta2 = 0.95f; hp.eps = 1e-8f; hp.stat_beta = -1.f;
+              hp.geometry = geometry; hp.source = source; hp.power_iters = iters; hp.math = math; hp.cache_rotated_moment = cache;
+              hp.stats_on_refresh_only = cache;
+              size_t st = 0, sc = 0;
+              expect(br_workspace_bytes(d.data(), (int32_t)d.size(), &hp, &st, &sc), BR_OK, "br_workspace_bytes");
+              if (st == 0 || sc == 0) { std::fprintf(stderr, "host-only: empty plan\n"); ++bad; }
+              ++planned;
+              // br_init's own checks, all ahead of any HIP call
+              br_ctx* ctx = nullptr;
+              expect(br_init(&ctx, d.data(), (int32_t)d.size(), &hp, nullptr, st + sc, nullptr), BR_ERR_INVALID_ARG, "br_init(null workspace)");
+              expect(br_init(&ctx, d.data(), (int32_t)d.size(), &hp, reinterpret_cast<void*>(0x1010), st + sc, nullptr), BR_ERR_WORKSPACE, "br_init(misaligned)");
+              expect(br_init(&ctx, d.data(), (int32_t)d.size(), &hp, reinterpret_cast<void*>(0x10000), st + sc - 1, nullptr), BR_ERR_WORKSPACE, "br_init(too small)");
+              if (ctx) { std::fprintf(stderr, "host-only: a failed br_init left a context\n"); ++bad; }
+            }
+  br_hparams hp;
+  std::memset(&hp, 0, sizeof(hp));
+  hp.beta1 = 0.9f; hp.beta2 = 0.95f; hp.eps = 1e-8f; hp.stat_beta = -1.f; hp.power_iters = 1;
+  br_matrix_desc one{8, 8, BR_F32, BR_F32, 1, 0};
+  size_t st = 0, sc = 0;
+  expect(br_workspace_bytes(nullptr, 1, &hp, &st, &sc), BR_ERR_INVALID_ARG, "null descriptors");
+  expect(br_workspace_bytes(&one, 0, &hp, &st, &sc), BR_ERR_INVALID_ARG, "n_mats = 0");
+  expect(br_workspace_bytes(&one, 1, &hp, nullptr, &sc), BR_ERR_INVALID_ARG, "null output");
+  br_matrix_desc neg{-4, 8, BR_F32, BR_F32, 1, 0}, dty{8, 8, 7, BR_F32, 1, 0}, res{8, 8, BR_F32, BR_F32, 1, 5};
+  expect(br_workspace_bytes(&neg, 1, &hp, &st, &sc), BR_ERR_SHAPE, "negative dimension");
+  expect(br_workspace_bytes(&dty, 1, &hp, &st, &sc), BR_ERR_DTYPE, "unknown dtype");
+  expect(br_workspace_bytes(&res, 1, &hp, &st, &sc), BR_ERR_INVALID_ARG, "reserved field");
+  br_hparams h2 = hp; h2.power_iters = 0;
+  expect(br_workspace_bytes(&one, 1, &h2, &st, &sc), BR_ERR_INVALID_ARG, "power_iters = 0");
+  h2 = hp; h2.math = 9;
+  expect(br_workspace_bytes(&one, 1, &h2, &st, &sc), BR_ERR_INVALID_ARG, "unknown math mode");
+  h2 = hp; h2.stats_on_refresh_only = 2;
+  expect(br_workspace_bytes(&one, 1, &h2, &st, &sc), BR_ERR_INVALID_ARG, "stats_on_refresh_only = 2");
+  // the entry point without a context: argument checks come before anything touches a device
+  void* g = reinterpret_cast<void*>(0x10000);
+  float result_stub[2];
+  expect(br_clip_gradients_static(nullptr, &g, 1, 1.f, result_stub, nullptr), BR_ERR_INVALID_ARG, "static clip: null descriptors");
+  expect(br_clip_gradients_static(&one, &g, BR_STATIC_CLIP_MAX_MATS + 1, 1.f, result_stub, nullptr), BR_ERR_WORKSPACE, "static clip: too many");
+  expect(br_clip_gradients_static(&one, &g, 1, 0.f, result_stub, nullptr), BR_ERR_INVALID_ARG, "static clip: max_norm = 0");
+  expect(br_clip_gradients_static(&neg, &g, 1, 1.f, result_stub, nullptr), BR_ERR_SHAPE, "static clip: negative dimension");
+  void* odd = reinterpret_cast<void*>(0x10004);
+  expect(br_clip_gradients_static(&one, &odd, 1, 1.f, result_stub, nullptr), BR_ERR_INVALID_ARG, "static clip: misaligned gradient");
+  std::printf("host-only: %zu configurations planned, %d surprises\n", planned, bad);
+  return bad;
 }
 
 int main(int argc, char** argv) {
-  if (argc == 11 && !std::strcmp(argv[1], "--f32-gemm"))
-    return f32_gemm_bench(std::atoi(argv[2]), std::atoi(argv[3]), std::atoi(argv[4]), std::atoi(argv[5]), std::atoi(argv[6]),
-                          std::atoi(argv[7]), std::atoi(argv[8]), std::atoi(argv[9]), (float)std::atof(argv[10]));
-  if (argc == 8 && !std::strcmp(argv[1], "--lowp-gemm"))
-    return lowp_gemm_bench(std::atoi(argv[2]), std::atoi(argv[3]), std::atoi(argv[4]), std::atoi(argv[5]), std::atoi(argv[6]),
-                           std::atoi(argv[7]));
-  int layers = 8, steps = 2, freq = 10, calib = 0, math = BR_MATH_F32;
+  if (argc == 2 && !std::strcmp(argv[1], "--host-only")) return host_only() ? 1 : 0;
+  int layers = 8, steps = 2, freq = 10, calib = 0, math = BR_MATH_F32, small = 0;
   for (int i = 1; i < argc; ++i) {
     if (!std::strcmp(argv[i], "--layers") && i + 1 < argc) layers = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--steps") && i + 1 < argc) steps = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--freq") && i + 1 < argc) freq = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--copy-calibration")) calib = 1;
     else if (!std::strcmp(argv[i], "--math") && i + 1 < argc) math = std::atoi(argv[++i]);
-    else if (!std::strcmp(argv[i], "--mfma-peak")) return mfma_peak();
-    else if (!std::strcmp(argv[i], "--stream-peak")) return stream_peak();
+    else if (!std::strcmp(argv[i], "--small")) small = 1;
     else { std::fprintf(stderr, "unknown argument %s\n", argv[i]); return 2; }
   }
-  const int64_t layer_shapes[7][2] = {{2560, 2560}, {2560, 2560}, {2560, 2560}, {2560, 2560},
-                                      {2560, 6912}, {2560, 6912}, {6912, 2560}};
+  const int64_t big_shapes[7][2] = {{2560, 2560}, {2560, 2560}, {2560, 2560}, {2560, 2560},
+                                    {2560, 6912}, {2560, 6912}, {6912, 2560}};
+  const int64_t small_shapes[7][2] = {{264, 136}, {264, 136}, {200, 200}, {37, 53}, {1700, 40}, {136, 264}, {600, 72}};
+  const int64_t (*layer_shapes)[2] = small ? small_shapes : big_shapes;
   std::vector<br_matrix_desc> descs;
   for (int l = 0; l < layers; ++l)
     for (int k = 0; k < 7; ++k) descs.push_back(br_matrix_desc{layer_shapes[k][0], layer_shapes[k][1], BR_F32, BR_F32, 1, 0});
