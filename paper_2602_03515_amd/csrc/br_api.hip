@@ -22,8 +22,10 @@ constexpr int kLowpChunk = 16;      // matrices per batched step launch in the B
 constexpr int64_t kMaxDim = 1 << 24;
 constexpr size_t kNormPartialBytes = (size_t)BR_MAXB * 2 * BR_NORM_BLOCKS * sizeof(float);
 constexpr size_t kSplitKBytes = (size_t)64 << 20;  // partial products of the QR's split-K contractions
-constexpr size_t kFailFlagBytes = 256;             // one int per factor of a refresh unit: "its factorisation was abandoned"
-static_assert(BR_MAXB * sizeof(int) <= kFailFlagBytes, "one flag per matrix of a batched launch");
+// Per refresh unit, behind its factors' scratch: one int per factor "its factorisation was abandoned" (first 256 bytes),
+// then two words per factor for the largest magnitudes of A and of the current power-iteration operand (256 bytes each).
+constexpr size_t kFailFlagBytes = 768;
+static_assert(BR_MAXB * sizeof(int) <= 256, "one flag per matrix of a batched launch");
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -187,7 +189,13 @@ struct RefreshScratch {
 // the number of passes over C.
 constexpr int kQrMaxLevels = 2;
 static_assert((BR_QR_NBM << kQrMaxLevels) == BR_QR_NBT, "widest top block = middle block doubled kQrMaxLevels times");
-inline int qr_levels(const br_hparams& hp) { return hp.math == BR_MATH_BF16 ? 2 : 1; }
+// Factors above this order run their large products (A Q, and the top blocks' updates of the QR) as split FP16
+// products on the 16-bit matrix cores, in every math mode; smaller ones stay on the FP32 matrix cores.
+constexpr int64_t kSplitRefreshMinOrder = 512;
+inline bool split_refresh(int64_t k) { return k > kSplitRefreshMinOrder; }
+inline int qr_levels(int64_t k) { return split_refresh(k) ? 2 : 1; }
+// Powers of two that centre the operands of the split FP16 products in the FP16 range (see qr_batch).
+constexpr float kScaleV = 64.f, kScaleY = 64.f, kScaleC = 128.f, kScaleW = 64.f;
 // floats before level l's pair of child factors in the Tl scratch
 inline size_t qr_level_offset(int l) {
   size_t off = 0;
@@ -219,12 +227,12 @@ RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   r.Z = off; off += align256((size_t)(BR_QR_NBT / 2) * (BR_QR_NBT / 2) * 4);  // T_0 (V_0^T V_1)
   r.diag = off; off += align256((size_t)k * 4);
   r.xch = off; off += align256(br_qr_panel_xch_floats((int)k) * 4);            // cluster exchange of one panel launch
-  // BF16 math mode: hi + lo planes of the statistics and of the transposed basis for the power iteration
-  const size_t pl = (hp.math == BR_MATH_BF16) ? align256(4 * br_plane_layout(k, k).elems) : 0;
+  // split products: hi + lo planes of the statistics and of the transposed basis for the power iteration
+  const size_t pl = split_refresh(k) ? align256(4 * br_plane_layout(k, k).elems) : 0;
   r.planesA = off; off += pl;
   r.planesB = off; off += pl;
   // ... and of V^T, V T, (V^T C)^T for the top blocks' updates of the QR
-  r.qrp = off; if (hp.math == BR_MATH_BF16) off += 3 * qr_plane_chunk(k);
+  r.qrp = off; if (split_refresh(k)) off += 3 * qr_plane_chunk(k);
   r.total = off;
   return r;
 }
@@ -353,6 +361,7 @@ bool gemm(br_ctx* c, BrGemmArgs a, const BrGemmBatch& b, bool step = true, float
     if (a.mirror) flops *= 0.5 * (1.0 + 1.0 / std::max(1, (a.M + 127) / 128));
     BrGemmArgs probe{0, 0, 0, 0, 0, 0, a.transA, a.transB, 0, 0, 0, 0};
     probe.adam_epilogue = a.adam_epilogue;
+    probe.mirror = a.mirror;
     (void)br_launch_gemm(nullptr, probe, b, &name);
     Timed tm(c, name, flops, 0.0);
     return hip_ok(c, br_launch_gemm(c->stream, a, b, nullptr), "gemm launch");
@@ -387,6 +396,15 @@ bool lowp_split(const LowpCtx& x, const float* const* src, int R, int Ccols, boo
   Timed tm(x.c, "br_split_planes", 0.0, (double)R * Ccols * x.B * (4.0 + (x.nprod == 3 ? 4.0 : 2.0)));
   return hip_ok(x.c, br_launch_split_planes(x.c->stream, src, dst, x.B, R, Ccols, ld, transpose ? 1 : 0,
                                             x.nprod == 3 ? 1 : 0), "plane split launch");
+}
+
+// hi + lo FP16 planes of scale * src[i] (the refresh's split products).  With maxbits the scale of matrix i is
+// multiplied by the power of two that brings its largest magnitude into [2^(target_exp-1), 2^target_exp).
+bool f16_split(const LowpCtx& x, const float* const* src, int R, int Ccols, bool transpose, uint16_t* const* dst, int ld,
+               float scale, const unsigned* maxbits = nullptr, int target_exp = 0) {
+  if (ld == 0) ld = Ccols;
+  return hip_ok(x.c, br_launch_split_planes(x.c->stream, src, dst, x.B, R, Ccols, ld, transpose ? 1 : 0, 1, 1, scale, maxbits,
+                                            target_exp), "plane split launch");
 }
 
 // C_i = alpha A_i B_i^T + beta C_i with A_i: M x K planes, B_i: N x K planes.  With an epilogue other
@@ -1008,7 +1026,7 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs,
                      char* base, size_t stride, float* partial, int* failed) {
   const int NB = BR_QR_NB, NBM = BR_QR_NBM;
-  const int levels = qr_levels(c->hp);
+  const int levels = qr_levels(k);
   const int NBT = NBM << levels;  // width of a top block
   const int ntop = (k + NBT - 1) / NBT;
   auto F = [&](int i, size_t off) { return reinterpret_cast<float*>(base + i * stride + off); };
@@ -1036,15 +1054,22 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
   }
   const int* skip_q = nullptr;  // set for the phase that writes Q
   // The update both phases share: C <- C - Yb (V^T C) for the rows x ncols blocks C (row stride k), with
-  // Yb = V T^T or V T already in Y.  BR_MATH_BF16 runs its two contractions on the BF16 matrix cores
-  // with hi + lo split operands and three partial products (16-bit mantissa inputs, FP32
-  // accumulation, C itself stays FP32): the bases of that mode come from statistics that are
-  // only BF16 accurate, and these two products are three quarters of the refresh.  The operand
+  // Yb = V T^T or V T already in Y.  Above kSplitRefreshMinOrder the two contractions run on the 16-bit
+  // matrix cores as split FP16 products: every operand is hi + lo FP16 (22 mantissa bits, or an absolute
+  // 2^-25 of the operand's scale for small entries; subnormal lo parts are kept and the matrix instruction
+  // honours them), three partial products hi*hi + hi*lo + lo*hi accumulated in FP32, C itself stays FP32.
+  // These two products are three quarters of the refresh, and they run at three to four times the rate of
+  // the FP32 matrix cores.  FP16's range is narrow, so each operand kind carries a fixed power-of-two scale
+  // (undone through alpha): reflectors are at most 1 in magnitude (x 64), V T likewise moderate (x 64); the
+  // matrix being factorised arrives normalised (largest entry of A below 2^-7, so |A Q| <= 1 up to order
+  // 16384 and its column norms, which bound every later entry of C, stay below 2^9; x 128), Q's entries are at
+  // most 1 (x 128), and |V^T C| <= sqrt(2) |c_j| (x 64).  Values beyond the range would be clamped, not
+  // turned into infinities.  The operand
   // planes of C^T are not made again for every block: the whole matrix is split once per phase
   // (planes of P^T, planes of Q^T), a block's C^T is a view into that set (blocks start at multiples
   // of 256), and the update's epilogue rewrites the view from the values it stores.  The product
   // V^T C leaves its kernel transposed and already split, as the operand of the second one.
-  const bool x3 = c->hp.math == BR_MATH_BF16;
+  const bool x3 = split_refresh(k);
   LowpCtx lx{c, nullptr, LowpLayout{}, B, 3, nullptr};
   lx.quiet = true;
   const size_t qchunk = qr_plane_chunk(k);
@@ -1057,7 +1082,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     const float* src[BR_MAXB];
     uint16_t* dst[BR_MAXB];
     for (int i = 0; i < B; ++i) { src[i] = Mx[i]; dst[i] = reinterpret_cast<uint16_t*>(base + i * stride + set); }
-    return lowp_split(lx, src, k, k, true, dst);
+    return f16_split(lx, src, k, k, true, dst, 0, kScaleC);
   };
   // Vb: the block's reflectors (rows x width, row stride NBT); Yb in Y (rows x width, row stride width);
   // Cp: the blocks C (FP32); set/row0/k0: where their transposes live as planes; emit: keep those planes current
@@ -1080,15 +1105,17 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       pw[i] = reinterpret_cast<uint16_t*>(q + 2 * qchunk);
     }
     for (int i = 0; i < B; ++i) src[i] = Vb[i];
-    if (!lowp_split(lx, src, rows, width, true, pv, NBT)) return false;     // planes of V^T   [width][rows]
+    if (!f16_split(lx, src, rows, width, true, pv, NBT, kScaleV)) return false;   // planes of V^T   [width][rows]
     for (int i = 0; i < B; ++i) src[i] = Y(i);
-    if (!lowp_split(lx, src, rows, width, false, py)) return false;         // planes of Yb    [rows][width]
+    if (!f16_split(lx, src, rows, width, false, py, 0, kScaleY)) return false;    // planes of Yb    [rows][width]
     BrLowpBatch lb;
     std::memset(&lb, 0, sizeof(lb));
     for (int i = 0; i < B; ++i) { lb.A[i] = pv[i]; lb.B[i] = view(set, i, row0, k0); lb.shadow[i] = pw[i]; }
-    BrLowpArgs wa{width, ncols, rows, 0, 1.f, 0.f, B, 0, 3};                // (V^T C)^T as planes [ncols][width]
+    BrLowpArgs wa{width, ncols, rows, 0, 1.f / (kScaleV * kScaleC), 0.f, B, 0, 3};  // (V^T C)^T as planes [ncols][width]
     wa.epilogue = BR_EPI_PLANES;
     wa.out_lo = 1;
+    wa.f16 = 1;
+    wa.out_scale = kScaleW;
     wa.b_stride_rows = (int)Lk.rows_p;
     wa.b_plane_elems = Lk.elems;
     if (!hip_ok(c, br_launch_gemm_lowp(s, wa, lb, nullptr), "qr bf16 product launch")) return false;
@@ -1097,8 +1124,10 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       lb.A[i] = py[i]; lb.B[i] = pw[i]; lb.C[i] = Cp[i];
       if (emit) lb.S[i] = reinterpret_cast<float*>(view(set, i, row0, k0));  // the updated C^T, for the next block
     }
-    BrLowpArgs ua{rows, ncols, width, k, -1.f, 1.f, B, 0, 3};
+    BrLowpArgs ua{rows, ncols, width, k, -1.f / (kScaleY * kScaleW), 1.f, B, 0, 3};
     ua.skip = skip_q;
+    ua.f16 = 1;
+    ua.out_scale = kScaleC;
     if (emit) {
       ua.out_lo = 1;
       ua.emit_transposed = 1;
@@ -1291,27 +1320,44 @@ br_status br_refresh_basis(br_ctx* ctx) {
         if (!gemm(c, a, one)) return BR_ERR_HIP;
       }
     }
-    // P <- A^iters Q.  In the BF16 math mode the product runs on the BF16 matrix cores with both
-    // operands split into hi + lo planes and three partial products (16-bit mantissa inputs), like
-    // the large updates of the QR that follows; BF16X3 keeps FP32 here: the QR amplifies an input
-    // error by the condition number of A, and 2^-17 per entry is already too much for that mode's
-    // 1e-4 bar.
+    // P <- A^iters Q.  Above kSplitRefreshMinOrder the product runs on the 16-bit matrix cores as a split FP16
+    // product (hi + lo FP16 operands, three partial products, FP32 accumulation: see qr_batch), in every math mode.
+    // The orthogonal factor does not depend on the scale of P, so both operands are normalised by powers of two
+    // taken from their largest magnitudes (A's into [2^8, 2^9), the multiplied matrix's into [2^5, 2^6)) and alpha is
+    // the constant 2^-22: P comes out as (A / a) (X / x) with a, x the largest entries rounded up to powers of two and
+    // divided by 2^-7 resp. 1, i.e. |P| <= sqrt(k) 2^-7, which is what the split products of the QR expect.
     float** src = Q;
     float** dst = P0;
-    const bool lowp = hp.math == BR_MATH_BF16;
+    const bool lowp = split_refresh(k);
     LowpCtx lx{c, nullptr, LowpLayout{}, B, 3, nullptr};
     uint16_t *plA[BR_MAXB], *plB[BR_MAXB];
     for (int i = 0; i < B && lowp; ++i) {
       plA[i] = reinterpret_cast<uint16_t*>(base + i * rs.total + rs.planesA);
       plB[i] = reinterpret_cast<uint16_t*>(base + i * rs.total + rs.planesB);
     }
-    if (lowp && !lowp_split(lx, A, k, k, false, plA)) return BR_ERR_HIP;
+    unsigned* maxA = reinterpret_cast<unsigned*>(base + (size_t)B * rs.total + 256);
+    unsigned* maxX = reinterpret_cast<unsigned*>(base + (size_t)B * rs.total + 512);
+    if (lowp) {
+      int* zp[1] = {reinterpret_cast<int*>(maxA)};
+      if (!hip_ok(c, br_launch_zero_ints(c->stream, zp, 1, BR_MAXB), "magnitude clear launch")) return BR_ERR_HIP;
+      if (!hip_ok(c, br_launch_absmax(c->stream, A, B, k, k, k, maxA), "magnitude launch")) return BR_ERR_HIP;
+      if (!f16_split(lx, A, k, k, false, plA, 0, 1.f, maxA, 9)) return BR_ERR_HIP;
+    }
     for (int it = 0; it < hp.power_iters; ++it) {
       if (lowp) {
         const float* s32[BR_MAXB];
         for (int i = 0; i < B; ++i) s32[i] = src[i];
-        if (!lowp_split(lx, s32, k, k, true, plB)) return BR_ERR_HIP;  // planes of src^T: B[j][l] = src[l][j]
-        if (!lowp_gemm(lx, plA, k, plB, k, k, dst, k, 1.f, 0.f, nullptr, false, 3)) return BR_ERR_HIP;
+        int* zp[1] = {reinterpret_cast<int*>(maxX)};
+        if (!hip_ok(c, br_launch_zero_ints(c->stream, zp, 1, BR_MAXB), "magnitude clear launch")) return BR_ERR_HIP;
+        if (!hip_ok(c, br_launch_absmax(c->stream, s32, B, k, k, k, maxX), "magnitude launch")) return BR_ERR_HIP;
+        if (!f16_split(lx, s32, k, k, true, plB, 0, 1.f, maxX, 6)) return BR_ERR_HIP;  // planes of src^T: B[j][l] = src[l][j]
+        BrLowpBatch lb;
+        std::memset(&lb, 0, sizeof(lb));
+        for (int i = 0; i < B; ++i) { lb.A[i] = plA[i]; lb.B[i] = plB[i]; lb.C[i] = dst[i]; }
+        BrLowpArgs la{k, k, k, k, std::ldexp(1.0f, -22), 0.f, B, 0, 3};
+        la.f16 = 1;
+        Timed tm(c, "br_gemm_f16_mfma<3>", 2.0 * k * (double)k * k * B, 0.0);
+        if (!hip_ok(c, br_launch_gemm_lowp(c->stream, la, lb, nullptr), "split product launch")) return BR_ERR_HIP;
       } else {
         for (int i = 0; i < B; ++i) { gb.A[i] = A[i]; gb.B[i] = src[i]; gb.C[i] = dst[i]; }
         if (!gemm(c, BrGemmArgs{k, k, k, k, k, k, 0, 0, 1.f, 0.f, B, 0}, gb)) return BR_ERR_HIP;

@@ -449,6 +449,8 @@ hipError_t br_launch_gemm(hipStream_t s, const BrGemmArgs& a, const BrGemmBatch&
   if (kernel_name) {
     *kernel_name = names[(a.qr_role ? 4 : 0) + (a.transA ? 2 : 0) + (a.transB ? 1 : 0)];
     if (a.adam_epilogue) *kernel_name = a.transA ? "br_gemm_f32_mfma<tn,adam>" : "br_gemm_f32_mfma<nn,adam>";
+    // symmetric products (the statistics) run the same kernels on the lower triangle of tiles, each stored twice
+    if (a.mirror && !a.qr_role) *kernel_name = a.transA ? "br_gemm_f32_mfma<tn,sym>" : "br_gemm_f32_mfma<nt,sym>";
   }
   if (a.batch <= 0 || a.M <= 0 || a.N <= 0) return hipSuccess;
   if (a.batch > BR_MAXB || a.K < 0) return hipErrorInvalidValue;

@@ -114,13 +114,24 @@ struct BrLowpArgs {
   int emit_transposed = 0;
   const int* skip = nullptr;   // BR_EPI_F32: device array, one int per matrix: non-zero = store nothing for that matrix
   int* health = nullptr;       // BR_EPI_F32: BR_HEALTH_NONFINITE_WEIGHT is bumped when a stored value is not finite
+  // FP16 planes (nprod = 3, BR_EPI_F32 or BR_EPI_PLANES): both operands are hi + lo FP16 planes of scaled values and
+  // the products are f16 matrix instructions; alpha carries the inverse of the operands' scales; emitted planes
+  // hold out_scale times the value.
+  int f16 = 0;
+  float out_scale = 1.f;
 };
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name);
 // hi = bf16(x), lo = bf16(x - hi) of an R x C FP32 matrix (row stride ld_src) into planes of
 // br_plane_layout(R, C); transpose != 0 writes the planes of the transposed matrix,
 // br_plane_layout(C, R).  The padding is written too (zeros).
+// f16 != 0: FP16 planes of scale * x instead (hi = fp16, lo = fp16 of the remainder; values beyond the FP16 range are
+// clamped).  With maxbits (one word per matrix, written by br_launch_absmax) the scale of matrix i is further
+// multiplied by the power of two that brings its largest magnitude into [2^(target_exp-1), 2^target_exp).
 hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
-                                  int ld_src, int transpose, int want_lo);
+                                  int ld_src, int transpose, int want_lo, int f16 = 0, float scale = 1.f,
+                                  const unsigned* maxbits = nullptr, int target_exp = 0);
+// maxbits[i] = bit pattern of max |src[i]| (R x Ccols, row stride ld_src).  maxbits must be ZERO beforehand.
+hipError_t br_launch_absmax(hipStream_t s, const float* const* src, int batch, int R, int Ccols, int ld_src, unsigned* maxbits);
 // The first moment and both plane sets of the R x C gradients G[i] (contiguous) in one pass:
 // M <- beta1 M + (1 - beta1) G, planes of G into P (br_plane_layout(R, C)), planes of G^T into PT.
 hipError_t br_launch_ingest_planes(hipStream_t s, const float* const* G, float* const* M, uint16_t* const* P, uint16_t* const* PT,

@@ -54,6 +54,7 @@ constexpr int LOADS = 4;                // 1 KB loads per wave and stage (one pe
 constexpr int FM = 4, FN = 2;           // 32 x 32 accumulators per wave (wave tile 128 x 64)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 struct LowpKernArgs {
@@ -73,6 +74,7 @@ struct LowpKernArgs {
   int b_stride;          // padded row count that addresses the B planes (Np, or a larger set's when B is a view into it)
   int out_stride;        // the same for the emitted planes
   int emit_t;            // EPI_F32: the transpose of the stored result also leaves as planes (pointer in the batch's S slot)
+  float out_scale;       // emitted planes hold out_scale times the value (FP16 planes: a power of two that centres the range)
   const int* skip;       // EPI_F32, optional: one int per matrix, non-zero = nothing is stored for that matrix
   int* health;           // EPI_F32, optional: a stored value that is not finite bumps BR_HEALTH_NONFINITE_WEIGHT
 };
@@ -89,6 +91,20 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// FP16 planes (the refresh's split products): hi = fp16(x), lo = fp16(x - hi), both round to nearest even, subnormal
+// results kept (the f16 matrix instruction honours them): 22 mantissa bits for |x| >= 2^-3, an absolute 2^-25 below.
+// Values beyond the FP16 range are clamped to it (the callers' scales keep operands far inside).
+__device__ __forceinline__ uint16_t f32_to_f16_rne(float f) {
+  f = fminf(fmaxf(f, -65504.0f), 65504.0f);
+  return __builtin_bit_cast(uint16_t, (_Float16)f);
+}
+__device__ __forceinline__ float f16_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+template <bool F16>
+__device__ __forceinline__ uint16_t to_plane(float f) { return F16 ? f32_to_f16_rne(f) : f32_to_bf16_rne(f); }
+template <bool F16>
+__device__ __forceinline__ float from_plane(uint16_t h) { return F16 ? f16_to_f32(h) : bf16_to_f32(h); }
 
 // The 16-byte half h (8 k) of row r inside a k-block sits at position h ^ swz(r).  The operand
 // reads of a wave touch 32 consecutive rows at one logical half: with the swap, any 8 or 16
@@ -122,12 +138,14 @@ __device__ __forceinline__ void emit_chunks(uint16_t* __restrict__ P, const uint
   }
 }
 
-__device__ __forceinline__ void pack_hi_lo(const float (&val)[4], uint32_t (&hi)[2], uint32_t (&lo)[2], bool want_lo) {
+template <bool F16>
+__device__ __forceinline__ void pack_hi_lo(const float (&val)[4], uint32_t (&hi)[2], uint32_t (&lo)[2], bool want_lo, float scale) {
   uint16_t h[4], l[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    h[e] = f32_to_bf16_rne(val[e]);
-    l[e] = want_lo ? f32_to_bf16_rne(val[e] - bf16_to_f32(h[e])) : (uint16_t)0;
+    const float x = F16 ? val[e] * scale : val[e];
+    h[e] = to_plane<F16>(x);
+    l[e] = want_lo ? to_plane<F16>(x - from_plane<F16>(h[e])) : (uint16_t)0;
   }
   hi[0] = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
   hi[1] = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
@@ -155,7 +173,9 @@ namespace br {
 //               Algorithm 1, from the rotated moment to the update) and X = M~ / sqrt(S~ + eps) leaves as planes like above.
 //               With adam_t the tile is G~^T instead (right factor only: G~^T = Q_R^T G^T), the
 //               moments are indexed [col][row], and what leaves are the planes of X itself.
-template <int NPROD, int EPI>
+// F16: the planes hold FP16 values and the products are v_mfma_f32_32x32x16_f16 (same shape, same lane layout and
+// rate as the BF16 instruction).
+template <int NPROD, int EPI, bool F16 = false>
 __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLowpBatch batch) {
   constexpr bool SPLIT = NPROD > 1;
   constexpr int KS = SPLIT ? 1 : 2;   // k-steps (16 k) per stage
@@ -233,7 +253,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
     }
   };
 
-  struct AFrag { bf16x8 hi[MPG], lo[MPG]; };
+  struct AFrag { bf16x8 hi[MPG], lo[MPG]; };  // FP16 planes travel in the same registers and are re-typed at the instruction
   struct BFrag { bf16x8 hi[FN], lo[FN]; };
   const int half = lk ^ swz(li);  // wave tile rows start at multiples of 32: swz(row) == swz(li)
   const int a_row = (wm * FM * 32 + li) * 2 + half, b_row = (wn * FN * 32 + li) * 2 + half;
@@ -253,6 +273,13 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
       if (SPLIT) f.lo[q] = __builtin_bit_cast(bf16x8, lds[base + SUB_U4 + q * 64]);
     }
   };
+#define BR_MMA(x, y, c)                                                                                                        \
+  do {                                                                                                                         \
+    if constexpr (F16)                                                                                                         \
+      c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, x), __builtin_bit_cast(half8, y), c, 0, 0, 0);      \
+    else                                                                                                                       \
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, c, 0, 0, 0);                                                           \
+  } while (0)
   // NPROD = 4 exists for the symmetric statistics, whose DIAGONAL would otherwise carry the bias
   // sum_k lo_k^2 (every term positive).  Off the diagonal the lo*lo terms have random signs and sum
   // to about 2^-18 / sqrt(K) of the matrix's scale, below FP32 resolution: only the tiles on the
@@ -264,13 +291,12 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
       const int mi = grp * MPG + q;
 #pragma unroll
       for (int ni = 0; ni < FN; ++ni) {
-        if (NPROD == 4 && lolo)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo[q], b.lo[ni], acc[mi][ni], 0, 0, 0);
+        if (NPROD == 4 && lolo) BR_MMA(a.lo[q], b.lo[ni], acc[mi][ni]);
         if (NPROD >= 3) {
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo[q], b.hi[ni], acc[mi][ni], 0, 0, 0);
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi[q], b.lo[ni], acc[mi][ni], 0, 0, 0);
+          BR_MMA(a.lo[q], b.hi[ni], acc[mi][ni]);
+          BR_MMA(a.hi[q], b.lo[ni], acc[mi][ni]);
         }
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi[q], b.hi[ni], acc[mi][ni], 0, 0, 0);
+        BR_MMA(a.hi[q], b.hi[ni], acc[mi][ni]);
       }
     }
   };
@@ -390,7 +416,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
               bad |= not_finite(val[e]);
             }
           }
-          if (g.emit_t) pack_hi_lo(val, wh[vg], wl[vg], g.out_lo != 0);
+          if (g.emit_t) pack_hi_lo<F16>(val, wh[vg], wl[vg], g.out_lo != 0, g.out_scale);
           if (off_diag && col < g.N && Mlim > 0) {
             // transposed copy of a symmetric result: this lane's four rows are four consecutive columns there
             float* dst = C + (size_t)col * (size_t)g.ldc + row0;
@@ -477,7 +503,7 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
               val[e] = x;
             }
           }
-          pack_hi_lo(val, wh[vg], wl[vg], g.out_lo != 0);
+          pack_hi_lo<F16>(val, wh[vg], wl[vg], g.out_lo != 0, g.out_scale);
         }
         {
           const int kbase = m0 + (wm * FM + mi) * 32;
@@ -501,25 +527,68 @@ struct SplitArgs {
   uint16_t* dst[BR_MAXB];  // hi plane; the lo plane follows at +plane elements
 };
 
-__device__ __forceinline__ void split8(const float* x, uint4* hi4, uint4* lo4) {
+// What a split kernel writes: BF16 planes of x, or FP16 planes of scale * x.
+struct PlaneFormat {
+  int f16;
+  float scale;
+};
+
+// scale = base * 2^(target - e) with max = f * 2^e, f in [0.5, 1): the largest entry lands in [2^(target-1), 2^target).
+__device__ __forceinline__ float normalising_scale(float base, const unsigned* maxbits, int target_exp) {
+  if (!maxbits) return base;
+  const float mx = __uint_as_float(maxbits[blockIdx.y]);
+  if (!(mx > 0.f) || (__float_as_uint(mx) & 0x7f800000u) == 0x7f800000u) return base;
+  int e;
+  (void)frexpf(mx, &e);
+  return ldexpf(base, target_exp - e);
+}
+
+template <bool F16>
+__device__ __forceinline__ void split8_as(const float* x, uint4* hi4, uint4* lo4, float scale) {
   uint32_t hi[4], lo[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const uint16_t h0 = f32_to_bf16_rne(x[2 * e]), h1 = f32_to_bf16_rne(x[2 * e + 1]);
+    const float x0 = F16 ? x[2 * e] * scale : x[2 * e], x1 = F16 ? x[2 * e + 1] * scale : x[2 * e + 1];
+    const uint16_t h0 = to_plane<F16>(x0), h1 = to_plane<F16>(x1);
     hi[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-    const uint16_t l0 = f32_to_bf16_rne(x[2 * e] - bf16_to_f32(h0));
-    const uint16_t l1 = f32_to_bf16_rne(x[2 * e + 1] - bf16_to_f32(h1));
+    const uint16_t l0 = to_plane<F16>(x0 - from_plane<F16>(h0));
+    const uint16_t l1 = to_plane<F16>(x1 - from_plane<F16>(h1));
     lo[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
   }
   *hi4 = make_uint4(hi[0], hi[1], hi[2], hi[3]);
   *lo4 = make_uint4(lo[0], lo[1], lo[2], lo[3]);
 }
 
+__device__ __forceinline__ void split8(const float* x, uint4* hi4, uint4* lo4, PlaneFormat f = PlaneFormat{0, 1.f}) {
+  if (f.f16) split8_as<true>(x, hi4, lo4, f.scale);
+  else split8_as<false>(x, hi4, lo4, 1.f);
+}
+
+// Largest magnitude of each matrix of a batch, as the bit pattern of a non-negative float (which orders like the
+// integer it is: an integer atomic maximum, the same result in any order).  maxbits must be zero beforehand.
+__global__ __launch_bounds__(256) void br_absmax(SplitArgs a, int R, int Ccols, int ld_src, unsigned* __restrict__ maxbits) {
+  __shared__ unsigned red[4];
+  const float* __restrict__ X = a.src[blockIdx.y];
+  const int64_t total = (int64_t)R * Ccols;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  float m = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int64_t r = i / Ccols;
+    m = fmaxf(m, fabsf(X[r * ld_src + (i - r * Ccols)]));
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = __float_as_uint(m);
+  __syncthreads();
+  if (threadIdx.x == 0) atomicMax(maxbits + blockIdx.y, max(max(red[0], red[1]), max(red[2], red[3])));
+}
+
 // Same orientation: plane rows = source rows, k = source column.  One thread per 16-byte chunk
 // of the padded plane, chunk index within 32 k fastest, then row, then 32-k group: a wave reads
 // 16 whole 128-byte lines of the source and writes two contiguous 512-byte runs of plane.
 __global__ __launch_bounds__(256) void br_split_planes(SplitArgs a, int R, int Ccols, int ld_src, int Rp, int Kp, size_t plane,
-                                                       int want_lo) {
+                                                       int want_lo, PlaneFormat fmt, const unsigned* maxbits, int target_exp) {
+  fmt.scale = normalising_scale(fmt.scale, maxbits, target_exp);
   const float* __restrict__ X = a.src[blockIdx.y];
   uint16_t* __restrict__ H = a.dst[blockIdx.y];
   const int64_t total = (int64_t)Rp * (Kp >> 3);
@@ -542,7 +611,7 @@ __global__ __launch_bounds__(256) void br_split_planes(SplitArgs a, int R, int C
       for (int e = 0; e < 8; ++e) x[e] = (r < R && c0 + e < Ccols) ? X[(size_t)r * ld_src + c0 + e] : 0.f;
     }
     uint4 hi4, lo4;
-    split8(x, &hi4, &lo4);
+    split8(x, &hi4, &lo4, fmt);
     const size_t o = (((size_t)(c0 >> 4) * Rp + r) * 2 + (((c0 >> 3) & 1) ^ swz(r))) * 8;
     *reinterpret_cast<uint4*>(H + o) = hi4;
     if (want_lo) *reinterpret_cast<uint4*>(H + plane + o) = lo4;
@@ -553,8 +622,9 @@ __global__ __launch_bounds__(256) void br_split_planes(SplitArgs a, int R, int C
 // blockIdx.x enumerates tiles over the PADDED plane (Kp / 64 along k, Rp / 64 along rows), so
 // the zero padding is written by the same pass.
 __global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int Ccols, int ld_src, int Rp, int Kp, size_t plane,
-                                                         int want_lo) {
+                                                         int want_lo, PlaneFormat fmt, const unsigned* maxbits, int target_exp) {
   __shared__ float tile[64][65];
+  fmt.scale = normalising_scale(fmt.scale, maxbits, target_exp);
   const float* __restrict__ X = a.src[blockIdx.y];
   uint16_t* __restrict__ H = a.dst[blockIdx.y];
   const int tiles_c = Rp >> 6;
@@ -595,7 +665,7 @@ __global__ __launch_bounds__(256) void br_split_planes_t(SplitArgs a, int R, int
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = tile[rch * 8 + e][cc];
     uint4 hi4, lo4;
-    split8(x, &hi4, &lo4);
+    split8(x, &hi4, &lo4, fmt);
     const size_t o = (((size_t)(k0 >> 4) * Rp + prow) * 2 + (((k0 >> 3) & 1) ^ swz(prow))) * 8;
     *reinterpret_cast<uint4*>(H + o) = hi4;
     if (want_lo) *reinterpret_cast<uint4*>(H + plane + o) = lo4;
@@ -701,8 +771,24 @@ __global__ __launch_bounds__(256) void br_ingest_planes(IngestArgs a, int R, int
 
 }  // namespace br
 
+hipError_t br_launch_absmax(hipStream_t s, const float* const* src, int batch, int R, int Ccols, int ld_src, unsigned* maxbits) {
+  if (batch <= 0 || R <= 0 || Ccols <= 0) return hipSuccess;
+  if (batch > BR_MAXB || ld_src < Ccols || !maxbits) return hipErrorInvalidValue;
+  br::SplitArgs a;
+  for (int i = 0; i < BR_MAXB; ++i) {
+    a.src[i] = (i < batch) ? src[i] : nullptr;
+    a.dst[i] = nullptr;
+  }
+  int64_t blocks = ((int64_t)R * Ccols + 256 * 16 - 1) / (256 * 16);
+  int64_t cap = (4096 + batch - 1) / batch;
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL(br::br_absmax, dim3((int)blocks, batch), dim3(256), 0, s, a, R, Ccols, ld_src, maxbits);
+  return hipGetLastError();
+}
+
 hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16_t* const* dst, int batch, int R, int Ccols,
-                                  int ld_src, int transpose, int want_lo) {
+                                  int ld_src, int transpose, int want_lo, int f16, float scale, const unsigned* maxbits,
+                                  int target_exp) {
   if (batch <= 0 || R <= 0 || Ccols <= 0) return hipSuccess;
   if (batch > BR_MAXB || ld_src < Ccols) return hipErrorInvalidValue;
   br::SplitArgs a;
@@ -712,17 +798,19 @@ hipError_t br_launch_split_planes(hipStream_t s, const float* const* src, uint16
   }
   const BrPlaneLayout pl = transpose ? br_plane_layout(Ccols, R) : br_plane_layout(R, Ccols);
   if (pl.rows_p > 0x7fffffffLL || pl.k_p > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (maxbits && !f16) return hipErrorInvalidValue;
+  const br::PlaneFormat fmt{f16 ? 1 : 0, f16 ? scale : 1.f};
   if (!transpose) {
     int64_t blocks = (pl.rows_p * (pl.k_p >> 3) + 255) / 256;
     int64_t cap = (8192 + batch - 1) / batch;
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(br::br_split_planes, dim3((int)blocks, batch), dim3(256), 0, s, a, R, Ccols, ld_src, (int)pl.rows_p,
-                       (int)pl.k_p, pl.elems, want_lo);
+                       (int)pl.k_p, pl.elems, want_lo, fmt, maxbits, target_exp);
   } else {
     int64_t tiles = (pl.k_p >> 6) * (pl.rows_p >> 6);
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(br::br_split_planes_t, dim3((int)tiles, batch), dim3(256), 0, s, a, R, Ccols, ld_src, (int)pl.rows_p,
-                       (int)pl.k_p, pl.elems, want_lo);
+                       (int)pl.k_p, pl.elems, want_lo, fmt, maxbits, target_exp);
   }
   return hipGetLastError();
 }
@@ -762,8 +850,10 @@ int lowp_resident_workgroups() {
 }
 
 template <int EPI>
-void launch_lowp(hipStream_t s, int nprod, int grid, const LowpKernArgs& k, const BrLowpBatch& b) {
-  if (nprod == 4)
+void launch_lowp(hipStream_t s, int nprod, int grid, const LowpKernArgs& k, const BrLowpBatch& b, bool f16) {
+  if (f16)  // FP16 planes: the three-product split only (callers check)
+    hipLaunchKernelGGL((br::br_gemm_bf16_mfma<3, EPI, true>), dim3(grid), dim3(512), 0, s, k, b);
+  else if (nprod == 4)
     hipLaunchKernelGGL((br::br_gemm_bf16_mfma<4, EPI>), dim3(grid), dim3(512), 0, s, k, b);
   else if (nprod == 3)
     hipLaunchKernelGGL((br::br_gemm_bf16_mfma<3, EPI>), dim3(grid), dim3(512), 0, s, k, b);
@@ -774,7 +864,9 @@ void launch_lowp(hipStream_t s, int nprod, int grid, const LowpKernArgs& k, cons
 
 hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpBatch& b, const char** kernel_name) {
   if (kernel_name)
-    *kernel_name = (a.nprod == 4) ? "br_gemm_bf16_mfma<4>" : (a.nprod == 3) ? "br_gemm_bf16_mfma<3>" : "br_gemm_bf16_mfma<1>";
+    *kernel_name = a.f16 ? "br_gemm_f16_mfma<3>"
+                         : (a.nprod == 4) ? "br_gemm_bf16_mfma<4>" : (a.nprod == 3) ? "br_gemm_bf16_mfma<3>" : "br_gemm_bf16_mfma<1>";
+  if (a.f16 && (a.nprod != 3 || a.epilogue == BR_EPI_ADAM || a.mirror)) return hipErrorInvalidValue;
   if (a.batch <= 0 || a.M <= 0 || a.N <= 0 || a.K <= 0) return hipSuccess;
   if (a.batch > BR_MAXB) return hipErrorInvalidValue;
   if (a.mirror && a.M != a.N) return hipErrorInvalidValue;
@@ -818,6 +910,7 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
   }
   k.skip = a.skip;
   k.health = a.health;
+  k.out_scale = a.f16 ? a.out_scale : 1.f;
   k.emit_t = a.emit_transposed ? 1 : 0;
   if (k.emit_t) {
     if (a.epilogue != BR_EPI_F32 || a.mirror) return hipErrorInvalidValue;
@@ -831,8 +924,8 @@ hipError_t br_launch_gemm_lowp(hipStream_t s, const BrLowpArgs& a, const BrLowpB
   const int resident = lowp_resident_workgroups();
   if (resident <= 0) return hipErrorInvalidDevice;
   if (grid > resident) grid = resident;
-  if (a.epilogue == BR_EPI_ADAM) launch_lowp<EPI_ADAM>(s, a.nprod, (int)grid, k, b);
-  else if (a.epilogue == BR_EPI_PLANES) launch_lowp<EPI_PLANES>(s, a.nprod, (int)grid, k, b);
-  else launch_lowp<EPI_F32>(s, a.nprod, (int)grid, k, b);
+  if (a.epilogue == BR_EPI_ADAM) launch_lowp<EPI_ADAM>(s, a.nprod, (int)grid, k, b, false);
+  else if (a.epilogue == BR_EPI_PLANES) launch_lowp<EPI_PLANES>(s, a.nprod, (int)grid, k, b, a.f16 != 0);
+  else launch_lowp<EPI_F32>(s, a.nprod, (int)grid, k, b, a.f16 != 0);
   return hipGetLastError();
 }

@@ -401,8 +401,9 @@ def test_refresh_alone_on_injected_statistics_several_top_blocks(harness, math):
     a minute here).  Injecting the statistics keeps the comparison about the refresh: in the BF16
     math mode the statistics themselves are only BF16 accurate, and a young second moment turns
     that into O(1) differences of single update entries on a matrix this large.
-    Bars: FP32 refresh (F32, BF16X3) 1e-5, measured 1.2e-6; BR_MATH_BF16, whose L Q product and
-    large QR updates take 16-bit mantissa inputs, 1e-4, measured 1.5e-5."""
+    Above order 512 the refresh is the same in every math mode: the product A Q and the QR's large updates are
+    split FP16 products (hi + lo FP16 operands, 22 mantissa bits, FP32 accumulation).  Bars: 1e-5 on the entries
+    and on orthogonality in all three modes."""
     m, n = 1100, 600
     rng = np.random.default_rng(77)
 
@@ -418,15 +419,16 @@ def test_refresh_alone_on_injected_statistics_several_top_blocks(harness, math):
     sb.opt.state(0, B.BR_STATE_R).copy_(torch.from_numpy(R32))
     B.br_notify_state_written(sb.opt.ctx)
     st.L, st.R = L32.astype(np.float64), R32.astype(np.float64)
-    bar, orth = (1e-4, 5e-5) if math == 1 else (1e-5, 1e-5)
+    bar, orth = 1e-5, 1e-5
     for rep in range(2):
         B.br_refresh_basis(sb.opt.ctx)
         torch.cuda.synchronize()
         oc.refresh(st, sb.hp, _lapack_qr)
         for kind, Q in ((B.BR_STATE_QL, st.QL), (B.BR_STATE_QR, st.QR)):
             q = harness.to_np(sb.opt.state(0, kind))
-            assert orthogonality_defect(q) < orth
-            e = rel_err(q, Q)
+            e, d = rel_err(q, Q), orthogonality_defect(q)
+            print(f"math {math} refresh {rep} order {q.shape[0]}: basis rel err {e:.2e}, orthogonality defect {d:.2e}")
+            assert d < orth
             assert e <= bar, f"refresh {rep}, state {kind}: basis rel err {e:.3e} > {bar:.1e}"
 
 
