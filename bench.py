@@ -359,7 +359,9 @@ def main():
         "config": {"workload": f"{args.workload}: {desc}", "params": n_params, "geometry": "unilateral" if stress else "bilateral",
                    "source": "second", "refresh_every": freq, "refreshes_in_timed_region": refreshes,
                    "power_iters": 2 if stress else 1, "delay_tau": TAU, "param_dtype": "f32", "grad_dtype": "f32",
-                   "math": {"f32": "fp32 MFMA", "bf16": "bf16 MFMA", "bf16x3": "bf16 MFMA, hi+lo split (3 products)"}[args.math], "state_bytes": None, "scratch_bytes": None},
+                   "math": {"f32": "fp32 MFMA", "bf16": "bf16 MFMA", "bf16x3": "bf16 MFMA, hi+lo split (3 products)"}[args.math],
+                   "refresh_math": "fp32 MFMA" if args.math == "f32" else "f16 MFMA, hi+lo split (3 products), FP32 accumulation",
+                   "state_bytes": None, "scratch_bytes": None},
         "roofline": roofline,
         "kernels": breakdown,
     }
@@ -400,6 +402,20 @@ def main():
                                   "warmup": 1, "dominant_kernel": d2["kernel"], "achieved_tflops": ach, "frac": ach / pk,
                                   "frac_issued": issue_factor(d2["kernel"]) * ach / pk,
                                   "state_bytes": o2.state_bytes, "scratch_bytes": o2.scratch_bytes}
+            del o2
+        if args.math == "f32" and not stress:
+            # the same FP32 step with the refresh's large products as split FP16 products (BR_REFRESH_F16X3)
+            torch.cuda.empty_cache()
+            el, pr, o2 = run_mode(B, BasisRotationAdam, torch, params, ring, "f32", 1, 10, refresh_math=B.BR_REFRESH_F16X3)
+            qr = next((p for p in pr if p["kernel"].startswith("qr_householder")), None)
+            lq = next((p for p in pr if p["kernel"].startswith("br_gemm_f16")), None)
+            out["modes"]["f32+f16x3_refresh"] = {
+                "value": n_params * 10 / el, "unit": "params/s", "ms_per_step": 1e2 * el, "steps": 10, "warmup": 1,
+                "what": "BR_MATH_F32 step contractions (FP32 MFMA); A Q and the QR's large updates as hi + lo FP16 split products",
+                "qr_region_ms_per_step": qr["ms"] / 10 if qr else None,
+                "qr_tflops_nominal": (qr["flops"] / (qr["ms"] * 1e-3) / 1e12) if qr else None,
+                "power_product_ms_per_step": lq["ms"] / 10 if lq else None,
+                "state_bytes": o2.state_bytes, "scratch_bytes": o2.scratch_bytes}
             del o2
     if not args.single_mode and args.workload == "stage3b":
         out["stream_2r1w"] = stream_ceiling(torch, dev)

@@ -88,11 +88,18 @@ typedef enum { BR_SRC_SECOND = 0, BR_SRC_FIRST = 1 } br_source;
 /* Input precision of the step's matrix-core contractions (statistics, rotations, rotate-back).
  * F32 issues FP32 MFMA.  BF16 rounds both operands to BF16 (parity bar 2e-2).  BF16X3 splits
  * each FP32 operand into hi + lo BF16 parts and adds the products hi*hi + hi*lo + lo*hi in FP32:
- * 16-bit mantissa inputs, same 1e-4 bar as F32, about a third of the matrix-core time.  The
- * refresh (its L Q product and the QR) runs in FP32, except under BR_MATH_BF16: there L Q and the
- * QR's large block-reflector updates take the hi/lo split with three partial products (panels and
- * merges stay FP32); the bases of that mode are orthogonal to about 2e-5 (FP32: 1e-6). */
+ * 16-bit mantissa inputs, same 1e-4 bar as F32, about a third of the matrix-core time.  What the
+ * refresh's large products run in is chosen separately (br_refresh_math). */
 typedef enum { BR_MATH_F32 = 0, BR_MATH_BF16 = 1, BR_MATH_BF16X3 = 2 } br_math;
+
+/* Arithmetic of the refresh's large products (A^k Q of the Power calls and the QR's block-reflector updates of 256
+ * and more columns) for factors above order 512; panels, merges and everything on smaller factors are FP32 always.
+ * F32: FP32 MFMA.  F16X3: each FP32 operand is scaled by a power of two and split into hi + lo FP16 parts
+ * (22 mantissa bits; for entries below 2^-3 of the operand's scale an absolute 2^-25 of it), the products
+ * hi*hi + hi*lo + lo*hi are accumulated in FP32 on the f16 matrix cores: bases agree with the float64 oracle to
+ * 1e-6 like the FP32 refresh's, at three to four times its rate.  AUTO: F32 under BR_MATH_F32, F16X3 under the
+ * BF16 math modes. */
+typedef enum { BR_REFRESH_AUTO = 0, BR_REFRESH_F32 = 1, BR_REFRESH_F16X3 = 2 } br_refresh_math;
 
 /* Which buffer br_get_state returns. */
 typedef enum {
@@ -135,6 +142,7 @@ typedef struct {
                           br_refresh_basis folds that gradient into L, R before its Power calls.  A
                           br_refresh_basis that is not preceded by this step's br_accumulate_stats
                           uses the statistics as they stand.                                    */
+  int32_t refresh_math; /* br_refresh_math                                                  */
   int32_t cache_rotated_moment; /* 1: also keep M~ = Q_L^T M Q_R in the state and, while the
                           basis is unchanged, advance it by M~ <- beta1 M~ + (1-beta1) G~
                           (equal to rotating M, by linearity) instead of rotating M every

@@ -28,6 +28,7 @@ BR_F32, BR_BF16 = 0, 1
 BR_BILATERAL, BR_UNILATERAL = 0, 1
 BR_SRC_SECOND, BR_SRC_FIRST = 0, 1
 BR_MATH_F32, BR_MATH_BF16, BR_MATH_BF16X3 = 0, 1, 2
+BR_REFRESH_AUTO, BR_REFRESH_F32, BR_REFRESH_F16X3 = 0, 1, 2
 BR_STATE_M, BR_STATE_S, BR_STATE_L, BR_STATE_R, BR_STATE_QL, BR_STATE_QR, BR_STATE_MASTER, BR_STATE_NORMS, \
     BR_STATE_MROT = range(9)
 
@@ -45,7 +46,7 @@ class br_hparams(C.Structure):
                 ("stat_beta", C.c_float), ("geometry", C.c_int32), ("source", C.c_int32),
                 ("power_iters", C.c_int32), ("bias_correction", C.c_int32), ("eps_outside_sqrt", C.c_int32),
                 ("math", C.c_int32), ("compute_norms", C.c_int32), ("stats_on_refresh_only", C.c_int32),
-                ("cache_rotated_moment", C.c_int32)]
+                ("refresh_math", C.c_int32), ("cache_rotated_moment", C.c_int32)]
 
 
 class br_profile_entry(C.Structure):
@@ -134,10 +135,10 @@ def make_descs(shapes: Sequence, param_dtype=BR_F32, grad_dtype=BR_F32, rotate=1
 
 def make_hparams(beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.0, stat_beta=-1.0, geometry=BR_BILATERAL,
                  source=BR_SRC_SECOND, power_iters=1, bias_correction=0, eps_outside_sqrt=0, math=BR_MATH_F32,
-                 compute_norms=0, cache_rotated_moment=1, stats_on_refresh_only=0) -> br_hparams:
+                 compute_norms=0, cache_rotated_moment=1, stats_on_refresh_only=0, refresh_math=0) -> br_hparams:
     return br_hparams(beta1, beta2, eps, weight_decay, stat_beta, geometry, source, power_iters,
                       int(bias_correction), int(eps_outside_sqrt), math, int(compute_norms),
-                      int(stats_on_refresh_only), int(cache_rotated_moment))
+                      int(stats_on_refresh_only), int(refresh_math), int(cache_rotated_moment))
 
 
 def _ptr_array(ptrs: Sequence[int]):

@@ -136,6 +136,7 @@ br_status validate(const br_matrix_desc* descs, int32_t n_mats, const br_hparams
   if (!(hp->stat_beta < 1.f)) { *why = "stat_beta must be below 1 (negative selects beta2)"; return BR_ERR_INVALID_ARG; }
   if (!(hp->eps >= 0.f) || !(hp->weight_decay >= 0.f)) { *why = "eps and weight_decay must be non-negative"; return BR_ERR_INVALID_ARG; }
   if (hp->cache_rotated_moment != 0 && hp->cache_rotated_moment != 1) { *why = "cache_rotated_moment must be 0 or 1"; return BR_ERR_INVALID_ARG; }
+  if (hp->refresh_math != BR_REFRESH_AUTO && hp->refresh_math != BR_REFRESH_F32 && hp->refresh_math != BR_REFRESH_F16X3) { *why = "unknown refresh_math"; return BR_ERR_INVALID_ARG; }
   if (hp->stats_on_refresh_only != 0 && hp->stats_on_refresh_only != 1) { *why = "stats_on_refresh_only must be 0 or 1"; return BR_ERR_INVALID_ARG; }
   for (int i = 0; i < n_mats; ++i) {
     const br_matrix_desc& d = descs[i];
@@ -190,10 +191,14 @@ struct RefreshScratch {
 constexpr int kQrMaxLevels = 2;
 static_assert((BR_QR_NBM << kQrMaxLevels) == BR_QR_NBT, "widest top block = middle block doubled kQrMaxLevels times");
 // Factors above this order run their large products (A Q, and the top blocks' updates of the QR) as split FP16
-// products on the 16-bit matrix cores, in every math mode; smaller ones stay on the FP32 matrix cores.
+// products on the 16-bit matrix cores when the refresh math says so (BR_REFRESH_F16X3; by default in the BF16 math
+// modes); smaller ones, and everything under BR_REFRESH_F32 (the default of BR_MATH_F32), stay on the FP32 matrix cores.
 constexpr int64_t kSplitRefreshMinOrder = 512;
-inline bool split_refresh(int64_t k) { return k > kSplitRefreshMinOrder; }
-inline int qr_levels(int64_t k) { return split_refresh(k) ? 2 : 1; }
+inline bool split_refresh(const br_hparams& hp, int64_t k) {
+  const bool wanted = hp.refresh_math == BR_REFRESH_F16X3 || (hp.refresh_math == BR_REFRESH_AUTO && hp.math != BR_MATH_F32);
+  return wanted && k > kSplitRefreshMinOrder;
+}
+inline int qr_levels(const br_hparams& hp, int64_t k) { return split_refresh(hp, k) ? 2 : 1; }
 // Powers of two that centre the operands of the split FP16 products in the FP16 range (see qr_batch).
 constexpr float kScaleV = 64.f, kScaleY = 64.f, kScaleC = 128.f, kScaleW = 64.f;
 // floats before level l's pair of child factors in the Tl scratch
@@ -228,11 +233,11 @@ RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   r.diag = off; off += align256((size_t)k * 4);
   r.xch = off; off += align256(br_qr_panel_xch_floats((int)k) * 4);            // cluster exchange of one panel launch
   // split products: hi + lo planes of the statistics and of the transposed basis for the power iteration
-  const size_t pl = split_refresh(k) ? align256(4 * br_plane_layout(k, k).elems) : 0;
+  const size_t pl = split_refresh(hp, k) ? align256(4 * br_plane_layout(k, k).elems) : 0;
   r.planesA = off; off += pl;
   r.planesB = off; off += pl;
   // ... and of V^T, V T, (V^T C)^T for the top blocks' updates of the QR
-  r.qrp = off; if (split_refresh(k)) off += 3 * qr_plane_chunk(k);
+  r.qrp = off; if (split_refresh(hp, k)) off += 3 * qr_plane_chunk(k);
   r.total = off;
   return r;
 }
@@ -1026,7 +1031,7 @@ br_status br_accumulate_stats(br_ctx* ctx, const void* const* grads, int32_t n_m
 static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, float* const* Q, const RefreshScratch& rs,
                      char* base, size_t stride, float* partial, int* failed) {
   const int NB = BR_QR_NB, NBM = BR_QR_NBM;
-  const int levels = qr_levels(k);
+  const int levels = qr_levels(c->hp, k);
   const int NBT = NBM << levels;  // width of a top block
   const int ntop = (k + NBT - 1) / NBT;
   auto F = [&](int i, size_t off) { return reinterpret_cast<float*>(base + i * stride + off); };
@@ -1069,7 +1074,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
   // (planes of P^T, planes of Q^T), a block's C^T is a view into that set (blocks start at multiples
   // of 256), and the update's epilogue rewrites the view from the values it stores.  The product
   // V^T C leaves its kernel transposed and already split, as the operand of the second one.
-  const bool x3 = split_refresh(k);
+  const bool x3 = split_refresh(c->hp, k);
   LowpCtx lx{c, nullptr, LowpLayout{}, B, 3, nullptr};
   lx.quiet = true;
   const size_t qchunk = qr_plane_chunk(k);
@@ -1328,7 +1333,7 @@ br_status br_refresh_basis(br_ctx* ctx) {
     // divided by 2^-7 resp. 1, i.e. |P| <= sqrt(k) 2^-7, which is what the split products of the QR expect.
     float** src = Q;
     float** dst = P0;
-    const bool lowp = split_refresh(k);
+    const bool lowp = split_refresh(hp, k);
     LowpCtx lx{c, nullptr, LowpLayout{}, B, 3, nullptr};
     uint16_t *plA[BR_MAXB], *plB[BR_MAXB];
     for (int i = 0; i < B && lowp; ++i) {

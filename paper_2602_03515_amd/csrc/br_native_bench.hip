@@ -3,7 +3,7 @@
 // the calls of include/br.h and nothing else.  It exists for hardware-counter runs (a profiler
 // attaches to a plain executable) and as a C usage example of the library.
 //
-//   br_native_bench [--layers N] [--steps K] [--freq F] [--math 0|1|2] [--small] [--copy-calibration]
+//   br_native_bench [--layers N] [--steps K] [--freq F] [--math 0|1|2] [--refresh-math 0|1|2] [--small] [--copy-calibration]
 //   br_native_bench --host-only
 //
 // --small uses one layer of small ragged matrices instead of the 3B-class shapes (a quick run of every
@@ -68,6 +68,7 @@ static int host_only() {
               hp.beta1 = 0.9f; hp.beta2 = 0.95f; hp.eps = 1e-8f; hp.stat_beta = -1.f;
               hp.geometry = geometry; hp.source = source; hp.power_iters = iters; hp.math = math; hp.cache_rotated_moment = cache;
               hp.stats_on_refresh_only = cache;
+              hp.refresh_math = (geometry + source + iters) % 3;
               size_t st = 0, sc = 0;
               expect(br_workspace_bytes(d.data(), (int32_t)d.size(), &hp, &st, &sc), BR_OK, "br_workspace_bytes");
               if (st == 0 || sc == 0) { std::fprintf(stderr, "host-only: empty plan\n"); ++bad; }
@@ -112,7 +113,7 @@ static int host_only() {
 
 int main(int argc, char** argv) {
   if (argc == 2 && !std::strcmp(argv[1], "--host-only")) return host_only() ? 1 : 0;
-  int layers = 8, steps = 2, freq = 10, calib = 0, math = BR_MATH_F32, small = 0;
+  int layers = 8, steps = 2, freq = 10, calib = 0, math = BR_MATH_F32, small = 0, refresh_math = BR_REFRESH_AUTO;
   for (int i = 1; i < argc; ++i) {
     if (!std::strcmp(argv[i], "--layers") && i + 1 < argc) layers = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--steps") && i + 1 < argc) steps = std::atoi(argv[++i]);
@@ -120,6 +121,7 @@ int main(int argc, char** argv) {
     else if (!std::strcmp(argv[i], "--copy-calibration")) calib = 1;
     else if (!std::strcmp(argv[i], "--math") && i + 1 < argc) math = std::atoi(argv[++i]);
     else if (!std::strcmp(argv[i], "--small")) small = 1;
+    else if (!std::strcmp(argv[i], "--refresh-math") && i + 1 < argc) refresh_math = std::atoi(argv[++i]);
     else { std::fprintf(stderr, "unknown argument %s\n", argv[i]); return 2; }
   }
   const int64_t big_shapes[7][2] = {{2560, 2560}, {2560, 2560}, {2560, 2560}, {2560, 2560},
@@ -134,6 +136,7 @@ int main(int argc, char** argv) {
   hp.beta1 = 0.9f; hp.beta2 = 0.95f; hp.eps = 1e-8f; hp.stat_beta = -1.f;
   hp.geometry = BR_BILATERAL; hp.source = BR_SRC_SECOND; hp.power_iters = 1; hp.math = math;
   hp.cache_rotated_moment = 1;
+  hp.refresh_math = refresh_math;
   size_t state = 0, scratch = 0;
   if (br_workspace_bytes(descs.data(), (int32_t)descs.size(), &hp, &state, &scratch) != BR_OK) {
     std::fprintf(stderr, "br_workspace_bytes: %s\n", br_last_error(nullptr));

@@ -26,6 +26,7 @@ def oracle_hyper(**kw):
     kw.pop("compute_norms", None)
     kw.pop("math", None)
     kw.pop("cache_rotated_moment", None)
+    kw.pop("refresh_math", None)
     assert not kw, kw
     return hp.rounded_to_f32()
 

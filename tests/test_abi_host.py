@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol(B):
 
 def test_struct_layouts_match_header(B):
     assert ctypes.sizeof(B.br_matrix_desc) == 32
-    assert ctypes.sizeof(B.br_hparams) == 56
+    assert ctypes.sizeof(B.br_hparams) == 60
     assert ctypes.sizeof(B.br_profile_entry) == 96
 
 

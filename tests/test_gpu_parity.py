@@ -56,8 +56,7 @@ def _run(h, W0s, grads_per_step, freq, lr, tol=TOL, check_q=True, **kw):
     for i, st in enumerate(sb.states):
         for which, Q in ((sb.B.BR_STATE_QL, st.QL), (sb.B.BR_STATE_QR, st.QR)):
             if Q is not None:
-                # BR_MATH_BF16 runs the QR's large updates on hi + lo split BF16 inputs (16-bit mantissas)
-                bar = 5e-5 if kw.get("math", 0) == 1 else 1e-5
+                bar = 1e-5
                 assert orthogonality_defect(h.to_np(sb.opt.state(i, which))) < bar
     return sb, worst
 
@@ -391,8 +390,8 @@ def _lapack_qr(P):
     return q * d[None, :], r * d[:, None]
 
 
-@pytest.mark.parametrize("math", [0, 1, 2])
-def test_refresh_alone_on_injected_statistics_several_top_blocks(harness, math):
+@pytest.mark.parametrize("math,refresh_math", [(0, 0), (0, 2), (1, 0), (2, 0), (2, 1)])
+def test_refresh_alone_on_injected_statistics_several_top_blocks(harness, math, refresh_math):
     """The refresh by itself at orders with three and two ragged top blocks of the QR (1100 and 600
     columns): well-conditioned statistics (Wishart, aspect 3, condition number 14) are written into
     the state, br_refresh_basis runs from Q = I and once more from its own result, and both bases
@@ -401,9 +400,9 @@ def test_refresh_alone_on_injected_statistics_several_top_blocks(harness, math):
     a minute here).  Injecting the statistics keeps the comparison about the refresh: in the BF16
     math mode the statistics themselves are only BF16 accurate, and a young second moment turns
     that into O(1) differences of single update entries on a matrix this large.
-    Above order 512 the refresh is the same in every math mode: the product A Q and the QR's large updates are
-    split FP16 products (hi + lo FP16 operands, 22 mantissa bits, FP32 accumulation).  Bars: 1e-5 on the entries
-    and on orthogonality in all three modes."""
+    Above order 512 the product A Q and the QR's large updates are either FP32 (refresh_math 1, and the default of
+    BR_MATH_F32) or split FP16 products (hi + lo FP16 operands, 22 mantissa bits, FP32 accumulation: refresh_math 2,
+    and the default of the BF16 math modes).  Bars: 1e-5 on the entries and on orthogonality for both."""
     m, n = 1100, 600
     rng = np.random.default_rng(77)
 
@@ -413,7 +412,7 @@ def test_refresh_alone_on_injected_statistics_several_top_blocks(harness, math):
 
     L32, R32 = wishart(m), wishart(n)
     W0 = rng.standard_normal((m, n)).astype(np.float32)
-    sb = harness.SideBySide([W0], freq=0, lr=1e-3, math=math)
+    sb = harness.SideBySide([W0], freq=0, lr=1e-3, math=math, refresh_math=refresh_math)
     B, st = sb.B, sb.states[0]
     sb.opt.state(0, B.BR_STATE_L).copy_(torch.from_numpy(L32))
     sb.opt.state(0, B.BR_STATE_R).copy_(torch.from_numpy(R32))
@@ -427,7 +426,8 @@ def test_refresh_alone_on_injected_statistics_several_top_blocks(harness, math):
         for kind, Q in ((B.BR_STATE_QL, st.QL), (B.BR_STATE_QR, st.QR)):
             q = harness.to_np(sb.opt.state(0, kind))
             e, d = rel_err(q, Q), orthogonality_defect(q)
-            print(f"math {math} refresh {rep} order {q.shape[0]}: basis rel err {e:.2e}, orthogonality defect {d:.2e}")
+            print(f"math {math} refresh_math {refresh_math} refresh {rep} order {q.shape[0]}: basis rel err {e:.2e}, "
+                  f"orthogonality defect {d:.2e}")
             assert d < orth
             assert e <= bar, f"refresh {rep}, state {kind}: basis rel err {e:.3e} > {bar:.1e}"
 
