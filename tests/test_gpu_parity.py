@@ -83,6 +83,34 @@ def test_config1_updates_from_zero_weights(harness):
     sb.compare_state(TOL)
 
 
+@pytest.mark.parametrize("math", [0, 2])
+@pytest.mark.parametrize("weight_decay", [0.0, 0.1])
+def test_every_step_update_read_directly(harness, math, weight_decay):
+    """The update of EVERY step read directly, at the bare 1e-4: the weights (the caller's memory) are set to zero
+    before each step on both sides, so what the step leaves in them is -lr * Q_L X Q_R^T itself, with nothing of
+    the weights' own magnitude in the comparison (no storage floor).  Config 1's gradients, 20 steps, refresh every 5;
+    two matrices so that a ragged one runs too.  (Decoupled decay acts on the pre-step weights, here zero, so the result
+    must not depend on it.)"""
+    _, g0 = synth.spiked_gradients(seed=0, m=256, n=256, steps=20, noise_std=0.1)
+    _, g1 = synth.spiked_gradients(seed=1, m=200, n=136, steps=20, noise_std=0.1)
+    sb = harness.SideBySide([np.zeros((256, 256), np.float32), np.zeros((200, 136), np.float32)], freq=5, lr=1e-3,
+                            math=math, weight_decay=weight_decay)
+    worst = 0.0
+    for t in range(20):
+        for i in range(2):
+            sb.params[i].zero_()
+            sb.W_ref[i] = np.zeros_like(sb.W_ref[i])
+        sb.step([g0[t], g1[t]])
+        for i in range(2):
+            ref_update = -sb.W_ref[i] / sb.lr                      # the oracle's Q_L X Q_R^T of this step
+            assert np.abs(ref_update - sb.states[i].last["dW"]).max() <= 1e-12 * np.abs(ref_update).max()
+            e = rel_err(harness.to_np(sb.params[i]), sb.W_ref[i])
+            worst = max(worst, e)
+            assert e <= TOL, f"step {t + 1} matrix {i}: update rel err {e:.3e}"
+    print(f"math {math}: worst per-step update error, read directly: {worst:.2e}")
+    sb.compare_state(TOL, check_q=True)
+
+
 @pytest.mark.parametrize("shape", [(200, 136), (136, 200), (37, 53), (1, 1), (257, 129)])
 def test_ragged_shapes_bilateral(harness, shape):
     m, n = shape
