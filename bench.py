@@ -289,6 +289,9 @@ def main():
     ap.add_argument("--math", default="f32", choices=sorted(MATH),
                     help="input precision of the step's contractions: f32 (FP32 MFMA, default), "
                          "bf16x3 (hi+lo BF16 split, same 1e-4 bar), bf16 (2e-2 bar)")
+    ap.add_argument("--refresh-math", default="auto", choices=["auto", "f32", "f16x3"],
+                    help="arithmetic of the refresh's large products: f32 (FP32 MFMA), f16x3 (hi+lo FP16 split products, FP32 "
+                         "accumulation), auto (f32 under --math f32, f16x3 under the BF16 math modes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single-mode", action="store_true",
                     help="skip the short runs of the other math modes (10 steps each, reported under 'modes') that "
@@ -324,6 +327,8 @@ def main():
     stress = args.workload == "stage3b_emb"
     freq = 1 if stress else FREQ
     extra = {"geometry": B.BR_UNILATERAL, "power_iters": 2} if stress else {}
+    extra["refresh_math"] = {"auto": B.BR_REFRESH_AUTO, "f32": B.BR_REFRESH_F32, "f16x3": B.BR_REFRESH_F16X3}[args.refresh_math]
+    split_refresh = args.refresh_math == "f16x3" or (args.refresh_math == "auto" and args.math != "f32")
     elapsed, prof, opt = run_mode(B, BasisRotationAdam, torch, params, ring, args.math, args.warmup, args.steps, freq=freq, **extra)
 
     ms_per_step = 1e3 * elapsed / args.steps
@@ -360,7 +365,7 @@ def main():
                    "source": "second", "refresh_every": freq, "refreshes_in_timed_region": refreshes,
                    "power_iters": 2 if stress else 1, "delay_tau": TAU, "param_dtype": "f32", "grad_dtype": "f32",
                    "math": {"f32": "fp32 MFMA", "bf16": "bf16 MFMA", "bf16x3": "bf16 MFMA, hi+lo split (3 products)"}[args.math],
-                   "refresh_math": "fp32 MFMA" if args.math == "f32" else "f16 MFMA, hi+lo split (3 products), FP32 accumulation",
+                   "refresh_math": "f16 MFMA, hi+lo split (3 products), FP32 accumulation" if split_refresh else "fp32 MFMA",
                    "state_bytes": None, "scratch_bytes": None},
         "roofline": roofline,
         "kernels": breakdown,
@@ -403,7 +408,7 @@ def main():
                                   "frac_issued": issue_factor(d2["kernel"]) * ach / pk,
                                   "state_bytes": o2.state_bytes, "scratch_bytes": o2.scratch_bytes}
             del o2
-        if args.math == "f32" and not stress:
+        if args.math == "f32" and not stress and not split_refresh:
             # the same FP32 step with the refresh's large products as split FP16 products (BR_REFRESH_F16X3)
             torch.cuda.empty_cache()
             el, pr, o2 = run_mode(B, BasisRotationAdam, torch, params, ring, "f32", 1, 10, refresh_math=B.BR_REFRESH_F16X3)
