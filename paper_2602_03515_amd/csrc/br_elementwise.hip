@@ -279,14 +279,25 @@ __global__ __launch_bounds__(256) void br_grad_sumsq(BrPtrBatch p, int64_t count
   const void* __restrict__ G = p.in0[blockIdx.y];
   const int64_t n4 = count >> 2;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  float s = 0.f;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-    float4 g = load_grad4(G, i, grad_bf16);
-    s += (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w);
+  // four independent 16-byte loads in flight per thread, each with a running sum of its own
+  auto sq = [](const float4& g) { return (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w); };
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n4; i += 4 * stride) {
+    const float4 g0 = nt_load_grad4(G, i, grad_bf16);
+    const float4 g1 = nt_load_grad4(G, i + stride, grad_bf16);
+    const float4 g2 = nt_load_grad4(G, i + 2 * stride, grad_bf16);
+    const float4 g3 = nt_load_grad4(G, i + 3 * stride, grad_bf16);
+    s0 += sq(g0);
+    s1 += sq(g1);
+    s2 += sq(g2);
+    s3 += sq(g3);
   }
+  for (; i < n4; i += stride) s0 += sq(nt_load_grad4(G, i, grad_bf16));
+  float s = (s0 + s1) + (s2 + s3);
   if (blockIdx.x == 0) {
-    for (int64_t i = (n4 << 2) + threadIdx.x; i < count; i += blockDim.x) {
-      float g = load_grad1(G, i, grad_bf16);
+    for (int64_t j = (n4 << 2) + threadIdx.x; j < count; j += blockDim.x) {
+      float g = load_grad1(G, j, grad_bf16);
       s += g * g;
     }
   }
