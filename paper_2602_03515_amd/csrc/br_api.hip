@@ -185,9 +185,9 @@ struct RefreshScratch {
 // Doubling levels of the QR's block-reflector merges above the LDS-merged middle block: level l
 // joins two factors of width BR_QR_NBM << l.  One level (top blocks of 256 columns) is what the
 // FP32 refresh uses: a second one (512) makes its K = 512 trailing updates 15 % faster and was
-// measured to give all of it back in the wider blocks' own merges and applies.  BR_MATH_BF16 takes
-// two: its top-block updates are bound by the bytes of C they move, and 512-column blocks halve
-// the number of passes over C.
+// measured to give all of it back in the wider blocks' own merges and applies.  The split FP16
+// refresh takes two: its top-block updates are short products (K = the block's width) whose
+// epilogues move 12 bytes per entry of C, and 512-column blocks halve the number of passes over C.
 constexpr int kQrMaxLevels = 2;
 static_assert((BR_QR_NBM << kQrMaxLevels) == BR_QR_NBT, "widest top block = middle block doubled kQrMaxLevels times");
 // Factors above this order run their large products (A Q, and the top blocks' updates of the QR) as split FP16
