@@ -412,6 +412,18 @@ def test_bf16_math_mode_meets_the_2e2_bar(harness, geometry):
     print("bf16 worst:", {k: f"{v:.2e}" for k, v in worst.items()})
 
 
+@pytest.mark.parametrize("math", [1, 2])
+@pytest.mark.parametrize("shape", [(1, 1), (1, 40), (40, 1), (130, 3)])
+def test_degenerate_shapes_in_the_bf16_modes(harness, shape, math):
+    """Single rows, single columns and a 1 x 1 matrix through the operand planes (padded to 256 rows and
+    64 k): statistics that cannot reach full rank, so the bases are checked for orthogonality only
+    (any orthonormal completion of the null space is a valid QR) while every update, the moments and the
+    statistics are compared, at the bar of the math mode."""
+    m, n = shape
+    W0, grads = synth.spiked_gradients(seed=7, m=m, n=n, steps=5, noise_std=0.1)
+    _run(harness, [W0], [[g] for g in grads], freq=5, lr=1e-3, check_q=False, math=math, tol=2e-2 if math == 1 else TOL)
+
+
 def _lapack_qr(P):
     q, r = np.linalg.qr(P)
     d = np.where(np.diag(r) < 0, -1.0, 1.0)
