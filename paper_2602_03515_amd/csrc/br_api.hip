@@ -200,7 +200,7 @@ inline bool split_refresh(const br_hparams& hp, int64_t k) {
 }
 inline int qr_levels(const br_hparams& hp, int64_t k) { return split_refresh(hp, k) ? 2 : 1; }
 // Powers of two that centre the operands of the split FP16 products in the FP16 range (see qr_batch).
-constexpr float kScaleV = 64.f, kScaleY = 64.f, kScaleC = 128.f, kScaleW = 64.f;
+constexpr float kScaleV = 64.f, kScaleY = 64.f, kScaleC = 128.f, kScaleW = 64.f, kScaleT = 64.f;
 // floats before level l's pair of child factors in the Tl scratch
 inline size_t qr_level_offset(int l) {
   size_t off = 0;
@@ -212,6 +212,9 @@ inline size_t qr_level_offset(int l) {
 inline size_t qr_plane_chunk(int64_t k) {
   return align256(4 * std::max(br_plane_layout(BR_QR_NBT, k).elems, br_plane_layout(k, BR_QR_NBT).elems));
 }
+
+// bytes of the hi + lo planes of a top block's triangular factor
+inline size_t qr_factor_plane_bytes() { return align256(4 * br_plane_layout(BR_QR_NBT, BR_QR_NBT).elems); }
 
 RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   RefreshScratch r;
@@ -236,8 +239,8 @@ RefreshScratch refresh_scratch(int64_t k, const br_hparams& hp) {
   const size_t pl = split_refresh(hp, k) ? align256(4 * br_plane_layout(k, k).elems) : 0;
   r.planesA = off; off += pl;
   r.planesB = off; off += pl;
-  // ... and of V^T, V T, (V^T C)^T for the top blocks' updates of the QR
-  r.qrp = off; if (split_refresh(hp, k)) off += 3 * qr_plane_chunk(k);
+  // ... and of V^T, V T, (V^T C)^T, V and T for the top blocks' updates of the QR
+  r.qrp = off; if (split_refresh(hp, k)) off += 4 * qr_plane_chunk(k) + qr_factor_plane_bytes();
   r.total = off;
   return r;
 }
@@ -1059,13 +1062,13 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
   }
   const int* skip_q = nullptr;  // set for the phase that writes Q
   // The update both phases share: C <- C - Yb (V^T C) for the rows x ncols blocks C (row stride k), with
-  // Yb = V T^T or V T already in Y.  Above kSplitRefreshMinOrder the two contractions run on the 16-bit
+  // Yb = V T^T or V T.  Above kSplitRefreshMinOrder the three contractions (Yb itself included) run on the 16-bit
   // matrix cores as split FP16 products: every operand is hi + lo FP16 (22 mantissa bits, or an absolute
   // 2^-25 of the operand's scale for small entries; subnormal lo parts are kept and the matrix instruction
   // honours them), three partial products hi*hi + hi*lo + lo*hi accumulated in FP32, C itself stays FP32.
   // These two products are three quarters of the refresh, and they run at three to four times the rate of
   // the FP32 matrix cores.  FP16's range is narrow, so each operand kind carries a fixed power-of-two scale
-  // (undone through alpha): reflectors are at most 1 in magnitude (x 64), V T likewise moderate (x 64); the
+  // (undone through alpha): reflectors are at most 1 in magnitude (x 64), T and V T likewise moderate (x 64); the
   // matrix being factorised arrives normalised (largest entry of A below 2^-7, so |A Q| <= 1 up to order
   // 16384 and its column norms, which bound every later entry of C, stay below 2^9; x 128), Q's entries are at
   // most 1 (x 128), and |V^T C| <= sqrt(2) |c_j| (x 64).  Values beyond the range would be clamped, not
@@ -1089,11 +1092,14 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     for (int i = 0; i < B; ++i) { src[i] = Mx[i]; dst[i] = reinterpret_cast<uint16_t*>(base + i * stride + set); }
     return f16_split(lx, src, k, k, true, dst, 0, kScaleC);
   };
-  // Vb: the block's reflectors (rows x width, row stride NBT); Yb in Y (rows x width, row stride width);
-  // Cp: the blocks C (FP32); set/row0/k0: where their transposes live as planes; emit: keep those planes current
-  auto apply_block = [&](float* const* Vb, int width, float* const* Cp, int rows, int ncols, size_t set, int row0, int k0,
-                         bool emit) -> bool {
+  // Vb: the block's reflectors (rows x width, row stride NBT); Tb (row stride ldt): the block's factor, Yb = Vb Tb^T, or
+  // Vb Tb with t_plain; Cp: the blocks C (FP32); set/row0/k0: where their transposes live as planes; emit: keep
+  // those planes current.  The FP32 path forms Yb in Y first; the split path forms it as planes directly.
+  auto apply_block = [&](float* const* Vb, int width, float* const* Tb, int ldt, bool t_plain, float* const* Cp, int rows,
+                         int ncols, size_t set, int row0, int k0, bool emit) -> bool {
     if (!x3 || width < 256) {
+      for (int i = 0; i < B; ++i) { gb.A[i] = Vb[i]; gb.B[i] = Tb[i]; gb.C[i] = Y(i); }
+      if (!mm(BrGemmArgs{rows, width, width, NBT, ldt, width, 0, t_plain ? 0 : 1, 1.f, 0.f, B, 0}, gb)) return false;
       for (int i = 0; i < B; ++i) { gb.A[i] = Vb[i]; gb.B[i] = Cp[i]; gb.C[i] = W(i); }
       if (!mm(BrGemmArgs{width, ncols, rows, NBT, k, ncols, 1, 0, 1.f, 0.f, B, 0}, gb)) return false;
       for (int i = 0; i < B; ++i) { gb.A[i] = Y(i); gb.B[i] = W(i); gb.C[i] = Cp[i]; }
@@ -1102,18 +1108,30 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       return mm(ua, gb);
     }
     const float* src[BR_MAXB];
-    uint16_t *pv[BR_MAXB], *py[BR_MAXB], *pw[BR_MAXB];
+    uint16_t *pv[BR_MAXB], *py[BR_MAXB], *pw[BR_MAXB], *pk[BR_MAXB], *pt[BR_MAXB];
     for (int i = 0; i < B; ++i) {
       char* q = base + i * stride + rs.qrp;
       pv[i] = reinterpret_cast<uint16_t*>(q);
       py[i] = reinterpret_cast<uint16_t*>(q + qchunk);
       pw[i] = reinterpret_cast<uint16_t*>(q + 2 * qchunk);
+      pk[i] = reinterpret_cast<uint16_t*>(q + 3 * qchunk);
+      pt[i] = reinterpret_cast<uint16_t*>(q + 4 * qchunk);
     }
     for (int i = 0; i < B; ++i) src[i] = Vb[i];
     if (!f16_split(lx, src, rows, width, true, pv, NBT, kScaleV)) return false;   // planes of V^T   [width][rows]
-    for (int i = 0; i < B; ++i) src[i] = Y(i);
-    if (!f16_split(lx, src, rows, width, false, py, 0, kScaleY)) return false;    // planes of Yb    [rows][width]
+    if (!f16_split(lx, src, rows, width, false, pk, NBT, kScaleV)) return false;  // planes of V     [rows][width]
+    for (int i = 0; i < B; ++i) src[i] = Tb[i];
+    if (!f16_split(lx, src, width, width, t_plain, pt, ldt, kScaleT)) return false;  // planes of Tb (or Tb^T)  [width][width]
     BrLowpBatch lb;
+    std::memset(&lb, 0, sizeof(lb));
+    // Yb^T = Tb V^T (or Tb^T V^T), leaving its kernel transposed and split: planes of Yb [rows][width]
+    for (int i = 0; i < B; ++i) { lb.A[i] = pt[i]; lb.B[i] = pk[i]; lb.shadow[i] = py[i]; }
+    BrLowpArgs ya{width, rows, width, 0, 1.f / (kScaleT * kScaleV), 0.f, B, 0, 3};
+    ya.epilogue = BR_EPI_PLANES;
+    ya.out_lo = 1;
+    ya.f16 = 1;
+    ya.out_scale = kScaleY;
+    if (!hip_ok(c, br_launch_gemm_lowp(s, ya, lb, nullptr), "qr factor product launch")) return false;
     std::memset(&lb, 0, sizeof(lb));
     for (int i = 0; i < B; ++i) { lb.A[i] = pv[i]; lb.B[i] = view(set, i, row0, k0); lb.shadow[i] = pw[i]; }
     BrLowpArgs wa{width, ncols, rows, 0, 1.f / (kScaleV * kScaleC), 0.f, B, 0, 3};  // (V^T C)^T as planes [ncols][width]
@@ -1212,12 +1230,10 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     if (!factor(level - 1, c0, n0, S0, 0, tb)) return false;
     if (n1 > 0) {
       // apply the first child to the second child's columns: Yt = V_0 T_0^T ; C <- C - Yt (V_0^T C)
-      for (int i = 0; i < B; ++i) { gb.A[i] = V0(i); gb.B[i] = Tl(i, level - 1, 0); gb.C[i] = Y(i); }
-      if (!mm(BrGemmArgs{r0, wc, wc, NBT, wc, wc, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
-      float *vb[BR_MAXB], *cp[BR_MAXB];
-      for (int i = 0; i < B; ++i) { vb[i] = V0(i); cp[i] = P[i] + (size_t)c0 * k + c0 + wc; }
+      float *vb[BR_MAXB], *cp[BR_MAXB], *t0[BR_MAXB];
+      for (int i = 0; i < B; ++i) { vb[i] = V0(i); t0[i] = Tl(i, level - 1, 0); cp[i] = P[i] + (size_t)c0 * k + c0 + wc; }
       // (these columns are factorised next and never read as planes again: nothing to keep current)
-      if (!apply_block(vb, wc, cp, r0, n1, rs.planesA, c0 + wc, c0, false)) return false;
+      if (!apply_block(vb, wc, t0, wc, false, cp, r0, n1, rs.planesA, c0 + wc, c0, false)) return false;
       if (!factor(level - 1, c0 + wc, n1, S0, 1, tb)) return false;
     }
     {  // merged factor: diagonal blocks, then the coupling block -T_0 (V_0^T V_1) T_1
@@ -1236,7 +1252,7 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     }
     return true;
   };
-  float *cblk[BR_MAXB], *vblk[BR_MAXB];
+  float *cblk[BR_MAXB], *vblk[BR_MAXB], *tblk[BR_MAXB];
   for (int tb = 0; tb < ntop; ++tb) {
     const int S0 = tb * NBT;
     const int ns = std::min(NBT, k - S0);  // columns of this top block
@@ -1250,10 +1266,8 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     const int nt = k - S0 - ns;
     if (nt <= 0) continue;
     // Yt = V T^T ; C <- C - Yt (V^T C)   on the trailing columns
-    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Ttop(i, tb); gb.C[i] = Y(i); }
-    if (!mm(BrGemmArgs{rows, NBT, NBT, NBT, NBT, NBT, 0, 1, 1.f, 0.f, B, 0}, gb)) return false;
-    for (int i = 0; i < B; ++i) { cblk[i] = P[i] + (size_t)S0 * k + S0 + ns; vblk[i] = V(i); }
-    if (!apply_block(vblk, NBT, cblk, rows, nt, rs.planesA, S0 + ns, S0, true)) return false;
+    for (int i = 0; i < B; ++i) { cblk[i] = P[i] + (size_t)S0 * k + S0 + ns; vblk[i] = V(i); tblk[i] = Ttop(i, tb); }
+    if (!apply_block(vblk, NBT, tblk, NBT, false, cblk, rows, nt, rs.planesA, S0 + ns, S0, true)) return false;
   }
   // Q = H_1 ... H_k applied to the identity, last block reflector first.  Before top block tb is
   // applied, Q differs from the identity only in Q[S1:, S1:] with S1 the next block's offset,
@@ -1275,10 +1289,8 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
     }
     if (!hip_ok(c, br_launch_qr_extract_v(s, pb, B, rows, ns, k, NBT), "qr extract launch")) return false;
     // Y = V T ; Qsub <- Qsub - Y (V^T Qsub),  Qsub = Q[S0:, S0:]
-    for (int i = 0; i < B; ++i) { gb.A[i] = V(i); gb.B[i] = Ttop(i, tb); gb.C[i] = Y(i); }
-    if (!mm(BrGemmArgs{rows, NBT, NBT, NBT, NBT, NBT, 0, 0, 1.f, 0.f, B, 0}, gb)) return false;
-    for (int i = 0; i < B; ++i) { cblk[i] = Q[i] + (size_t)S0 * k + S0; vblk[i] = V(i); }
-    if (!apply_block(vblk, NBT, cblk, rows, rows, rs.planesB, S0, S0, true)) return false;
+    for (int i = 0; i < B; ++i) { cblk[i] = Q[i] + (size_t)S0 * k + S0; vblk[i] = V(i); tblk[i] = Ttop(i, tb); }
+    if (!apply_block(vblk, NBT, tblk, NBT, true, cblk, rows, rows, rs.planesB, S0, S0, true)) return false;
   }
   return true;
 }
