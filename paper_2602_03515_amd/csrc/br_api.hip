@@ -1232,8 +1232,9 @@ static bool qr_batch(br_ctx* c, hipStream_t s, int B, int k, float* const* P, fl
       // apply the first child to the second child's columns: Yt = V_0 T_0^T ; C <- C - Yt (V_0^T C)
       float *vb[BR_MAXB], *cp[BR_MAXB], *t0[BR_MAXB];
       for (int i = 0; i < B; ++i) { vb[i] = V0(i); t0[i] = Tl(i, level - 1, 0); cp[i] = P[i] + (size_t)c0 * k + c0 + wc; }
-      // (these columns are factorised next and never read as planes again: nothing to keep current)
-      if (!apply_block(vb, wc, t0, wc, false, cp, r0, n1, rs.planesA, c0 + wc, c0, false)) return false;
+      // (these columns are factorised next; their planes are read again only if that factorisation has split
+      // applies of its own, i.e. children of 256 columns or more)
+      if (!apply_block(vb, wc, t0, wc, false, cp, r0, n1, rs.planesA, c0 + wc, c0, wc >= 512)) return false;
       if (!factor(level - 1, c0 + wc, n1, S0, 1, tb)) return false;
     }
     {  // merged factor: diagonal blocks, then the coupling block -T_0 (V_0^T V_1) T_1
