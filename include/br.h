@@ -28,7 +28,7 @@
  *              pointers into the workspace until br_destroy.
  *   streams    all work is enqueued on the HIP stream given to br_init (a
  *              hipStream_t passed as void*, NULL = the null stream).  No call
- *              synchronises with the host except br_profile_end.
+ *              synchronises with the host except br_profile_end and br_check_health.
  *   graphs     br_accumulate_stats, br_refresh_basis, br_step, br_clip_gradients and
  *              br_delay_compensate only launch kernels (no allocation, no memset, no
  *              synchronisation), so they may be issued while the stream is being
@@ -92,8 +92,8 @@ typedef enum { BR_SRC_SECOND = 0, BR_SRC_FIRST = 1 } br_source;
  * refresh's large products run in is chosen separately (br_refresh_math). */
 typedef enum { BR_MATH_F32 = 0, BR_MATH_BF16 = 1, BR_MATH_BF16X3 = 2 } br_math;
 
-/* Arithmetic of the refresh's large products (A^k Q of the Power calls and the QR's block-reflector updates of 256
- * and more columns) for factors above order 512; panels, merges and everything on smaller factors are FP32 always.
+/* Arithmetic of the refresh's large products (A^k Q of the Power calls and the products of the QR's block reflectors
+ * of 256 and more columns: V T, V^T C and the update of C) for factors above order 512; panels, merges and everything on smaller factors are FP32 always.
  * F32: FP32 MFMA.  F16X3: each FP32 operand is scaled by a power of two and split into hi + lo FP16 parts
  * (22 mantissa bits; for entries below 2^-3 of the operand's scale an absolute 2^-25 of it), the products
  * hi*hi + hi*lo + lo*hi are accumulated in FP32 on the f16 matrix cores: bases agree with the float64 oracle to
