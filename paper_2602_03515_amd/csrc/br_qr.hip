@@ -19,6 +19,8 @@
 // T.  Each pass therefore reads and writes the active part of the panel exactly once.
 #include "br_internal.h"
 
+#include <algorithm>
+
 namespace br {
 
 constexpr int QR_THREADS = 1024;
@@ -127,24 +129,36 @@ __device__ __forceinline__ float xch_wait(const unsigned long long* slot, unsign
   return __builtin_nanf("");
 }
 
-// Threads 0..31 pass their column's partial sum and get the cluster's sum back; threads 64..95
-// carry the next pivot row (read from pivnext in workgroup 0, written to it in the others).  No
-// barrier inside: the caller's barrier after its own use of the sums also publishes pivnext.
-__device__ __forceinline__ float cluster_combine(const Cluster& cl, int step, float part, float* pivnext, int tid) {
+// Threads 0..31 pass their column's partial sum and get the cluster's sum back.  The partners' words are
+// polled side by side, not one after the other: group g of 32 threads (g = tid / 32) waits for workgroup g's
+// 32 sums and parks them in LDS, so the exchange stays one store and one load deep whatever the size of the
+// cluster, and threads 0..31 then add the partials in workgroup order.  The last group of 32 threads carries
+// the next pivot row (read from pivnext in workgroup 0, written to it in the others).  One barrier inside.
+// Clusters of more workgroups than there are groups to spare fall back to polling in turn.
+constexpr int QR_POLL_GROUPS = QR_THREADS / 32 - 1;  // groups of 32 threads besides the one for the pivot row
+constexpr int QR_WIDE_CLUSTER = 8;                   // widest cluster chosen for speed alone (taller panels take what their rows need)
+__device__ __forceinline__ float cluster_combine(const Cluster& cl, int step, float part, float* pivnext, float (*xs)[32], int tid) {
   const unsigned tag = cl.tag0 + (unsigned)step + 1u;
   unsigned long long* base = cl.xch + (size_t)step * cl.nw * QR_XCH_SLOTS;
   float s = 0.f;
   bool gave_up = false;
-  if (tid < 32) {
+  const int grp = tid >> 5, col = tid & 31;
+  if (tid < 32)
     __hip_atomic_store(base + (size_t)cl.w * QR_XCH_SLOTS + tid, xch_pack(part, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (grp == QR_POLL_GROUPS) {  // another wave than the first sums': the waits overlap
+    if (cl.w == 0)
+      __hip_atomic_store(base + 32 + col, xch_pack(pivnext[col], tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+      pivnext[col] = xch_wait(base + 32 + col, tag, cl.spin_limit, gave_up);
+  }
+  if (cl.nw <= QR_POLL_GROUPS) {
+    if (grp < cl.nw && grp != cl.w) xs[grp][col] = xch_wait(base + (size_t)grp * QR_XCH_SLOTS + col, tag, cl.spin_limit, gave_up);
+    __syncthreads();
+    if (tid < 32)
+      for (int ww = 0; ww < cl.nw; ++ww) s += (ww == cl.w) ? part : xs[ww][tid];
+  } else if (tid < 32) {
     for (int ww = 0; ww < cl.nw; ++ww)
       s += (ww == cl.w) ? part : xch_wait(base + (size_t)ww * QR_XCH_SLOTS + tid, tag, cl.spin_limit, gave_up);
-  } else if (tid >= 64 && tid < 96) {  // another wave than the sums': the two waits overlap
-    const int t = tid - 64;
-    if (cl.w == 0)
-      __hip_atomic_store(base + 32 + t, xch_pack(pivnext[t], tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else
-      pivnext[t] = xch_wait(base + 32 + t, tag, cl.spin_limit, gave_up);
   }
   if (gave_up) {  // rare: flag the matrix (plain store; every writer stores the same 1) and count it
     *cl.failed = 1;
@@ -220,6 +234,7 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   __shared__ float Sl[32][33];  // Sl[l][j] = v_l^T v_j for l < j: the strict upper triangle of V^T V
   __shared__ float Xl[32][33];  // columns of T while they are being solved for
   __shared__ float taus[32];
+  __shared__ float xs[QR_POLL_GROUPS][32];  // the partner workgroups' partial sums of one exchange
 
   float* __restrict__ A = p.A[blockIdx.x];
   float* __restrict__ Vc = p.Vc[blockIdx.x];
@@ -278,7 +293,7 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
   }
   {
     float sum = panel_reduce(acc, red, tid);
-    if (cl.nw > 1) sum = cluster_combine(cl, 0, sum, pivrow[0], tid);
+    if (cl.nw > 1) sum = cluster_combine(cl, 0, sum, pivrow[0], xs, tid);
     if (tid < 32) dvec[tid] = sum;
     __syncthreads();
   }
@@ -334,7 +349,7 @@ __global__ __launch_bounds__(QR_THREADS) void br_qr_panel(BrQrPanelBatch p, int 
       // Column sums of this pass: for c > j the dot products of the next pass, for c < j the entries
       // v_c^T v_j of the Gram matrix of the reflectors.
       float sum = panel_reduce(acc, red, tid);
-      if (cl.nw > 1) sum = cluster_combine(cl, j + 1, sum, pivrow[cur ^ 1], tid);
+      if (cl.nw > 1) sum = cluster_combine(cl, j + 1, sum, pivrow[cur ^ 1], xs, tid);
       if (tid < 32) {
         if (tid > j) dvec[tid] = sum;
         else if (tid < j) Sl[tid][j] = sum;
@@ -646,8 +661,11 @@ __global__ __launch_bounds__(512) void br_qr_panel_apply(PanelApplyArgs a, int r
 
 int br_qr_panel_cluster(int rows) { return (rows + br::QR_MAX_SLAB - 1) / br::QR_MAX_SLAB; }
 
+// Room for the widest cluster a launch may choose: the workgroups the rows need, or QR_WIDE_CLUSTER
+// when a small batch leaves compute units free.
 size_t br_qr_panel_xch_floats(int rows) {
-  return (size_t)(BR_QR_NB + 1) * br_qr_panel_cluster(rows) * br::QR_XCH_SLOTS * 2;  // 8-byte slots
+  const int nw = std::max(br_qr_panel_cluster(rows), br::QR_WIDE_CLUSTER);
+  return (size_t)(BR_QR_NB + 1) * nw * br::QR_XCH_SLOTS * 2;  // 8-byte slots
 }
 
 hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQrClusterBatch& cb, int batch, int rows, int nb,
@@ -657,13 +675,6 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
     return hipErrorInvalidValue;
   int vec = (lda % 4 == 0);
   for (int i = 0; i < batch && vec; ++i) vec = ((reinterpret_cast<uintptr_t>(p.A[i]) & 15u) == 0);
-  const int nw = br_qr_panel_cluster(rows);
-  if (nw > 1)
-    for (int i = 0; i < batch; ++i)
-      if (!cb.xch[i] || !cb.failed[i]) return hipErrorInvalidValue;
-  // balanced slabs, whole sweeps
-  int slab = (rows + nw - 1) / nw;
-  slab = (slab + br::QR_ROWS_PER_SWEEP - 1) / br::QR_ROWS_PER_SWEEP * br::QR_ROWS_PER_SWEEP;
   // A cluster waits for all of its workgroups: every workgroup of a launch must be resident at
   // the same time (one 1024-thread workgroup per compute unit), so large batches go in pieces.
   // How many fit is asked of the device once (three quarters of its compute units, at most
@@ -679,6 +690,27 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
     cap_of_device[dev] = cap < 1 ? 1 : (cap > BR_QR_MAX_RESIDENT ? BR_QR_MAX_RESIDENT : cap);
   }
   const int resident_cap = cap_of_device[dev];
+  // Workgroups per panel: what the rows need at least; more (up to QR_WIDE_CLUSTER) when the whole batch then
+  // still fits in one launch.  A panel costs about 40 us + 10 us per sweep of 128 rows in a workgroup of its own
+  // and 25 to 40 us more in a cluster (an exchange per column, nearly the same for two workgroups as for eight,
+  // the partners' words being polled side by side): shorter slabs on more compute units pay for tall panels of
+  // a small batch (measured on the 3B-class stage: 50.4 -> 44.0 ms of panel time per refresh; no further gain
+  // beyond eight).  At least four sweeps of rows per workgroup: panels of up to 1023 rows stay in one workgroup,
+  // where an exchange would cost what the shorter sweeps save.
+  int nw = br_qr_panel_cluster(rows);
+  {
+    const int fits = resident_cap / batch;
+    const int by_rows = rows / (4 * br::QR_ROWS_PER_SWEEP);
+    const int wide = std::min(std::min(fits, br::QR_WIDE_CLUSTER), std::min(by_rows, br::QR_POLL_GROUPS));
+    if (wide > nw) nw = wide;
+  }
+  // balanced slabs, whole sweeps, no workgroup without rows
+  int slab = (rows + nw - 1) / nw;
+  slab = (slab + br::QR_ROWS_PER_SWEEP - 1) / br::QR_ROWS_PER_SWEEP * br::QR_ROWS_PER_SWEEP;
+  nw = (rows + slab - 1) / slab;
+  if (nw > 1)
+    for (int i = 0; i < batch; ++i)
+      if (!cb.xch[i] || !cb.failed[i]) return hipErrorInvalidValue;
   const int per_launch = resident_cap / nw;
   if (per_launch < 1) return hipErrorInvalidValue;
   for (int off = 0; off < batch; off += per_launch) {
@@ -698,8 +730,14 @@ hipError_t br_launch_qr_panel(hipStream_t s, const BrQrPanelBatch& p, const BrQr
       cc.xch[i] = live ? cb.xch[off + i] : nullptr;
     }
     const int sweeps = slab / br::QR_ROWS_PER_SWEEP;
-    if (sweeps <= 5)
+    if (sweeps <= 3)
+      hipLaunchKernelGGL((br::br_qr_panel<3>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda, vec, ldv, pre_rows,
+                         slab, cc);
+    else if (sweeps <= 5)
       hipLaunchKernelGGL((br::br_qr_panel<5>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda, vec, ldv, pre_rows,
+                         slab, cc);
+    else if (sweeps <= 7)
+      hipLaunchKernelGGL((br::br_qr_panel<7>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda, vec, ldv, pre_rows,
                          slab, cc);
     else if (sweeps <= 10)
       hipLaunchKernelGGL((br::br_qr_panel<10>), dim3(b, nw), dim3(br::QR_THREADS), 0, s, pp, rows, nb, lda, vec, ldv, pre_rows,
