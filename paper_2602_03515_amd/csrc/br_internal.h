@@ -196,9 +196,10 @@ struct BrQrPanelBatch {
   float* T[BR_MAXB];     // BR_QR_NB x BR_QR_NB upper-triangular block-reflector factor
   float* diag[BR_MAXB];  // nb diagonal entries of R for this panel
 };
-// Panels taller than one workgroup's register capacity are factorised by a cluster of
-// br_qr_panel_cluster(rows) workgroups per matrix, which exchange partial sums through xch
-// (br_qr_panel_xch_floats(rows) floats per matrix, 8-byte aligned).  Every exchanged word carries the
+// Panels taller than one workgroup's register capacity are factorised by a cluster of at least
+// br_qr_panel_cluster(rows) workgroups per matrix (more, for speed, when a small batch of tall panels leaves
+// compute units free), which exchange partial sums through xch (br_qr_panel_xch_floats(rows) floats per matrix,
+// 8-byte aligned: room for the widest cluster the launcher may choose).  Every exchanged word carries the
 // tag tag0 + step + 1 (step <= 32): xch must be ZERO before the first panel of a factorisation,
 // and tag0 must differ by at least 64 between the panels that share it afterwards.
 #define BR_QR_MAX_RESIDENT 192  // most workgroups of one panel launch (all of them must be on the chip at once)
