@@ -49,11 +49,12 @@ __device__ __forceinline__ float adam_quotient(float m, float s, const BrAdamArg
   return a.eps_outside ? num / (sqrtf(den) + a.eps) : num / sqrtf(den + a.eps);
 }
 
+// Round to nearest even; NaN stays NaN (quiet).  Branch-free: both results are computed, one is selected.
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+  const uint32_t u = __float_as_uint(f);
+  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t quiet = (u >> 16) | 0x0040u;
+  return (uint16_t)(((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded);
 }
 
 // Load four consecutive elements of a stored row; out-of-range elements read as zero.

@@ -83,11 +83,13 @@ __device__ __forceinline__ bool not_finite(float v) { return (__float_as_uint(v)
 
 enum { EPI_F32 = 0, EPI_PLANES = 1, EPI_ADAM = 2 };
 
+// Round to nearest even; NaN stays NaN (quiet).  Both results are computed and one is selected: a branch here
+// would be taken apart per lane, a hundred times over in the plane-emitting epilogues.
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+  const uint32_t u = __float_as_uint(f);
+  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t quiet = (u >> 16) | 0x0040u;
+  return (uint16_t)(((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded);
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
