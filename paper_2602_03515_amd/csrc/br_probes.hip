@@ -4,6 +4,7 @@
 //
 //   br_probes --mfma-peak
 //   br_probes --stream-peak
+//   br_probes --tile-store
 //   br_probes --lowp-gemm M N K BATCH NPROD MIRROR
 //   br_probes --f32-gemm M N K BATCH TA TB QR LDC BETA
 //
@@ -74,6 +75,79 @@ __global__ __launch_bounds__(256) void br_stream(const br_f4* __restrict__ a, br
     else __builtin_nontemporal_store(0.9f * __builtin_nontemporal_load(b + i) + 0.1f * __builtin_nontemporal_load(a + i), b + i);
   }
   if (mode == 0 && acc.x == 1.2345f) b[0] = acc;
+}
+
+// ---- --tile-store ----------------------------------------------------------------------------
+// What one 512-thread workgroup per compute unit can write: each workgroup stores 256 x 256 FP32 tiles of a
+// large row-major matrix, one after the other, waiting for its stores at the end of every tile (as a contraction
+// kernel's epilogue does).  mode 0: 4-byte stores in the arrangement of a 32 x 32 matrix-instruction accumulator
+// (a lane = one column, four consecutive rows per group); mode 1: the same values in 16-byte stores (a lane = four
+// consecutive columns of one row); mode 2: 16-byte stores, a wave writing one whole 1 KB tile row per instruction.
+__global__ __launch_bounds__(512) void br_tile_store(float* __restrict__ C, int ldc, int tiles_n, int total_tiles, int mode) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3, li = lane & 31, lk = lane >> 5;
+  for (int v = blockIdx.x; v < total_tiles; v += gridDim.x) {
+    const int tm = v / tiles_n, tn = v - tm * tiles_n;
+    float* __restrict__ T = C + (size_t)tm * 256 * ldc + (size_t)tn * 256;
+    const float x = (float)v;
+    if (mode == 0) {
+#pragma unroll
+      for (int a = 0; a < 8; ++a) {
+        const int mi = a >> 1, ni = a & 1;
+        const int col = (wn * 2 + ni) * 32 + li;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = (wm * 4 + mi) * 32 + 8 * (e >> 2) + 4 * lk + (e & 3);
+          T[(size_t)row * ldc + col] = x + e;
+        }
+      }
+    } else if (mode == 1) {
+#pragma unroll
+      for (int a = 0; a < 8; ++a) {
+        const int mi = a >> 1, ni = a & 1;
+        const int colq = (wn * 2 + ni) * 32 + (li & ~3);
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+          const int row = (wm * 4 + mi) * 32 + 8 * vg + 4 * lk + (lane & 3);
+          *reinterpret_cast<br_f4*>(T + (size_t)row * ldc + colq) = br_f4{x, x + 1.f, x + 2.f, x + 3.f};
+        }
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 32; ++r) {
+        const int row = wave * 32 + r;
+        *reinterpret_cast<br_f4*>(T + (size_t)row * ldc + lane * 4) = br_f4{x, x + 1.f, x + 2.f, x + 3.f};
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  }
+}
+
+static int tile_store() {
+  const int n = 16384, tiles_n = n / 256, total = tiles_n * tiles_n;
+  float* c;
+  CHECK_HIP(hipMalloc(&c, (size_t)n * n * 4));
+  CHECK_HIP(hipMemset(c, 0, (size_t)n * n * 4));
+  hipEvent_t e0, e1;
+  CHECK_HIP(hipEventCreate(&e0));
+  CHECK_HIP(hipEventCreate(&e1));
+  for (int grid : {256, 64})
+    for (int mode = 0; mode < 3; ++mode) {
+      hipLaunchKernelGGL(br_tile_store, dim3(grid), dim3(512), 0, 0, c, n, tiles_n, total, mode);
+      CHECK_HIP(hipDeviceSynchronize());
+      CHECK_HIP(hipEventRecord(e0, 0));
+      for (int r = 0; r < 5; ++r) hipLaunchKernelGGL(br_tile_store, dim3(grid), dim3(512), 0, 0, c, n, tiles_n, total, mode);
+      CHECK_HIP(hipEventRecord(e1, 0));
+      CHECK_HIP(hipEventSynchronize(e1));
+      float ms = 0.f;
+      CHECK_HIP(hipEventElapsedTime(&ms, e0, e1));
+      const double per_tile_us = ms / 5 * 1e3 / ((double)total / grid);
+      std::printf("br_tile_store grid %3d mode %d: %.3f ms per GiB, %.2f us per 256 KB tile and workgroup, %.0f GB/s\n", grid, mode, ms / 5,
+                  per_tile_us, (double)n * n * 4 / (ms / 5 * 1e-3) / 1e9);
+    }
+  CHECK_HIP(hipFree(c));
+  return 0;
 }
 
 static int stream_peak() {
@@ -356,7 +430,8 @@ int main(int argc, char** argv) {
                            std::atoi(argv[7]));
   if (argc == 2 && !std::strcmp(argv[1], "--mfma-peak")) return mfma_peak();
   if (argc == 2 && !std::strcmp(argv[1], "--stream-peak")) return stream_peak();
-  std::fprintf(stderr, "usage: br_probes --mfma-peak | --stream-peak | --lowp-gemm M N K BATCH NPROD MIRROR | "
+  if (argc == 2 && !std::strcmp(argv[1], "--tile-store")) return tile_store();
+  std::fprintf(stderr, "usage: br_probes --mfma-peak | --stream-peak | --tile-store | --lowp-gemm M N K BATCH NPROD MIRROR | "
                        "--f32-gemm M N K BATCH TA TB QR LDC BETA\n");
   return 2;
 }
