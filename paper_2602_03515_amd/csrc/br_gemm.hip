@@ -312,6 +312,47 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
     float* __restrict__ Mr = batch.Mrot[mat];
     const BrAdamArgs ad = g.adam;
     const float w1 = 1.0f - ad.beta1, w2 = 1.0f - ad.beta2;
+    if (m0 + BM <= g.M && n0 + BN <= g.N) {
+      // Tile wholly inside the matrix: no bounds tests; one lane offset walks the lane's 32 rows in the order the
+      // accumulators hold them (steps of one row and of five rows, the same for every lane; the two 32-wide column
+      // blocks of a row are 128 bytes apart), the moments of eight rows are fetched before the first store to them.
+      const size_t ld = (size_t)g.ldc;
+      size_t o = (size_t)(m0 + wm * 64 + 4 * lk) * ld + (n0 + wn * 64 + li);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {  // units of eight rows
+        const int mi = u >> 1, h = u & 1;
+        float so[8][2], mo[8][2];
+        size_t ol = o;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni) {
+            so[r][ni] = S[ol + ni * 32];
+            mo[r][ni] = Mr[ol + ni * 32];
+          }
+          ol += ((r & 3) == 3) ? 5 * ld : ld;
+          asm volatile("" : "+v"(ol));
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+#pragma unroll
+          for (int ni = 0; ni < 2; ++ni) {
+            const float gt = g.alpha * acc[mi][ni][h * 8 + r];
+            float mt = mo[r][ni];
+            if (ad.update_mrot) {
+              mt = ad.beta1 * mt + w1 * gt;
+              Mr[o + ni * 32] = mt;
+            }
+            const float st = ad.beta2 * so[r][ni] + w2 * (gt * gt);
+            S[o + ni * 32] = st;
+            C[o + ni * 32] = adam_quotient(mt, st, ad);
+          }
+          o += ((r & 3) == 3) ? 5 * ld : ld;
+          asm volatile("" : "+v"(o));
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
 #pragma unroll
