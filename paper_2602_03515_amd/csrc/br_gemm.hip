@@ -24,6 +24,7 @@ constexpr int BK = 16;
 constexpr int LDS_LD = 132;  // 128 + 4: keeps float4 rows 16-byte aligned, shifts banks by 4 per k
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 8;
+constexpr int SYM_GROUP_M = 8;  // band height of the symmetric launches' triangular tile order (5 to 16 measure the same)
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -186,12 +187,27 @@ __global__ __launch_bounds__(256, 4) void br_gemm_f32_mfma(GemmKernArgs g, BrGem
     mat = bid / per_mat;
     int t = bid - mat * per_mat;
     if (g.mirror) {
-      // t enumerates tiles with tm >= tn: t = tm (tm + 1) / 2 + tn
+      // Tiles with tm >= tn, in bands of SYM_GROUP_M tile rows, column by column inside a band (as the unmirrored
+      // order below: the tiles in flight on one XCD then share a band's few row panels instead of each row
+      // bringing its own).  A band starts where the plain row-by-row count t = tm (tm + 1) / 2 + tn puts its
+      // first row, so the row of t in that count names the band.
       int r = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
       while ((r + 1) * (r + 2) / 2 <= t) ++r;
       while (r * (r + 1) / 2 > t) --r;
-      tm = r;
-      tn = t - r * (r + 1) / 2;
+      const int first = r / SYM_GROUP_M * SYM_GROUP_M;
+      const int gm = min(SYM_GROUP_M, g.tiles_m - first);
+      int local = t - first * (first + 1) / 2;
+      const int rect = first * gm;  // the band's full columns, left of its diagonal block
+      if (local < rect) {
+        tn = local / gm;
+        tm = first + (local - tn * gm);
+      } else {
+        local -= rect;
+        int j = 0;
+        while (local >= gm - j) { local -= gm - j; ++j; }  // column first + j holds rows first + j .. first + gm - 1
+        tn = first + j;
+        tm = first + j + local;
+      }
     } else {
       // Grouped order: GROUP_M tile rows at a time, column by column inside the group, so that the
       // ~128 tiles in flight on one XCD form an 8 x 16 patch (24 operand panels) instead of
