@@ -879,8 +879,11 @@ __global__ __launch_bounds__(256) void br_ingest_planes(IngestArgs a, int R, int
     for (int i = 0; i < 4; ++i) {
       const int rr = i * 16 + (tid >> 4), c4 = (tid & 15) * 4;
       const size_t o = (size_t)(r0 + rr) * Cc + c0 + c4;
-      g[i] = *reinterpret_cast<const float4*>(G + o);
-      m[i] = *reinterpret_cast<const float4*>(M + o);
+      typedef float nt_f4 __attribute__((ext_vector_type(4)));
+      const nt_f4 gv = __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(G + o));
+      const nt_f4 mv = __builtin_nontemporal_load(reinterpret_cast<const nt_f4*>(M + o));
+      g[i] = make_float4(gv.x, gv.y, gv.z, gv.w);
+      m[i] = make_float4(mv.x, mv.y, mv.z, mv.w);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -890,7 +893,11 @@ __global__ __launch_bounds__(256) void br_ingest_planes(IngestArgs a, int R, int
       m[i].y = beta1 * m[i].y + w * g[i].y;
       m[i].z = beta1 * m[i].z + w * g[i].z;
       m[i].w = beta1 * m[i].w + w * g[i].w;
-      *reinterpret_cast<float4*>(M + o) = m[i];
+      {
+        typedef float nt_f4 __attribute__((ext_vector_type(4)));
+        const nt_f4 mo = {m[i].x, m[i].y, m[i].z, m[i].w};
+        __builtin_nontemporal_store(mo, reinterpret_cast<nt_f4*>(M + o));
+      }
       tile[rr][c4 + 0] = g[i].x;
       tile[rr][c4 + 1] = g[i].y;
       tile[rr][c4 + 2] = g[i].z;
