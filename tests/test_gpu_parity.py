@@ -680,15 +680,17 @@ def test_health_words_qr_wait_given_up_keeps_previous_basis(harness):
     opt.close()
 
 
+@pytest.mark.parametrize("shape", [(72, 40), (512, 256)])
 @pytest.mark.parametrize("math", [0, 1])
-def test_health_word_counts_non_finite_weights(harness, math):
+def test_health_word_counts_non_finite_weights(harness, math, shape):
     """An infinite learning rate (not rejected: only NaN is) makes the stored weights non-finite; the kernels
-    that store weights count it, for rotated matrices and for plain-Adam tensors."""
+    that store weights count it, for rotated matrices and for plain-Adam tensors; the second shape has tiles that
+    lie wholly inside the matrix (the epilogues' paths without bounds tests)."""
     from paper_2602_03515_amd import binding as B
     from paper_2602_03515_amd.optimizer import BasisRotationAdam
     for rotate in (True, False):
-        W = torch.ones(72, 40, device="cuda")
-        g = torch.ones(72, 40, device="cuda")
+        W = torch.ones(*shape, device="cuda")
+        g = torch.ones(*shape, device="cuda")
         opt = BasisRotationAdam([W], freq=0, lr=1e-3, rotate=[rotate], math=math)
         opt.step([g], 1e-3)
         assert B.br_check_health(opt.ctx) == [0, 0, 0, 0]
