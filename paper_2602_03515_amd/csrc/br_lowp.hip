@@ -450,7 +450,8 @@ __global__ __launch_bounds__(512, 1) void br_gemm_bf16_mfma(LowpKernArgs g, BrLo
             const int e = h * 8 + r;
 #pragma unroll
             for (int ni = 0; ni < FN; ++ni) {
-              const float val = g.alpha * acc[mi][ni][e] + g.beta * oldf[u & 1][r * FN + ni];
+              // beta times the old value goes into the fused multiply-add unrounded: one rounding at the size of C
+              const float val = __builtin_fmaf(g.beta, oldf[u & 1][r * FN + ni], g.alpha * acc[mi][ni][e]);
               ps[ni * 32] = val;
               if (g.health) bad |= not_finite(val);
             }

@@ -231,6 +231,17 @@ def test_textbook_flags_power_iters_and_stat_beta(harness):
          power_iters=2, stat_beta=0.9, eps=1e-6, beta1=0.8, beta2=0.99)
 
 
+@pytest.mark.parametrize("math", [0, 2, 1])
+@pytest.mark.parametrize("cache", [1, 0])
+def test_textbook_flags_on_interior_tiles(harness, math, cache):
+    """Bias correction, eps outside the root, weight decay, with and without the cached rotated moment, at a shape
+    whose tiles lie partly wholly inside the matrix (300 x 520: the epilogues' paths without bounds tests and the
+    general ones side by side), in every math mode."""
+    W0, grads = synth.spiked_gradients(seed=13, m=300, n=520, steps=9, noise_std=0.1)
+    _run(harness, [W0], [[g] for g in grads], freq=5, lr=1e-3, bias_correction=1, eps_outside_sqrt=1, eps=1e-6,
+         weight_decay=0.01, cache_rotated_moment=cache, math=math, tol=2e-2 if math == 1 else TOL, check_q=(math != 1))
+
+
 @pytest.mark.parametrize("shape", [(48, 200), (200, 48)])
 def test_first_moment_source_unilateral(harness, shape):
     """First-order source (Algorithm 2, first-order branch): Power(M M^T, U) with no L/R buffers.  A wide
