@@ -506,6 +506,17 @@ def test_bf16_modes_injected_basis_midway(harness, math):
     sb.compare_state(tol)
 
 
+@pytest.mark.parametrize("math", [0, 2, 1])
+@pytest.mark.parametrize("shape", [(640, 300), (300, 640)])
+def test_unilateral_with_interior_tiles(harness, shape, math):
+    """Unilateral rotation (right factor for the tall matrix, left factor for the wide one) at shapes whose 256 x 256
+    tiles lie partly wholly inside the matrices, with refreshes, in every math mode."""
+    m, n = shape
+    W0, grads = synth.spiked_gradients(seed=35, m=m, n=n, steps=8, noise_std=0.1)
+    _run(harness, [W0], [[g] for g in grads], freq=4, lr=1e-3, geometry=1, math=math, weight_decay=0.01,
+         tol=2e-2 if math == 1 else TOL, check_q=(math != 1))
+
+
 @pytest.mark.parametrize("math", [1, 2])
 def test_bf16_modes_right_factor_only_chain(harness, math):
     """Unilateral rotation of a tall matrix rotates the right side only.  In the BF16 modes that chain
